@@ -1,0 +1,183 @@
+/*
+ * lp.h -- C ABI of the LayerPipe training hot path on one MI355X (gfx950).
+ *
+ * The library runs one training iteration of a feed-forward network split into the per-layer tasks
+ * of the paper (Sec. I, Sec. II-A, Fig. 1(b)):
+ *
+ *   F   forward product            Z_l  = A_{l-1} . W_l,  A_l = f(Z_l)        Eq. 1, Eq. 2
+ *   dX  activation-gradient product dA_{l-1} = dY_l . W_l^T                    Eq. 4   ("delta")
+ *   f'  Hadamard part               dY_l = dA_l (.) f'(Z_l)                    Eq. 3, executed in the
+ *                                   stage that owns Z_l (inter-layer split, Sec. III-B)
+ *   dW  weight-gradient product     G_l  = A_{l-1}^T . dY_l                    Eq. 5   ("G")
+ *   U   delayed update              W_l(n) = W_l(n-1) - eta G_l(n - d_l)       Eq. 6, d_l delay
+ *                                   elements per layer (Sec. III-A)
+ *
+ * Notation.  The paper is column-vector (z = W a, W of shape [out, in]).  This ABI is batched and
+ * row-major: activations are [batch, features], and the stored weight is the transpose of the
+ * paper's, W_l of shape [in, out], so that Z = A.W, dA = dY.W^T and G = A^T.dY (G has W's shape).
+ * Layers are numbered l = 1..L and training steps n = 1, 2, ... as in the paper.
+ *
+ * Tensors.  All tensor pointers are DEVICE pointers unless a parameter says otherwise; dense,
+ * row-major, 16-byte aligned.  "act type" is the context's dtype: LP_F32 -> float, LP_BF16 -> bfloat16
+ * (upper 16 bits of an IEEE float, round-to-nearest-even).  Gradients G, master weights and the loss
+ * are always float.  Convolution layers (3x3, stride 1, zero pad 1, cross-correlation, no bias) use
+ * NHWC activations [batch, H, W, C] and weights [3][3][C_in][C_out]; an optional 2x2 stride-2 max-pool
+ * follows the activation (first maximum in (row, column) order wins a tie).  No layer has a bias
+ * (Eq. 1 has none).
+ *
+ * Ownership.  The library allocates NO device memory.  The caller owns every buffer, including the
+ * workspace whose size lp_workspace_bytes reports (master weights, working weights, one ring of
+ * d_l + 1 gradient slots per layer, and the activation stashes lp_step uses).  The context itself
+ * (host memory, HIP events) is owned by the library and freed by lp_destroy.
+ *
+ * Execution.  Compute entry points validate their arguments synchronously, then enqueue kernels on
+ * the given hipStream_t (passed as void*; NULL = the default stream) and return without waiting.
+ * Every function returns an lp_status; on error nothing has been enqueued and lp_last_error gives
+ * a message.  No function throws or aborts.  A context is not thread-safe.
+ */
+#ifndef LAYERPIPE_LP_H
+#define LAYERPIPE_LP_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct lp_ctx lp_ctx;
+
+typedef enum {
+  LP_OK = 0,
+  LP_ERR_NULL = 1,      /* a required pointer is NULL */
+  LP_ERR_SHAPE = 2,     /* a size or range is impossible (batch <= 0, col range, H/W odd with pool ...) */
+  LP_ERR_DTYPE = 3,     /* unknown dtype / loss / activation / layer kind */
+  LP_ERR_LAYER = 4,     /* layer index outside 1..L, or consecutive layers do not fit */
+  LP_ERR_DELAY = 5,     /* negative delay */
+  LP_ERR_STATE = 6,     /* call needs a bound workspace or weights that were never set */
+  LP_ERR_WORKSPACE = 7, /* workspace too small or misaligned */
+  LP_ERR_HIP = 8        /* a HIP runtime call failed (message holds hipGetErrorString) */
+} lp_status;
+
+typedef enum { LP_F32 = 0, LP_BF16 = 1 } lp_dtype;
+typedef enum { LP_LOSS_SOFTMAX_CE = 0, LP_LOSS_MSE = 1 } lp_loss;
+typedef enum { LP_LINEAR = 0, LP_CONV3X3 = 1 } lp_kind;
+typedef enum { LP_ACT_IDENTITY = 0, LP_ACT_RELU = 1, LP_ACT_GELU = 2 } lp_act;
+
+/* One layer.  LINEAR: in/out are feature counts, H = W = pool = 0.  CONV3X3: in/out are channel
+ * counts, H x W the (input = output) image size, pool 0 or 2.  `delay` = d_l >= 0, the number of
+ * delay elements on this layer's gradient->update edge (Sec. III-A: twice the number of pipeline
+ * stages after the layer). */
+typedef struct {
+  int kind;   /* lp_kind */
+  int in;
+  int out;
+  int H;
+  int W;
+  int act;    /* lp_act; the last layer must be LP_ACT_IDENTITY (its output feeds the loss) */
+  int pool;
+  int delay;
+} lp_layer_desc;
+
+/* Which internal tensor lp_tensor returns. */
+typedef enum {
+  LP_T_MASTER_W = 0,   /* float [in,out] (conv: [3][3][in][out]), the weights Eq. 6 updates          */
+  LP_T_WORK_W = 1,     /* act type, the copy F and dX currently read (same buffer as master for F32) */
+  LP_T_A = 2,          /* act type, A_l as written by lp_step (after the pool, if any)                */
+  LP_T_Z = 3,          /* act type, Z_l as written by lp_step; NULL if the step does not keep it       */
+  LP_T_DA = 4,         /* act type, dA_l = dE/dA_l (shape of A_l); NULL for l = L                      */
+  LP_T_DY = 5,         /* act type, dY_l = delta_l (shape of Z_l)                                     */
+  LP_T_G_LAST = 6      /* float, ring slot holding the gradient of the most recent finished step     */
+} lp_tensor_id;
+
+/* ---- life cycle (host only; touches no device) ---------------------------------------------- */
+
+/* Builds a context for L layers and a fixed batch size.  `layers` is copied.  Checks that layer
+ * l's output size equals layer l+1's input size (a conv output feeding a linear layer is flattened
+ * in NHWC order).  lr is eta of Eq. 6.  *out is set only on LP_OK. */
+int lp_create(const lp_layer_desc* layers, int L, int batch, int dtype, int loss, float lr, lp_ctx** out);
+int lp_destroy(lp_ctx* ctx);
+/* Message of the last failing call on ctx (owned by ctx; valid until the next call).  ctx == NULL
+ * returns the message of the last failing lp_create. */
+const char* lp_last_error(const lp_ctx* ctx);
+
+/* Bytes of device workspace this context needs (multiple of 256). */
+int lp_workspace_bytes(const lp_ctx* ctx, size_t* bytes);
+/* Hands the workspace to the context.  dev_ptr: 256-byte aligned device memory of at least
+ * lp_workspace_bytes, owned by the caller, which must outlive the context's use of it.  Contents
+ * need not be initialised.  Rebinding resets the step counter and marks all weights unset. */
+int lp_bind_workspace(lp_ctx* ctx, void* dev_ptr, size_t bytes);
+
+/* Copies float weights of layer l into the master copy and (BF16) rounds them into the working copy.
+ * W: [in,out] or [3][3][in][out]; host pointer if is_device == 0 (copied synchronously), else a
+ * device pointer (copied on `stream`). */
+int lp_set_weights(lp_ctx* ctx, int l, const float* W, int is_device, void* stream);
+/* Copies the master weights of layer l to dst (host: synchronous after draining `stream`). */
+int lp_get_weights(lp_ctx* ctx, int l, float* dst, int is_device, void* stream);
+
+/* ---- the per-layer tasks ------------------------------------------------------------------- */
+
+/* F (Eq. 1, Eq. 2).  X: A_{l-1}, act type, [batch, in] (conv: [batch,H,W,in]).  Writes Z_l (shape
+ * [batch,out] / [batch,H,W,out]) and A_l = f(Z_l) (conv with pool: [batch,H/2,W/2,out]); either
+ * may be NULL to skip that output, except that a pooled layer needs Z.  A is computed from the
+ * stored (rounded) Z.  Reads the current working weights W_l(n-1). */
+int lp_forward(lp_ctx* ctx, int l, const void* X, void* Z, void* A, void* stream);
+
+/* Error at the output and delta of the last layer (the paper only says the error is computed from
+ * the ground truth; this library offers two).  ZL: act type [batch, D_L].  SOFTMAX_CE: target =
+ * int labels [batch] in [0, D_L); E = -mean_b log softmax(z_b)[y_b]; dYL = (softmax - onehot)/batch.
+ * MSE: target = act type [batch, D_L]; E = mean (z - t)^2; dYL = 2 (z - t) / (batch * D_L).
+ * loss_dev: device float, may be NULL.  Needs a bound workspace (row partials). */
+int lp_loss_grad(lp_ctx* ctx, const void* ZL, const void* target, void* dYL, float* loss_dev, void* stream);
+
+/* The Hadamard part of Eq. 3 for layer l, the piece the inter-layer split moves into the stage that
+ * holds Z_l:  dY_l = dA_l (.) f'(Z_l).  S is the stashed Z_l; for a ReLU layer without pool the
+ * stashed A_l works as well (same sign).  For a pooled layer dA has the pooled shape and is routed
+ * to the first maximum of each 2x2 window of S before the mask is applied.  dY may alias dA only if
+ * the layer is not pooled.  ReLU'(0) = 0; GELU' = Phi(z) + z phi(z). */
+int lp_act_grad(lp_ctx* ctx, int l, const void* dA, const void* S, void* dY, void* stream);
+
+/* dX (Eq. 4): dA_{l-1}[:, col0:col1] = dY_l . W_l[col0:col1, :]^T with the current working weights.
+ * dX is the full [batch, in] tensor (conv: [batch,H,W,in]); only columns (channels) [col0, col1)
+ * of the previous layer's features are written.  (0, in) computes all of it; two calls with
+ * complementary ranges are the delta' / delta'' partition of Sec. III-B and may run concurrently. */
+int lp_grad_act(lp_ctx* ctx, int l, const void* dY, void* dX, int col0, int col1, void* stream);
+
+/* dW (Eq. 5): G_l = A_{l-1}^T . dY_l, float, shape of W_l.  G == NULL writes into the ring slot of
+ * the step in progress, (n+1) mod (d_l+1), where lp_update will find it d_l steps later. */
+int lp_grad_weight(lp_ctx* ctx, int l, const void* X, const void* dY, float* G, void* stream);
+
+/* U (Eq. 6).  G != NULL: W_l <- W_l - eta G.  G == NULL: uses G_l((n+1) - d_l) from the ring; does
+ * nothing if (n+1) - d_l < 1 (the delay elements start empty).  Updates the float master and (BF16)
+ * writes the rounded working copy into the *other* of two buffers, which becomes current for calls
+ * made after this one; kernels already enqueued keep reading the old version (weight stashing,
+ * Sec. III-A).  F32 contexts update in place: order the call after the readers of W_l. */
+int lp_update(lp_ctx* ctx, int l, const float* G, void* stream);
+
+/* Ends a step driven through the per-layer calls: n <- n + 1. */
+int lp_advance(lp_ctx* ctx);
+
+/* One whole training iteration for one minibatch: F for l = 1..L, the loss, then for l = L..1 the
+ * tasks dW_l, dX_l and the moved Hadamard of layer l-1, and every layer's delayed update; n <- n+1.
+ * X0: act type input batch.  target: as in lp_loss_grad.  delay: optional int[L] overriding the
+ * descriptors' d_l for the rest of the context's life (the rings are sized by lp_create, so
+ * delay[l] may not exceed the descriptor's value); NULL keeps them.  loss_dev: device float or NULL.
+ * streams[0..n_streams): hipStream_t handles.  With one stream all tasks run in order on it.  With
+ * more, the critical chain (F, loss, dX, Hadamard) runs on streams[0], dW on streams[1], updates on
+ * streams[2 % n_streams]: the G task is off the critical loop (Sec. III-C) and W_l(n) only has to
+ * exist before step n+1.  All side-stream work is joined back into streams[0] before returning, so
+ * the caller orders against streams[0] only.  X0 and target must stay unchanged until then.
+ * With every delay 0 the result equals the per-layer calls made in textbook order. */
+int lp_step(lp_ctx* ctx, const void* X0, const void* target, const int* delay, float* loss_dev,
+            void* const* streams, int n_streams);
+
+/* Number of finished steps n. */
+int lp_step_index(const lp_ctx* ctx, long* n);
+/* Blocks until every stream the context has enqueued work on is idle. */
+int lp_sync(lp_ctx* ctx);
+/* Device address and size of an internal tensor (see lp_tensor_id) for inspection. */
+int lp_tensor(lp_ctx* ctx, int l, int which, void** dev_ptr, size_t* bytes);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LAYERPIPE_LP_H */

@@ -1,0 +1,373 @@
+// Bandwidth-bound tasks of the training step: the Hadamard part of Eq. 3 (run in the stage that
+// holds Z_l), the error at the output with the last layer's delta, the delayed SGD update of Eq. 6,
+// and the max-pool helpers of convolution layers.  All kernels stream 16-byte vectors per lane with
+// consecutive lanes on consecutive addresses; row reductions stay inside one 64-lane wavefront.
+#include "lp_kernels.h"
+
+namespace lp {
+namespace {
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ unsigned short f2bf(float v) {
+  __bf16 b = (__bf16)v;  // round-to-nearest-even
+  return __builtin_bit_cast(unsigned short, b);
+}
+__device__ __forceinline__ float bf2f(unsigned short b) { return __uint_as_float(((unsigned)b) << 16); }
+
+template <int ACT>
+__device__ __forceinline__ float act_f(float z) {
+  if (ACT == ACT_RELU) return z > 0.f ? z : 0.f;
+  if (ACT == ACT_GELU) return 0.5f * z * (1.f + erff(z * 0.70710678118654752440f));
+  return z;
+}
+template <int ACT>
+__device__ __forceinline__ float act_df(float z) {
+  if (ACT == ACT_RELU) return z > 0.f ? 1.f : 0.f;
+  if (ACT == ACT_GELU) {
+    const float cdf = 0.5f * (1.f + erff(z * 0.70710678118654752440f));
+    const float pdf = 0.39894228040143267794f * __expf(-0.5f * z * z);
+    return cdf + z * pdf;
+  }
+  return 1.f;
+}
+
+template <typename T>
+struct Elem;
+template <>
+struct Elem<unsigned short> {
+  static __device__ __forceinline__ float ld(unsigned short v) { return bf2f(v); }
+  static __device__ __forceinline__ unsigned short st(float v) { return f2bf(v); }
+};
+template <>
+struct Elem<float> {
+  static __device__ __forceinline__ float ld(float v) { return v; }
+  static __device__ __forceinline__ float st(float v) { return v; }
+};
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+// sum over a 256-thread block, result valid in every thread; fixed order
+__device__ __forceinline__ float block_sum_256(float v, float* sh4) {
+  v = wave_sum(v);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) sh4[threadIdx.x >> 6] = v;
+  __syncthreads();
+  return (sh4[0] + sh4[1]) + (sh4[2] + sh4[3]);
+}
+
+// ---- dY = dA (.) f'(S) ---------------------------------------------------------------------------
+constexpr int EW_VEC_PER_THREAD = 4;
+
+template <int ACT>
+__global__ void __launch_bounds__(256) act_grad_bf16_kernel(const u32x4* __restrict__ dA, const u32x4* __restrict__ S,
+                                                            u32x4* __restrict__ dY, size_t nvec, size_t n) {
+  const size_t base = (size_t)blockIdx.x * (256 * EW_VEC_PER_THREAD) + threadIdx.x;
+  u32x4 a[EW_VEC_PER_THREAD], s[EW_VEC_PER_THREAD];
+#pragma unroll
+  for (int u = 0; u < EW_VEC_PER_THREAD; ++u) {
+    const size_t i = base + (size_t)u * 256;
+    if (i < nvec) { a[u] = __builtin_nontemporal_load(dA + i); s[u] = __builtin_nontemporal_load(S + i); }
+  }
+#pragma unroll
+  for (int u = 0; u < EW_VEC_PER_THREAD; ++u) {
+    const size_t i = base + (size_t)u * 256;
+    if (i < nvec) {
+      u32x4 o;
+#pragma unroll
+      for (int d = 0; d < 4; ++d) {
+        const float a0 = bf2f((unsigned short)(a[u][d] & 0xffffu)), a1 = bf2f((unsigned short)(a[u][d] >> 16));
+        const float s0 = bf2f((unsigned short)(s[u][d] & 0xffffu)), s1 = bf2f((unsigned short)(s[u][d] >> 16));
+        o[d] = (unsigned)f2bf(a0 * act_df<ACT>(s0)) | ((unsigned)f2bf(a1 * act_df<ACT>(s1)) << 16);
+      }
+      __builtin_nontemporal_store(o, dY + i);
+    }
+  }
+  // scalar tail (n not a multiple of 8) by the first lanes of block 0
+  if (blockIdx.x == 0) {
+    const size_t i = nvec * 8 + threadIdx.x;
+    if (i < n) {
+      const unsigned short* a16 = (const unsigned short*)dA;
+      const unsigned short* s16 = (const unsigned short*)S;
+      ((unsigned short*)dY)[i] = f2bf(bf2f(a16[i]) * act_df<ACT>(bf2f(s16[i])));
+    }
+  }
+}
+
+template <int ACT>
+__global__ void __launch_bounds__(256) act_grad_f32_kernel(const f32x4* __restrict__ dA, const f32x4* __restrict__ S,
+                                                           f32x4* __restrict__ dY, size_t nvec, size_t n) {
+  const size_t base = (size_t)blockIdx.x * (256 * EW_VEC_PER_THREAD) + threadIdx.x;
+#pragma unroll
+  for (int u = 0; u < EW_VEC_PER_THREAD; ++u) {
+    const size_t i = base + (size_t)u * 256;
+    if (i < nvec) {
+      const f32x4 a = dA[i], s = S[i];
+      f32x4 o;
+#pragma unroll
+      for (int d = 0; d < 4; ++d) o[d] = a[d] * act_df<ACT>(s[d]);
+      dY[i] = o;
+    }
+  }
+  if (blockIdx.x == 0) {
+    const size_t i = nvec * 4 + threadIdx.x;
+    if (i < n) ((float*)dY)[i] = ((const float*)dA)[i] * act_df<ACT>(((const float*)S)[i]);
+  }
+}
+
+// ---- max-pool helpers (NHWC, 2x2 stride 2) -------------------------------------------------------
+template <typename T, int ACT>
+__global__ void __launch_bounds__(256) relu_pool_kernel(const T* __restrict__ z, T* __restrict__ a, int B, int H, int W, int C) {
+  const size_t total = (size_t)B * (H / 2) * (W / 2) * C;
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= total) return;
+  const int c = (int)(i % C);
+  size_t t = i / C;
+  const int x = (int)(t % (W / 2)); t /= (W / 2);
+  const int y = (int)(t % (H / 2));
+  const int b = (int)(t / (H / 2));
+  float best = 0.f;
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    const size_t off = (((size_t)b * H + (2 * y + (k >> 1))) * W + (2 * x + (k & 1))) * C + c;
+    const float v = Elem<T>::ld(Elem<T>::st(act_f<ACT>(Elem<T>::ld(z[off]))));
+    if (k == 0 || v > best) best = v;
+  }
+  a[i] = Elem<T>::st(best);
+}
+
+template <typename T, int ACT>
+__global__ void __launch_bounds__(256) act_grad_pool_kernel(const T* __restrict__ dA, const T* __restrict__ Z, T* __restrict__ dY,
+                                                            int B, int H, int W, int C) {
+  const size_t total = (size_t)B * (H / 2) * (W / 2) * C;
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= total) return;
+  const int c = (int)(i % C);
+  size_t t = i / C;
+  const int x = (int)(t % (W / 2)); t /= (W / 2);
+  const int y = (int)(t % (H / 2));
+  const int b = (int)(t / (H / 2));
+  size_t off[4];
+  float zv[4];
+  float best = 0.f;
+  int arg = 0;
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    off[k] = (((size_t)b * H + (2 * y + (k >> 1))) * W + (2 * x + (k & 1))) * C + c;
+    zv[k] = Elem<T>::ld(Z[off[k]]);
+    const float v = Elem<T>::ld(Elem<T>::st(act_f<ACT>(zv[k])));
+    if (k == 0 || v > best) { best = v; arg = k; }   // strict '>' keeps the first maximum
+  }
+  const float da = Elem<T>::ld(dA[i]);
+#pragma unroll
+  for (int k = 0; k < 4; ++k) dY[off[k]] = Elem<T>::st(k == arg ? da * act_df<ACT>(zv[k]) : 0.f);
+}
+
+// ---- loss + delta of the output layer ------------------------------------------------------------
+// one wavefront per row
+template <typename T>
+__global__ void __launch_bounds__(256) softmax_ce_kernel(const T* __restrict__ Z, const int* __restrict__ labels, T* __restrict__ dY,
+                                                         float* __restrict__ row_loss, int rows, int cols) {
+  const int lane = threadIdx.x & 63;
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const T* z = Z + (size_t)row * cols;
+  float m = -INFINITY;
+  for (int c = lane; c < cols; c += 64) m = fmaxf(m, Elem<T>::ld(z[c]));
+  m = wave_max(m);
+  float sum = 0.f;
+  for (int c = lane; c < cols; c += 64) sum += expf(Elem<T>::ld(z[c]) - m);
+  sum = wave_sum(sum);
+  const int y = labels[row];
+  const float inv = 1.f / sum, invB = 1.f / (float)rows;
+  T* dy = dY + (size_t)row * cols;
+  for (int c = lane; c < cols; c += 64) {
+    const float p = expf(Elem<T>::ld(z[c]) - m) * inv;
+    dy[c] = Elem<T>::st((p - (c == y ? 1.f : 0.f)) * invB);
+  }
+  if (lane == 0) row_loss[row] = (m + logf(sum)) - Elem<T>::ld(z[y]);
+}
+
+constexpr int MSE_PER_BLOCK = 256 * 16;
+
+template <typename T>
+__global__ void __launch_bounds__(256) mse_kernel(const T* __restrict__ Z, const T* __restrict__ Tg, T* __restrict__ dY,
+                                                  float* __restrict__ partial, size_t n, float scale) {
+  __shared__ float sh4[4];
+  float acc = 0.f;
+  const size_t b0 = (size_t)blockIdx.x * MSE_PER_BLOCK;
+#pragma unroll 4
+  for (int u = 0; u < MSE_PER_BLOCK / 256; ++u) {
+    const size_t i = b0 + (size_t)u * 256 + threadIdx.x;
+    if (i < n) {
+      const float d = Elem<T>::ld(Z[i]) - Elem<T>::ld(Tg[i]);
+      acc += d * d;
+      dY[i] = Elem<T>::st(d * scale);
+    }
+  }
+  acc = block_sum_256(acc, sh4);
+  if (threadIdx.x == 0) partial[blockIdx.x] = acc;
+}
+
+// loss = scale * sum(partials), fixed summation order
+__global__ void __launch_bounds__(256) finalize_loss_kernel(const float* __restrict__ partial, size_t count, float scale,
+                                                            float* __restrict__ loss) {
+  __shared__ float sh4[4];
+  float acc = 0.f;
+  for (size_t i = threadIdx.x; i < count; i += 256) acc += partial[i];
+  acc = block_sum_256(acc, sh4);
+  if (threadIdx.x == 0) *loss = acc * scale;
+}
+
+// ---- Eq. 6 -----------------------------------------------------------------------------------------
+template <bool BF16>
+__global__ void __launch_bounds__(256) sgd_kernel(f32x4* __restrict__ master, const f32x4* __restrict__ g, u32x2* __restrict__ work,
+                                                  float neg_lr, size_t nvec, size_t n) {
+  const size_t base = (size_t)blockIdx.x * (256 * EW_VEC_PER_THREAD) + threadIdx.x;
+  f32x4 w[EW_VEC_PER_THREAD], gg[EW_VEC_PER_THREAD];
+#pragma unroll
+  for (int u = 0; u < EW_VEC_PER_THREAD; ++u) {
+    const size_t i = base + (size_t)u * 256;
+    if (i < nvec) { gg[u] = __builtin_nontemporal_load(g + i); w[u] = master[i]; }
+  }
+#pragma unroll
+  for (int u = 0; u < EW_VEC_PER_THREAD; ++u) {
+    const size_t i = base + (size_t)u * 256;
+    if (i < nvec) {
+      f32x4 o;
+#pragma unroll
+      for (int d = 0; d < 4; ++d) o[d] = fmaf(neg_lr, gg[u][d], w[u][d]);
+      master[i] = o;
+      if (BF16) {
+        u32x2 b;
+        b[0] = (unsigned)f2bf(o[0]) | ((unsigned)f2bf(o[1]) << 16);
+        b[1] = (unsigned)f2bf(o[2]) | ((unsigned)f2bf(o[3]) << 16);
+        work[i] = b;
+      }
+    }
+  }
+  if (blockIdx.x == 0) {
+    const size_t i = nvec * 4 + threadIdx.x;
+    if (i < n) {
+      float* m = (float*)master;
+      const float o = fmaf(neg_lr, ((const float*)g)[i], m[i]);
+      m[i] = o;
+      if (BF16) ((unsigned short*)work)[i] = f2bf(o);
+    }
+  }
+}
+
+__global__ void __launch_bounds__(256) cast_bf16_kernel(const float* __restrict__ src, unsigned short* __restrict__ dst, size_t n) {
+  const size_t i = ((size_t)blockIdx.x * 256 + threadIdx.x) * 4;
+  if (i + 3 < n) {
+    const f32x4 v = *(const f32x4*)(src + i);
+    u32x2 b;
+    b[0] = (unsigned)f2bf(v[0]) | ((unsigned)f2bf(v[1]) << 16);
+    b[1] = (unsigned)f2bf(v[2]) | ((unsigned)f2bf(v[3]) << 16);
+    *(u32x2*)(dst + i) = b;
+  } else {
+    for (size_t j = i; j < n; ++j) dst[j] = f2bf(src[j]);
+  }
+}
+
+inline unsigned blocks_for(size_t items, size_t per_block) { return (unsigned)((items + per_block - 1) / per_block); }
+
+}  // namespace
+
+hipError_t launch_act_grad(bool bf16, int act, const void* dA, const void* S, void* dY, size_t n, hipStream_t s) {
+  if (n == 0) return hipSuccess;
+  if (act == ACT_IDENTITY) {
+    if (dA == dY) return hipSuccess;
+    return hipMemcpyAsync(dY, dA, n * (bf16 ? 2 : 4), hipMemcpyDeviceToDevice, s);
+  }
+  const size_t per = bf16 ? 8 : 4, nvec = n / per;
+  const unsigned nb = blocks_for(nvec > 0 ? nvec : 1, 256 * EW_VEC_PER_THREAD);
+  if (bf16) {
+    if (act == ACT_RELU) hipLaunchKernelGGL(act_grad_bf16_kernel<ACT_RELU>, dim3(nb), dim3(256), 0, s, (const u32x4*)dA, (const u32x4*)S, (u32x4*)dY, nvec, n);
+    else hipLaunchKernelGGL(act_grad_bf16_kernel<ACT_GELU>, dim3(nb), dim3(256), 0, s, (const u32x4*)dA, (const u32x4*)S, (u32x4*)dY, nvec, n);
+  } else {
+    if (act == ACT_RELU) hipLaunchKernelGGL(act_grad_f32_kernel<ACT_RELU>, dim3(nb), dim3(256), 0, s, (const f32x4*)dA, (const f32x4*)S, (f32x4*)dY, nvec, n);
+    else hipLaunchKernelGGL(act_grad_f32_kernel<ACT_GELU>, dim3(nb), dim3(256), 0, s, (const f32x4*)dA, (const f32x4*)S, (f32x4*)dY, nvec, n);
+  }
+  return hipGetLastError();
+}
+
+template <typename T>
+static hipError_t relu_pool_t(const void* z, void* a, int B, int H, int W, int C, int act, hipStream_t s) {
+  const size_t total = (size_t)B * (H / 2) * (W / 2) * C;
+  const unsigned nb = blocks_for(total, 256);
+  if (act == ACT_RELU) hipLaunchKernelGGL((relu_pool_kernel<T, ACT_RELU>), dim3(nb), dim3(256), 0, s, (const T*)z, (T*)a, B, H, W, C);
+  else if (act == ACT_GELU) hipLaunchKernelGGL((relu_pool_kernel<T, ACT_GELU>), dim3(nb), dim3(256), 0, s, (const T*)z, (T*)a, B, H, W, C);
+  else hipLaunchKernelGGL((relu_pool_kernel<T, ACT_IDENTITY>), dim3(nb), dim3(256), 0, s, (const T*)z, (T*)a, B, H, W, C);
+  return hipGetLastError();
+}
+hipError_t launch_relu_pool(bool bf16, const void* z, void* a, int B, int H, int W, int C, int act, hipStream_t s) {
+  return bf16 ? relu_pool_t<unsigned short>(z, a, B, H, W, C, act, s) : relu_pool_t<float>(z, a, B, H, W, C, act, s);
+}
+
+template <typename T>
+static hipError_t act_grad_pool_t(int act, const void* dA, const void* Z, void* dY, int B, int H, int W, int C, hipStream_t s) {
+  const size_t total = (size_t)B * (H / 2) * (W / 2) * C;
+  const unsigned nb = blocks_for(total, 256);
+  if (act == ACT_RELU) hipLaunchKernelGGL((act_grad_pool_kernel<T, ACT_RELU>), dim3(nb), dim3(256), 0, s, (const T*)dA, (const T*)Z, (T*)dY, B, H, W, C);
+  else if (act == ACT_GELU) hipLaunchKernelGGL((act_grad_pool_kernel<T, ACT_GELU>), dim3(nb), dim3(256), 0, s, (const T*)dA, (const T*)Z, (T*)dY, B, H, W, C);
+  else hipLaunchKernelGGL((act_grad_pool_kernel<T, ACT_IDENTITY>), dim3(nb), dim3(256), 0, s, (const T*)dA, (const T*)Z, (T*)dY, B, H, W, C);
+  return hipGetLastError();
+}
+hipError_t launch_act_grad_pool(bool bf16, int act, const void* dA, const void* Z, void* dY, int B, int H, int W, int C, hipStream_t s) {
+  return bf16 ? act_grad_pool_t<unsigned short>(act, dA, Z, dY, B, H, W, C, s) : act_grad_pool_t<float>(act, dA, Z, dY, B, H, W, C, s);
+}
+
+size_t loss_partials_count(int loss_is_mse, int rows, int cols) {
+  if (!loss_is_mse) return (size_t)rows;
+  return ((size_t)rows * cols + MSE_PER_BLOCK - 1) / MSE_PER_BLOCK;
+}
+
+hipError_t launch_softmax_ce(bool bf16, const void* Z, const int* labels, void* dY, float* loss, float* partials, int rows, int cols, hipStream_t s) {
+  const unsigned nb = (unsigned)((rows + 3) / 4);
+  if (bf16) hipLaunchKernelGGL(softmax_ce_kernel<unsigned short>, dim3(nb), dim3(256), 0, s, (const unsigned short*)Z, labels, (unsigned short*)dY, partials, rows, cols);
+  else hipLaunchKernelGGL(softmax_ce_kernel<float>, dim3(nb), dim3(256), 0, s, (const float*)Z, labels, (float*)dY, partials, rows, cols);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess || !loss) return e;
+  hipLaunchKernelGGL(finalize_loss_kernel, dim3(1), dim3(256), 0, s, (const float*)partials, (size_t)rows, 1.f / (float)rows, loss);
+  return hipGetLastError();
+}
+
+hipError_t launch_mse(bool bf16, const void* Z, const void* T, void* dY, float* loss, float* partials, int rows, int cols, hipStream_t s) {
+  const size_t n = (size_t)rows * cols;
+  const unsigned nb = (unsigned)loss_partials_count(1, rows, cols);
+  const float scale = 2.f / (float)n;
+  if (bf16) hipLaunchKernelGGL(mse_kernel<unsigned short>, dim3(nb), dim3(256), 0, s, (const unsigned short*)Z, (const unsigned short*)T, (unsigned short*)dY, partials, n, scale);
+  else hipLaunchKernelGGL(mse_kernel<float>, dim3(nb), dim3(256), 0, s, (const float*)Z, (const float*)T, (float*)dY, partials, n, scale);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess || !loss) return e;
+  hipLaunchKernelGGL(finalize_loss_kernel, dim3(1), dim3(256), 0, s, (const float*)partials, (size_t)nb, 1.f / (float)n, loss);
+  return hipGetLastError();
+}
+
+hipError_t launch_sgd(float* master, const float* g, void* work_out_bf16, float lr, size_t n, hipStream_t s) {
+  if (n == 0) return hipSuccess;
+  const size_t nvec = n / 4;
+  const unsigned nb = blocks_for(nvec > 0 ? nvec : 1, 256 * EW_VEC_PER_THREAD);
+  if (work_out_bf16) hipLaunchKernelGGL(sgd_kernel<true>, dim3(nb), dim3(256), 0, s, (f32x4*)master, (const f32x4*)g, (u32x2*)work_out_bf16, -lr, nvec, n);
+  else hipLaunchKernelGGL(sgd_kernel<false>, dim3(nb), dim3(256), 0, s, (f32x4*)master, (const f32x4*)g, (u32x2*)nullptr, -lr, nvec, n);
+  return hipGetLastError();
+}
+
+hipError_t launch_cast_bf16(const float* src, void* dst_bf16, size_t n, hipStream_t s) {
+  if (n == 0) return hipSuccess;
+  hipLaunchKernelGGL(cast_bf16_kernel, dim3(blocks_for(n, 1024)), dim3(256), 0, s, src, (unsigned short*)dst_bf16, n);
+  return hipGetLastError();
+}
+
+}  // namespace lp

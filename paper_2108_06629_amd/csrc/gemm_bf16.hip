@@ -1,0 +1,143 @@
+// bf16 x bf16 -> fp32 GEMM launchers for the three products of a fully connected layer
+// (Eq. 1, Eq. 4, Eq. 5):
+//
+//     F   Z  = A_prev . W        A: k contiguous,  B = W  [K][N]: k strided
+//     dX  dA = dY . W^T          A: k contiguous,  B = W  [N][K]: k contiguous
+//     dW  G  = A_prev^T . dY     A: k strided,     B = dY [K][N]: k strided
+//
+// The kernel body is gemm_core.h; this file binds plain 2-D operands to it and picks a tile shape.
+#include "gemm_core.h"
+#include "lp_kernels.h"
+
+namespace lp {
+namespace {
+
+using namespace core;
+
+struct GemmKArgs {
+  const unsigned short* A;
+  const unsigned short* B;
+  unsigned short* out_z;
+  unsigned short* out_a;
+  float* out_f32;
+  int M, N, K, lda, ldb, ldc, act;
+  unsigned a_bytes, b_bytes;
+  int vec_out;
+};
+
+template <bool KC, int R, int BK, int NT, bool ALIGNED>
+struct StageSel {
+  using type = StageKC<R, BK, NT, ALIGNED>;
+};
+template <int R, int BK, int NT, bool ALIGNED>
+struct StageSel<false, R, BK, NT, ALIGNED> {
+  using type = StageKS<R, BK, NT, ALIGNED>;
+};
+
+template <int BM, int BN, int BK, int WM, int WN, bool AKC, bool BKC, bool ALIGNED>
+__global__ void __launch_bounds__(WM* WN * 64) gemm_bf16_kernel(GemmKArgs p) {
+  constexpr int NT = WM * WN * 64;
+  extern __shared__ __attribute__((aligned(16))) unsigned short smem[];
+  int tm, tn;
+  tile_of_block(blockIdx.x, (p.M + BM - 1) / BM, (p.N + BN - 1) / BN, tm, tn);
+  const int m0 = tm * BM, n0 = tn * BN;
+  const int tid = threadIdx.x;
+
+  typename StageSel<AKC, BM, BK, NT, ALIGNED>::type sa;
+  sa.rs = make_rsrc(p.A, p.a_bytes);
+  sa.r0 = m0; sa.Rtot = p.M; sa.Ktot = p.K; sa.ld = p.lda; sa.tid = tid;
+  typename StageSel<BKC, BN, BK, NT, ALIGNED>::type sb;
+  sb.rs = make_rsrc(p.B, p.b_bytes);
+  sb.r0 = n0; sb.Rtot = p.N; sb.Ktot = p.K; sb.ld = p.ldb;
+  sb.tid = BKC ? tid : (tid + NT / 2) % NT;  // when both operands are transposed in registers, start B's blocks on the other waves
+
+  StoreEpilogue epi{p.out_z, p.out_a, p.out_f32, p.M, p.N, p.ldc, p.act, m0, n0, p.vec_out != 0};
+  gemm_tile<BM, BN, BK, WM, WN>(sa, sb, 0, (p.K + BK - 1) / BK, smem, epi);
+}
+
+struct TileCfg {
+  const char* name;
+  int bm, bn;
+};
+constexpr TileCfg kCfgs[] = {{"256x256x64_w2x2", 256, 256}, {"128x128x64_w2x2", 128, 128}, {"64x64x64_w2x2", 64, 64}};
+
+template <int BM, int BN, int BK, int WM, int WN, bool AKC, bool BKC, bool ALIGNED>
+hipError_t launch_one(const GemmKArgs& a, hipStream_t s) {
+  auto kern = gemm_bf16_kernel<BM, BN, BK, WM, WN, AKC, BKC, ALIGNED>;
+  constexpr size_t lds = 2ull * (BM + BN) * BK * sizeof(unsigned short);
+  static bool attr_done = false;
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  const int nb = ((a.M + BM - 1) / BM) * ((a.N + BN - 1) / BN);
+  hipLaunchKernelGGL(kern, dim3(nb), dim3(WM * WN * 64), lds, s, a);
+  return hipGetLastError();
+}
+
+template <bool AKC, bool BKC, bool ALIGNED>
+hipError_t launch_cfg(int cfg, const GemmKArgs& a, hipStream_t s) {
+  switch (cfg) {
+    case 0: return launch_one<256, 256, 64, 2, 2, AKC, BKC, ALIGNED>(a, s);
+    case 1: return launch_one<128, 128, 64, 2, 2, AKC, BKC, ALIGNED>(a, s);
+    case 2: return launch_one<64, 64, 64, 2, 2, AKC, BKC, ALIGNED>(a, s);
+  }
+  return hipErrorInvalidValue;
+}
+
+template <bool ALIGNED>
+hipError_t launch_layout(bool akc, bool bkc, int cfg, const GemmKArgs& a, hipStream_t s) {
+  if (akc && bkc) return launch_cfg<true, true, ALIGNED>(cfg, a, s);
+  if (akc && !bkc) return launch_cfg<true, false, ALIGNED>(cfg, a, s);
+  if (!akc && !bkc) return launch_cfg<false, false, ALIGNED>(cfg, a, s);
+  return launch_cfg<false, true, ALIGNED>(cfg, a, s);
+}
+
+}  // namespace
+
+int gemm_bf16_num_cfgs() { return (int)(sizeof(kCfgs) / sizeof(kCfgs[0])); }
+const char* gemm_bf16_cfg_name(int cfg) { return (cfg >= 0 && cfg < gemm_bf16_num_cfgs()) ? kCfgs[cfg].name : "?"; }
+
+hipError_t launch_gemm_bf16(const GemmDesc& d, hipStream_t s, int tile_cfg) {
+  if (d.M <= 0 || d.N <= 0 || d.K <= 0 || !d.A || !d.B) return hipErrorInvalidValue;
+  const unsigned long long a_elems = d.a_kcontig ? (unsigned long long)(d.M - 1) * d.lda + d.K
+                                                 : (unsigned long long)(d.K - 1) * d.lda + d.M;
+  const unsigned long long b_elems = d.b_kcontig ? (unsigned long long)(d.N - 1) * d.ldb + d.K
+                                                 : (unsigned long long)(d.K - 1) * d.ldb + d.N;
+  // byte offsets are 32-bit inside the kernel and 0x80000000 marks "out of range"
+  if (a_elems * 2 >= 0x7fffffffull || b_elems * 2 >= 0x7fffffffull) return hipErrorInvalidValue;
+
+  GemmKArgs a;
+  a.A = (const unsigned short*)d.A;
+  a.B = (const unsigned short*)d.B;
+  a.out_z = (unsigned short*)d.out_z;
+  a.out_a = (unsigned short*)d.out_a;
+  a.out_f32 = d.out_f32;
+  a.M = d.M; a.N = d.N; a.K = d.K;
+  a.lda = d.lda; a.ldb = d.ldb; a.ldc = d.ldc;
+  a.act = d.act;
+  a.a_bytes = (unsigned)(a_elems * 2);
+  a.b_bytes = (unsigned)(b_elems * 2);
+  a.vec_out = (d.N % 4 == 0) && (d.ldc % 4 == 0) && ((uintptr_t)d.out_z % 8 == 0) && ((uintptr_t)d.out_a % 8 == 0) &&
+              ((uintptr_t)d.out_f32 % 16 == 0);
+
+  // 16-byte loads need every contiguous run to start on a multiple of 8 elements
+  const int a_contig = d.a_kcontig ? d.K : d.M, b_contig = d.b_kcontig ? d.K : d.N;
+  const bool aligned = (d.lda % 8 == 0) && (d.ldb % 8 == 0) && (a_contig % 8 == 0) && (b_contig % 8 == 0) &&
+                       ((uintptr_t)d.A % 16 == 0) && ((uintptr_t)d.B % 16 == 0);
+
+  int cfg = tile_cfg;
+  if (cfg < 0) {
+    cfg = gemm_bf16_num_cfgs() - 1;
+    for (int c = 0; c < gemm_bf16_num_cfgs(); ++c) {
+      const long tiles = (long)((d.M + kCfgs[c].bm - 1) / kCfgs[c].bm) * ((d.N + kCfgs[c].bn - 1) / kCfgs[c].bn);
+      if (tiles >= 192) { cfg = c; break; }
+    }
+  }
+  if (cfg >= gemm_bf16_num_cfgs()) return hipErrorInvalidValue;
+  return aligned ? launch_layout<true>(d.a_kcontig, d.b_kcontig, cfg, a, s)
+                 : launch_layout<false>(d.a_kcontig, d.b_kcontig, cfg, a, s);
+}
+
+}  // namespace lp

@@ -1,0 +1,296 @@
+// Device-side building blocks of the bf16 matrix-core GEMMs (fully connected and implicit-GEMM
+// convolution products of Eq. 1, Eq. 4, Eq. 5).
+//
+// Each workgroup owns a BM x BN tile of C and walks K in steps of BK.  Both operand tiles are staged
+// in LDS in one canonical form, [row][k] with k contiguous, so the MFMA fragment reads are the same
+// 16-byte ds_read for every product; an operand whose k index is strided in memory is transposed in
+// registers (8x8 blocks of 16-bit values) on its way from global memory to LDS.  LDS rows are
+// XOR-swizzled in 16-byte chunks so that the 16 lanes of a fragment read touch all banks.  Global
+// loads go through buffer resources, so out-of-range chunks read as zero without branches.  Two LDS
+// buffers: the global loads of tile t+1 are issued before the MFMAs of tile t and land in the other
+// buffer after them, one barrier per K step.  Accumulators are 32x32 MFMA tiles
+// (v_mfma_f32_32x32x16_bf16), TM x TN of them per wave.
+//
+// A "stage" object owns the addressing of one operand: gload(k0) fetches its part of the tile that
+// starts at reduction index k0 into registers, sstore(lds) writes it to LDS.
+#pragma once
+#include <hip/hip_runtime.h>
+
+namespace lp {
+namespace core {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ unsigned short bf16_bits(float v) {
+  __bf16 b = (__bf16)v;  // round-to-nearest-even
+  return __builtin_bit_cast(unsigned short, b);
+}
+__device__ __forceinline__ float bf16_to_f32(unsigned short b) { return __uint_as_float(((unsigned)b) << 16); }
+
+__device__ __forceinline__ float apply_act(float z, int act) {
+  if (act == 1) return z > 0.f ? z : 0.f;                                          // ReLU
+  if (act == 2) return 0.5f * z * (1.f + erff(z * 0.70710678118654752440f));      // GELU (erf form)
+  return z;
+}
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, unsigned bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc((void*)p, 0, (int)bytes, 0x00020000);
+}
+
+constexpr unsigned kOOB = 0x80000000u;  // byte offset past any buffer this library accepts: reads 0
+
+// 8 consecutive 16-bit elements starting at element offset `eoff`; the first `nvalid` (<= 8) exist.
+template <bool ALIGNED>
+__device__ __forceinline__ u32x4 load8(__amdgpu_buffer_rsrc_t r, unsigned eoff, int nvalid) {
+  if constexpr (ALIGNED) {
+    return __builtin_amdgcn_raw_buffer_load_b128(r, nvalid > 0 ? eoff * 2u : kOOB, 0, 0);
+  } else {
+    unsigned e[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+      e[i] = (unsigned short)__builtin_amdgcn_raw_buffer_load_b16(r, i < nvalid ? (eoff + i) * 2u : kOOB, 0, 0);
+    u32x4 v;
+    v[0] = e[0] | (e[1] << 16);
+    v[1] = e[2] | (e[3] << 16);
+    v[2] = e[4] | (e[5] << 16);
+    v[3] = e[6] | (e[7] << 16);
+    return v;
+  }
+}
+
+__device__ __forceinline__ int clamp8(int n) { return n < 0 ? 0 : (n > 8 ? 8 : n); }
+
+// x[j][e] (8 rows of 8 halves)  ->  y[e][j]
+__device__ __forceinline__ void transpose8x8(const u32x4 (&x)[8], u32x4 (&y)[8]) {
+#pragma unroll
+  for (int dp = 0; dp < 4; ++dp) {  // source dword dp holds columns e = 2dp, 2dp+1
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {   // destination dword d holds rows j = 2d, 2d+1
+      const unsigned lo = x[2 * d][dp], hi = x[2 * d + 1][dp];
+      y[2 * dp][d] = (lo & 0xffffu) | (hi << 16);
+      y[2 * dp + 1][d] = (lo >> 16) | (hi & 0xffff0000u);
+    }
+  }
+}
+
+// element offset of 16-byte chunk `chunk` of row `row` in a swizzled [rows][BK] LDS tile
+template <int BK>
+__device__ __forceinline__ int lds_off(int row, int chunk) {
+  constexpr int CPR = BK / 8;                          // chunks per row
+  constexpr int RP = (128 / BK) > 0 ? (128 / BK) : 1;  // rows per 256 bytes
+  return row * BK + ((chunk ^ ((row / RP) % CPR)) * 8);
+}
+
+// ---- plain 2-D operands ---------------------------------------------------------------------------
+// k contiguous in memory: element (r,k) at base[r*ld + k]
+template <int R, int BK, int NT, bool ALIGNED>
+struct StageKC {
+  static constexpr int NCH = R * BK / 8;
+  static constexpr int CH = (NCH + NT - 1) / NT;
+  __amdgpu_buffer_rsrc_t rs;
+  int r0, Rtot, Ktot, ld, tid;
+  u32x4 v[CH];
+  __device__ __forceinline__ void gload(int k0) {
+#pragma unroll
+    for (int it = 0; it < CH; ++it) {
+      const int id = it * NT + tid;
+      const int row = id / (BK / 8), kc = id % (BK / 8);
+      const int gr = r0 + row, gk = k0 + kc * 8;
+      const int nv = (gr < Rtot && (NCH % NT == 0 || id < NCH)) ? clamp8(Ktot - gk) : 0;
+      v[it] = load8<ALIGNED>(rs, (unsigned)gr * (unsigned)ld + (unsigned)gk, nv);
+    }
+  }
+  __device__ __forceinline__ void sstore(unsigned short* lds) {
+#pragma unroll
+    for (int it = 0; it < CH; ++it) {
+      const int id = it * NT + tid;
+      if (NCH % NT == 0 || id < NCH) *(u32x4*)(lds + lds_off<BK>(id / (BK / 8), id % (BK / 8))) = v[it];
+    }
+  }
+};
+
+// k strided in memory: element (r,k) at base[k*ld + r]; threads move 8(k) x 8(r) blocks
+template <int R, int BK, int NT, bool ALIGNED>
+struct StageKS {
+  static constexpr int NB = (BK / 8) * (R / 8);
+  static constexpr int IT = (NB + NT - 1) / NT;
+  __amdgpu_buffer_rsrc_t rs;
+  int r0, Rtot, Ktot, ld, tid;  // tid may be rotated by the caller to spread work over waves
+  u32x4 v[IT][8];
+  __device__ __forceinline__ void gload(int k0) {
+#pragma unroll
+    for (int it = 0; it < IT; ++it) {
+      const int id = it * NT + tid;
+      if (NB % NT == 0 || id < NB) {
+        const int rc = id % (R / 8), kg = id / (R / 8);
+        const int gr = r0 + rc * 8;
+        const int nvr = clamp8(Rtot - gr);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          const int gk = k0 + kg * 8 + j;
+          v[it][j] = load8<ALIGNED>(rs, (unsigned)gk * (unsigned)ld + (unsigned)gr, gk < Ktot ? nvr : 0);
+        }
+      }
+    }
+  }
+  __device__ __forceinline__ void sstore(unsigned short* lds) {
+#pragma unroll
+    for (int it = 0; it < IT; ++it) {
+      const int id = it * NT + tid;
+      if (NB % NT == 0 || id < NB) {
+        const int rc = id % (R / 8), kg = id / (R / 8);
+        u32x4 y[8];
+        transpose8x8(v[it], y);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) *(u32x4*)(lds + lds_off<BK>(rc * 8 + e, kg)) = y[e];
+      }
+    }
+  }
+};
+
+// logical tile of a workgroup: ids congruent mod 8 share an XCD (and its L2), so give each XCD a
+// contiguous range of logical ids, then walk groups of GM tile rows column by column
+__device__ __forceinline__ void tile_of_block(int pid, int nbm, int nbn, int& tm, int& tn) {
+  const int nb = nbm * nbn;
+  const int xcd = pid % 8, loc = pid / 8;
+  const int per = nb / 8, rem = nb % 8;
+  const int lid = xcd * per + (xcd < rem ? xcd : rem) + loc;
+  constexpr int GM = 8;
+  const int width = GM * nbn;
+  const int first = (lid / width) * GM;
+  const int gsz = (nbm - first) < GM ? (nbm - first) : GM;
+  tm = first + (lid % width) % gsz;
+  tn = (lid % width) / gsz;
+}
+
+// Accumulates K tiles [kt0, kt1) of the BM x BN tile and hands the result to epi(row_in_tile,
+// col_in_tile, four consecutive columns).  smem: 2 * (BM + BN) * BK halves.
+template <int BM, int BN, int BK, int WM, int WN, class SA, class SB, class Epi>
+__device__ __forceinline__ void gemm_tile(SA& sa, SB& sb, int kt0, int kt1, unsigned short* smem, Epi epi) {
+  constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
+  constexpr int A_ELEMS = BM * BK, B_ELEMS = BN * BK;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wm = wave / WN, wn = wave % WN;
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  if (kt0 < kt1) {
+    sa.gload(kt0 * BK);
+    sb.gload(kt0 * BK);
+    sa.sstore(smem);
+    sb.sstore(smem + A_ELEMS);
+  }
+  __syncthreads();
+
+  const int frow_a = wm * (TM * 32) + (lane & 31);
+  const int frow_b = wn * (TN * 32) + (lane & 31);
+  const int fchunk = lane >> 5;
+
+  for (int kt = kt0; kt < kt1; ++kt) {
+    const int cur = (kt - kt0) & 1;
+    const unsigned short* As = smem + cur * (A_ELEMS + B_ELEMS);
+    const unsigned short* Bs = As + A_ELEMS;
+    const bool more = kt + 1 < kt1;
+    if (more) {
+      sa.gload((kt + 1) * BK);
+      sb.gload((kt + 1) * BK);
+    }
+#pragma unroll
+    for (int kk = 0; kk < BK / 16; ++kk) {
+      bf16x8 a[TM], b[TN];
+#pragma unroll
+      for (int i = 0; i < TM; ++i) a[i] = *(const bf16x8*)(As + lds_off<BK>(frow_a + i * 32, kk * 2 + fchunk));
+#pragma unroll
+      for (int j = 0; j < TN; ++j) b[j] = *(const bf16x8*)(Bs + lds_off<BK>(frow_b + j * 32, kk * 2 + fchunk));
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+    }
+    if (more) {
+      unsigned short* nxt = smem + (cur ^ 1) * (A_ELEMS + B_ELEMS);
+      sa.sstore(nxt);
+      sb.sstore(nxt + A_ELEMS);
+    }
+    __syncthreads();
+  }
+
+  // Epilogue through LDS (free after the last barrier): each wave parks one 32-row band of its
+  // sub-tile as fp32 in a private LDS region, then reads it back row-major, four columns per lane,
+  // so that global stores are 8- or 16-byte vectors covering whole contiguous row segments.
+  // A lane holds, per 32x32 MFMA tile, column (lane & 31) of rows 8*(r/4) + 4*(lane/32) + r%4.
+  constexpr int EP_LD = TN * 32 + 8;  // +8 floats: the two half-waves (4 rows apart) hit different banks
+  static_assert(WM * WN * 32 * EP_LD * 4 <= 2 * (BM + BN) * BK * 2, "epilogue band does not fit the main-loop LDS");
+  float* ep = reinterpret_cast<float*>(smem) + wave * (32 * EP_LD);
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        ep[((r >> 2) * 8 + (lane >> 5) * 4 + (r & 3)) * EP_LD + j * 32 + (lane & 31)] = acc[i][j][r];
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll 1
+    for (int e = lane; e < 32 * TN * 8; e += 64) {
+      const int row = e / (TN * 8), c4 = e % (TN * 8);
+      const f32x4 v = *reinterpret_cast<const f32x4*>(ep + row * EP_LD + c4 * 4);
+      epi(wm * (TM * 32) + i * 32 + row, wn * (TN * 32) + c4 * 4, v);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  }
+}
+
+// Writes four consecutive elements of a row of C in up to three forms (see lp::GemmDesc).
+// vec: N, ldc and the output pointers allow 8-/16-byte stores.
+struct StoreEpilogue {
+  unsigned short* out_z;
+  unsigned short* out_a;
+  float* out_f32;
+  int M, N, ldc, act, m0, n0;
+  bool vec;
+  __device__ __forceinline__ void operator()(int r, int c, const f32x4& v) const {
+    const int row = m0 + r, col = n0 + c;
+    if (row >= M || col >= N) return;
+    const size_t o = (size_t)row * ldc + col;
+    unsigned short zb[4], ab[4];
+    if (out_z || out_a) {
+#pragma unroll
+      for (int t = 0; t < 4; ++t) zb[t] = bf16_bits(v[t]);
+      if (out_a) {
+#pragma unroll
+        for (int t = 0; t < 4; ++t) ab[t] = bf16_bits(apply_act(bf16_to_f32(zb[t]), act));
+      }
+    }
+    if (vec) {  // col + 3 < N follows from N % 4 == 0
+      if (out_f32) *reinterpret_cast<f32x4*>(out_f32 + o) = v;
+      if (out_z) *reinterpret_cast<u32x2*>(out_z + o) = u32x2{(unsigned)zb[0] | ((unsigned)zb[1] << 16), (unsigned)zb[2] | ((unsigned)zb[3] << 16)};
+      if (out_a) *reinterpret_cast<u32x2*>(out_a + o) = u32x2{(unsigned)ab[0] | ((unsigned)ab[1] << 16), (unsigned)ab[2] | ((unsigned)ab[3] << 16)};
+    } else {
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        if (col + t < N) {
+          if (out_f32) out_f32[o + t] = v[t];
+          if (out_z) out_z[o + t] = zb[t];
+          if (out_a) out_a[o + t] = ab[t];
+        }
+      }
+    }
+  }
+};
+
+}  // namespace core
+}  // namespace lp

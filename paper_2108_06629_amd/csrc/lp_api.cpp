@@ -1,0 +1,572 @@
+// C-ABI layer of the LayerPipe hot path: argument checking, workspace layout, the gradient rings
+// that realise the delay elements of Eq. 6, and the stream/event graph of one training step.
+// All arithmetic lives in the HIP kernels behind lp_kernels.h; nothing here computes on the host.
+#include "../../include/lp.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "lp_kernels.h"
+
+namespace {
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+
+struct Layer {
+  lp_layer_desc d;
+  size_t n_params = 0;
+  size_t in_elems = 0, z_elems = 0, a_elems = 0;  // whole batch
+  int in_feat = 0, out_feat = 0;                  // per-sample flattened sizes
+  size_t off_master = 0, off_work[2] = {0, 0}, off_ring = 0;
+  size_t off_A = 0, off_Z = 0, off_dA = 0, off_dY = 0;
+  bool has_A = false, has_Z = false, has_dA = false;
+  int ring_slots = 1;
+  int delay = 0;       // active d_l
+  int cur = 0;         // working-weight buffer F and dX read now
+  bool weights_set = false;
+};
+
+std::string g_create_error;
+
+}  // namespace
+
+struct lp_ctx {
+  std::vector<Layer> layers;
+  int L = 0, batch = 0, dtype = 0, loss = 0;
+  float lr = 0.f;
+  size_t ws_bytes = 0;
+  size_t off_partials = 0, off_conv_scratch = 0;
+  char* ws = nullptr;
+  long n = 0;
+  std::string err;
+  bool events_ready = false;
+  std::vector<hipEvent_t> ev_dy, ev_dx, ev_dw;
+  hipEvent_t ev_fork = nullptr, ev_join_w = nullptr, ev_join_u = nullptr;
+  std::vector<hipStream_t> streams_seen;
+};
+
+namespace {
+
+int fail(lp_ctx* c, int code, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof(buf), fmt, ap);
+  va_end(ap);
+  if (c) c->err = buf; else g_create_error = buf;
+  return code;
+}
+int fail_hip(lp_ctx* c, hipError_t e, const char* what) {
+  return fail(c, LP_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+#define LP_HIP(c, call)                                   \
+  do {                                                    \
+    hipError_t e__ = (call);                              \
+    if (e__ != hipSuccess) return fail_hip(c, e__, #call); \
+  } while (0)
+
+inline bool is_bf16(const lp_ctx* c) { return c->dtype == LP_BF16; }
+inline size_t esize(const lp_ctx* c) { return is_bf16(c) ? 2 : 4; }
+inline void note_stream(lp_ctx* c, hipStream_t s) {
+  for (hipStream_t t : c->streams_seen)
+    if (t == s) return;
+  c->streams_seen.push_back(s);
+}
+
+int check_layer(lp_ctx* c, int l) {
+  if (l < 1 || l > c->L) return fail(c, LP_ERR_LAYER, "layer index %d outside 1..%d", l, c->L);
+  return LP_OK;
+}
+int need_ws(lp_ctx* c) {
+  if (!c->ws) return fail(c, LP_ERR_STATE, "no workspace bound (call lp_bind_workspace)");
+  return LP_OK;
+}
+int need_weights(lp_ctx* c, int l) {
+  if (int r = need_ws(c)) return r;
+  if (!c->layers[l - 1].weights_set) return fail(c, LP_ERR_STATE, "weights of layer %d were never set", l);
+  return LP_OK;
+}
+
+inline void* work_w(lp_ctx* c, Layer& ly) {
+  return is_bf16(c) ? (void*)(c->ws + ly.off_work[ly.cur]) : (void*)(c->ws + ly.off_master);
+}
+inline float* ring_slot(lp_ctx* c, Layer& ly, long step) {
+  return (float*)(c->ws + ly.off_ring) + (size_t)(step % ly.ring_slots) * ly.n_params;
+}
+inline lp::ConvDesc conv_desc(const lp_ctx* c, const Layer& ly) {
+  lp::ConvDesc cd;
+  cd.B = c->batch; cd.H = ly.d.H; cd.W = ly.d.W; cd.Cin = ly.d.in; cd.Cout = ly.d.out;
+  return cd;
+}
+
+// ---- the tasks, shared by the per-layer entry points and lp_step -------------------------------
+hipError_t do_forward(lp_ctx* c, Layer& ly, const void* X, void* Z, void* A, hipStream_t s) {
+  if (ly.d.kind == LP_LINEAR) {
+    lp::GemmDesc g;
+    g.A = X; g.B = work_w(c, ly);
+    g.M = c->batch; g.N = ly.d.out; g.K = ly.d.in;
+    g.lda = ly.d.in; g.ldb = ly.d.out; g.ldc = ly.d.out;
+    g.a_kcontig = true; g.b_kcontig = false;
+    g.out_z = Z; g.out_a = A; g.act = ly.d.act;
+    return is_bf16(c) ? lp::launch_gemm_bf16(g, s) : lp::launch_gemm_f32(g, s);
+  }
+  const lp::ConvDesc cd = conv_desc(c, ly);
+  if (ly.d.pool == 2) {
+    hipError_t e = lp::launch_conv_fwd(cd, is_bf16(c), X, work_w(c, ly), Z, nullptr, ly.d.act, s);
+    if (e != hipSuccess || !A) return e;
+    return lp::launch_relu_pool(is_bf16(c), Z, A, c->batch, ly.d.H, ly.d.W, ly.d.out, ly.d.act, s);
+  }
+  return lp::launch_conv_fwd(cd, is_bf16(c), X, work_w(c, ly), Z, A, ly.d.act, s);
+}
+
+hipError_t do_grad_act(lp_ctx* c, Layer& ly, const void* dY, void* dX, int c0, int c1, hipStream_t s) {
+  if (ly.d.kind == LP_LINEAR) {
+    lp::GemmDesc g;
+    const size_t es = esize(c);
+    g.A = dY; g.B = (const char*)work_w(c, ly) + (size_t)c0 * ly.d.out * es;
+    g.M = c->batch; g.N = c1 - c0; g.K = ly.d.out;
+    g.lda = ly.d.out; g.ldb = ly.d.out; g.ldc = ly.d.in;
+    g.a_kcontig = true; g.b_kcontig = true;
+    g.out_z = (char*)dX + (size_t)c0 * es;
+    return is_bf16(c) ? lp::launch_gemm_bf16(g, s) : lp::launch_gemm_f32(g, s);
+  }
+  return lp::launch_conv_grad_act(conv_desc(c, ly), is_bf16(c), dY, work_w(c, ly), dX, c0, c1, s);
+}
+
+hipError_t do_grad_weight(lp_ctx* c, Layer& ly, const void* X, const void* dY, float* G, hipStream_t s) {
+  if (ly.d.kind == LP_LINEAR) {
+    lp::GemmDesc g;
+    g.A = X; g.B = dY;
+    g.M = ly.d.in; g.N = ly.d.out; g.K = c->batch;
+    g.lda = ly.d.in; g.ldb = ly.d.out; g.ldc = ly.d.out;
+    g.a_kcontig = false; g.b_kcontig = false;
+    g.out_f32 = G;
+    return is_bf16(c) ? lp::launch_gemm_bf16(g, s) : lp::launch_gemm_f32(g, s);
+  }
+  return lp::launch_conv_grad_weight(conv_desc(c, ly), is_bf16(c), X, dY, G, (float*)(c->ws + c->off_conv_scratch), s);
+}
+
+hipError_t do_act_grad(lp_ctx* c, Layer& ly, const void* dA, const void* S, void* dY, hipStream_t s) {
+  if (ly.d.kind == LP_CONV3X3 && ly.d.pool == 2)
+    return lp::launch_act_grad_pool(is_bf16(c), ly.d.act, dA, S, dY, c->batch, ly.d.H, ly.d.W, ly.d.out, s);
+  return lp::launch_act_grad(is_bf16(c), ly.d.act, dA, S, dY, ly.z_elems, s);
+}
+
+hipError_t do_loss(lp_ctx* c, const void* ZL, const void* target, void* dYL, float* loss_dev, hipStream_t s) {
+  const Layer& last = c->layers[c->L - 1];
+  float* partials = (float*)(c->ws + c->off_partials);
+  if (c->loss == LP_LOSS_SOFTMAX_CE)
+    return lp::launch_softmax_ce(is_bf16(c), ZL, (const int*)target, dYL, loss_dev, partials, c->batch, last.out_feat, s);
+  return lp::launch_mse(is_bf16(c), ZL, target, dYL, loss_dev, partials, c->batch, last.out_feat, s);
+}
+
+// Applies W <- W - lr*G; BF16 writes the other working buffer.  Does not flip `cur`.
+hipError_t do_update(lp_ctx* c, Layer& ly, const float* G, hipStream_t s) {
+  float* master = (float*)(c->ws + ly.off_master);
+  void* work_out = is_bf16(c) ? (void*)(c->ws + ly.off_work[ly.cur ^ 1]) : nullptr;
+  return lp::launch_sgd(master, G, work_out, c->lr, ly.n_params, s);
+}
+
+int ensure_events(lp_ctx* c) {
+  if (c->events_ready) return LP_OK;
+  auto mk = [&](hipEvent_t* e) { return hipEventCreateWithFlags(e, hipEventDisableTiming); };
+  c->ev_dy.assign(c->L, nullptr);
+  c->ev_dx.assign(c->L, nullptr);
+  c->ev_dw.assign(c->L, nullptr);
+  for (int l = 0; l < c->L; ++l) {
+    LP_HIP(c, mk(&c->ev_dy[l]));
+    LP_HIP(c, mk(&c->ev_dx[l]));
+    LP_HIP(c, mk(&c->ev_dw[l]));
+  }
+  LP_HIP(c, mk(&c->ev_fork));
+  LP_HIP(c, mk(&c->ev_join_w));
+  LP_HIP(c, mk(&c->ev_join_u));
+  c->events_ready = true;
+  return LP_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int lp_create(const lp_layer_desc* layers, int L, int batch, int dtype, int loss, float lr, lp_ctx** out) {
+  if (!layers || !out) return fail(nullptr, LP_ERR_NULL, "lp_create: layers/out is NULL");
+  if (L < 1) return fail(nullptr, LP_ERR_SHAPE, "lp_create: L = %d", L);
+  if (batch < 1) return fail(nullptr, LP_ERR_SHAPE, "lp_create: batch = %d", batch);
+  if (dtype != LP_F32 && dtype != LP_BF16) return fail(nullptr, LP_ERR_DTYPE, "lp_create: unknown dtype %d", dtype);
+  if (loss != LP_LOSS_SOFTMAX_CE && loss != LP_LOSS_MSE) return fail(nullptr, LP_ERR_DTYPE, "lp_create: unknown loss %d", loss);
+  lp_ctx* c = new (std::nothrow) lp_ctx;
+  if (!c) return fail(nullptr, LP_ERR_STATE, "lp_create: out of host memory");
+  c->L = L; c->batch = batch; c->dtype = dtype; c->loss = loss; c->lr = lr;
+  c->layers.resize(L);
+  const size_t es = dtype == LP_BF16 ? 2 : 4;
+  int prev_out_feat = -1, prevH = 0, prevW = 0, prevC = 0;
+  bool prev_conv = false;
+  for (int i = 0; i < L; ++i) {
+    Layer& ly = c->layers[i];
+    ly.d = layers[i];
+    const lp_layer_desc& d = ly.d;
+    auto bad = [&](int code, const char* msg) {
+      int r = fail(nullptr, code, "lp_create: layer %d: %s", i + 1, msg);
+      delete c;
+      return r;
+    };
+    if (d.kind != LP_LINEAR && d.kind != LP_CONV3X3) return bad(LP_ERR_DTYPE, "unknown kind");
+    if (d.act != LP_ACT_IDENTITY && d.act != LP_ACT_RELU && d.act != LP_ACT_GELU) return bad(LP_ERR_DTYPE, "unknown activation");
+    if (d.in < 1 || d.out < 1) return bad(LP_ERR_SHAPE, "in/out must be positive");
+    if (d.delay < 0) return bad(LP_ERR_DELAY, "negative delay");
+    if (i == L - 1 && d.act != LP_ACT_IDENTITY) return bad(LP_ERR_DTYPE, "the last layer must have identity activation");
+    if (d.kind == LP_LINEAR) {
+      if (d.pool != 0 || d.H != 0 || d.W != 0) return bad(LP_ERR_SHAPE, "H, W, pool must be 0 for a linear layer");
+      ly.in_feat = d.in; ly.out_feat = d.out;
+      ly.n_params = (size_t)d.in * d.out;
+      ly.in_elems = (size_t)batch * d.in;
+      ly.z_elems = ly.a_elems = (size_t)batch * d.out;
+      if (i > 0 && prev_out_feat != d.in) return bad(LP_ERR_LAYER, "input width differs from the previous layer's output");
+      prev_conv = false;
+    } else {
+      if (d.H < 1 || d.W < 1) return bad(LP_ERR_SHAPE, "conv needs H, W >= 1");
+      if (d.pool != 0 && d.pool != 2) return bad(LP_ERR_SHAPE, "pool must be 0 or 2");
+      if (d.pool == 2 && (d.H % 2 || d.W % 2)) return bad(LP_ERR_SHAPE, "pool needs even H and W");
+      if (i == L - 1 && d.pool) return bad(LP_ERR_SHAPE, "the last layer cannot pool");
+      if (i > 0) {
+        if (!prev_conv) return bad(LP_ERR_LAYER, "a conv layer cannot follow a linear layer");
+        if (prevH != d.H || prevW != d.W || prevC != d.in) return bad(LP_ERR_LAYER, "conv input shape differs from the previous layer's output");
+      }
+      const int p = d.pool == 2 ? 2 : 1;
+      ly.in_feat = d.H * d.W * d.in;
+      ly.out_feat = (d.H / p) * (d.W / p) * d.out;
+      ly.n_params = (size_t)9 * d.in * d.out;
+      ly.in_elems = (size_t)batch * ly.in_feat;
+      ly.z_elems = (size_t)batch * d.H * d.W * d.out;
+      ly.a_elems = (size_t)batch * ly.out_feat;
+      prev_conv = true; prevH = d.H / p; prevW = d.W / p; prevC = d.out;
+    }
+    prev_out_feat = ly.out_feat;
+    ly.delay = d.delay;
+    ly.ring_slots = d.delay + 1;
+  }
+  // workspace layout
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes); return o; };
+  size_t conv_scratch = 0;
+  for (int i = 0; i < L; ++i) {
+    Layer& ly = c->layers[i];
+    const bool last = i == L - 1;
+    const bool pooled = ly.d.kind == LP_CONV3X3 && ly.d.pool == 2;
+    ly.off_master = take(ly.n_params * 4);
+    if (dtype == LP_BF16) { ly.off_work[0] = take(ly.n_params * 2); ly.off_work[1] = take(ly.n_params * 2); }
+    ly.off_ring = take((size_t)ly.ring_slots * ly.n_params * 4);
+    ly.has_A = !last;
+    ly.has_Z = last || pooled || ly.d.act == LP_ACT_GELU;
+    ly.has_dA = !last;
+    if (ly.has_A) ly.off_A = take(ly.a_elems * es);
+    if (ly.has_Z) ly.off_Z = take(ly.z_elems * es);
+    if (ly.has_dA) ly.off_dA = take(ly.a_elems * es);
+    // identity hidden layer without pool: delta equals dA, share the buffer
+    if (ly.has_dA && ly.d.act == LP_ACT_IDENTITY && !pooled) ly.off_dY = ly.off_dA;
+    else ly.off_dY = take(ly.z_elems * es);
+    if (ly.d.kind == LP_CONV3X3) {
+      size_t sc = lp::conv_grad_weight_scratch_bytes(conv_desc(c, ly));
+      if (sc > conv_scratch) conv_scratch = sc;
+    }
+  }
+  const Layer& lastl = c->layers[L - 1];
+  c->off_partials = take(lp::loss_partials_count(loss == LP_LOSS_MSE, batch, lastl.out_feat) * 4);
+  c->off_conv_scratch = take(conv_scratch);
+  c->ws_bytes = off;
+  *out = c;
+  return LP_OK;
+}
+
+int lp_destroy(lp_ctx* c) {
+  if (!c) return LP_ERR_NULL;
+  if (c->events_ready) {
+    for (auto* v : {&c->ev_dy, &c->ev_dx, &c->ev_dw})
+      for (hipEvent_t e : *v)
+        if (e) (void)hipEventDestroy(e);
+    for (hipEvent_t e : {c->ev_fork, c->ev_join_w, c->ev_join_u})
+      if (e) (void)hipEventDestroy(e);
+  }
+  delete c;
+  return LP_OK;
+}
+
+const char* lp_last_error(const lp_ctx* c) { return c ? c->err.c_str() : g_create_error.c_str(); }
+
+int lp_workspace_bytes(const lp_ctx* c, size_t* bytes) {
+  if (!c || !bytes) return LP_ERR_NULL;
+  *bytes = c->ws_bytes;
+  return LP_OK;
+}
+
+int lp_bind_workspace(lp_ctx* c, void* dev_ptr, size_t bytes) {
+  if (!c) return LP_ERR_NULL;
+  if (!dev_ptr) return fail(c, LP_ERR_NULL, "lp_bind_workspace: dev_ptr is NULL");
+  if ((uintptr_t)dev_ptr % kAlign) return fail(c, LP_ERR_WORKSPACE, "lp_bind_workspace: pointer not %zu-byte aligned", kAlign);
+  if (bytes < c->ws_bytes) return fail(c, LP_ERR_WORKSPACE, "lp_bind_workspace: %zu bytes given, %zu needed", bytes, c->ws_bytes);
+  c->ws = (char*)dev_ptr;
+  c->n = 0;
+  for (Layer& ly : c->layers) { ly.weights_set = false; ly.cur = 0; }
+  return LP_OK;
+}
+
+int lp_set_weights(lp_ctx* c, int l, const float* W, int is_device, void* stream) {
+  if (!c) return LP_ERR_NULL;
+  if (int r = check_layer(c, l)) return r;
+  if (!W) return fail(c, LP_ERR_NULL, "lp_set_weights: W is NULL");
+  if (int r = need_ws(c)) return r;
+  Layer& ly = c->layers[l - 1];
+  hipStream_t s = (hipStream_t)stream;
+  note_stream(c, s);
+  float* master = (float*)(c->ws + ly.off_master);
+  if (is_device) LP_HIP(c, hipMemcpyAsync(master, W, ly.n_params * 4, hipMemcpyDeviceToDevice, s));
+  else {
+    LP_HIP(c, hipStreamSynchronize(s));
+    LP_HIP(c, hipMemcpy(master, W, ly.n_params * 4, hipMemcpyHostToDevice));
+  }
+  if (is_bf16(c)) LP_HIP(c, lp::launch_cast_bf16(master, c->ws + ly.off_work[ly.cur], ly.n_params, s));
+  ly.weights_set = true;
+  return LP_OK;
+}
+
+int lp_get_weights(lp_ctx* c, int l, float* dst, int is_device, void* stream) {
+  if (!c) return LP_ERR_NULL;
+  if (int r = check_layer(c, l)) return r;
+  if (!dst) return fail(c, LP_ERR_NULL, "lp_get_weights: dst is NULL");
+  if (int r = need_weights(c, l)) return r;
+  Layer& ly = c->layers[l - 1];
+  hipStream_t s = (hipStream_t)stream;
+  const float* master = (const float*)(c->ws + ly.off_master);
+  if (is_device) LP_HIP(c, hipMemcpyAsync(dst, master, ly.n_params * 4, hipMemcpyDeviceToDevice, s));
+  else {
+    LP_HIP(c, hipStreamSynchronize(s));
+    LP_HIP(c, hipMemcpy(dst, master, ly.n_params * 4, hipMemcpyDeviceToHost));
+  }
+  return LP_OK;
+}
+
+int lp_forward(lp_ctx* c, int l, const void* X, void* Z, void* A, void* stream) {
+  if (!c) return LP_ERR_NULL;
+  if (int r = check_layer(c, l)) return r;
+  if (!X) return fail(c, LP_ERR_NULL, "lp_forward: X is NULL");
+  if (!Z && !A) return fail(c, LP_ERR_NULL, "lp_forward: both outputs are NULL");
+  Layer& ly = c->layers[l - 1];
+  if (ly.d.kind == LP_CONV3X3 && ly.d.pool == 2 && !Z) return fail(c, LP_ERR_NULL, "lp_forward: a pooled layer needs Z");
+  if (int r = need_weights(c, l)) return r;
+  note_stream(c, (hipStream_t)stream);
+  LP_HIP(c, do_forward(c, ly, X, Z, A, (hipStream_t)stream));
+  return LP_OK;
+}
+
+int lp_loss_grad(lp_ctx* c, const void* ZL, const void* target, void* dYL, float* loss_dev, void* stream) {
+  if (!c) return LP_ERR_NULL;
+  if (!ZL || !target || !dYL) return fail(c, LP_ERR_NULL, "lp_loss_grad: ZL/target/dYL is NULL");
+  if (int r = need_ws(c)) return r;
+  note_stream(c, (hipStream_t)stream);
+  LP_HIP(c, do_loss(c, ZL, target, dYL, loss_dev, (hipStream_t)stream));
+  return LP_OK;
+}
+
+int lp_act_grad(lp_ctx* c, int l, const void* dA, const void* S, void* dY, void* stream) {
+  if (!c) return LP_ERR_NULL;
+  if (int r = check_layer(c, l)) return r;
+  Layer& ly = c->layers[l - 1];
+  if (!dA || !dY || (!S && ly.d.act != LP_ACT_IDENTITY)) return fail(c, LP_ERR_NULL, "lp_act_grad: dA/S/dY is NULL");
+  if (ly.d.kind == LP_CONV3X3 && ly.d.pool == 2) {
+    if (!S) return fail(c, LP_ERR_NULL, "lp_act_grad: a pooled layer needs S = Z");
+    if (dA == dY) return fail(c, LP_ERR_SHAPE, "lp_act_grad: dY may not alias dA on a pooled layer");
+  }
+  note_stream(c, (hipStream_t)stream);
+  LP_HIP(c, do_act_grad(c, ly, dA, S, dY, (hipStream_t)stream));
+  return LP_OK;
+}
+
+int lp_grad_act(lp_ctx* c, int l, const void* dY, void* dX, int col0, int col1, void* stream) {
+  if (!c) return LP_ERR_NULL;
+  if (int r = check_layer(c, l)) return r;
+  if (!dY || !dX) return fail(c, LP_ERR_NULL, "lp_grad_act: dY/dX is NULL");
+  Layer& ly = c->layers[l - 1];
+  if (col0 < 0 || col1 > ly.d.in || col0 >= col1) return fail(c, LP_ERR_SHAPE, "lp_grad_act: column range [%d,%d) outside [0,%d)", col0, col1, ly.d.in);
+  if (int r = need_weights(c, l)) return r;
+  note_stream(c, (hipStream_t)stream);
+  LP_HIP(c, do_grad_act(c, ly, dY, dX, col0, col1, (hipStream_t)stream));
+  return LP_OK;
+}
+
+int lp_grad_weight(lp_ctx* c, int l, const void* X, const void* dY, float* G, void* stream) {
+  if (!c) return LP_ERR_NULL;
+  if (int r = check_layer(c, l)) return r;
+  if (!X || !dY) return fail(c, LP_ERR_NULL, "lp_grad_weight: X/dY is NULL");
+  if (int r = need_ws(c)) return r;
+  Layer& ly = c->layers[l - 1];
+  if (!G) G = ring_slot(c, ly, c->n + 1);
+  note_stream(c, (hipStream_t)stream);
+  LP_HIP(c, do_grad_weight(c, ly, X, dY, G, (hipStream_t)stream));
+  return LP_OK;
+}
+
+int lp_update(lp_ctx* c, int l, const float* G, void* stream) {
+  if (!c) return LP_ERR_NULL;
+  if (int r = check_layer(c, l)) return r;
+  if (int r = need_weights(c, l)) return r;
+  Layer& ly = c->layers[l - 1];
+  if (!G) {
+    const long src = c->n + 1 - ly.delay;
+    if (src < 1) return LP_OK;  // the delay elements are still empty
+    G = ring_slot(c, ly, src);
+  }
+  note_stream(c, (hipStream_t)stream);
+  LP_HIP(c, do_update(c, ly, G, (hipStream_t)stream));
+  if (is_bf16(c)) ly.cur ^= 1;
+  return LP_OK;
+}
+
+int lp_advance(lp_ctx* c) {
+  if (!c) return LP_ERR_NULL;
+  c->n += 1;
+  return LP_OK;
+}
+
+int lp_step(lp_ctx* c, const void* X0, const void* target, const int* delay, float* loss_dev, void* const* streams, int n_streams) {
+  if (!c) return LP_ERR_NULL;
+  if (!X0 || !target) return fail(c, LP_ERR_NULL, "lp_step: X0/target is NULL");
+  if (!streams || n_streams < 1) return fail(c, LP_ERR_NULL, "lp_step: needs at least one stream");
+  if (int r = need_ws(c)) return r;
+  for (int l = 1; l <= c->L; ++l)
+    if (int r = need_weights(c, l)) return r;
+  if (delay) {
+    for (int l = 0; l < c->L; ++l)
+      if (delay[l] < 0 || delay[l] > c->layers[l].d.delay)
+        return fail(c, LP_ERR_DELAY, "lp_step: delay[%d] = %d outside [0, %d]", l, delay[l], c->layers[l].d.delay);
+    for (int l = 0; l < c->L; ++l) c->layers[l].delay = delay[l];
+  }
+  const bool multi = n_streams > 1;
+  hipStream_t sC = (hipStream_t)streams[0];
+  hipStream_t sW = multi ? (hipStream_t)streams[1] : sC;
+  hipStream_t sU = multi ? (hipStream_t)streams[2 % n_streams] : sC;
+  note_stream(c, sC); note_stream(c, sW); note_stream(c, sU);
+  if (multi)
+    if (int r = ensure_events(c)) return r;
+
+  const int L = c->L;
+  const long n = c->n + 1;  // the step in progress
+  const bool bf = is_bf16(c);
+  std::vector<char> updated(L, 0);
+
+  if (multi) {
+    LP_HIP(c, hipEventRecord(c->ev_fork, sC));
+    if (sW != sC) LP_HIP(c, hipStreamWaitEvent(sW, c->ev_fork, 0));
+    if (sU != sC) LP_HIP(c, hipStreamWaitEvent(sU, c->ev_fork, 0));
+  }
+
+  // Delayed updates whose gradient is already in the ring (d_l > 0).  BF16 keeps two versions of
+  // the working weights, so W_l(n) can be produced while this step still reads W_l(n-1).
+  auto issue_update = [&](int i) -> int {
+    Layer& ly = c->layers[i];
+    const long src = n - ly.delay;
+    if (src >= 1) {
+      LP_HIP(c, do_update(c, ly, ring_slot(c, ly, src), sU));
+      updated[i] = 1;
+    }
+    return LP_OK;
+  };
+  if (bf)
+    for (int i = L - 1; i >= 0; --i)
+      if (c->layers[i].delay > 0)
+        if (int r = issue_update(i)) return r;
+
+  // forward chain
+  const void* a_prev = X0;
+  for (int i = 0; i < L; ++i) {
+    Layer& ly = c->layers[i];
+    void* Z = ly.has_Z ? c->ws + ly.off_Z : nullptr;
+    void* A = ly.has_A ? c->ws + ly.off_A : nullptr;
+    LP_HIP(c, do_forward(c, ly, a_prev, Z, A, sC));
+    a_prev = A;
+  }
+  Layer& last = c->layers[L - 1];
+  LP_HIP(c, do_loss(c, c->ws + last.off_Z, target, c->ws + last.off_dY, loss_dev, sC));
+  if (multi) LP_HIP(c, hipEventRecord(c->ev_dy[L - 1], sC));
+
+  // backward: the delta chain on sC first (critical loop), G on sW, updates on sU
+  for (int i = L - 1; i >= 0; --i) {
+    Layer& ly = c->layers[i];
+    const void* x_in = i == 0 ? X0 : (const void*)(c->ws + c->layers[i - 1].off_A);
+    const void* dY = c->ws + ly.off_dY;
+    if (i > 0) {
+      Layer& pv = c->layers[i - 1];
+      LP_HIP(c, do_grad_act(c, ly, dY, c->ws + pv.off_dA, 0, ly.d.in, sC));
+      if (multi) LP_HIP(c, hipEventRecord(c->ev_dx[i], sC));
+      if (pv.off_dY != pv.off_dA) {
+        const void* S = pv.has_Z ? c->ws + pv.off_Z : c->ws + pv.off_A;
+        LP_HIP(c, do_act_grad(c, pv, c->ws + pv.off_dA, S, c->ws + pv.off_dY, sC));
+      }
+      if (multi) LP_HIP(c, hipEventRecord(c->ev_dy[i - 1], sC));
+    }
+    if (multi && sW != sC) LP_HIP(c, hipStreamWaitEvent(sW, c->ev_dy[i], 0));
+    LP_HIP(c, do_grad_weight(c, ly, x_in, dY, ring_slot(c, ly, n), sW));
+    if (multi) LP_HIP(c, hipEventRecord(c->ev_dw[i], sW));
+    if (!updated[i]) {
+      // d_l = 0 needs this step's G; an F32 context updates in place, so it also has to wait for
+      // the last reader of W_l(n-1), which is dX_l (layer 1: the forward pass, long finished)
+      if (multi) {
+        if (ly.delay == 0 && sU != sW) LP_HIP(c, hipStreamWaitEvent(sU, c->ev_dw[i], 0));
+        if (!bf && sU != sC) LP_HIP(c, hipStreamWaitEvent(sU, i > 0 ? c->ev_dx[i] : c->ev_dy[L - 1], 0));
+      }
+      if (int r = issue_update(i)) return r;
+    }
+  }
+
+  if (multi) {
+    if (sW != sC) { LP_HIP(c, hipEventRecord(c->ev_join_w, sW)); LP_HIP(c, hipStreamWaitEvent(sC, c->ev_join_w, 0)); }
+    if (sU != sC) { LP_HIP(c, hipEventRecord(c->ev_join_u, sU)); LP_HIP(c, hipStreamWaitEvent(sC, c->ev_join_u, 0)); }
+  }
+  if (bf)
+    for (int i = 0; i < L; ++i)
+      if (updated[i]) c->layers[i].cur ^= 1;
+  c->n = n;
+  return LP_OK;
+}
+
+int lp_step_index(const lp_ctx* c, long* n) {
+  if (!c || !n) return LP_ERR_NULL;
+  *n = c->n;
+  return LP_OK;
+}
+
+int lp_sync(lp_ctx* c) {
+  if (!c) return LP_ERR_NULL;
+  for (hipStream_t s : c->streams_seen) LP_HIP(c, hipStreamSynchronize(s));
+  return LP_OK;
+}
+
+int lp_tensor(lp_ctx* c, int l, int which, void** dev_ptr, size_t* bytes) {
+  if (!c) return LP_ERR_NULL;
+  if (!dev_ptr || !bytes) return fail(c, LP_ERR_NULL, "lp_tensor: dev_ptr/bytes is NULL");
+  if (int r = check_layer(c, l)) return r;
+  if (int r = need_ws(c)) return r;
+  Layer& ly = c->layers[l - 1];
+  const size_t es = esize(c);
+  *dev_ptr = nullptr; *bytes = 0;
+  switch (which) {
+    case LP_T_MASTER_W: *dev_ptr = c->ws + ly.off_master; *bytes = ly.n_params * 4; break;
+    case LP_T_WORK_W: *dev_ptr = work_w(c, ly); *bytes = ly.n_params * es; break;
+    case LP_T_A: if (ly.has_A) { *dev_ptr = c->ws + ly.off_A; *bytes = ly.a_elems * es; } break;
+    case LP_T_Z: if (ly.has_Z) { *dev_ptr = c->ws + ly.off_Z; *bytes = ly.z_elems * es; } break;
+    case LP_T_DA: if (ly.has_dA) { *dev_ptr = c->ws + ly.off_dA; *bytes = ly.a_elems * es; } break;
+    case LP_T_DY: *dev_ptr = c->ws + ly.off_dY; *bytes = ly.z_elems * es; break;
+    case LP_T_G_LAST: if (c->n >= 1) { *dev_ptr = ring_slot(c, ly, c->n); *bytes = ly.n_params * 4; } break;
+    default: return fail(c, LP_ERR_DTYPE, "lp_tensor: unknown tensor id %d", which);
+  }
+  return LP_OK;
+}
+
+}  // extern "C"

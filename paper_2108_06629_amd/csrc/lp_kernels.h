@@ -1,0 +1,70 @@
+// Internal launch interface between the C-ABI layer (lp_api.cpp) and the HIP kernels.
+// Not part of the public boundary; see include/lp.h for that.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace lp {
+
+enum Act { ACT_IDENTITY = 0, ACT_RELU = 1, ACT_GELU = 2 };
+
+// C[M,N] = sum_k Aop(m,k) * Bop(n,k), fp32 accumulate.
+//   a_kcontig:  Aop(m,k) = A[m*lda + k]   else  Aop(m,k) = A[k*lda + m]
+//   b_kcontig:  Bop(n,k) = B[n*ldb + k]   else  Bop(n,k) = B[k*ldb + n]
+// Outputs (any may be null): out_z = C rounded to the act type; out_a = act(out_z value) in the act
+// type; out_f32 = C as float.  All outputs share ldc.
+struct GemmDesc {
+  const void* A = nullptr;
+  const void* B = nullptr;
+  int M = 0, N = 0, K = 0;
+  int lda = 0, ldb = 0, ldc = 0;
+  bool a_kcontig = true, b_kcontig = true;
+  void* out_z = nullptr;
+  void* out_a = nullptr;
+  float* out_f32 = nullptr;
+  int act = ACT_IDENTITY;
+};
+
+// tile_cfg < 0: pick by problem size.  Returns hipErrorInvalidValue for impossible shapes.
+hipError_t launch_gemm_bf16(const GemmDesc& d, hipStream_t s, int tile_cfg = -1);
+hipError_t launch_gemm_f32(const GemmDesc& d, hipStream_t s);
+int gemm_bf16_num_cfgs();
+const char* gemm_bf16_cfg_name(int cfg);
+
+// 3x3 stride-1 pad-1 convolution tasks as implicit GEMMs over NHWC bf16 tensors.
+struct ConvDesc {
+  int B = 0, H = 0, W = 0, Cin = 0, Cout = 0;
+};
+// F: z[b,y,x,o] = sum xpad[b,y+kh,x+kw,c] w[kh,kw,c,o]; writes out_z and/or out_a=act(z) (full res).
+hipError_t launch_conv_fwd(const ConvDesc& c, bool bf16, const void* x, const void* w, void* out_z, void* out_a,
+                           int act, hipStream_t s);
+// dX: dx[b,y,x,c] for c in [c0,c1) (dx has Cin channels).
+hipError_t launch_conv_grad_act(const ConvDesc& c, bool bf16, const void* dy, const void* w, void* dx, int c0, int c1,
+                                hipStream_t s);
+// dW: g[kh,kw,c,o] fp32.  `partial` is scratch of conv_grad_weight_scratch_bytes().
+hipError_t launch_conv_grad_weight(const ConvDesc& c, bool bf16, const void* x, const void* dy, float* g,
+                                   float* partial, hipStream_t s);
+size_t conv_grad_weight_scratch_bytes(const ConvDesc& c);
+
+// dY = dA (.) f'(S), n elements.
+hipError_t launch_act_grad(bool bf16, int act, const void* dA, const void* S, void* dY, size_t n, hipStream_t s);
+// pooled conv layer: a[b,y/2,x/2,c] = max over window of relu(z)
+hipError_t launch_relu_pool(bool bf16, const void* z, void* a, int B, int H, int W, int C, int act, hipStream_t s);
+// pooled conv layer backward: dy (full res) from da (pooled) and z (full res)
+hipError_t launch_act_grad_pool(bool bf16, int act, const void* dA, const void* Z, void* dY, int B, int H, int W, int C,
+                                hipStream_t s);
+
+// loss + delta of the last layer.  partials: float scratch with >= loss_partials_count() entries.
+size_t loss_partials_count(int loss_is_mse, int rows, int cols);
+hipError_t launch_softmax_ce(bool bf16, const void* Z, const int* labels, void* dY, float* loss, float* partials,
+                             int rows, int cols, hipStream_t s);
+hipError_t launch_mse(bool bf16, const void* Z, const void* T, void* dY, float* loss, float* partials, int rows,
+                      int cols, hipStream_t s);
+
+// master <- master - lr * g;  work_out (bf16, may be null) <- round(master)
+hipError_t launch_sgd(float* master, const float* g, void* work_out_bf16, float lr, size_t n, hipStream_t s);
+// dst_bf16 <- round(src)
+hipError_t launch_cast_bf16(const float* src, void* dst_bf16, size_t n, hipStream_t s);
+
+}  // namespace lp

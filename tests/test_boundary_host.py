@@ -1,0 +1,118 @@
+"""Host-side checks of the C-ABI boundary: the shared library loads without a GPU, exports every
+function include/lp.h declares, and rejects bad arguments with the documented status codes before
+touching any device."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import lp_workloads as WL
+import paper_2108_06629_amd as lp
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "lp.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(lp_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_functions()
+    assert len(names) >= 18 and {"lp_forward", "lp_grad_act", "lp_grad_weight", "lp_update", "lp_step"} <= set(names)
+    raw = C.CDLL(lp.LIB_PATH)
+    for n in names:
+        assert hasattr(raw, n), n
+    assert sorted(lp.EXPORTS) == names          # the Python binding covers the same set
+
+
+def descs(wl, delays=None):
+    return lp.make_descs(wl.layers, wl.delays if delays is None else delays)
+
+
+def create_status(d, L, batch, dtype, loss):
+    ctx = C.c_void_p()
+    st = lp.lib().lp_create(d, L, batch, dtype, loss, 0.01, C.byref(ctx))
+    if st == 0:
+        lp.lib().lp_destroy(ctx)
+    return st
+
+
+def test_create_rejects_bad_arguments():
+    wl = WL.mlp_small()
+    ok = descs(wl)
+    assert create_status(ok, wl.L, 32, lp.LP_F32, lp.LP_LOSS_SOFTMAX_CE) == 0
+    assert create_status(None, wl.L, 32, lp.LP_F32, 0) == 1                      # LP_ERR_NULL
+    assert create_status(ok, 0, 32, lp.LP_F32, 0) == 2                           # LP_ERR_SHAPE
+    assert create_status(ok, wl.L, 0, lp.LP_F32, 0) == 2
+    assert create_status(ok, wl.L, 32, 7, 0) == 3                                # LP_ERR_DTYPE
+    assert create_status(ok, wl.L, 32, lp.LP_F32, 9) == 3
+    bad = descs(wl); bad[1].in_ = 255
+    assert create_status(bad, wl.L, 32, lp.LP_F32, 0) == 4                       # LP_ERR_LAYER (widths do not chain)
+    bad = descs(wl); bad[2].delay = -1
+    assert create_status(bad, wl.L, 32, lp.LP_F32, 0) == 5                       # LP_ERR_DELAY
+    bad = descs(wl); bad[3].act = lp.LP_ACT_RELU
+    assert create_status(bad, wl.L, 32, lp.LP_F32, 0) == 3                       # last layer must be identity
+    bad = descs(wl); bad[0].kind = 5
+    assert create_status(bad, wl.L, 32, lp.LP_F32, 0) == 3
+    assert b"layer 1" in lp.lib().lp_last_error(None)
+    cnn = WL.vgg_small(batch=2, hw=8, chans=(8, 8))
+    assert create_status(descs(cnn), cnn.L, 2, lp.LP_BF16, 0) == 0
+    bad = descs(cnn); bad[1].H = 7
+    assert create_status(bad, cnn.L, 2, lp.LP_BF16, 0) in (2, 4)
+    bad = descs(cnn); bad[2].in_ = 100
+    assert create_status(bad, cnn.L, 2, lp.LP_BF16, 0) == 4
+
+
+def test_workspace_size_accounts_for_rings_and_weight_versions():
+    wl = WL.mlp_4096()
+    ctx = lp.lp_create(descs(wl), wl.L, wl.batch, lp.LP_BF16, lp.LP_LOSS_SOFTMAX_CE, 1e-3)
+    n = lp.lp_workspace_bytes(ctx)
+    ring = sum((d + 1) * ly.n_params * 4 for d, ly in zip(wl.delays, wl.layers))
+    weights = wl.n_params * (4 + 2 + 2)
+    assert n % 256 == 0 and ring + weights <= n <= ring + weights + 64 * 2 ** 20
+    ctx0 = lp.lp_create(descs(wl, [0] * wl.L), wl.L, wl.batch, lp.LP_BF16, lp.LP_LOSS_SOFTMAX_CE, 1e-3)
+    assert lp.lp_workspace_bytes(ctx0) == n - sum(d * ly.n_params * 4 for d, ly in zip(wl.delays, wl.layers))
+    lp.lp_destroy(ctx); lp.lp_destroy(ctx0)
+    big = WL.ffn_stack()
+    ctx = lp.lp_create(descs(big), big.L, big.batch, lp.LP_BF16, lp.LP_LOSS_MSE, 1e-3)
+    assert 68.7e9 + 6.4e9 < lp.lp_workspace_bytes(ctx) < 90e9      # fits one 288 GB device
+    lp.lp_destroy(ctx)
+
+
+def test_state_and_argument_errors_before_any_launch():
+    wl = WL.mlp_small()
+    ctx = lp.lp_create(descs(wl), wl.L, wl.batch, lp.LP_F32, lp.LP_LOSS_SOFTMAX_CE, 0.01)
+    L = lp.lib()
+    fake = 0x10000        # never dereferenced: every call below must fail in validation
+    assert L.lp_forward(ctx, 1, fake, fake, fake, None) == 6                  # LP_ERR_STATE: no workspace
+    assert b"workspace" in L.lp_last_error(ctx)
+    assert L.lp_bind_workspace(ctx, None, 1 << 30) == 1
+    assert L.lp_bind_workspace(ctx, 0x10008, 1 << 30) == 7                    # LP_ERR_WORKSPACE: misaligned
+    assert L.lp_bind_workspace(ctx, 0x10000, 16) == 7                         # too small
+    assert L.lp_bind_workspace(ctx, 0x10000, 1 << 30) == 0                    # accepted (host bookkeeping only)
+    assert L.lp_forward(ctx, 1, fake, fake, fake, None) == 6                  # weights never set
+    assert b"weights" in L.lp_last_error(ctx)
+    assert L.lp_forward(ctx, 0, fake, fake, fake, None) == 4                  # LP_ERR_LAYER
+    assert L.lp_forward(ctx, 5, fake, fake, fake, None) == 4
+    assert L.lp_forward(ctx, 1, None, fake, fake, None) == 1
+    assert L.lp_forward(ctx, 1, fake, None, None, None) == 1
+    assert L.lp_grad_act(ctx, 2, fake, fake, 10, 5, None) == 2                # LP_ERR_SHAPE: empty column range
+    assert L.lp_grad_act(ctx, 2, fake, fake, 0, 257, None) == 2
+    assert L.lp_grad_weight(ctx, 1, None, fake, None, None) == 1
+    assert L.lp_update(ctx, 1, None, None) == 6
+    assert L.lp_loss_grad(ctx, None, fake, fake, None, None) == 1
+    assert L.lp_act_grad(ctx, 1, None, fake, fake, None) == 1
+    streams = (C.c_void_p * 1)(None)
+    assert L.lp_step(ctx, fake, fake, None, None, streams, 1) == 6
+    assert L.lp_step(ctx, None, fake, None, None, streams, 1) == 1
+    assert L.lp_step(ctx, fake, fake, None, None, None, 0) == 1
+    n = C.c_long(-1)
+    assert L.lp_step_index(ctx, C.byref(n)) == 0 and n.value == 0
+    assert L.lp_advance(ctx) == 0 and L.lp_step_index(ctx, C.byref(n)) == 0 and n.value == 1
+    assert L.lp_destroy(ctx) == 0
+    assert L.lp_destroy(None) == 1
+    with pytest.raises(lp.LpError):
+        lp.lp_create(descs(wl), wl.L, -3, lp.LP_F32, 0, 0.1)
