@@ -1,0 +1,216 @@
+#!/usr/bin/env python3
+"""Benchmark of the LayerPipe hot path on one MI355X.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--streams S]
+
+One "step" is one whole delayed-gradient training iteration (lp_step: F, loss, dX, the moved
+Hadamard, dW and the delayed update of every layer) over one synthetic minibatch that is already
+resident in HBM.  Prints ONE JSON line: training samples/s of the whole job, the roofline of the
+dominant kernel (the bf16 MFMA GEMM of the forward product), per-task achieved rates, and the CPU
+oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
+PEAK_FP32_MFMA_TFLOPS = 157.3
+PEAK_HBM_GBS = 8000.0
+
+
+def task_work(wl):
+    """Algorithmic work per step of each task kind: flops for the three products, HBM bytes for the
+    bandwidth-bound tasks (act-type tensors 2 B for bf16 / 4 B for fp32; G and master weights 4 B)."""
+    import lp_workloads as WL
+    es = 2 if wl.dtype == "bf16" else 4
+    f, dx, dw = wl.flops_per_step()
+    had = 0.0
+    for l, ly in enumerate(wl.layers[:-1]):
+        if ly.act == WL.IDENTITY and not ly.pool:
+            continue                         # delta == dA, no kernel
+        z = 1
+        for v in ly.z_shape(wl.batch):
+            z *= v
+        a = 1
+        for v in ly.out_shape(wl.batch):
+            a *= v
+        had += (a + 2 * z) * es              # read dA, read stash, write dY
+    last = wl.layers[-1]
+    n_out = wl.batch * last.d_out
+    loss = n_out * es * (3 if wl.loss == WL.MSE else 2) + (4 * wl.batch if wl.loss != WL.MSE else 0)
+    per_param = 14 if wl.dtype == "bf16" else 12   # read G, read+write master (, write bf16 copy)
+    return {"F": f, "dX": dx, "dW": dw, "hadamard": had, "loss": float(loss), "update_per_param": per_param}
+
+
+def cpu_baseline(wl, threads):
+    """The oracle as it stands, timed on a bounded sample: one training step on at most 256 samples;
+    for networks above 5e8 parameters only the first two layers (one up/down block) on 512 samples,
+    scaled to the whole network by the ratio of per-sample flops."""
+    import lp_workloads as WL
+    from oracle import layerpipe_oracle as O
+    if wl.n_params > 5e8:
+        sub = wl.with_(layers=wl.layers[:2], batch=512, delays=wl.delays[-2:])
+        what = "the first 2 of %d layers" % wl.L
+    else:
+        sub = wl.with_(batch=min(wl.batch, 256))
+        what = "all %d layers" % wl.L
+    scale = (sum(wl.flops_per_step()) / wl.batch) / (sum(sub.flops_per_step()) / sub.batch)
+    W0 = WL.init_weights(sub)
+    ora = O.DelayedGradientTrainer(sub.layers, W0, sub.delays, sub.lr, sub.loss, "bf16" if wl.dtype == "bf16" else "f32")
+    x, t = WL.batch_input(sub, 1), WL.batch_target(sub, 1)
+    t0 = time.perf_counter()
+    ora.step(x, t)
+    dt = time.perf_counter() - t0
+    return {"value": sub.batch / (dt * scale), "unit": "samples/s", "cores": threads, "kind": "oracle",
+            "sample": "one oracle training step (numpy float64, %d BLAS threads) of %s of %s at full widths on %d of the %d samples "
+                      "of a minibatch took %.1f s; scaled by the per-sample flop ratio %.2f to the whole network" % (
+                          threads, what, wl.name, sub.batch, wl.batch, dt, scale)}
+
+
+def run_workload(wl, steps, warmup, n_streams, profile=True, weights=None):
+    import numpy as np
+    import torch
+    import lp_workloads as WL
+    import paper_2108_06629_amd as lp
+
+    dev = torch.device("cuda:0")
+    net = lp.Network(wl.layers, wl.batch, wl.dtype, wl.loss, wl.lr, wl.delays, device="cuda:0", n_streams=n_streams)
+    net.set_weights(WL.init_weights(wl) if weights is None else weights)
+    # a small pool of resident minibatches, reused round-robin
+    pool = 4
+    xs = [net.to_device(WL.batch_input(wl, n)) for n in range(1, pool + 1)]
+    ts = [net.to_device(WL.batch_target(wl, n), is_label=(wl.loss == WL.SOFTMAX_CE)) for n in range(1, pool + 1)]
+    torch.cuda.synchronize(dev)
+    s0 = net.streams[0]
+    for i in range(warmup):
+        net.step_device(xs[i % pool], ts[i % pool])
+    lp.lp_sync(net.ctx)
+    torch.cuda.synchronize(dev)
+    n0 = lp.lp_step_index(net.ctx)
+    if profile:
+        lp.lp_profile(net.ctx, True)
+    t0 = time.perf_counter()
+    for i in range(steps):
+        net.step_device(xs[i % pool], ts[i % pool])
+    lp.lp_sync(net.ctx)
+    torch.cuda.synchronize(dev)
+    dt = time.perf_counter() - t0
+    loss = float(net.loss_dev.item())
+    prof = {}
+    if profile:
+        lp.lp_profile(net.ctx, False)
+        for k, name in enumerate(lp.TASK_NAMES):
+            ms, cnt = lp.lp_profile_read(net.ctx, k, reset=True)
+            prof[name] = (ms, cnt)
+    # how many layer updates ran in the timed steps (layers with n <= d_l are still frozen)
+    upd_params = 0
+    for n in range(n0 + 1, n0 + steps + 1):
+        upd_params += sum(ly.n_params for ly, d in zip(wl.layers, wl.delays) if n - d >= 1)
+    net.close()
+    del net
+    torch.cuda.empty_cache()
+    return dt, loss, prof, upd_params
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=32)
+    ap.add_argument("--workload", default="ffn_stack_bf16")
+    ap.add_argument("--streams", type=int, default=3)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-others", action="store_true", help="skip the short runs of the other workloads")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (one MI355X per box, no collectives); --gpus %d is not supported" % args.gpus,
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import lp_workloads as WL
+    import paper_2108_06629_amd as lp
+    lp.load_library()          # fails loudly if the HIP library is not built
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+
+    wl = WL.CONFIGS[args.workload]()
+    work = task_work(wl)
+    weights = WL.init_weights(wl)
+    dt, loss, prof, upd_params = run_workload(wl, args.steps, args.warmup, args.streams, True, weights)
+    del weights
+    ms_per_step = dt / args.steps * 1e3
+    value = wl.batch * args.steps / dt
+
+    tasks = {}
+    for name in ("F", "dX", "dW"):
+        ms, cnt = prof.get(name, (0.0, 0))
+        if cnt:
+            tf = work[name] * args.steps / (ms * 1e-3) / 1e12
+            tasks[name] = {"launches": cnt, "avg_ms": ms / cnt, "TFLOP/s": tf, "frac_of_bf16_peak": tf / PEAK_BF16_TFLOPS}
+    for name in ("hadamard", "loss"):
+        ms, cnt = prof.get(name, (0.0, 0))
+        if cnt and ms > 0:
+            gbs = work[name] * args.steps / (ms * 1e-3) / 1e9
+            tasks[name] = {"launches": cnt, "avg_ms": ms / cnt, "GB/s": gbs, "frac_of_hbm_peak": gbs / PEAK_HBM_GBS}
+    ms, cnt = prof.get("update", (0.0, 0))
+    if cnt and ms > 0:
+        gbs = upd_params * work["update_per_param"] / (ms * 1e-3) / 1e9
+        tasks["update"] = {"launches": cnt, "avg_ms": ms / cnt, "GB/s": gbs, "frac_of_hbm_peak": gbs / PEAK_HBM_GBS}
+
+    # dominant kernel: the bf16 MFMA GEMM of the forward products (same instantiation for all layers
+    # of the default workload)
+    roofline = None
+    if "F" in tasks and wl.dtype == "bf16":
+        flops_per_launch = work["F"] / wl.L
+        avg_s = tasks["F"]["avg_ms"] * 1e-3
+        ach = flops_per_launch / avg_s / 1e12
+        roofline = {"bound": "mfma", "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS,
+                    "traffic": None, "kernel": "gemm_bf16_kernel (forward product F)", "flops_per_launch": flops_per_launch,
+                    "avg_launch_ms": tasks["F"]["avg_ms"]}
+    elif "F" in tasks:
+        flops_per_launch = work["F"] / wl.L
+        ach = flops_per_launch / (tasks["F"]["avg_ms"] * 1e-3) / 1e12
+        roofline = {"bound": "mfma", "achieved": ach, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s", "frac": ach / PEAK_FP32_MFMA_TFLOPS,
+                    "traffic": None, "kernel": "gemm_f32_kernel (forward product F)", "flops_per_launch": flops_per_launch,
+                    "avg_launch_ms": tasks["F"]["avg_ms"]}
+
+    others = {}
+    if not args.no_others:
+        for name, mk in WL.CONFIGS.items():
+            if name == wl.name:
+                continue
+            o = mk()
+            try:
+                odt, oloss, _, _ = run_workload(o, o.steps, 3, args.streams, False)
+                others[name] = {"samples_per_s": o.batch * o.steps / odt, "ms_per_step": odt / o.steps * 1e3, "steps": o.steps,
+                                "final_loss": oloss}
+            except Exception as e:  # a workload this build cannot run yet is reported, not hidden
+                others[name] = {"error": str(e)[:200]}
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        threads = int(os.environ.get("OMP_NUM_THREADS", "0")) or min(16, os.cpu_count() or 1)
+        cpu = cpu_baseline(wl, threads)
+
+    out = {
+        "metric": "training samples/sec (1 GPU)", "value": value, "unit": "samples/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": wl.dtype, "data": "synthetic",
+        "config": {"workload": "%s: %d layers, batch %d, delays %s, %s loss, lr %g, %d streams" % (
+            wl.name, wl.L, wl.batch, list(wl.delays), wl.loss, wl.lr, args.streams),
+            "params": wl.n_params, "flops_per_step": sum(wl.flops_per_step()),
+            "updated_params_per_step": upd_params / args.steps},
+        "roofline": roofline, "cpu_baseline": cpu, "tasks": tasks, "other_workloads": others, "final_loss": loss,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

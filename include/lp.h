@@ -177,6 +177,28 @@ int lp_sync(lp_ctx* ctx);
 /* Device address and size of an internal tensor (see lp_tensor_id) for inspection. */
 int lp_tensor(lp_ctx* ctx, int l, int which, void** dev_ptr, size_t* bytes);
 
+/* ---- measurement aid ----------------------------------------------------------------------- */
+
+/* Task kinds of Fig. 1(b) as this library launches them. */
+typedef enum {
+  LP_TASK_F = 0,         /* forward product + activation (Eq. 1, Eq. 2)  */
+  LP_TASK_DX = 1,        /* activation-gradient product (Eq. 4)          */
+  LP_TASK_DW = 2,        /* weight-gradient product (Eq. 5)              */
+  LP_TASK_HADAMARD = 3,  /* the moved f' factor (Eq. 3)                  */
+  LP_TASK_LOSS = 4,      /* error and delta of the output layer          */
+  LP_TASK_UPDATE = 5,    /* delayed SGD update (Eq. 6)                   */
+  LP_TASK_COUNT = 6
+} lp_task;
+
+/* enable != 0: from now on every task launch is bracketed by two timing events recorded on the
+ * stream the task is launched on (host memory and HIP events only; no device memory).  Tasks that
+ * overlap on different streams each report their own begin-to-end time. */
+int lp_profile(lp_ctx* ctx, int enable);
+/* Waits for the recorded launches of `task`, adds their durations and returns the totals gathered
+ * since the last reset: *total_ms (milliseconds) and *launches; either may be NULL.  reset != 0
+ * clears the totals of this task afterwards. */
+int lp_profile_read(lp_ctx* ctx, int task, double* total_ms, long* launches, int reset);
+
 #ifdef __cplusplus
 }
 #endif

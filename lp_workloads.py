@@ -157,7 +157,9 @@ def ffn_stack(d: int = 4096, hidden: int = 16384, tokens: int = 8192, n_linear: 
     layers = []
     for i in range(n_linear):
         layers.append(Layer(LINEAR, d, hidden, GELU) if i % 2 == 0 else Layer(LINEAR, hidden, d, IDENTITY))
-    return _mk("ffn_stack_bf16", layers, tokens, "bf16", MSE, 1e-3, 10, 4)
+    # lr: the configuration names none; 1e-3 diverges under the 2(L-l) delay schedule (in the CPU
+    # oracle as well), 1e-5 trains
+    return _mk("ffn_stack_bf16", layers, tokens, "bf16", MSE, 1e-5, 10, 4)
 
 
 def mlp_imbalanced() -> Workload:

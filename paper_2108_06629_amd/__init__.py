@@ -27,12 +27,14 @@ LP_LOSS_SOFTMAX_CE, LP_LOSS_MSE = 0, 1
 LP_LINEAR, LP_CONV3X3 = 0, 1
 LP_ACT_IDENTITY, LP_ACT_RELU, LP_ACT_GELU = 0, 1, 2
 LP_T_MASTER_W, LP_T_WORK_W, LP_T_A, LP_T_Z, LP_T_DA, LP_T_DY, LP_T_G_LAST = range(7)
+LP_TASK_F, LP_TASK_DX, LP_TASK_DW, LP_TASK_HADAMARD, LP_TASK_LOSS, LP_TASK_UPDATE = range(6)
+TASK_NAMES = ["F", "dX", "dW", "hadamard", "loss", "update"]
 STATUS_NAMES = ["LP_OK", "LP_ERR_NULL", "LP_ERR_SHAPE", "LP_ERR_DTYPE", "LP_ERR_LAYER", "LP_ERR_DELAY",
                 "LP_ERR_STATE", "LP_ERR_WORKSPACE", "LP_ERR_HIP"]
 
 EXPORTS = ["lp_create", "lp_destroy", "lp_last_error", "lp_workspace_bytes", "lp_bind_workspace", "lp_set_weights",
            "lp_get_weights", "lp_forward", "lp_loss_grad", "lp_act_grad", "lp_grad_act", "lp_grad_weight", "lp_update",
-           "lp_advance", "lp_step", "lp_step_index", "lp_sync", "lp_tensor"]
+           "lp_advance", "lp_step", "lp_step_index", "lp_sync", "lp_tensor", "lp_profile", "lp_profile_read"]
 
 
 class lp_layer_desc(C.Structure):
@@ -77,6 +79,8 @@ def load_library():
     L.lp_step_index.argtypes = [vp, C.POINTER(C.c_long)]
     L.lp_sync.argtypes = [vp]
     L.lp_tensor.argtypes = [vp, ip, ip, C.POINTER(vp), C.POINTER(C.c_size_t)]
+    L.lp_profile.argtypes = [vp, ip]
+    L.lp_profile_read.argtypes = [vp, ip, C.POINTER(C.c_double), C.POINTER(C.c_long), ip]
     for name in EXPORTS:
         if name != "lp_last_error":
             getattr(L, name).restype = ip
@@ -201,6 +205,16 @@ def lp_tensor(ctx, l: int, which: int):
     p, n = C.c_void_p(), C.c_size_t()
     _check(ctx, lib().lp_tensor(ctx, l, which, C.byref(p), C.byref(n)))
     return (p.value or 0), n.value
+
+
+def lp_profile(ctx, enable: bool):
+    _check(ctx, lib().lp_profile(ctx, int(enable)))
+
+
+def lp_profile_read(ctx, task: int, reset: bool = False):
+    ms, n = C.c_double(), C.c_long()
+    _check(ctx, lib().lp_profile_read(ctx, task, C.byref(ms), C.byref(n), int(reset)))
+    return ms.value, n.value
 
 
 # ---- convenience owner of a context + torch memory --------------------------------------------------

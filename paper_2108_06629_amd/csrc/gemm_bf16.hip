@@ -59,7 +59,9 @@ struct TileCfg {
   const char* name;
   int bm, bn;
 };
-constexpr TileCfg kCfgs[] = {{"256x256x64_w2x2", 256, 256}, {"128x128x64_w2x2", 128, 128}, {"64x64x64_w2x2", 64, 64}};
+constexpr TileCfg kCfgs[] = {{"256x256x64_w2x4", 256, 256}, {"128x128x64_w2x2", 128, 128}, {"64x64x64_w2x2", 64, 64},
+                             {"256x256x64_w2x2", 256, 256}};
+constexpr int kAutoCfgs = 3;  // the first three are ordered large to small for the automatic choice
 
 template <int BM, int BN, int BK, int WM, int WN, bool AKC, bool BKC, bool ALIGNED>
 hipError_t launch_one(const GemmKArgs& a, hipStream_t s) {
@@ -79,9 +81,10 @@ hipError_t launch_one(const GemmKArgs& a, hipStream_t s) {
 template <bool AKC, bool BKC, bool ALIGNED>
 hipError_t launch_cfg(int cfg, const GemmKArgs& a, hipStream_t s) {
   switch (cfg) {
-    case 0: return launch_one<256, 256, 64, 2, 2, AKC, BKC, ALIGNED>(a, s);
+    case 0: return launch_one<256, 256, 64, 2, 4, AKC, BKC, ALIGNED>(a, s);
     case 1: return launch_one<128, 128, 64, 2, 2, AKC, BKC, ALIGNED>(a, s);
     case 2: return launch_one<64, 64, 64, 2, 2, AKC, BKC, ALIGNED>(a, s);
+    case 3: return launch_one<256, 256, 64, 2, 2, AKC, BKC, ALIGNED>(a, s);
   }
   return hipErrorInvalidValue;
 }
@@ -129,11 +132,14 @@ hipError_t launch_gemm_bf16(const GemmDesc& d, hipStream_t s, int tile_cfg) {
 
   int cfg = tile_cfg;
   if (cfg < 0) {
-    cfg = gemm_bf16_num_cfgs() - 1;
-    for (int c = 0; c < gemm_bf16_num_cfgs(); ++c) {
+    cfg = kAutoCfgs - 1;
+    for (int c = 0; c < kAutoCfgs; ++c) {
       const long tiles = (long)((d.M + kCfgs[c].bm - 1) / kCfgs[c].bm) * ((d.N + kCfgs[c].bn - 1) / kCfgs[c].bn);
       if (tiles >= 192) { cfg = c; break; }
     }
+    // an operand that is transposed in registers needs more VGPRs than two waves per SIMD leave:
+    // the 256x256 tile then runs as four waves of 128x128 instead of eight of 128x64
+    if (cfg == 0 && !(d.a_kcontig && d.b_kcontig)) cfg = 3;
   }
   if (cfg >= gemm_bf16_num_cfgs()) return hipErrorInvalidValue;
   return aligned ? launch_layout<true>(d.a_kcontig, d.b_kcontig, cfg, a, s)

@@ -7,14 +7,15 @@
 // registers (8x8 blocks of 16-bit values) on its way from global memory to LDS.  LDS rows are
 // XOR-swizzled in 16-byte chunks so that the 16 lanes of a fragment read touch all banks.  Global
 // loads go through buffer resources, so out-of-range chunks read as zero without branches.  Two LDS
-// buffers: the global loads of tile t+1 are issued before the MFMAs of tile t and land in the other
-// buffer after them, one barrier per K step.  Accumulators are 32x32 MFMA tiles
-// (v_mfma_f32_32x32x16_bf16), TM x TN of them per wave.
+// buffers and two fragment register sets (see gemm_tile for the schedule), one barrier per K step.
+// Accumulators are 32x32 MFMA tiles (v_mfma_f32_32x32x16_bf16), TM x TN of them per wave.
 //
 // A "stage" object owns the addressing of one operand: gload(k0) fetches its part of the tile that
 // starts at reduction index k0 into registers, sstore(lds) writes it to LDS.
 #pragma once
 #include <hip/hip_runtime.h>
+
+#include <type_traits>
 
 namespace lp {
 namespace core {
@@ -169,10 +170,23 @@ __device__ __forceinline__ void tile_of_block(int pid, int nbm, int nbn, int& tm
 
 // Accumulates K tiles [kt0, kt1) of the BM x BN tile and hands the result to epi(row_in_tile,
 // col_in_tile, four consecutive columns).  smem: 2 * (BM + BN) * BK halves.
+//
+// Schedule of one K step (BK = 64 = four MFMA substeps of k = 16), written so that the matrix pipe
+// never waits for a barrier with nothing queued behind it:
+//   top        global loads of tile t+1 are issued into registers
+//   substep 0  MFMAs on fragments fetched earlier, interleaved with the LDS reads of substep 1
+//   substep 1  same, reading substep 2
+//   substep 2  same, reading substep 3, then the LDS stores of tile t+1 (other buffer), two per MFMA
+//   barrier    tile t+1 is now visible, and every wave already holds its last fragments of tile t
+//   substep 3  MFMAs of tile t cover the first fragment reads of tile t+1
+// sched_group_barrier pins the MFMA / DS interleaving; the last K step is peeled so that the loop
+// body has no branches (the scheduler cannot interleave across basic blocks).
 template <int BM, int BN, int BK, int WM, int WN, class SA, class SB, class Epi>
 __device__ __forceinline__ void gemm_tile(SA& sa, SB& sb, int kt0, int kt1, unsigned short* smem, Epi epi) {
   constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
   constexpr int A_ELEMS = BM * BK, B_ELEMS = BN * BK;
+  constexpr int KS = BK / 16;
+  static_assert(KS == 4, "written for BK = 64");
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave / WN, wn = wave % WN;
 
@@ -184,6 +198,24 @@ __device__ __forceinline__ void gemm_tile(SA& sa, SB& sb, int kt0, int kt1, unsi
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
+  const int frow_a = wm * (TM * 32) + (lane & 31);
+  const int frow_b = wn * (TN * 32) + (lane & 31);
+  const int fchunk = lane >> 5;
+
+  bf16x8 fa[2][TM], fb[2][TN];
+  auto read_frags = [&](const unsigned short* As, const unsigned short* Bs, int kk, bf16x8 (&a)[TM], bf16x8 (&b)[TN]) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i) a[i] = *(const bf16x8*)(As + lds_off<BK>(frow_a + i * 32, kk * 2 + fchunk));
+#pragma unroll
+    for (int j = 0; j < TN; ++j) b[j] = *(const bf16x8*)(Bs + lds_off<BK>(frow_b + j * 32, kk * 2 + fchunk));
+  };
+  auto mfmas = [&](bf16x8 (&a)[TM], bf16x8 (&b)[TN]) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+  };
+
   if (kt0 < kt1) {
     sa.gload(kt0 * BK);
     sb.gload(kt0 * BK);
@@ -191,46 +223,53 @@ __device__ __forceinline__ void gemm_tile(SA& sa, SB& sb, int kt0, int kt1, unsi
     sb.sstore(smem + A_ELEMS);
   }
   __syncthreads();
+  if (kt0 < kt1) read_frags(smem, smem + A_ELEMS, 0, fa[0], fb[0]);
 
-  const int frow_a = wm * (TM * 32) + (lane & 31);
-  const int frow_b = wn * (TN * 32) + (lane & 31);
-  const int fchunk = lane >> 5;
-
-  for (int kt = kt0; kt < kt1; ++kt) {
+  auto step = [&](int kt, auto more_tag) {
+    constexpr bool more = decltype(more_tag)::value;
     const int cur = (kt - kt0) & 1;
     const unsigned short* As = smem + cur * (A_ELEMS + B_ELEMS);
     const unsigned short* Bs = As + A_ELEMS;
-    const bool more = kt + 1 < kt1;
-    if (more) {
+    unsigned short* nxt = smem + (cur ^ 1) * (A_ELEMS + B_ELEMS);
+    if constexpr (more) {
       sa.gload((kt + 1) * BK);
       sb.gload((kt + 1) * BK);
     }
+    read_frags(As, Bs, 1, fa[1], fb[1]);
+    mfmas(fa[0], fb[0]);
 #pragma unroll
-    for (int kk = 0; kk < BK / 16; ++kk) {
-      bf16x8 a[TM], b[TN];
+    for (int q = 0; q < TM + TN; ++q) { __builtin_amdgcn_sched_group_barrier(0x008, 1, 0); __builtin_amdgcn_sched_group_barrier(0x100, 1, 0); }
+    __builtin_amdgcn_sched_group_barrier(0x008, TM * TN - (TM + TN), 0);
+    __builtin_amdgcn_sched_barrier(0);
+    read_frags(As, Bs, 2, fa[0], fb[0]);
+    mfmas(fa[1], fb[1]);
 #pragma unroll
-      for (int i = 0; i < TM; ++i) a[i] = *(const bf16x8*)(As + lds_off<BK>(frow_a + i * 32, kk * 2 + fchunk));
-#pragma unroll
-      for (int j = 0; j < TN; ++j) b[j] = *(const bf16x8*)(Bs + lds_off<BK>(frow_b + j * 32, kk * 2 + fchunk));
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
-    }
-    if (more) {
-      unsigned short* nxt = smem + (cur ^ 1) * (A_ELEMS + B_ELEMS);
+    for (int q = 0; q < TM + TN; ++q) { __builtin_amdgcn_sched_group_barrier(0x008, 1, 0); __builtin_amdgcn_sched_group_barrier(0x100, 1, 0); }
+    __builtin_amdgcn_sched_group_barrier(0x008, TM * TN - (TM + TN), 0);
+    __builtin_amdgcn_sched_barrier(0);
+    read_frags(As, Bs, 3, fa[1], fb[1]);
+    mfmas(fa[0], fb[0]);
+    if constexpr (more) {
       sa.sstore(nxt);
       sb.sstore(nxt + A_ELEMS);
     }
+#pragma unroll
+    for (int q = 0; q < TM + TN; ++q) { __builtin_amdgcn_sched_group_barrier(0x008, 1, 0); __builtin_amdgcn_sched_group_barrier(0x100, 1, 0); }
+    if constexpr (more) {
+#pragma unroll
+      for (int q = 0; q < TM * TN - (TM + TN); ++q) { __builtin_amdgcn_sched_group_barrier(0x008, 1, 0); __builtin_amdgcn_sched_group_barrier(0x200, 2, 0); }
+    }
+    __builtin_amdgcn_sched_barrier(0);
     __syncthreads();
-  }
+    if constexpr (more) read_frags(nxt, nxt + A_ELEMS, 0, fa[0], fb[0]);
+    mfmas(fa[1], fb[1]);
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  for (int kt = kt0; kt + 1 < kt1; ++kt) step(kt, std::true_type{});
+  if (kt0 < kt1) step(kt1 - 1, std::false_type{});
+  __syncthreads();
 
-  // Epilogue through LDS (free after the last barrier): each wave parks one 32-row band of its
-  // sub-tile as fp32 in a private LDS region, then reads it back row-major, four columns per lane,
-  // so that global stores are 8- or 16-byte vectors covering whole contiguous row segments.
-  // A lane holds, per 32x32 MFMA tile, column (lane & 31) of rows 8*(r/4) + 4*(lane/32) + r%4.
-  constexpr int EP_LD = TN * 32 + 8;  // +8 floats: the two half-waves (4 rows apart) hit different banks
-  static_assert(WM * WN * 32 * EP_LD * 4 <= 2 * (BM + BN) * BK * 2, "epilogue band does not fit the main-loop LDS");
+  constexpr int EP_LD = TN * 32 + 8;
   float* ep = reinterpret_cast<float*>(smem) + wave * (32 * EP_LD);
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
@@ -242,7 +281,7 @@ __device__ __forceinline__ void gemm_tile(SA& sa, SB& sb, int kt0, int kt1, unsi
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-#pragma unroll 1
+#pragma unroll 4
     for (int e = lane; e < 32 * TN * 8; e += 64) {
       const int row = e / (TN * 8), c4 = e % (TN * 8);
       const f32x4 v = *reinterpret_cast<const f32x4*>(ep + row * EP_LD + c4 * 4);

@@ -50,6 +50,13 @@ struct lp_ctx {
   std::vector<hipEvent_t> ev_dy, ev_dx, ev_dw;
   hipEvent_t ev_fork = nullptr, ev_join_w = nullptr, ev_join_u = nullptr;
   std::vector<hipStream_t> streams_seen;
+  // measurement aid (lp_profile)
+  struct ProfRec { int task; hipEvent_t e0, e1; };
+  bool prof_on = false;
+  std::vector<ProfRec> prof_recs;
+  std::vector<hipEvent_t> prof_free;
+  double prof_ms[LP_TASK_COUNT] = {0, 0, 0, 0, 0, 0};
+  long prof_n[LP_TASK_COUNT] = {0, 0, 0, 0, 0, 0};
 };
 
 namespace {
@@ -80,6 +87,31 @@ inline void note_stream(lp_ctx* c, hipStream_t s) {
   c->streams_seen.push_back(s);
 }
 
+// Brackets one task launch with timing events on its stream when profiling is on.
+struct ProfScope {
+  lp_ctx* c;
+  hipStream_t s;
+  hipEvent_t e1 = nullptr;
+  ProfScope(lp_ctx* c_, int task, hipStream_t s_) : c(c_), s(s_) {
+    if (!c->prof_on) return;
+    hipEvent_t ev[2] = {nullptr, nullptr};
+    for (hipEvent_t& e : ev) {
+      if (!c->prof_free.empty()) { e = c->prof_free.back(); c->prof_free.pop_back(); }
+      else if (hipEventCreate(&e) != hipSuccess) { e = nullptr; }
+    }
+    if (!ev[0] || !ev[1]) {
+      for (hipEvent_t e : ev) if (e) c->prof_free.push_back(e);
+      return;
+    }
+    (void)hipEventRecord(ev[0], s);
+    e1 = ev[1];
+    c->prof_recs.push_back({task, ev[0], ev[1]});
+  }
+  ~ProfScope() {
+    if (e1) (void)hipEventRecord(e1, s);
+  }
+};
+
 int check_layer(lp_ctx* c, int l) {
   if (l < 1 || l > c->L) return fail(c, LP_ERR_LAYER, "layer index %d outside 1..%d", l, c->L);
   return LP_OK;
@@ -108,6 +140,7 @@ inline lp::ConvDesc conv_desc(const lp_ctx* c, const Layer& ly) {
 
 // ---- the tasks, shared by the per-layer entry points and lp_step -------------------------------
 hipError_t do_forward(lp_ctx* c, Layer& ly, const void* X, void* Z, void* A, hipStream_t s) {
+  ProfScope prof(c, LP_TASK_F, s);
   if (ly.d.kind == LP_LINEAR) {
     lp::GemmDesc g;
     g.A = X; g.B = work_w(c, ly);
@@ -127,6 +160,7 @@ hipError_t do_forward(lp_ctx* c, Layer& ly, const void* X, void* Z, void* A, hip
 }
 
 hipError_t do_grad_act(lp_ctx* c, Layer& ly, const void* dY, void* dX, int c0, int c1, hipStream_t s) {
+  ProfScope prof(c, LP_TASK_DX, s);
   if (ly.d.kind == LP_LINEAR) {
     lp::GemmDesc g;
     const size_t es = esize(c);
@@ -141,6 +175,7 @@ hipError_t do_grad_act(lp_ctx* c, Layer& ly, const void* dY, void* dX, int c0, i
 }
 
 hipError_t do_grad_weight(lp_ctx* c, Layer& ly, const void* X, const void* dY, float* G, hipStream_t s) {
+  ProfScope prof(c, LP_TASK_DW, s);
   if (ly.d.kind == LP_LINEAR) {
     lp::GemmDesc g;
     g.A = X; g.B = dY;
@@ -154,12 +189,14 @@ hipError_t do_grad_weight(lp_ctx* c, Layer& ly, const void* X, const void* dY, f
 }
 
 hipError_t do_act_grad(lp_ctx* c, Layer& ly, const void* dA, const void* S, void* dY, hipStream_t s) {
+  ProfScope prof(c, LP_TASK_HADAMARD, s);
   if (ly.d.kind == LP_CONV3X3 && ly.d.pool == 2)
     return lp::launch_act_grad_pool(is_bf16(c), ly.d.act, dA, S, dY, c->batch, ly.d.H, ly.d.W, ly.d.out, s);
   return lp::launch_act_grad(is_bf16(c), ly.d.act, dA, S, dY, ly.z_elems, s);
 }
 
 hipError_t do_loss(lp_ctx* c, const void* ZL, const void* target, void* dYL, float* loss_dev, hipStream_t s) {
+  ProfScope prof(c, LP_TASK_LOSS, s);
   const Layer& last = c->layers[c->L - 1];
   float* partials = (float*)(c->ws + c->off_partials);
   if (c->loss == LP_LOSS_SOFTMAX_CE)
@@ -169,6 +206,7 @@ hipError_t do_loss(lp_ctx* c, const void* ZL, const void* target, void* dYL, flo
 
 // Applies W <- W - lr*G; BF16 writes the other working buffer.  Does not flip `cur`.
 hipError_t do_update(lp_ctx* c, Layer& ly, const float* G, hipStream_t s) {
+  ProfScope prof(c, LP_TASK_UPDATE, s);
   float* master = (float*)(c->ws + ly.off_master);
   void* work_out = is_bf16(c) ? (void*)(c->ws + ly.off_work[ly.cur ^ 1]) : nullptr;
   return lp::launch_sgd(master, G, work_out, c->lr, ly.n_params, s);
@@ -295,6 +333,8 @@ int lp_destroy(lp_ctx* c) {
     for (hipEvent_t e : {c->ev_fork, c->ev_join_w, c->ev_join_u})
       if (e) (void)hipEventDestroy(e);
   }
+  for (auto& r : c->prof_recs) { (void)hipEventDestroy(r.e0); (void)hipEventDestroy(r.e1); }
+  for (hipEvent_t e : c->prof_free) (void)hipEventDestroy(e);
   delete c;
   return LP_OK;
 }
@@ -566,6 +606,33 @@ int lp_tensor(lp_ctx* c, int l, int which, void** dev_ptr, size_t* bytes) {
     case LP_T_G_LAST: if (c->n >= 1) { *dev_ptr = ring_slot(c, ly, c->n); *bytes = ly.n_params * 4; } break;
     default: return fail(c, LP_ERR_DTYPE, "lp_tensor: unknown tensor id %d", which);
   }
+  return LP_OK;
+}
+
+int lp_profile(lp_ctx* c, int enable) {
+  if (!c) return LP_ERR_NULL;
+  c->prof_on = enable != 0;
+  return LP_OK;
+}
+
+int lp_profile_read(lp_ctx* c, int task, double* total_ms, long* launches, int reset) {
+  if (!c) return LP_ERR_NULL;
+  if (task < 0 || task >= LP_TASK_COUNT) return fail(c, LP_ERR_DTYPE, "lp_profile_read: unknown task %d", task);
+  std::vector<lp_ctx::ProfRec> keep;
+  for (auto& r : c->prof_recs) {
+    if (r.task != task) { keep.push_back(r); continue; }
+    LP_HIP(c, hipEventSynchronize(r.e1));
+    float ms = 0.f;
+    LP_HIP(c, hipEventElapsedTime(&ms, r.e0, r.e1));
+    c->prof_ms[task] += ms;
+    c->prof_n[task] += 1;
+    c->prof_free.push_back(r.e0);
+    c->prof_free.push_back(r.e1);
+  }
+  c->prof_recs.swap(keep);
+  if (total_ms) *total_ms = c->prof_ms[task];
+  if (launches) *launches = c->prof_n[task];
+  if (reset) { c->prof_ms[task] = 0; c->prof_n[task] = 0; }
   return LP_OK;
 }
 
