@@ -1,0 +1,243 @@
+// bf16 matrix-core GEMM main loop with direct global->LDS loads and a four-stage LDS ring.
+//
+// Used for the three products of a layer (Eq. 1, Eq. 4, Eq. 5) whenever every contiguous run of both
+// operands starts on a multiple of 8 elements (16-byte chunks); other shapes take the register-staged
+// loop of gemm_core.h.  Differences from that loop:
+//   * tiles travel global -> LDS with buffer_load ... lds (16 bytes per lane, a wave fills 1 KB of LDS
+//     in lane order): no staging registers, no LDS store instructions, and the loads of tile t+4 are
+//     issued while tile t is being multiplied, so about three K steps of latency are covered;
+//   * an operand whose k index is strided in memory stays in its memory order in LDS ([k][row], row
+//     contiguous) and is transposed by the LDS read itself (ds_read_b64_tr_b16): within a group of 16
+//     lanes, lane 4j+a supplies the address of four consecutive elements of k-row j, and lane i
+//     receives element i of each of the four k-rows;
+//   * K step 32 (two MFMA substeps), one barrier per step, placed between the substeps: before it a
+//     wave waits for its own loads of tile t+1, after it stage t%4 is free and receives tile t+4, and
+//     the second substep's MFMAs cover the first fragment reads of tile t+1.
+// The swizzle that keeps LDS reads conflict-free is applied on the global side: the lane that owns
+// LDS chunk p of a row fetches global chunk p ^ f(row).
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <type_traits>
+
+#include "gemm_core.h"
+
+namespace lp {
+namespace dl {
+
+using core::bf16x8;
+using core::f32x16;
+using core::f32x4;
+using core::kOOB;
+
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+
+constexpr int BK = 32;      // K step
+constexpr int NSTAGE = 4;   // LDS ring depth
+
+typedef __attribute__((address_space(3))) unsigned int* lds_u32_ptr;
+typedef __attribute__((address_space(3))) s16x4* lds_s16x4_ptr;
+
+// One wave copies 64 x 16 bytes from a buffer to LDS: lane L's bytes land at lds_base + 16 L.
+// Written as inline assembly so that the compiler does not track the asynchronous LDS write: it
+// would otherwise drain *all* loads in flight (vmcnt(0)) in front of the transposing LDS reads.
+// Ordering is explicit instead: wait_vmcnt + barrier before a stage is read.  lds_base is
+// wave-uniform; voff is the per-lane byte offset (kOOB = out of range: zeros are written).
+__device__ __forceinline__ void load_to_lds_16(__amdgpu_buffer_rsrc_t rs, unsigned voff, unsigned short* lds_base) {
+  const unsigned addr = __builtin_amdgcn_readfirstlane((unsigned)(size_t)(lds_u32_ptr)lds_base);
+  asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" : : "s"(addr), "v"(voff), "s"(rs) : "memory");
+}
+
+// ---- operand with k contiguous in memory: element (r,k) at base[r*ld + k] ------------------------
+// LDS stage: [R][32] halves, 64 bytes per row, chunk p of row r holds global chunk p ^ ((r>>2)&3).
+template <int R, int NWAVES>
+struct OperandKC {
+  static constexpr int STAGE_ELEMS = R * BK;
+  static constexpr int WAVELOADS = R / 16;                  // 1 KB each: 16 rows
+  static constexpr int PER_WAVE = WAVELOADS / NWAVES;
+  static_assert(WAVELOADS % NWAVES == 0, "rows must split evenly over the waves");
+  __amdgpu_buffer_rsrc_t rs;
+  int r0, Rtot, Ktot, ld;
+  // lane-constant parts
+  int lrow, lchunk;
+  __device__ __forceinline__ void init(const void* p, unsigned bytes, int r0_, int Rtot_, int Ktot_, int ld_) {
+    rs = core::make_rsrc(p, bytes);
+    r0 = r0_; Rtot = Rtot_; Ktot = Ktot_; ld = ld_;
+    const int lane = threadIdx.x & 63;
+    lrow = lane >> 2;
+    lchunk = (lane & 3) ^ ((lrow >> 2) & 3);
+  }
+  // all waves together fill one stage with the tile that starts at reduction index k0
+  __device__ __forceinline__ void issue(int k0, unsigned short* stage, int wave_u) const {
+#pragma unroll
+    for (int i = 0; i < PER_WAVE; ++i) {
+      const int g = wave_u * PER_WAVE + i;                  // group of 16 rows
+      const int row = r0 + g * 16 + lrow, k = k0 + lchunk * 8;
+      const unsigned off = (row < Rtot && k < Ktot) ? ((unsigned)row * (unsigned)ld + (unsigned)k) * 2u : kOOB;
+      load_to_lds_16(rs, off, stage + g * 512);
+    }
+  }
+  // fragment of MFMA tile rows [row0, row0+32), k substep kk: lane (r = lane&31, g = lane>>5) gets k = 16kk + 8g + 0..7
+  __device__ __forceinline__ bf16x8 frag(const unsigned short* stage, int row0, int kk) const {
+    const int lane = threadIdx.x & 63;
+    const int row = row0 + (lane & 31), chunk = kk * 2 + (lane >> 5);
+    return *(const bf16x8*)(stage + row * BK + ((chunk ^ ((row >> 2) & 3)) * 8));
+  }
+};
+
+// ---- operand with k strided in memory: element (r,k) at base[k*ld + r] ---------------------------
+// LDS stage: [32][R] halves, chunk p of k-row k holds global chunk p ^ ((k&3)<<2).
+template <int R, int NWAVES>
+struct OperandKS {
+  static_assert(R == 128 || R == 256, "row length of 16 or 32 chunks");
+  static constexpr int STAGE_ELEMS = R * BK;
+  static constexpr int CPR = R / 8;                          // chunks per k-row
+  static constexpr int ROWS_PER_LOAD = 64 / CPR;             // k-rows per 1 KB wave load
+  static constexpr int WAVELOADS = BK / ROWS_PER_LOAD;
+  static constexpr int PER_WAVE = WAVELOADS / NWAVES;
+  static_assert(WAVELOADS % NWAVES == 0, "k-rows must split evenly over the waves");
+  __amdgpu_buffer_rsrc_t rs;
+  int r0, Rtot, Ktot, ld;
+  int lk, lpos;
+  __device__ __forceinline__ void init(const void* p, unsigned bytes, int r0_, int Rtot_, int Ktot_, int ld_) {
+    rs = core::make_rsrc(p, bytes);
+    r0 = r0_; Rtot = Rtot_; Ktot = Ktot_; ld = ld_;
+    const int lane = threadIdx.x & 63;
+    lk = lane / CPR;
+    lpos = lane % CPR;
+  }
+  __device__ __forceinline__ void issue(int k0, unsigned short* stage, int wave_u) const {
+#pragma unroll
+    for (int i = 0; i < PER_WAVE; ++i) {
+      const int g = wave_u * PER_WAVE + i;
+      const int kr = g * ROWS_PER_LOAD + lk;                 // k-row inside the tile
+      const int chunk = lpos ^ ((kr & 3) << 2);
+      const int k = k0 + kr, r = r0 + chunk * 8;
+      const unsigned off = (k < Ktot && r < Rtot) ? ((unsigned)k * (unsigned)ld + (unsigned)r) * 2u : kOOB;
+      load_to_lds_16(rs, off, stage + g * 512);
+    }
+  }
+  __device__ __forceinline__ bf16x8 frag(const unsigned short* stage, int row0, int kk) const {
+    const int lane = threadIdx.x & 63;
+    const int l16 = lane & 15, j = l16 >> 2, a = l16 & 3;
+    const int col = row0 + ((lane >> 4) & 1) * 16 + a * 4;  // first of the four elements this lane points at
+    const int k = kk * 16 + (lane >> 5) * 8 + j;             // k & 3 == j for both halves
+    const int chunk = (col >> 3) ^ (j << 2);
+    const unsigned short* p = stage + k * R + chunk * 8 + (col & 7);
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)p);
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p + 4 * R));
+    const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, v);
+  }
+};
+
+template <bool KC, int R, int NWAVES>
+struct OperandSel {
+  using type = OperandKC<R, NWAVES>;
+};
+template <int R, int NWAVES>
+struct OperandSel<false, R, NWAVES> {
+  using type = OperandKS<R, NWAVES>;
+};
+
+// s_waitcnt with vmcnt <= n (expcnt and lgkmcnt untouched)
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  static_assert(N >= 0 && N < 64, "");
+  __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
+}
+
+// smem: NSTAGE * (BM + BN) * BK halves.  KT = number of K tiles.
+template <int BM, int BN, int WM, int WN, class OA, class OB, class Epi>
+__device__ __forceinline__ void gemm_tile_dl(const OA& oa, const OB& ob, int KT, unsigned short* smem, Epi epi) {
+  constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
+  constexpr int A_ELEMS = BM * BK, B_ELEMS = BN * BK, STAGE = A_ELEMS + B_ELEMS;
+  constexpr int LOADS = OA::PER_WAVE + OB::PER_WAVE;        // buffer loads per lane per tile
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int wm = wave / WN, wn = wave % WN;
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  bf16x8 fa[2][TM], fb[2][TN];
+  auto read_frags = [&](const unsigned short* st, int kk, bf16x8 (&a)[TM], bf16x8 (&b)[TN]) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i) a[i] = oa.frag(st, wm * (TM * 32) + i * 32, kk);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) b[j] = ob.frag(st + A_ELEMS, wn * (TN * 32) + j * 32, kk);
+  };
+  auto mfmas = [&](bf16x8 (&a)[TM], bf16x8 (&b)[TN]) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+  };
+  // tiles past the end are "loaded" too (every chunk out of range, so zeros and no memory traffic):
+  // the number of loads in flight stays the same in every iteration, which keeps the vmcnt waits exact
+  auto issue = [&](int t) {
+    unsigned short* st = smem + (t % NSTAGE) * STAGE;
+    oa.issue(t * BK, st, wave);
+    ob.issue(t * BK, st + A_ELEMS, wave);
+  };
+
+#pragma unroll
+  for (int t = 0; t < NSTAGE; ++t) issue(t);
+  wait_vmcnt<(NSTAGE - 1) * LOADS>();
+  __syncthreads();
+  read_frags(smem, 0, fa[0], fb[0]);
+
+  for (int t = 0; t < KT; ++t) {
+    const unsigned short* cur = smem + (t % NSTAGE) * STAGE;
+    const unsigned short* nxt = smem + ((t + 1) % NSTAGE) * STAGE;
+    read_frags(cur, 1, fa[1], fb[1]);
+    mfmas(fa[0], fb[0]);
+#pragma unroll
+    for (int q = 0; q < TM + TN; ++q) { __builtin_amdgcn_sched_group_barrier(0x008, 1, 0); __builtin_amdgcn_sched_group_barrier(0x100, 1, 0); }
+    __builtin_amdgcn_sched_barrier(0);
+    wait_vmcnt<(NSTAGE - 2) * LOADS>();   // this wave's part of tile t+1 has landed
+    __syncthreads();                      // ... and everyone's; nobody reads tile t's stage any more
+    issue(t + NSTAGE);
+    read_frags(nxt, 0, fa[0], fb[0]);
+    mfmas(fa[1], fb[1]);
+#pragma unroll
+    for (int q = 0; q < TM + TN; ++q) { __builtin_amdgcn_sched_group_barrier(0x008, 1, 0); __builtin_amdgcn_sched_group_barrier(0x100, 1, 0); }
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  wait_vmcnt<0>();   // the trailing (empty) tiles still write LDS
+  __syncthreads();
+
+  // epilogue through LDS, as in gemm_core.h
+  constexpr int EP_LD = TN * 32 + 8;
+  static_assert(WM * WN * 32 * EP_LD * 4 <= NSTAGE * STAGE * 2, "epilogue band does not fit the ring");
+  float* ep = reinterpret_cast<float*>(smem) + wave * (32 * EP_LD);
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        ep[((r >> 2) * 8 + (lane >> 5) * 4 + (r & 3)) * EP_LD + j * 32 + (lane & 31)] = acc[i][j][r];
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll 4
+    for (int e = lane; e < 32 * TN * 8; e += 64) {
+      const int row = e / (TN * 8), c4 = e % (TN * 8);
+      const f32x4 v = *reinterpret_cast<const f32x4*>(ep + row * EP_LD + c4 * 4);
+      epi(wm * (TM * 32) + i * 32 + row, wn * (TN * 32) + c4 * 4, v);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  }
+}
+
+}  // namespace dl
+}  // namespace lp
