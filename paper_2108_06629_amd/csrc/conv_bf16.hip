@@ -1,8 +1,380 @@
-// placeholder: convolution tasks are added after the fully connected path
+// 3x3, stride 1, zero pad 1 convolution tasks as implicit GEMMs on the bf16 matrix cores (NHWC
+// activations, weights [3][3][C_in][C_out], cross-correlation, no bias):
+//
+//   F   z[(b,y,x), o]   = sum_{(tap,c)} x[b, y+kh-1, x+kw-1, c] * w[(tap,c), o]          Eq. 1
+//   dX  dx[(b,y,x), c]  = sum_{(tap,o)} dy[b, y-kh+1, x-kw+1, o] * w[tap, c, o]          Eq. 4
+//   dW  g[(tap,c), o]   = sum_{(b,y,x)} x[b, y+kh-1, x+kw-1, c] * dy[(b,y,x), o]         Eq. 5
+//
+// with tap = 3*kh + kw.  No im2col buffer exists: the operand that is a shifted view of an image is
+// gathered chunk by chunk while its tile is staged into LDS (zero padding = an out-of-range buffer
+// offset), and everything after that is the main loop of gemm_core.h.  dW reduces over B*H*W pixels
+// into a small [9*C_in, C_out] result, so it is split over K across workgroups; the fp32 partials are
+// summed by a second kernel in a fixed order.
+#include "gemm_core.h"
 #include "lp_kernels.h"
+
 namespace lp {
-hipError_t launch_conv_fwd(const ConvDesc&, bool, const void*, const void*, void*, void*, int, hipStream_t) { return hipErrorNotSupported; }
-hipError_t launch_conv_grad_act(const ConvDesc&, bool, const void*, const void*, void*, int, int, hipStream_t) { return hipErrorNotSupported; }
-hipError_t launch_conv_grad_weight(const ConvDesc&, bool, const void*, const void*, float*, float*, hipStream_t) { return hipErrorNotSupported; }
-size_t conv_grad_weight_scratch_bytes(const ConvDesc&) { return 0; }
+namespace {
+
+using namespace core;
+
+constexpr int BM = 128, BN = 64, BK = 64, WM = 2, WN = 2, NT = WM * WN * 64;
+
+struct ConvKArgs {
+  const unsigned short* img;   // F: x, dX: dy, dW: x
+  const unsigned short* mat;   // F: w, dX: w, dW: dy
+  unsigned short* out_z;
+  unsigned short* out_a;
+  float* out_f32;
+  int B, H, W, Cimg;           // channels of the gathered image
+  int M, N, K;                 // GEMM view
+  int Cin, Cout;
+  int c0;                      // dX: first input channel of the range
+  int ldc, act;
+  unsigned img_bytes, mat_bytes;
+  int kt_per_split;            // dW: K tiles per workgroup in y
+  int vec_out;
+};
+
+__device__ __forceinline__ void tap_offsets(int tap, bool flip, int& dy, int& dx) {
+  const int kh = tap / 3, kw = tap - kh * 3;
+  dy = flip ? 1 - kh : kh - 1;
+  dx = flip ? 1 - kw : kw - 1;
+}
+
+// A operand of F and dX: rows are pixels (b,y,x), k = (tap, c) with c contiguous in memory.
+template <bool ALIGNED>
+struct StagePixelsKC {
+  static constexpr int NCH = BM * BK / 8;
+  static constexpr int CH = NCH / NT;
+  static_assert(NCH % NT == 0, "");
+  __amdgpu_buffer_rsrc_t rs;
+  int Ktot, C, H, W, tid;
+  bool flip;
+  int pix[CH], yx[CH];   // pixel index and (y << 16 | x) of this thread's rows; pix < 0: row past M
+  u32x4 v[CH];
+  __device__ __forceinline__ void init(const ConvKArgs& p, int m0, bool flip_) {
+    rs = make_rsrc(p.img, p.img_bytes);
+    Ktot = p.K; C = p.Cimg; H = p.H; W = p.W; tid = threadIdx.x; flip = flip_;
+#pragma unroll
+    for (int it = 0; it < CH; ++it) {
+      const int row = (it * NT + tid) / (BK / 8);
+      const int m = m0 + row;
+      if (m < p.M) {
+        const int x = m % W, t = m / W;
+        pix[it] = m; yx[it] = ((t % H) << 16) | x;
+      } else {
+        pix[it] = -1; yx[it] = 0;
+      }
+    }
+  }
+  __device__ __forceinline__ unsigned elem_off(int it, int k, bool& ok) const {
+    const int tap = k / C, c = k - tap * C;
+    int dy, dx;
+    tap_offsets(tap, flip, dy, dx);
+    const int yy = (yx[it] >> 16) + dy, xx = (yx[it] & 0xffff) + dx;
+    ok = pix[it] >= 0 && k < Ktot && yy >= 0 && yy < H && xx >= 0 && xx < W;
+    return (unsigned)((pix[it] + dy * W + dx) * C + c);
+  }
+  __device__ __forceinline__ void gload(int k0) {
+#pragma unroll
+    for (int it = 0; it < CH; ++it) {
+      const int kc = (it * NT + tid) % (BK / 8);
+      const int k = k0 + kc * 8;
+      if constexpr (ALIGNED) {   // C % 8 == 0: the 8 elements share one tap
+        bool ok;
+        const unsigned e = elem_off(it, k, ok);
+        v[it] = __builtin_amdgcn_raw_buffer_load_b128(rs, ok ? e * 2u : kOOB, 0, 0);
+      } else {
+        unsigned h[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          bool ok;
+          const unsigned e = elem_off(it, k + j, ok);
+          h[j] = (unsigned short)__builtin_amdgcn_raw_buffer_load_b16(rs, ok ? e * 2u : kOOB, 0, 0);
+        }
+        v[it] = u32x4{h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16)};
+      }
+    }
+  }
+  __device__ __forceinline__ void sstore(unsigned short* lds) {
+#pragma unroll
+    for (int it = 0; it < CH; ++it) {
+      const int id = it * NT + tid;
+      *(u32x4*)(lds + lds_off<BK>(id / (BK / 8), id % (BK / 8))) = v[it];
+    }
+  }
+};
+
+// B operand of dX: rows are input channels c, k = (tap, o) with o contiguous: w[(tap*Cin + c)*Cout + o]
+struct StageWeightsDX {
+  static constexpr int NCH = BN * BK / 8;
+  static constexpr int CH = NCH / NT;
+  static_assert(NCH % NT == 0, "");
+  __amdgpu_buffer_rsrc_t rs;
+  int n0, Ntot, Ktot, Cin, Cout, c0, tid;
+  u32x4 v[CH];
+  __device__ __forceinline__ void init(const ConvKArgs& p, int n0_) {
+    rs = make_rsrc(p.mat, p.mat_bytes);
+    n0 = n0_; Ntot = p.N; Ktot = p.K; Cin = p.Cin; Cout = p.Cout; c0 = p.c0; tid = threadIdx.x;
+  }
+  __device__ __forceinline__ void gload(int k0) {
+#pragma unroll
+    for (int it = 0; it < CH; ++it) {
+      const int id = it * NT + tid;
+      const int n = n0 + id / (BK / 8), k = k0 + (id % (BK / 8)) * 8;
+      const int tap = k / Cout, o = k - tap * Cout;   // Cout % 8 == 0: one tap per chunk
+      const bool ok = n < Ntot && k < Ktot;
+      const unsigned e = (unsigned)((tap * Cin + c0 + n) * Cout + o);
+      v[it] = __builtin_amdgcn_raw_buffer_load_b128(rs, ok ? e * 2u : kOOB, 0, 0);
+    }
+  }
+  __device__ __forceinline__ void sstore(unsigned short* lds) {
+#pragma unroll
+    for (int it = 0; it < CH; ++it) {
+      const int id = it * NT + tid;
+      *(u32x4*)(lds + lds_off<BK>(id / (BK / 8), id % (BK / 8))) = v[it];
+    }
+  }
+};
+
+// A operand of dW: rows are (tap, c), k runs over pixels (b,y,x): x[b, y+kh-1, x+kw-1, c].
+// Threads move 8 (pixels) x 8 (channels) blocks and transpose them in registers.
+template <bool ALIGNED>
+struct StagePixelsKS {
+  static constexpr int NB = (BK / 8) * (BM / 8);
+  static constexpr int IT = (NB + NT - 1) / NT;
+  __amdgpu_buffer_rsrc_t rs;
+  int m0, Mtot, Ktot, C, H, W, tid;
+  u32x4 v[IT][8];
+  __device__ __forceinline__ void init(const ConvKArgs& p, int m0_) {
+    rs = make_rsrc(p.img, p.img_bytes);
+    m0 = m0_; Mtot = p.M; Ktot = p.K; C = p.Cimg; H = p.H; W = p.W; tid = threadIdx.x;
+  }
+  __device__ __forceinline__ void gload(int k0) {
+#pragma unroll
+    for (int it = 0; it < IT; ++it) {
+      const int id = it * NT + tid;
+      if (NB % NT == 0 || id < NB) {
+        const int rc = id % (BM / 8), kg = id / (BM / 8);
+        const int m = m0 + rc * 8;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          const int pxl = k0 + kg * 8 + j;
+          const int x = pxl % W, t = pxl / W, y = t % H;
+          if constexpr (ALIGNED) {   // C % 8 == 0: the 8 rows share one tap
+            const int tap = m / C, c = m - tap * C;
+            int dy, dx;
+            tap_offsets(tap, false, dy, dx);
+            const int yy = y + dy, xx = x + dx;
+            const bool ok = m < Mtot && pxl < Ktot && yy >= 0 && yy < H && xx >= 0 && xx < W;
+            const unsigned e = (unsigned)((pxl + dy * W + dx) * C + c);
+            v[it][j] = __builtin_amdgcn_raw_buffer_load_b128(rs, ok ? e * 2u : kOOB, 0, 0);
+          } else {
+            unsigned h[8];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+              const int mm = m + q;
+              const int tap = mm / C, c = mm - tap * C;
+              int dy, dx;
+              tap_offsets(tap, false, dy, dx);
+              const int yy = y + dy, xx = x + dx;
+              const bool ok = mm < Mtot && pxl < Ktot && yy >= 0 && yy < H && xx >= 0 && xx < W;
+              const unsigned e = (unsigned)((pxl + dy * W + dx) * C + c);
+              h[q] = (unsigned short)__builtin_amdgcn_raw_buffer_load_b16(rs, ok ? e * 2u : kOOB, 0, 0);
+            }
+            v[it][j] = u32x4{h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16)};
+          }
+        }
+      }
+    }
+  }
+  __device__ __forceinline__ void sstore(unsigned short* lds) {
+#pragma unroll
+    for (int it = 0; it < IT; ++it) {
+      const int id = it * NT + tid;
+      if (NB % NT == 0 || id < NB) {
+        const int rc = id % (BM / 8), kg = id / (BM / 8);
+        u32x4 y[8];
+        transpose8x8(v[it], y);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) *(u32x4*)(lds + lds_off<BK>(rc * 8 + e, kg)) = y[e];
+      }
+    }
+  }
+};
+
+template <bool ALIGNED_A, bool ALIGNED_B>
+__global__ void __launch_bounds__(NT) conv_fwd_kernel(ConvKArgs p) {
+  extern __shared__ __attribute__((aligned(16))) unsigned short smem[];
+  int tm, tn;
+  tile_of_block(blockIdx.x, (p.M + BM - 1) / BM, (p.N + BN - 1) / BN, tm, tn);
+  StagePixelsKC<ALIGNED_A> sa;
+  sa.init(p, tm * BM, false);
+  StageKS<BN, BK, NT, ALIGNED_B> sb;
+  sb.rs = make_rsrc(p.mat, p.mat_bytes);
+  sb.r0 = tn * BN; sb.Rtot = p.N; sb.Ktot = p.K; sb.ld = p.Cout; sb.tid = threadIdx.x;
+  StoreEpilogue epi{p.out_z, p.out_a, nullptr, p.M, p.N, p.ldc, p.act, tm * BM, tn * BN, p.vec_out != 0};
+  gemm_tile<BM, BN, BK, WM, WN>(sa, sb, 0, (p.K + BK - 1) / BK, smem, epi);
+}
+
+__global__ void __launch_bounds__(NT) conv_dx_kernel(ConvKArgs p) {
+  extern __shared__ __attribute__((aligned(16))) unsigned short smem[];
+  int tm, tn;
+  tile_of_block(blockIdx.x, (p.M + BM - 1) / BM, (p.N + BN - 1) / BN, tm, tn);
+  StagePixelsKC<true> sa;
+  sa.init(p, tm * BM, true);
+  StageWeightsDX sb;
+  sb.init(p, tn * BN);
+  StoreEpilogue epi{p.out_z, nullptr, nullptr, p.M, p.N, p.ldc, 0, tm * BM, tn * BN, p.vec_out != 0};
+  gemm_tile<BM, BN, BK, WM, WN>(sa, sb, 0, (p.K + BK - 1) / BK, smem, epi);
+}
+
+template <bool ALIGNED_A, bool ALIGNED_B>
+__global__ void __launch_bounds__(NT) conv_dw_kernel(ConvKArgs p) {
+  extern __shared__ __attribute__((aligned(16))) unsigned short smem[];
+  const int nbn = (p.N + BN - 1) / BN;
+  const int tm = blockIdx.x / nbn, tn = blockIdx.x % nbn;
+  StagePixelsKS<ALIGNED_A> sa;
+  sa.init(p, tm * BM);
+  StageKS<BN, BK, NT, ALIGNED_B> sb;
+  sb.rs = make_rsrc(p.mat, p.mat_bytes);
+  sb.r0 = tn * BN; sb.Rtot = p.N; sb.Ktot = p.K; sb.ld = p.Cout; sb.tid = (threadIdx.x + NT / 2) % NT;
+  const int KT = (p.K + BK - 1) / BK;
+  const int kt0 = blockIdx.y * p.kt_per_split;
+  const int kt1 = kt0 + p.kt_per_split < KT ? kt0 + p.kt_per_split : KT;
+  float* out = p.out_f32 + (size_t)blockIdx.y * p.M * p.N;   // split s writes partial s (gridDim.y == 1: the result)
+  StoreEpilogue epi{nullptr, nullptr, out, p.M, p.N, p.ldc, 0, tm * BM, tn * BN, p.vec_out != 0};
+  gemm_tile<BM, BN, BK, WM, WN>(sa, sb, kt0, kt1, smem, epi);
+}
+
+__global__ void __launch_bounds__(256) reduce_partials_kernel(const float* __restrict__ part, float* __restrict__ g, size_t n, int splits) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n) return;
+  float acc = 0.f;
+  for (int s = 0; s < splits; ++s) acc += part[(size_t)s * n + i];
+  g[i] = acc;
+}
+
+constexpr size_t kLds = 2ull * (BM + BN) * BK * sizeof(unsigned short);
+
+template <class K>
+hipError_t set_lds(K kern) {
+  return hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLds);
+}
+
+int dw_splits(const ConvDesc& c) {
+  const long M = 9L * c.Cin, N = c.Cout, K = (long)c.B * c.H * c.W;
+  const long tiles = ((M + BM - 1) / BM) * ((N + BN - 1) / BN);
+  const long KT = (K + BK - 1) / BK;
+  long s = (512 + tiles - 1) / tiles;   // aim at about two workgroups per CU
+  if (s > KT) s = KT;
+  if (s > 64) s = 64;
+  if (s < 1) s = 1;
+  return (int)s;
+}
+
+bool fits32(const ConvDesc& c) {
+  const unsigned long long img = (unsigned long long)c.B * c.H * c.W * (c.Cin > c.Cout ? c.Cin : c.Cout) * 2;
+  return img < 0x7fffffffull && c.B > 0 && c.H > 0 && c.W > 0 && c.H < 32768 && c.W < 32768 && c.Cin > 0 && c.Cout > 0;
+}
+
+}  // namespace
+
+size_t conv_grad_weight_scratch_bytes(const ConvDesc& c) {
+  const int s = dw_splits(c);
+  return s > 1 ? (size_t)s * 9 * c.Cin * c.Cout * sizeof(float) : 0;
+}
+
+hipError_t launch_conv_fwd(const ConvDesc& c, bool bf16, const void* x, const void* w, void* out_z, void* out_a, int act, hipStream_t s) {
+  if (!bf16) return hipErrorNotSupported;
+  if (!fits32(c) || !x || !w) return hipErrorInvalidValue;
+  ConvKArgs p{};
+  p.img = (const unsigned short*)x; p.mat = (const unsigned short*)w;
+  p.out_z = (unsigned short*)out_z; p.out_a = (unsigned short*)out_a;
+  p.B = c.B; p.H = c.H; p.W = c.W; p.Cimg = c.Cin; p.Cin = c.Cin; p.Cout = c.Cout;
+  p.M = c.B * c.H * c.W; p.N = c.Cout; p.K = 9 * c.Cin;
+  p.ldc = c.Cout; p.act = act;
+  p.img_bytes = (unsigned)((size_t)p.M * c.Cin * 2); p.mat_bytes = (unsigned)((size_t)p.K * c.Cout * 2);
+  p.vec_out = (c.Cout % 4 == 0) && ((uintptr_t)out_z % 8 == 0) && ((uintptr_t)out_a % 8 == 0);
+  const bool al_a = c.Cin % 8 == 0 && (uintptr_t)x % 16 == 0, al_b = c.Cout % 8 == 0 && (uintptr_t)w % 16 == 0;
+  const int nb = ((p.M + BM - 1) / BM) * ((p.N + BN - 1) / BN);
+  static bool attr = false;
+  if (!attr) {
+    hipError_t e = set_lds(conv_fwd_kernel<true, true>);
+    if (e == hipSuccess) e = set_lds(conv_fwd_kernel<false, true>);
+    if (e == hipSuccess) e = set_lds(conv_fwd_kernel<true, false>);
+    if (e == hipSuccess) e = set_lds(conv_fwd_kernel<false, false>);
+    if (e != hipSuccess) return e;
+    attr = true;
+  }
+  if (al_a && al_b) hipLaunchKernelGGL((conv_fwd_kernel<true, true>), dim3(nb), dim3(NT), kLds, s, p);
+  else if (!al_a && al_b) hipLaunchKernelGGL((conv_fwd_kernel<false, true>), dim3(nb), dim3(NT), kLds, s, p);
+  else if (al_a && !al_b) hipLaunchKernelGGL((conv_fwd_kernel<true, false>), dim3(nb), dim3(NT), kLds, s, p);
+  else hipLaunchKernelGGL((conv_fwd_kernel<false, false>), dim3(nb), dim3(NT), kLds, s, p);
+  return hipGetLastError();
+}
+
+hipError_t launch_conv_grad_act(const ConvDesc& c, bool bf16, const void* dy, const void* w, void* dx, int c0, int c1, hipStream_t s) {
+  if (!bf16) return hipErrorNotSupported;
+  if (!fits32(c) || !dy || !w || !dx || c0 < 0 || c1 > c.Cin || c0 >= c1) return hipErrorInvalidValue;
+  // 16-byte chunks of dy and of w along the output channels
+  if (c.Cout % 8 != 0 || (uintptr_t)dy % 16 != 0 || (uintptr_t)w % 16 != 0) return hipErrorNotSupported;
+  ConvKArgs p{};
+  p.img = (const unsigned short*)dy; p.mat = (const unsigned short*)w;
+  p.out_z = (unsigned short*)dx + c0;
+  p.B = c.B; p.H = c.H; p.W = c.W; p.Cimg = c.Cout; p.Cin = c.Cin; p.Cout = c.Cout; p.c0 = c0;
+  p.M = c.B * c.H * c.W; p.N = c1 - c0; p.K = 9 * c.Cout;
+  p.ldc = c.Cin; p.act = 0;
+  p.img_bytes = (unsigned)((size_t)p.M * c.Cout * 2); p.mat_bytes = (unsigned)((size_t)9 * c.Cin * c.Cout * 2);
+  p.vec_out = (p.N % 4 == 0) && (c.Cin % 4 == 0) && ((uintptr_t)p.out_z % 8 == 0);
+  const int nb = ((p.M + BM - 1) / BM) * ((p.N + BN - 1) / BN);
+  static bool attr = false;
+  if (!attr) {
+    hipError_t e = set_lds(conv_dx_kernel);
+    if (e != hipSuccess) return e;
+    attr = true;
+  }
+  hipLaunchKernelGGL(conv_dx_kernel, dim3(nb), dim3(NT), kLds, s, p);
+  return hipGetLastError();
+}
+
+hipError_t launch_conv_grad_weight(const ConvDesc& c, bool bf16, const void* x, const void* dy, float* g, float* partial, hipStream_t s) {
+  if (!bf16) return hipErrorNotSupported;
+  if (!fits32(c) || !x || !dy || !g) return hipErrorInvalidValue;
+  const int splits = dw_splits(c);
+  if (splits > 1 && !partial) return hipErrorInvalidValue;
+  ConvKArgs p{};
+  p.img = (const unsigned short*)x; p.mat = (const unsigned short*)dy;
+  p.out_f32 = splits > 1 ? partial : g;
+  p.B = c.B; p.H = c.H; p.W = c.W; p.Cimg = c.Cin; p.Cin = c.Cin; p.Cout = c.Cout;
+  p.M = 9 * c.Cin; p.N = c.Cout; p.K = c.B * c.H * c.W;
+  p.ldc = c.Cout; p.act = 0;
+  p.img_bytes = (unsigned)((size_t)p.K * c.Cin * 2); p.mat_bytes = (unsigned)((size_t)p.K * c.Cout * 2);
+  const int KT = (p.K + BK - 1) / BK;
+  p.kt_per_split = (KT + splits - 1) / splits;
+  p.vec_out = (c.Cout % 4 == 0) && ((uintptr_t)p.out_f32 % 16 == 0) && (((size_t)p.M * p.N) % 4 == 0);
+  const bool al_a = c.Cin % 8 == 0 && (uintptr_t)x % 16 == 0, al_b = c.Cout % 8 == 0 && (uintptr_t)dy % 16 == 0;
+  const int nb = ((p.M + BM - 1) / BM) * ((p.N + BN - 1) / BN);
+  static bool attr = false;
+  if (!attr) {
+    hipError_t e = set_lds(conv_dw_kernel<true, true>);
+    if (e == hipSuccess) e = set_lds(conv_dw_kernel<false, true>);
+    if (e == hipSuccess) e = set_lds(conv_dw_kernel<true, false>);
+    if (e == hipSuccess) e = set_lds(conv_dw_kernel<false, false>);
+    if (e != hipSuccess) return e;
+    attr = true;
+  }
+  const dim3 grid(nb, splits);
+  if (al_a && al_b) hipLaunchKernelGGL((conv_dw_kernel<true, true>), grid, dim3(NT), kLds, s, p);
+  else if (!al_a && al_b) hipLaunchKernelGGL((conv_dw_kernel<false, true>), grid, dim3(NT), kLds, s, p);
+  else if (al_a && !al_b) hipLaunchKernelGGL((conv_dw_kernel<true, false>), grid, dim3(NT), kLds, s, p);
+  else hipLaunchKernelGGL((conv_dw_kernel<false, false>), grid, dim3(NT), kLds, s, p);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess || splits == 1) return e;
+  const size_t n = (size_t)p.M * p.N;
+  hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, (const float*)partial, g, n, splits);
+  return hipGetLastError();
+}
+
 }  // namespace lp

@@ -225,6 +225,13 @@ __device__ __forceinline__ void gemm_tile(SA& sa, SB& sb, int kt0, int kt1, unsi
   __syncthreads();
   if (kt0 < kt1) read_frags(smem, smem + A_ELEMS, 0, fa[0], fb[0]);
 
+  // scheduling pattern of one substep: one LDS fragment read after each of the first MFMAs
+  constexpr int NREAD = TM + TN, NMFMA = TM * TN, NPAIR = NREAD < NMFMA ? NREAD : NMFMA;
+  auto interleave_reads = [&]() {
+#pragma unroll
+    for (int q = 0; q < NPAIR; ++q) { __builtin_amdgcn_sched_group_barrier(0x008, 1, 0); __builtin_amdgcn_sched_group_barrier(0x100, 1, 0); }
+    if constexpr (NREAD > NPAIR) __builtin_amdgcn_sched_group_barrier(0x100, NREAD - NPAIR, 0);
+  };
   auto step = [&](int kt, auto more_tag) {
     constexpr bool more = decltype(more_tag)::value;
     const int cur = (kt - kt0) & 1;
@@ -237,15 +244,13 @@ __device__ __forceinline__ void gemm_tile(SA& sa, SB& sb, int kt0, int kt1, unsi
     }
     read_frags(As, Bs, 1, fa[1], fb[1]);
     mfmas(fa[0], fb[0]);
-#pragma unroll
-    for (int q = 0; q < TM + TN; ++q) { __builtin_amdgcn_sched_group_barrier(0x008, 1, 0); __builtin_amdgcn_sched_group_barrier(0x100, 1, 0); }
-    __builtin_amdgcn_sched_group_barrier(0x008, TM * TN - (TM + TN), 0);
+    interleave_reads();
+    if constexpr (NMFMA > NPAIR) __builtin_amdgcn_sched_group_barrier(0x008, NMFMA - NPAIR, 0);
     __builtin_amdgcn_sched_barrier(0);
     read_frags(As, Bs, 2, fa[0], fb[0]);
     mfmas(fa[1], fb[1]);
-#pragma unroll
-    for (int q = 0; q < TM + TN; ++q) { __builtin_amdgcn_sched_group_barrier(0x008, 1, 0); __builtin_amdgcn_sched_group_barrier(0x100, 1, 0); }
-    __builtin_amdgcn_sched_group_barrier(0x008, TM * TN - (TM + TN), 0);
+    interleave_reads();
+    if constexpr (NMFMA > NPAIR) __builtin_amdgcn_sched_group_barrier(0x008, NMFMA - NPAIR, 0);
     __builtin_amdgcn_sched_barrier(0);
     read_frags(As, Bs, 3, fa[1], fb[1]);
     mfmas(fa[0], fb[0]);
@@ -253,8 +258,7 @@ __device__ __forceinline__ void gemm_tile(SA& sa, SB& sb, int kt0, int kt1, unsi
       sa.sstore(nxt);
       sb.sstore(nxt + A_ELEMS);
     }
-#pragma unroll
-    for (int q = 0; q < TM + TN; ++q) { __builtin_amdgcn_sched_group_barrier(0x008, 1, 0); __builtin_amdgcn_sched_group_barrier(0x100, 1, 0); }
+    interleave_reads();
     if constexpr (more) {
 #pragma unroll
       for (int q = 0; q < TM * TN - (TM + TN); ++q) { __builtin_amdgcn_sched_group_barrier(0x008, 1, 0); __builtin_amdgcn_sched_group_barrier(0x200, 2, 0); }

@@ -187,6 +187,13 @@ __device__ __forceinline__ void gemm_tile_dl(const OA& oa, const OB& ob, int KT,
     ob.issue(t * BK, st + A_ELEMS, wave);
   };
 
+  // scheduling pattern of one substep: one LDS fragment read after each of the first MFMAs
+  constexpr int NREAD = TM + TN, NMFMA = TM * TN, NPAIR = NREAD < NMFMA ? NREAD : NMFMA;
+  auto interleave_reads = [&]() {
+#pragma unroll
+    for (int q = 0; q < NPAIR; ++q) { __builtin_amdgcn_sched_group_barrier(0x008, 1, 0); __builtin_amdgcn_sched_group_barrier(0x100, 1, 0); }
+  };
+
 #pragma unroll
   for (int t = 0; t < NSTAGE; ++t) issue(t);
   wait_vmcnt<(NSTAGE - 1) * LOADS>();
@@ -198,16 +205,14 @@ __device__ __forceinline__ void gemm_tile_dl(const OA& oa, const OB& ob, int KT,
     const unsigned short* nxt = smem + ((t + 1) % NSTAGE) * STAGE;
     read_frags(cur, 1, fa[1], fb[1]);
     mfmas(fa[0], fb[0]);
-#pragma unroll
-    for (int q = 0; q < TM + TN; ++q) { __builtin_amdgcn_sched_group_barrier(0x008, 1, 0); __builtin_amdgcn_sched_group_barrier(0x100, 1, 0); }
+    interleave_reads();
     __builtin_amdgcn_sched_barrier(0);
     wait_vmcnt<(NSTAGE - 2) * LOADS>();   // this wave's part of tile t+1 has landed
     __syncthreads();                      // ... and everyone's; nobody reads tile t's stage any more
     issue(t + NSTAGE);
     read_frags(nxt, 0, fa[0], fb[0]);
     mfmas(fa[1], fb[1]);
-#pragma unroll
-    for (int q = 0; q < TM + TN; ++q) { __builtin_amdgcn_sched_group_barrier(0x008, 1, 0); __builtin_amdgcn_sched_group_barrier(0x100, 1, 0); }
+    interleave_reads();
     __builtin_amdgcn_sched_barrier(0);
   }
   wait_vmcnt<0>();   // the trailing (empty) tiles still write LDS

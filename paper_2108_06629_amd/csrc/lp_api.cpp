@@ -270,7 +270,9 @@ int lp_create(const lp_layer_desc* layers, int L, int batch, int dtype, int loss
       if (i > 0 && prev_out_feat != d.in) return bad(LP_ERR_LAYER, "input width differs from the previous layer's output");
       prev_conv = false;
     } else {
+      if (dtype != LP_BF16) return bad(LP_ERR_DTYPE, "convolution layers need an LP_BF16 context");
       if (d.H < 1 || d.W < 1) return bad(LP_ERR_SHAPE, "conv needs H, W >= 1");
+      if (i > 0 && d.out % 8 != 0) return bad(LP_ERR_SHAPE, "a conv layer other than the first needs out % 8 == 0 (dX reads 16-byte chunks)");
       if (d.pool != 0 && d.pool != 2) return bad(LP_ERR_SHAPE, "pool must be 0 or 2");
       if (d.pool == 2 && (d.H % 2 || d.W % 2)) return bad(LP_ERR_SHAPE, "pool needs even H and W");
       if (i == L - 1 && d.pool) return bad(LP_ERR_SHAPE, "the last layer cannot pool");

@@ -1,0 +1,195 @@
+"""Parity of the convolution tasks (implicit GEMM) and of CNN training runs against the CPU oracle.
+Needs a real MI355X.  Tolerances as in test_gpu_parity.py."""
+import numpy as np
+import pytest
+import torch
+
+import lp_workloads as WL
+import paper_2108_06629_amd as lp
+from oracle import layerpipe_oracle as O
+from test_gpu_parity import DEV, dev, host, relerr, frob
+
+pytestmark = pytest.mark.gpu
+
+
+def conv_net(B, H, W, cin, cout, pool=0, act="relu"):
+    p = 2 if pool else 1
+    layers = (WL.Layer(WL.CONV3X3, cin, cout, act, H=H, W=W, pool=pool),
+              WL.Layer(WL.LINEAR, (H // p) * (W // p) * cout, 8, WL.IDENTITY))
+    net = lp.Network(layers, B, "bf16", WL.SOFTMAX_CE, 0.01, (0, 0))
+    rng = np.random.default_rng(B * 1000 + cin * 10 + cout)
+    Wt = [(rng.standard_normal(l.weight_shape) * np.sqrt(2.0 / l.fan_in)).astype(np.float32) for l in layers]
+    net.set_weights(Wt)
+    return net, Wt, rng
+
+
+# (B, H, W, C_in, C_out): first-layer shape (3 channels: unaligned gather), aligned shapes spanning
+# several 128x64 tiles and K tiles, ragged pixel counts, the smallest image
+CONV_SHAPES = [(2, 8, 8, 3, 16), (3, 6, 10, 8, 24), (2, 16, 16, 64, 64), (5, 8, 8, 16, 136), (1, 2, 2, 8, 8), (4, 32, 32, 3, 64)]
+
+
+@pytest.mark.parametrize("shape", CONV_SHAPES)
+def test_conv_forward(shape):
+    B, H, W, ci, co = shape
+    net, Wt, rng = conv_net(B, H, W, ci, co)
+    x = rng.standard_normal((B, H, W, ci)).astype(np.float32)
+    Z = torch.empty(B, H, W, co, dtype=torch.bfloat16, device=DEV)
+    A = torch.empty_like(Z)
+    lp.lp_forward(net.ctx, 1, dev(x, torch.bfloat16), Z, A, net.streams[0])
+    lp.lp_sync(net.ctx)
+    ref = O.store(O.conv3x3(O.round_bf16(x), O.round_bf16(Wt[0])), "bf16")
+    assert relerr(host(Z), ref) <= 2e-2
+    assert np.array_equal(host(A), O.store(O.activation(host(Z), "relu"), "bf16"))
+    net.close()
+
+
+@pytest.mark.parametrize("shape", [s for s in CONV_SHAPES if s[4] % 8 == 0])
+def test_conv_grad_act_and_channel_partition(shape):
+    B, H, W, ci, co = shape
+    net, Wt, rng = conv_net(B, H, W, ci, co)
+    dy = (rng.standard_normal((B, H, W, co)) / np.sqrt(9 * co)).astype(np.float32)
+    dyd = dev(dy, torch.bfloat16)
+    dX = torch.full((B, H, W, ci), float("nan"), dtype=torch.bfloat16, device=DEV)
+    lp.lp_grad_act(net.ctx, 1, dyd, dX, 0, ci, net.streams[0])
+    lp.lp_sync(net.ctx)
+    ref = O.store(O.grad_act(O.round_bf16(dy), O.round_bf16(Wt[0])), "bf16")
+    assert relerr(host(dX), ref) <= 2e-2
+    if ci >= 2:
+        cut = max(1, ci // 3)
+        parts = torch.full((B, H, W, ci), float("nan"), dtype=torch.bfloat16, device=DEV)
+        lp.lp_grad_act(net.ctx, 1, dyd, parts, 0, cut, net.streams[0])
+        lp.lp_grad_act(net.ctx, 1, dyd, parts, cut, ci, net.streams[1])
+        lp.lp_sync(net.ctx)
+        assert torch.equal(parts.view(torch.int16), dX.view(torch.int16))
+    net.close()
+
+
+@pytest.mark.parametrize("shape", CONV_SHAPES)
+def test_conv_grad_weight(shape):
+    B, H, W, ci, co = shape
+    net, Wt, rng = conv_net(B, H, W, ci, co)
+    x = rng.standard_normal((B, H, W, ci)).astype(np.float32)
+    dy = (rng.standard_normal((B, H, W, co)) / (B * H * W)).astype(np.float32)
+    G = torch.full((3, 3, ci, co), float("nan"), dtype=torch.float32, device=DEV)
+    lp.lp_grad_weight(net.ctx, 1, dev(x, torch.bfloat16), dev(dy, torch.bfloat16), G, net.streams[0])
+    lp.lp_sync(net.ctx)
+    ref = O.grad_weight(O.round_bf16(x), O.round_bf16(dy))
+    assert relerr(host(G), ref) <= 2e-4
+    net.close()
+
+
+def test_pool_forward_and_routing_with_ties():
+    B, H, W, C = 2, 4, 6, 8
+    net, Wt, rng = conv_net(B, H, W, 8, C, pool=2)
+    # quantised values make ties between window entries frequent
+    z = (rng.integers(-3, 4, size=(B, H, W, C)) * 0.5).astype(np.float32)
+    zd = dev(z, torch.bfloat16)
+    # forward through the library: use lp_forward's pool path by checking relu_pool against the oracle on a real conv output
+    x = rng.standard_normal((B, H, W, 8)).astype(np.float32)
+    Z = torch.empty(B, H, W, C, dtype=torch.bfloat16, device=DEV)
+    A = torch.empty(B, H // 2, W // 2, C, dtype=torch.bfloat16, device=DEV)
+    lp.lp_forward(net.ctx, 1, dev(x, torch.bfloat16), Z, A, net.streams[0])
+    lp.lp_sync(net.ctx)
+    pooled, _ = O.maxpool2x2(O.activation(host(Z), "relu"))
+    assert np.array_equal(host(A), pooled)
+    # backward routing on the tie-rich tensor: exact
+    da = rng.standard_normal((B, H // 2, W // 2, C)).astype(np.float32)
+    dad = dev(da, torch.bfloat16)
+    dY = torch.full((B, H, W, C), float("nan"), dtype=torch.bfloat16, device=DEV)
+    lp.lp_act_grad(net.ctx, 1, dad, zd, dY, net.streams[0])
+    lp.lp_sync(net.ctx)
+    a_full = O.activation(host(zd), "relu")
+    _, idx = O.maxpool2x2(a_full)
+    ref = O.store(O.act_grad(host(dad), host(zd), "relu", idx), "bf16")
+    assert np.array_equal(host(dY), ref)
+    net.close()
+
+
+def run_cnn(wl, steps):
+    W0 = WL.init_weights(wl)
+    net = lp.Network(wl.layers, wl.batch, wl.dtype, wl.loss, wl.lr, wl.delays)
+    net.set_weights(W0)
+    ora = O.DelayedGradientTrainer(wl.layers, W0, wl.delays, wl.lr, wl.loss, "bf16")
+    exact = O.DelayedGradientTrainer(wl.layers, W0, wl.delays, wl.lr, wl.loss, "f64")
+    G_hist = [dict() for _ in range(wl.L)]
+    for n in range(1, steps + 1):
+        x, t = WL.batch_input(wl, n), WL.batch_target(wl, n)
+        W_before = [net.get_weights(l) for l in range(1, wl.L + 1)]
+        loss = net.step(x, t)
+        ref = ora.step(x, t)
+        exact.step(x, t)
+        assert abs(loss - ref) <= 2e-2 * max(abs(ref), 1e-3), (n, loss, ref)
+        zl = net.tensor_np(wl.L, lp.LP_T_Z).reshape(ora.trace["Z"][-1].shape)
+        assert relerr(zl, ora.trace["Z"][-1]) <= 2e-2
+        # task by task on the tensors the GPU tasks actually read
+        Wk = [O.round_bf16(w) for w in W_before]
+        A = [O.round_bf16(x)]
+        for l in range(1, wl.L + 1):
+            ly = wl.layers[l - 1]
+            a_in = A[-1]
+            if ly.kind == WL.LINEAR and a_in.ndim == 4:
+                a_in = a_in.reshape(a_in.shape[0], -1)
+            z_ref = O.store(O.forward_product(a_in, Wk[l - 1]), "bf16")
+            z_gpu = net.tensor_np(l, lp.LP_T_Z)
+            if z_gpu is not None:
+                z_gpu = z_gpu.reshape(z_ref.shape)
+                assert relerr(z_gpu, z_ref) <= 2e-2, ("F/Z", l, n)
+            if l < wl.L:
+                a_gpu = net.tensor_np(l, lp.LP_T_A).reshape(ly.out_shape(wl.batch))
+                a_ref = O.store(O.activation(z_gpu if z_gpu is not None else z_ref, ly.act), "bf16")
+                if ly.pool == 2:
+                    a_ref, _ = O.maxpool2x2(a_ref)
+                    assert np.array_equal(a_gpu, a_ref), ("pool", l, n)      # computed from the stored Z: exact
+                else:
+                    assert relerr(a_gpu, a_ref) <= 2e-2, ("F/A", l, n)
+                A.append(a_gpu)
+        for l in range(wl.L, 0, -1):
+            ly = wl.layers[l - 1]
+            dy = net.tensor_np(l, lp.LP_T_DY).reshape(ly.z_shape(wl.batch))
+            a_in = A[l - 1]
+            if ly.kind == WL.LINEAR and a_in.ndim == 4:
+                a_in = a_in.reshape(a_in.shape[0], -1)
+            g = net.tensor_np(l, lp.LP_T_G_LAST).reshape(Wk[l - 1].shape)
+            assert relerr(g, O.grad_weight(a_in, dy)) <= 2e-4, ("dW", l, n)
+            G_hist[l - 1][n] = g
+            floor = frob(ora.trace["G"][l - 1], exact.trace["G"][l - 1])
+            assert frob(g, ora.trace["G"][l - 1]) <= max(2e-2, floor), ("G free-running", l, n)
+            if l > 1:
+                prev = wl.layers[l - 2]
+                da = net.tensor_np(l - 1, lp.LP_T_DA).reshape(prev.out_shape(wl.batch))
+                da_ref = O.store(O.grad_act(dy, Wk[l - 1]), "bf16").reshape(da.shape)
+                assert relerr(da, da_ref) <= 2e-2, ("dX", l, n)
+                dyp = net.tensor_np(l - 1, lp.LP_T_DY).reshape(prev.z_shape(wl.batch))
+                if prev.pool == 2:
+                    zp = net.tensor_np(l - 1, lp.LP_T_Z).reshape(prev.z_shape(wl.batch))
+                    _, idx = O.maxpool2x2(O.activation(zp, prev.act))
+                    ref_dy = O.store(O.act_grad(da, zp, prev.act, idx), "bf16")
+                else:
+                    ref_dy = O.store(O.act_grad(da, A[l - 1], prev.act), "bf16")
+                assert np.array_equal(dyp, ref_dy), ("Hadamard/pool routing", l - 1, n)
+            src = n - wl.delays[l - 1]
+            w_new = net.get_weights(l)
+            if src < 1:
+                assert np.array_equal(w_new, W_before[l - 1])
+            else:
+                upd = O.store(O.delayed_sgd(W_before[l - 1].astype(np.float64), G_hist[l - 1].pop(src), float(np.float32(wl.lr))), "f32")
+                assert np.max(np.abs(w_new - upd)) <= 2.0 ** -22 * np.max(np.abs(upd)), ("update", l, n)
+            assert relerr(w_new, ora.W[l - 1]) <= 2e-2, ("W free-running", l, n)
+    net.close()
+
+
+def test_trajectory_cnn_small_unaligned_first_layer():
+    run_cnn(WL.vgg_small(batch=4, hw=8, chans=(8, 8, 16, 16)), 8)
+
+
+def test_trajectory_cnn_vgg_channels_reduced_batch():
+    wl = WL.vgg_small(batch=8, hw=32)      # the full channel plan 64,64,128,128,256,256 and 32x32 images, 8 of the 128 samples
+    assert [l.d_out for l in wl.layers] == [64, 64, 128, 128, 256, 256, 10] and wl.delays == (12, 10, 8, 6, 4, 2, 0)
+    run_cnn(wl, 3)
+
+
+def test_conv_needs_bf16_context():
+    wl = WL.vgg_small(batch=2, hw=8, chans=(8, 8))
+    with pytest.raises(lp.LpError) as ei:
+        lp.lp_create(lp.make_descs(wl.layers, wl.delays), wl.L, 2, lp.LP_F32, lp.LP_LOSS_SOFTMAX_CE, 0.1)
+    assert ei.value.status == 3
