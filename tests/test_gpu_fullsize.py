@@ -1,0 +1,112 @@
+"""Parity at the full sizes of the benchmark workloads, in the launch configuration bench.py times
+(lp_step on three streams).  The three mid-size workloads run whole steps against the oracle; the
+largest one (16 x 4096<->16384, 8192 tokens) is checked on sampled rows and columns of every task's
+output, each recomputed by the oracle operators from the tensors that task read on the GPU.
+Needs a real MI355X."""
+import numpy as np
+import pytest
+import torch
+
+import lp_workloads as WL
+import paper_2108_06629_amd as lp
+from oracle import layerpipe_oracle as O
+from test_gpu_parity import relerr, run_trajectory
+from test_gpu_conv import run_cnn
+
+pytestmark = pytest.mark.gpu
+
+
+def test_mlp_4096_full_size_steps():
+    wl = WL.mlp_4096()
+    assert wl.batch == 256 and wl.L == 8 and wl.layers[0].d_in == 4096 and wl.layers[-1].d_out == 1000
+    run_trajectory(wl, 3)
+
+
+def test_mlp_imbalanced_full_size_step():
+    wl = WL.mlp_imbalanced()
+    assert wl.batch == 1024 and wl.L == 12
+    run_trajectory(wl, 2)
+
+
+def test_vgg_small_full_size_steps():
+    wl = WL.vgg_small()
+    assert wl.batch == 128 and wl.gemm_dims(0) == (131072, 64, 27)
+    run_cnn(wl, 2)
+
+
+def f64(t):
+    return t.to(torch.float32).cpu().numpy().astype(np.float64)
+
+
+def test_ffn_stack_full_size_sampled():
+    wl = WL.ffn_stack()
+    assert wl.batch == 8192 and wl.L == 16 and wl.n_params == 16 * 4096 * 16384
+    rng = np.random.default_rng(7)
+    W0 = WL.init_weights(wl)
+    net = lp.Network(wl.layers, wl.batch, wl.dtype, wl.loss, wl.lr, wl.delays)
+    net.set_weights(W0)
+    x, t = WL.batch_input(wl, 1), WL.batch_target(wl, 1)
+    loss = net.step(x, t)
+    B, L = wl.batch, wl.L
+    rows = np.sort(rng.choice(B, 12, replace=False))
+    rows[0], rows[-1] = 0, B - 1                                   # first and last tile rows
+    rt = torch.from_numpy(rows).to("cuda:0")
+
+    def view(l, which, width):
+        tns = net.tensor(l, which)
+        return None if tns is None else tns.view(B, width)
+
+    A = [net.to_device(x)] + [view(l, lp.LP_T_A, wl.layers[l - 1].d_out) for l in range(1, L)]
+    for l in range(1, L + 1):
+        ly = wl.layers[l - 1]
+        cols = np.sort(rng.choice(ly.d_out, 48, replace=False)); cols[0], cols[-1] = 0, ly.d_out - 1
+        kin = np.sort(rng.choice(ly.d_in, 48, replace=False)); kin[0], kin[-1] = 0, ly.d_in - 1
+        ct, kt = torch.from_numpy(cols).to("cuda:0"), torch.from_numpy(kin).to("cuda:0")
+        Wk = O.round_bf16(W0[l - 1])
+        a_rows = f64(A[l - 1][rt])                                                   # [12, d_in]
+        # F (Eq. 1, Eq. 2)
+        z_ref = O.store(a_rows @ Wk[:, cols], "bf16")
+        zg = view(l, lp.LP_T_Z, ly.d_out)
+        if zg is not None:
+            z_gpu = f64(zg[rt][:, ct])
+            assert relerr(z_gpu, z_ref) <= 2e-2, ("F/Z", l)
+        else:
+            z_gpu = z_ref
+        if l < L:
+            a_gpu = f64(A[l][rt][:, ct])
+            assert relerr(a_gpu, O.store(O.activation(z_gpu, ly.act), "bf16")) <= 2e-2, ("F/A", l)
+        dY = view(l, lp.LP_T_DY, ly.d_out)
+        # dW (Eq. 5): G[kin, cols] = A_{l-1}[:, kin]^T . dY[:, cols], full reduction over the 8192 tokens
+        g_ref = f64(A[l - 1][:, kt]).T @ f64(dY[:, ct])
+        g_gpu = net.tensor(l, lp.LP_T_G_LAST).view(ly.d_in, ly.d_out)[kt][:, ct].cpu().numpy().astype(np.float64)
+        assert relerr(g_gpu, g_ref) <= 2e-4, ("dW", l)
+        if l > 1:
+            prev = wl.layers[l - 2]
+            # dX (Eq. 4): dA_{l-1}[rows, kin] = dY[rows] . W[kin, :]^T
+            da_ref = O.store(f64(dY[rt]) @ Wk[kin, :].T, "bf16")
+            dAg = view(l - 1, lp.LP_T_DA, prev.d_out)
+            assert relerr(f64(dAg[rt][:, kt]), da_ref) <= 2e-2, ("dX", l)
+            # the moved Hadamard (Eq. 3) on whole sampled rows
+            stash = view(l - 1, lp.LP_T_Z, prev.d_out)
+            stash = A[l - 1] if stash is None else stash
+            dy_prev_ref = O.store(O.act_grad(f64(dAg[rt]), f64(stash[rt]), prev.act), "bf16")
+            dy_prev = f64(view(l - 1, lp.LP_T_DY, prev.d_out)[rt])
+            if prev.act == WL.GELU:
+                assert relerr(dy_prev, dy_prev_ref) <= 2.0 ** -7, ("Hadamard", l - 1)
+            else:
+                assert np.array_equal(dy_prev, dy_prev_ref), ("Hadamard", l - 1)
+        # Eq. 6 at n = 1: only layers with d_l = 0 move; the others are bit-identical to their initial value
+        w_gpu = net.tensor(l, lp.LP_T_MASTER_W).view(ly.d_in, ly.d_out)[kt][:, ct].cpu().numpy()
+        w0 = W0[l - 1][np.ix_(kin, cols)]
+        if wl.delays[l - 1] == 0:
+            ref = O.store(O.delayed_sgd(w0.astype(np.float64), g_gpu, float(np.float32(wl.lr))), "f32")
+            assert np.max(np.abs(w_gpu - ref)) <= 2.0 ** -22 * np.max(np.abs(ref)), ("update", l)
+            assert not np.array_equal(w_gpu, w0)
+        else:
+            assert np.array_equal(w_gpu, w0), ("frozen", l)
+    # loss and delta of the output layer on the whole tensor
+    zL = f64(view(L, lp.LP_T_Z, wl.layers[-1].d_out))
+    loss_ref, dy_ref = O.mse(zL, O.round_bf16(t))
+    assert abs(loss - loss_ref) <= 1e-5 * loss_ref
+    assert relerr(f64(view(L, lp.LP_T_DY, wl.layers[-1].d_out)), O.store(dy_ref, "bf16")) <= 2.0 ** -7
+    net.close()
