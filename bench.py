@@ -128,6 +128,8 @@ def main():
     ap.add_argument("--streams", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-others", action="store_true", help="skip the short runs of the other workloads")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="only run five 1 GiB device-to-device copy kernels (reference for the FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (one MI355X per box, no collectives); --gpus %d is not supported" % args.gpus,
@@ -139,6 +141,15 @@ def main():
     import paper_2108_06629_amd as lp
     lp.load_library()          # fails loudly if the HIP library is not built
     assert torch.cuda.is_available(), "bench.py needs a GPU"
+
+    if args.calibrate_copy:
+        src = torch.empty(1 << 29, dtype=torch.bfloat16, device="cuda:0").normal_()
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy": {"bytes_read": src.numel() * 2, "bytes_written": src.numel() * 2, "copies": 5}}))
+        return
 
     wl = WL.CONFIGS[args.workload]()
     work = task_work(wl)

@@ -208,7 +208,7 @@ template <bool ALIGNED_A, bool ALIGNED_B>
 __global__ void __launch_bounds__(NT) conv_fwd_kernel(ConvKArgs p) {
   extern __shared__ __attribute__((aligned(16))) unsigned short smem[];
   int tm, tn;
-  tile_of_block(blockIdx.x, (p.M + BM - 1) / BM, (p.N + BN - 1) / BN, tm, tn);
+  tile_of_block<false>(blockIdx.x, (p.M + BM - 1) / BM, (p.N + BN - 1) / BN, tm, tn);
   StagePixelsKC<ALIGNED_A> sa;
   sa.init(p, tm * BM, false);
   StageKS<BN, BK, NT, ALIGNED_B> sb;
@@ -221,7 +221,7 @@ __global__ void __launch_bounds__(NT) conv_fwd_kernel(ConvKArgs p) {
 __global__ void __launch_bounds__(NT) conv_dx_kernel(ConvKArgs p) {
   extern __shared__ __attribute__((aligned(16))) unsigned short smem[];
   int tm, tn;
-  tile_of_block(blockIdx.x, (p.M + BM - 1) / BM, (p.N + BN - 1) / BN, tm, tn);
+  tile_of_block<false>(blockIdx.x, (p.M + BM - 1) / BM, (p.N + BN - 1) / BN, tm, tn);
   StagePixelsKC<true> sa;
   sa.init(p, tm * BM, true);
   StageWeightsDX sb;

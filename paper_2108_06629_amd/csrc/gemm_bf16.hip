@@ -42,7 +42,7 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_bf16_kernel(GemmKArgs p) {
   constexpr int NT = WM * WN * 64;
   extern __shared__ __attribute__((aligned(16))) unsigned short smem[];
   int tm, tn;
-  tile_of_block(blockIdx.x, (p.M + BM - 1) / BM, (p.N + BN - 1) / BN, tm, tn);
+  tile_of_block<(BM == 256 && BN == 256)>(blockIdx.x, (p.M + BM - 1) / BM, (p.N + BN - 1) / BN, tm, tn);
   const int m0 = tm * BM, n0 = tn * BN;
   const int tid = threadIdx.x;
 
@@ -63,7 +63,7 @@ template <int BM, int BN, int WM, int WN, bool AKC, bool BKC>
 __global__ void __launch_bounds__(WM* WN * 64) gemm_bf16_dl_kernel(GemmKArgs p) {
   extern __shared__ __attribute__((aligned(16))) unsigned short smem[];
   int tm, tn;
-  tile_of_block(blockIdx.x, (p.M + BM - 1) / BM, (p.N + BN - 1) / BN, tm, tn);
+  tile_of_block<(BM == 256 && BN == 256)>(blockIdx.x, (p.M + BM - 1) / BM, (p.N + BN - 1) / BN, tm, tn);
   typename dl::OperandSel<AKC, BM, WM * WN>::type oa;
   typename dl::OperandSel<BKC, BN, WM * WN>::type ob;
   oa.init(p.A, p.a_bytes, tm * BM, p.M, p.K, p.lda);

@@ -153,11 +153,26 @@ struct StageKS {
   }
 };
 
-// logical tile of a workgroup: ids congruent mod 8 share an XCD (and its L2), so give each XCD a
-// contiguous range of logical ids, then walk groups of GM tile rows column by column
+// Tile of a workgroup.  Workgroup ids that are congruent mod 8 run on the same XCD and share its L2;
+// ids are handed out in increasing order, so with one resident workgroup per CU the 256 CUs work on
+// ids [256 w, 256 w + 256) at about the same time.
+//
+// SUPER = true (tile grid a multiple of 16 x 16, one workgroup per CU): each XCD takes an 8 x 4 block
+// of tiles (its 32 CUs share 8 A panels and 4 B panels through L2) and the eight XCDs' blocks form a
+// 16 x 16 super-block, so operand panels that several XCDs need at the same time come out of HBM once.
+// Otherwise: each XCD gets a contiguous range of logical ids, walked in groups of 8 tile rows.
+template <bool SUPER>
 __device__ __forceinline__ void tile_of_block(int pid, int nbm, int nbn, int& tm, int& tn) {
-  const int nb = nbm * nbn;
   const int xcd = pid % 8, loc = pid / 8;
+  if (SUPER && nbm % 16 == 0 && nbn % 16 == 0) {
+    const int w = loc / 32, i = loc % 32;       // super-block, tile inside the XCD's 8 x 4 block
+    const int sbm = nbm / 16;
+    const int sr = w % sbm, sc = w / sbm;       // super-blocks walked down the rows first
+    tm = sr * 16 + (xcd % 2) * 8 + (i % 8);
+    tn = sc * 16 + (xcd / 2) * 4 + (i / 8);
+    return;
+  }
+  const int nb = nbm * nbn;
   const int per = nb / 8, rem = nb % 8;
   const int lid = xcd * per + (xcd < rem ? xcd : rem) + loc;
   constexpr int GM = 8;
