@@ -59,23 +59,23 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_bf16_kernel(GemmKArgs p) {
 }
 
 // direct-to-LDS variant (256x256 tile, K step 32, four LDS stages)
-template <int BM, int BN, int WM, int WN, bool AKC, bool BKC>
+template <int BM, int BN, int BK, int NSTAGE, int WM, int WN, bool AKC, bool BKC>
 __global__ void __launch_bounds__(WM* WN * 64) gemm_bf16_dl_kernel(GemmKArgs p) {
   extern __shared__ __attribute__((aligned(16))) unsigned short smem[];
   int tm, tn;
   tile_of_block<(BM == 256 && BN == 256)>(blockIdx.x, (p.M + BM - 1) / BM, (p.N + BN - 1) / BN, tm, tn);
-  typename dl::OperandSel<AKC, BM, WM * WN>::type oa;
-  typename dl::OperandSel<BKC, BN, WM * WN>::type ob;
+  typename dl::OperandSel<AKC, BM, BK, WM * WN>::type oa;
+  typename dl::OperandSel<BKC, BN, BK, WM * WN>::type ob;
   oa.init(p.A, p.a_bytes, tm * BM, p.M, p.K, p.lda);
   ob.init(p.B, p.b_bytes, tn * BN, p.N, p.K, p.ldb);
   StoreEpilogue epi{p.out_z, p.out_a, p.out_f32, p.M, p.N, p.ldc, p.act, tm * BM, tn * BN, p.vec_out != 0};
-  dl::gemm_tile_dl<BM, BN, WM, WN>(oa, ob, (p.K + dl::BK - 1) / dl::BK, smem, epi);
+  dl::gemm_tile_dl<BM, BN, BK, NSTAGE, WM, WN>(oa, ob, (p.K + BK - 1) / BK, smem, epi);
 }
 
-template <int BM, int BN, int WM, int WN, bool AKC, bool BKC>
+template <int BM, int BN, int BK, int NSTAGE, int WM, int WN, bool AKC, bool BKC>
 hipError_t launch_dl(const GemmKArgs& a, hipStream_t s) {
-  auto kern = gemm_bf16_dl_kernel<BM, BN, WM, WN, AKC, BKC>;
-  constexpr size_t lds = (size_t)dl::NSTAGE * (BM + BN) * dl::BK * sizeof(unsigned short);
+  auto kern = gemm_bf16_dl_kernel<BM, BN, BK, NSTAGE, WM, WN, AKC, BKC>;
+  constexpr size_t lds = (size_t)NSTAGE * (BM + BN) * BK * sizeof(unsigned short);
   static bool attr_done = false;
   if (!attr_done) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -92,8 +92,9 @@ struct TileCfg {
   int bm, bn;
 };
 constexpr TileCfg kCfgs[] = {{"256x256x64_w2x4", 256, 256}, {"128x128x64_w2x2", 128, 128}, {"64x64x64_w2x2", 64, 64},
-                             {"256x256x64_w2x2", 256, 256}, {"256x256x32_dl_w2x4", 256, 256}};
-constexpr int kCfgDL = 4;
+                             {"256x256x64_w2x2", 256, 256}, {"256x256x32_dl_w2x4", 256, 256},
+                             {"256x256x64_dl2_w2x4", 256, 256}};
+constexpr int kCfgDL = 4, kCfgDL64 = 5;
 constexpr int kAutoCfgs = 3;  // the first three are ordered large to small for the automatic choice
 
 template <int BM, int BN, int BK, int WM, int WN, bool AKC, bool BKC, bool ALIGNED>
@@ -170,17 +171,24 @@ hipError_t launch_gemm_bf16(const GemmDesc& d, hipStream_t s, int tile_cfg) {
       const long tiles = (long)((d.M + kCfgs[c].bm - 1) / kCfgs[c].bm) * ((d.N + kCfgs[c].bn - 1) / kCfgs[c].bn);
       if (tiles >= 192) { cfg = c; break; }
     }
-    // a k-strided operand: direct-to-LDS loop with transposing LDS reads when the shape allows 16-byte
-    // chunks; otherwise the register-transposing loop, which needs more VGPRs than two waves per SIMD
-    // leave, so the 256x256 tile then runs as four waves of 128x128 instead of eight of 128x64
-    if (cfg == 0 && !(d.a_kcontig && d.b_kcontig)) cfg = aligned ? kCfgDL : 3;
+    // 256x256 tiles: the direct-to-LDS loop (K step 64, two stages) whenever the shape allows 16-byte
+    // chunks.  Otherwise the register-staged loop; with a k-strided operand it transposes in registers
+    // and needs more VGPRs than two waves per SIMD leave, so it then runs as four waves of 128x128.
+    if (cfg == 0) cfg = aligned ? kCfgDL64 : ((d.a_kcontig && d.b_kcontig) ? 0 : 3);
   }
   if (cfg == kCfgDL) {
     if (!aligned) return hipErrorInvalidValue;
-    if (d.a_kcontig && d.b_kcontig) return launch_dl<256, 256, 2, 4, true, true>(a, s);
-    if (d.a_kcontig && !d.b_kcontig) return launch_dl<256, 256, 2, 4, true, false>(a, s);
-    if (!d.a_kcontig && !d.b_kcontig) return launch_dl<256, 256, 2, 4, false, false>(a, s);
-    return launch_dl<256, 256, 2, 4, false, true>(a, s);
+    if (d.a_kcontig && d.b_kcontig) return launch_dl<256, 256, 32, 4, 2, 4, true, true>(a, s);
+    if (d.a_kcontig && !d.b_kcontig) return launch_dl<256, 256, 32, 4, 2, 4, true, false>(a, s);
+    if (!d.a_kcontig && !d.b_kcontig) return launch_dl<256, 256, 32, 4, 2, 4, false, false>(a, s);
+    return launch_dl<256, 256, 32, 4, 2, 4, false, true>(a, s);
+  }
+  if (cfg == kCfgDL64) {
+    if (!aligned) return hipErrorInvalidValue;
+    if (d.a_kcontig && d.b_kcontig) return launch_dl<256, 256, 64, 2, 2, 4, true, true>(a, s);
+    if (d.a_kcontig && !d.b_kcontig) return launch_dl<256, 256, 64, 2, 2, 4, true, false>(a, s);
+    if (!d.a_kcontig && !d.b_kcontig) return launch_dl<256, 256, 64, 2, 2, 4, false, false>(a, s);
+    return launch_dl<256, 256, 64, 2, 2, 4, false, true>(a, s);
   }
   if (cfg >= gemm_bf16_num_cfgs()) return hipErrorInvalidValue;
   return aligned ? launch_layout<true>(d.a_kcontig, d.b_kcontig, cfg, a, s)

@@ -1,4 +1,4 @@
-// bf16 matrix-core GEMM main loop with direct global->LDS loads and a four-stage LDS ring.
+// bf16 matrix-core GEMM main loop with direct global->LDS loads and a ring of LDS stages.
 //
 // Used for the three products of a layer (Eq. 1, Eq. 4, Eq. 5) whenever every contiguous run of both
 // operands starts on a multiple of 8 elements (16-byte chunks); other shapes take the register-staged
@@ -10,9 +10,10 @@
 //     contiguous) and is transposed by the LDS read itself (ds_read_b64_tr_b16): within a group of 16
 //     lanes, lane 4j+a supplies the address of four consecutive elements of k-row j, and lane i
 //     receives element i of each of the four k-rows;
-//   * K step 32 (two MFMA substeps), one barrier per step, placed between the substeps: before it a
-//     wave waits for its own loads of tile t+1, after it stage t%4 is free and receives tile t+4, and
-//     the second substep's MFMAs cover the first fragment reads of tile t+1.
+//   * K step BK (BK/16 MFMA substeps), NSTAGE stages, one barrier per step, placed before the last
+//     substep: before it a wave waits for its own loads of tile t+1, after it stage t%NSTAGE is free and
+//     receives tile t+NSTAGE, and the last substep's MFMAs cover the first fragment reads of tile t+1.
+//     (BK, NSTAGE) = (32, 4) or (64, 2): both fill 128 KB of LDS for a 256 x 256 tile.
 // The swizzle that keeps LDS reads conflict-free is applied on the global side: the lane that owns
 // LDS chunk p of a row fetches global chunk p ^ f(row).
 #pragma once
@@ -33,8 +34,6 @@ using core::kOOB;
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
 
-constexpr int BK = 32;      // K step
-constexpr int NSTAGE = 4;   // LDS ring depth
 
 typedef __attribute__((address_space(3))) unsigned int* lds_u32_ptr;
 typedef __attribute__((address_space(3))) s16x4* lds_s16x4_ptr;
@@ -50,30 +49,36 @@ __device__ __forceinline__ void load_to_lds_16(__amdgpu_buffer_rsrc_t rs, unsign
 }
 
 // ---- operand with k contiguous in memory: element (r,k) at base[r*ld + k] ------------------------
-// LDS stage: [R][32] halves, 64 bytes per row, chunk p of row r holds global chunk p ^ ((r>>2)&3).
-template <int R, int NWAVES>
+// LDS stage: [R][BK] halves; chunk p of row r holds global chunk p ^ swz(r), swz as in core::lds_off.
+template <int R, int BK, int NWAVES>
 struct OperandKC {
   static constexpr int STAGE_ELEMS = R * BK;
-  static constexpr int WAVELOADS = R / 16;                  // 1 KB each: 16 rows
+  static constexpr int CPR = BK / 8;                         // chunks per row
+  static constexpr int RP = 128 / BK;                        // rows per 256 bytes
+  static constexpr int ROWS_PER_LOAD = 64 / CPR;             // rows per 1 KB wave load
+  static constexpr int WAVELOADS = R / ROWS_PER_LOAD;
   static constexpr int PER_WAVE = WAVELOADS / NWAVES;
+  static_assert(BK == 32 || BK == 64, "");
   static_assert(WAVELOADS % NWAVES == 0, "rows must split evenly over the waves");
   __amdgpu_buffer_rsrc_t rs;
   int r0, Rtot, Ktot, ld;
   // lane-constant parts
-  int lrow, lchunk;
+  int lrow, lpos;
   __device__ __forceinline__ void init(const void* p, unsigned bytes, int r0_, int Rtot_, int Ktot_, int ld_) {
     rs = core::make_rsrc(p, bytes);
     r0 = r0_; Rtot = Rtot_; Ktot = Ktot_; ld = ld_;
     const int lane = threadIdx.x & 63;
-    lrow = lane >> 2;
-    lchunk = (lane & 3) ^ ((lrow >> 2) & 3);
+    lrow = lane / CPR;
+    lpos = lane % CPR;
   }
   // all waves together fill one stage with the tile that starts at reduction index k0
   __device__ __forceinline__ void issue(int k0, unsigned short* stage, int wave_u) const {
 #pragma unroll
     for (int i = 0; i < PER_WAVE; ++i) {
-      const int g = wave_u * PER_WAVE + i;                  // group of 16 rows
-      const int row = r0 + g * 16 + lrow, k = k0 + lchunk * 8;
+      const int g = wave_u * PER_WAVE + i;                  // group of ROWS_PER_LOAD rows
+      const int trow = g * ROWS_PER_LOAD + lrow;           // row inside the tile
+      const int chunk = lpos ^ ((trow / RP) % CPR);         // the swizzle of core::lds_off, applied on the global side
+      const int row = r0 + trow, k = k0 + chunk * 8;
       const unsigned off = (row < Rtot && k < Ktot) ? ((unsigned)row * (unsigned)ld + (unsigned)k) * 2u : kOOB;
       load_to_lds_16(rs, off, stage + g * 512);
     }
@@ -82,13 +87,13 @@ struct OperandKC {
   __device__ __forceinline__ bf16x8 frag(const unsigned short* stage, int row0, int kk) const {
     const int lane = threadIdx.x & 63;
     const int row = row0 + (lane & 31), chunk = kk * 2 + (lane >> 5);
-    return *(const bf16x8*)(stage + row * BK + ((chunk ^ ((row >> 2) & 3)) * 8));
+    return *(const bf16x8*)(stage + core::lds_off<BK>(row, chunk));
   }
 };
 
 // ---- operand with k strided in memory: element (r,k) at base[k*ld + r] ---------------------------
-// LDS stage: [32][R] halves, chunk p of k-row k holds global chunk p ^ ((k&3)<<2).
-template <int R, int NWAVES>
+// LDS stage: [BK][R] halves, chunk p of k-row k holds global chunk p ^ ((k&3)<<2).
+template <int R, int BK, int NWAVES>
 struct OperandKS {
   static_assert(R == 128 || R == 256, "row length of 16 or 32 chunks");
   static constexpr int STAGE_ELEMS = R * BK;
@@ -132,13 +137,13 @@ struct OperandKS {
   }
 };
 
-template <bool KC, int R, int NWAVES>
+template <bool KC, int R, int BK, int NWAVES>
 struct OperandSel {
-  using type = OperandKC<R, NWAVES>;
+  using type = OperandKC<R, BK, NWAVES>;
 };
-template <int R, int NWAVES>
-struct OperandSel<false, R, NWAVES> {
-  using type = OperandKS<R, NWAVES>;
+template <int R, int BK, int NWAVES>
+struct OperandSel<false, R, BK, NWAVES> {
+  using type = OperandKS<R, BK, NWAVES>;
 };
 
 // s_waitcnt with vmcnt <= n (expcnt and lgkmcnt untouched)
@@ -149,7 +154,7 @@ __device__ __forceinline__ void wait_vmcnt() {
 }
 
 // smem: NSTAGE * (BM + BN) * BK halves.  KT = number of K tiles.
-template <int BM, int BN, int WM, int WN, class OA, class OB, class Epi>
+template <int BM, int BN, int BK, int NSTAGE, int WM, int WN, class OA, class OB, class Epi>
 __device__ __forceinline__ void gemm_tile_dl(const OA& oa, const OB& ob, int KT, unsigned short* smem, Epi epi) {
   constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
   constexpr int A_ELEMS = BM * BK, B_ELEMS = BN * BK, STAGE = A_ELEMS + B_ELEMS;
@@ -200,18 +205,22 @@ __device__ __forceinline__ void gemm_tile_dl(const OA& oa, const OB& ob, int KT,
   __syncthreads();
   read_frags(smem, 0, fa[0], fb[0]);
 
+  constexpr int KS = BK / 16;   // MFMA substeps per K step
   for (int t = 0; t < KT; ++t) {
     const unsigned short* cur = smem + (t % NSTAGE) * STAGE;
     const unsigned short* nxt = smem + ((t + 1) % NSTAGE) * STAGE;
-    read_frags(cur, 1, fa[1], fb[1]);
-    mfmas(fa[0], fb[0]);
-    interleave_reads();
-    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int kk = 0; kk + 1 < KS; ++kk) {
+      read_frags(cur, kk + 1, fa[(kk + 1) & 1], fb[(kk + 1) & 1]);
+      mfmas(fa[kk & 1], fb[kk & 1]);
+      interleave_reads();
+      __builtin_amdgcn_sched_barrier(0);
+    }
     wait_vmcnt<(NSTAGE - 2) * LOADS>();   // this wave's part of tile t+1 has landed
     __syncthreads();                      // ... and everyone's; nobody reads tile t's stage any more
     issue(t + NSTAGE);
-    read_frags(nxt, 0, fa[0], fb[0]);
-    mfmas(fa[1], fb[1]);
+    read_frags(nxt, 0, fa[KS & 1], fb[KS & 1]);
+    mfmas(fa[(KS - 1) & 1], fb[(KS - 1) & 1]);
     interleave_reads();
     __builtin_amdgcn_sched_barrier(0);
   }
