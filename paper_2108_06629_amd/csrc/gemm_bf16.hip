@@ -87,15 +87,19 @@ hipError_t launch_dl(const GemmKArgs& a, hipStream_t s) {
   return hipGetLastError();
 }
 
+// kind: 0 = register-staged loop (gemm_core.h), 1 = direct-to-LDS loop (gemm_dl.h, K step 64, two stages)
 struct TileCfg {
   const char* name;
-  int bm, bn;
+  int bm, bn, kind;
 };
-constexpr TileCfg kCfgs[] = {{"256x256x64_w2x4", 256, 256}, {"128x128x64_w2x2", 128, 128}, {"64x64x64_w2x2", 64, 64},
-                             {"256x256x64_w2x2", 256, 256}, {"256x256x32_dl_w2x4", 256, 256},
-                             {"256x256x64_dl2_w2x4", 256, 256}};
-constexpr int kCfgDL = 4, kCfgDL64 = 5;
-constexpr int kAutoCfgs = 3;  // the first three are ordered large to small for the automatic choice
+constexpr TileCfg kCfgs[] = {
+    {"256x256x64_w2x4", 256, 256, 0},     // 0
+    {"128x128x64_w2x2", 128, 128, 0},     // 1
+    {"64x64x64_w2x2", 64, 64, 0},         // 2
+    {"256x256x64_w2x2", 256, 256, 0},     // 3
+    {"256x256x64_dl_w2x4", 256, 256, 1},  // 4
+    {"128x128x64_dl_w2x2", 128, 128, 1},  // 5
+};
 
 template <int BM, int BN, int BK, int WM, int WN, bool AKC, bool BKC, bool ALIGNED>
 hipError_t launch_one(const GemmKArgs& a, hipStream_t s) {
@@ -123,12 +127,13 @@ hipError_t launch_cfg(int cfg, const GemmKArgs& a, hipStream_t s) {
   return hipErrorInvalidValue;
 }
 
-template <bool ALIGNED>
-hipError_t launch_layout(bool akc, bool bkc, int cfg, const GemmKArgs& a, hipStream_t s) {
-  if (akc && bkc) return launch_cfg<true, true, ALIGNED>(cfg, a, s);
-  if (akc && !bkc) return launch_cfg<true, false, ALIGNED>(cfg, a, s);
-  if (!akc && !bkc) return launch_cfg<false, false, ALIGNED>(cfg, a, s);
-  return launch_cfg<false, true, ALIGNED>(cfg, a, s);
+template <bool AKC, bool BKC>
+hipError_t launch_cfg_dl(int cfg, const GemmKArgs& a, hipStream_t s) {
+  switch (cfg) {
+    case 4: return launch_dl<256, 256, 64, 2, 2, 4, AKC, BKC>(a, s);
+    case 5: return launch_dl<128, 128, 64, 2, 2, 2, AKC, BKC>(a, s);
+  }
+  return hipErrorInvalidValue;
 }
 
 }  // namespace
@@ -163,36 +168,39 @@ hipError_t launch_gemm_bf16(const GemmDesc& d, hipStream_t s, int tile_cfg) {
   const int a_contig = d.a_kcontig ? d.K : d.M, b_contig = d.b_kcontig ? d.K : d.N;
   const bool aligned = (d.lda % 8 == 0) && (d.ldb % 8 == 0) && (a_contig % 8 == 0) && (b_contig % 8 == 0) &&
                        ((uintptr_t)d.A % 16 == 0) && ((uintptr_t)d.B % 16 == 0);
+  const bool both_kc = d.a_kcontig && d.b_kcontig;
 
   int cfg = tile_cfg;
   if (cfg < 0) {
-    cfg = kAutoCfgs - 1;
-    for (int c = 0; c < kAutoCfgs; ++c) {
-      const long tiles = (long)((d.M + kCfgs[c].bm - 1) / kCfgs[c].bm) * ((d.N + kCfgs[c].bn - 1) / kCfgs[c].bn);
-      if (tiles >= 192) { cfg = c; break; }
-    }
-    // 256x256 tiles: the direct-to-LDS loop (K step 64, two stages) whenever the shape allows 16-byte
-    // chunks.  Otherwise the register-staged loop; with a k-strided operand it transposes in registers
-    // and needs more VGPRs than two waves per SIMD leave, so it then runs as four waves of 128x128.
-    if (cfg == 0) cfg = aligned ? kCfgDL64 : ((d.a_kcontig && d.b_kcontig) ? 0 : 3);
+    // 256x256 tiles when they give (nearly) every CU one; else 128x128 (two workgroups per CU), which
+    // measured faster than 64x64 down to a handful of tiles with the direct-to-LDS loop.  Aligned
+    // shapes take the direct-to-LDS loop.  Otherwise the register-staged loop; with a k-strided
+    // operand it transposes in registers and needs more VGPRs than two waves per SIMD leave, so
+    // 256x256 then runs as four waves of 128x128; its 128x128 form needs 64 tiles to beat 64x64.
+    const long t256 = (long)((d.M + 255) / 256) * ((d.N + 255) / 256);
+    const long t128 = (long)((d.M + 127) / 128) * ((d.N + 127) / 128);
+    if (t256 >= 192) cfg = aligned ? 4 : (both_kc ? 0 : 3);
+    else if (aligned) cfg = 5;
+    else cfg = t128 >= 64 ? 1 : 2;
   }
-  if (cfg == kCfgDL) {
+  if (cfg < 0 || cfg >= gemm_bf16_num_cfgs()) return hipErrorInvalidValue;
+  if (kCfgs[cfg].kind == 1) {
     if (!aligned) return hipErrorInvalidValue;
-    if (d.a_kcontig && d.b_kcontig) return launch_dl<256, 256, 32, 4, 2, 4, true, true>(a, s);
-    if (d.a_kcontig && !d.b_kcontig) return launch_dl<256, 256, 32, 4, 2, 4, true, false>(a, s);
-    if (!d.a_kcontig && !d.b_kcontig) return launch_dl<256, 256, 32, 4, 2, 4, false, false>(a, s);
-    return launch_dl<256, 256, 32, 4, 2, 4, false, true>(a, s);
+    if (d.a_kcontig && d.b_kcontig) return launch_cfg_dl<true, true>(cfg, a, s);
+    if (d.a_kcontig && !d.b_kcontig) return launch_cfg_dl<true, false>(cfg, a, s);
+    if (!d.a_kcontig && !d.b_kcontig) return launch_cfg_dl<false, false>(cfg, a, s);
+    return launch_cfg_dl<false, true>(cfg, a, s);
   }
-  if (cfg == kCfgDL64) {
-    if (!aligned) return hipErrorInvalidValue;
-    if (d.a_kcontig && d.b_kcontig) return launch_dl<256, 256, 64, 2, 2, 4, true, true>(a, s);
-    if (d.a_kcontig && !d.b_kcontig) return launch_dl<256, 256, 64, 2, 2, 4, true, false>(a, s);
-    if (!d.a_kcontig && !d.b_kcontig) return launch_dl<256, 256, 64, 2, 2, 4, false, false>(a, s);
-    return launch_dl<256, 256, 64, 2, 2, 4, false, true>(a, s);
+  if (aligned) {
+    if (d.a_kcontig && d.b_kcontig) return launch_cfg<true, true, true>(cfg, a, s);
+    if (d.a_kcontig && !d.b_kcontig) return launch_cfg<true, false, true>(cfg, a, s);
+    if (!d.a_kcontig && !d.b_kcontig) return launch_cfg<false, false, true>(cfg, a, s);
+    return launch_cfg<false, true, true>(cfg, a, s);
   }
-  if (cfg >= gemm_bf16_num_cfgs()) return hipErrorInvalidValue;
-  return aligned ? launch_layout<true>(d.a_kcontig, d.b_kcontig, cfg, a, s)
-                 : launch_layout<false>(d.a_kcontig, d.b_kcontig, cfg, a, s);
+  if (d.a_kcontig && d.b_kcontig) return launch_cfg<true, true, false>(cfg, a, s);
+  if (d.a_kcontig && !d.b_kcontig) return launch_cfg<true, false, false>(cfg, a, s);
+  if (!d.a_kcontig && !d.b_kcontig) return launch_cfg<false, false, false>(cfg, a, s);
+  return launch_cfg<false, true, false>(cfg, a, s);
 }
 
 }  // namespace lp

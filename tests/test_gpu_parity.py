@@ -44,11 +44,13 @@ def one_layer_net(d_in, d_out, batch, act="relu", dtype="bf16", seed=0):
     return net, W, rng
 
 
-# shapes: (batch, d_in, d_out).  Chosen to hit every tile shape of the bf16 kernel (>=192 tiles of
-# 256x256, of 128x128, else 64x64), ragged tails in all three dimensions, the unaligned (not a
-# multiple of 8) loader, and degenerate sizes.
+# shapes: (batch, d_in, d_out).  Chosen to hit every kernel variant (>=192 tiles of 256x256, else
+# 128x128, else 64x64 for unaligned shapes with few tiles; direct-to-LDS loop when every run is a
+# multiple of 8, register-staged loop otherwise), ragged tails in all three dimensions, and
+# degenerate sizes.
 FWD_SHAPES = [(96, 200, 136), (33, 77, 19), (1, 8, 8), (7, 1, 3), (300, 520, 264), (64, 4096, 64),
-              (1100, 72, 3000), (2304, 96, 5632), (256, 512, 1000)]
+              (1100, 72, 3000), (2304, 96, 5632), (256, 512, 1000), (1024, 136, 6200), (2300, 100, 5700),
+              (1101, 71, 3001)]
 
 
 @pytest.mark.parametrize("shape", FWD_SHAPES)
