@@ -247,12 +247,13 @@ __global__ void __launch_bounds__(256) sgd_kernel(f32x4* __restrict__ master, co
       f32x4 o;
 #pragma unroll
       for (int d = 0; d < 4; ++d) o[d] = fmaf(neg_lr, gg[u][d], w[u][d]);
-      master[i] = o;
+      // streaming stores: neither copy is read again before the next step
+      __builtin_nontemporal_store(o, master + i);
       if (BF16) {
         u32x2 b;
         b[0] = (unsigned)f2bf(o[0]) | ((unsigned)f2bf(o[1]) << 16);
         b[1] = (unsigned)f2bf(o[2]) | ((unsigned)f2bf(o[3]) << 16);
-        work[i] = b;
+        __builtin_nontemporal_store(b, work + i);
       }
     }
   }
