@@ -24,6 +24,11 @@ PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 PEAK_FP32_MFMA_TFLOPS = 157.3
 PEAK_HBM_GBS = 8000.0
 
+# bytes the L2s request from the fabric (Infinity Cache + HBM) plus bytes written, per launch of the F
+# kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script, scaled by a 1 GiB copy
+# (profiles/hbm_traffic_ffn_stack.md)
+MEASURED_TRAFFIC_BYTES = {"ffn_stack_bf16": 1.6115e9 + 3.020e8}
+
 
 def task_work(wl):
     """Algorithmic work per step of each task kind: flops for the three products, HBM bytes for the
@@ -183,7 +188,8 @@ def main():
         avg_s = tasks["F"]["avg_ms"] * 1e-3
         ach = flops_per_launch / avg_s / 1e12
         roofline = {"bound": "mfma", "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS,
-                    "traffic": None, "kernel": "gemm_bf16_kernel (forward product F)", "flops_per_launch": flops_per_launch,
+                    "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name), "kernel": "gemm_bf16_dl_kernel<256,256,64,2,2,4,true,false> (forward product F)",
+                    "flops_per_launch": flops_per_launch,
                     "avg_launch_ms": tasks["F"]["avg_ms"]}
     elif "F" in tasks:
         flops_per_launch = work["F"] / wl.L
