@@ -177,6 +177,18 @@ int lp_sync(lp_ctx* ctx);
 /* Device address and size of an internal tensor (see lp_tensor_id) for inspection. */
 int lp_tensor(lp_ctx* ctx, int l, int which, void** dev_ptr, size_t* bytes);
 
+/* ---- balanced pipeline partitioning (host only) --------------------------------------------- */
+
+/* Algorithm 1 (Sec. III-C).  t_fix[l]: time of layer l's immovable tasks (forward + weight gradient),
+ * t_flex[l]: time of its delta task (Eq. 4), l = 0..L-1, any unit, >= 0.  n_proc >= 1 processors,
+ * alpha > 1 the relaxation factor of the target load.  Outputs (host arrays owned by the caller):
+ * stage_fix[L]: stage (0 = first layers) of each layer's immovable tasks; borrowed_frac[L]: fraction of
+ * layer l's delta task that the stage of layer l+1 executes (delta''; 0 if none);
+ * stage_delta_rest[L]: stage that executes the rest (delta'); stage_time[n_proc]: load per stage;
+ * *t_p (may be NULL): the final target load.  Touches no device. */
+int lp_partition(const double* t_fix, const double* t_flex, int L, int n_proc, double alpha, int* stage_fix,
+                 int* stage_delta_rest, double* borrowed_frac, double* stage_time, double* t_p);
+
 /* ---- measurement aid ----------------------------------------------------------------------- */
 
 /* Task kinds of Fig. 1(b) as this library launches them. */
