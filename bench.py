@@ -79,6 +79,83 @@ def cpu_baseline(wl, threads):
                           threads, what, wl.name, sub.batch, wl.batch, dt, scale)}
 
 
+def partition_report(wl, max_stages):
+    """Per-layer task times measured on one stream (no overlap), fed to the library's Algorithm 1:
+    T_fix = F + dW, T_flex = dX (Sec. III-C).  For each stage count: the balanced stage times, the
+    delta'' fractions, and the best assignment of whole layers to contiguous stages for comparison;
+    then one run with the delta'' column splits applied inside lp_step."""
+    import torch
+    import lp_workloads as WL
+    import paper_2108_06629_amd as lp
+    net = lp.Network(wl.layers, wl.batch, wl.dtype, wl.loss, wl.lr, wl.delays, n_streams=1)
+    net.set_weights(WL.init_weights(wl))
+    x = net.to_device(WL.batch_input(wl, 1))
+    t = net.to_device(WL.batch_target(wl, 1), is_label=(wl.loss == WL.SOFTMAX_CE))
+    for _ in range(5):
+        net.step_device(x, t)
+    lp.lp_sync(net.ctx)
+    lp.lp_profile(net.ctx, True)
+    reps = 20
+    for _ in range(reps):
+        net.step_device(x, t)
+    lp.lp_sync(net.ctx)
+    lp.lp_profile(net.ctx, False)
+    per = {}
+    for k, name in enumerate(lp.TASK_NAMES[:3]):
+        per[name] = [lp.lp_profile_read_layer(net.ctx, k, l)[0] / reps for l in range(1, wl.L + 1)]
+    net.close()
+    t_fix = [f + w for f, w in zip(per["F"], per["dW"])]
+    t_flex = per["dX"]
+    tot = [a + b for a, b in zip(t_fix, t_flex)]
+
+    def best_whole_layers(n):       # minimise the bottleneck over contiguous whole-layer stages (dynamic programme)
+        L = len(tot)
+        pre = [0.0]
+        for v in tot:
+            pre.append(pre[-1] + v)
+        INF = float("inf")
+        dp = [[INF] * (L + 1) for _ in range(n + 1)]
+        dp[0][0] = 0.0
+        for s in range(1, n + 1):
+            for j in range(1, L + 1):
+                for i in range(s - 1, j):
+                    dp[s][j] = min(dp[s][j], max(dp[s - 1][i], pre[j] - pre[i]))
+        return min(dp[s][L] for s in range(1, n + 1))
+
+    rows = []
+    for n in range(2, max_stages + 1):
+        r = lp.lp_partition(t_fix, t_flex, n, 1.01)
+        rows.append({"stages": n, "balanced_bottleneck_ms": max(r["stage_time"]), "whole_layer_bottleneck_ms": best_whole_layers(n),
+                     "speedup_vs_1": sum(tot) / max(r["stage_time"]), "whole_layer_speedup_vs_1": sum(tot) / best_whole_layers(n),
+                     "stage_fix": r["stage_fix"], "borrowed_frac": [round(v, 4) for v in r["borrowed_frac"]],
+                     "stage_time_ms": [round(v, 4) for v in r["stage_time"]]})
+    # apply the last partition's delta'' fractions as column splits and time the step
+    r = lp.lp_partition(t_fix, t_flex, max_stages, 1.01)
+    times = {}
+    for label, use in (("unsplit", False), ("split", True)):
+        net = lp.Network(wl.layers, wl.batch, wl.dtype, wl.loss, wl.lr, wl.delays, n_streams=3)
+        net.set_weights(WL.init_weights(wl))
+        if use:
+            for l in range(2, wl.L + 1):
+                cols = int(round(r["borrowed_frac"][l - 1] * wl.layers[l - 1].d_in / 8.0)) * 8
+                lp.lp_set_delta_split(net.ctx, l, min(max(cols, 0), wl.layers[l - 1].d_in - 8))
+        x = net.to_device(WL.batch_input(wl, 1))
+        t = net.to_device(WL.batch_target(wl, 1), is_label=(wl.loss == WL.SOFTMAX_CE))
+        for _ in range(5):
+            net.step_device(x, t)
+        lp.lp_sync(net.ctx)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(20):
+            net.step_device(x, t)
+        lp.lp_sync(net.ctx)
+        torch.cuda.synchronize()
+        times[label] = (time.perf_counter() - t0) / 20 * 1e3
+        net.close()
+    return {"workload": wl.name, "per_layer_ms": {k: [round(v, 4) for v in vals] for k, vals in per.items()},
+            "partitions": rows, "step_ms_three_streams": times}
+
+
 def run_workload(wl, steps, warmup, n_streams, profile=True, weights=None):
     import numpy as np
     import torch
@@ -133,6 +210,9 @@ def main():
     ap.add_argument("--streams", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-others", action="store_true", help="skip the short runs of the other workloads")
+    ap.add_argument("--partition", type=int, default=0, metavar="NP",
+                    help="instead of the benchmark line: measure every layer's task times, run Algorithm 1 for 2..NP stages and "
+                         "print the balanced stage times next to the best whole-layer (PipeDream-style) assignment")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run five 1 GiB device-to-device copy kernels (reference for the FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
@@ -157,6 +237,9 @@ def main():
         return
 
     wl = WL.CONFIGS[args.workload]()
+    if args.partition:
+        print(json.dumps(partition_report(wl, args.partition)))
+        return
     work = task_work(wl)
     weights = WL.init_weights(wl)
     dt, loss, prof, upd_params = run_workload(wl, args.steps, args.warmup, args.streams, True, weights)

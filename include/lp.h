@@ -153,6 +153,14 @@ int lp_grad_weight(lp_ctx* ctx, int l, const void* X, const void* dY, float* G, 
  * Sec. III-A).  F32 contexts update in place: order the call after the readers of W_l. */
 int lp_update(lp_ctx* ctx, int l, const float* G, void* stream);
 
+/* Inter-layer split of the delta product inside lp_step (Sec. III-B): the last `cols` of layer l's D_{l-1}
+ * output columns (input channels for a convolution) are computed by a second, independent kernel
+ * (delta'', the part the following stage borrows) on streams[1], ahead of that layer's G task, while
+ * the first D_{l-1} - cols columns (delta') stay on the critical stream; the moved Hadamard of layer
+ * l-1 waits for both.  cols = 0 (default) computes the product in one piece.  Results do not depend
+ * on cols.  0 <= cols < D_{l-1}; layer 1 has no delta task. */
+int lp_set_delta_split(lp_ctx* ctx, int l, int cols);
+
 /* Ends a step driven through the per-layer calls: n <- n + 1. */
 int lp_advance(lp_ctx* ctx);
 
@@ -210,6 +218,8 @@ int lp_profile(lp_ctx* ctx, int enable);
  * since the last reset: *total_ms (milliseconds) and *launches; either may be NULL.  reset != 0
  * clears the totals of this task afterwards. */
 int lp_profile_read(lp_ctx* ctx, int task, double* total_ms, long* launches, int reset);
+/* The same for one layer l = 1..L (the loss task belongs to no layer and is only in the totals). */
+int lp_profile_read_layer(lp_ctx* ctx, int task, int l, double* total_ms, long* launches, int reset);
 
 #ifdef __cplusplus
 }

@@ -34,7 +34,7 @@ STATUS_NAMES = ["LP_OK", "LP_ERR_NULL", "LP_ERR_SHAPE", "LP_ERR_DTYPE", "LP_ERR_
 
 EXPORTS = ["lp_create", "lp_destroy", "lp_last_error", "lp_workspace_bytes", "lp_bind_workspace", "lp_set_weights",
            "lp_get_weights", "lp_forward", "lp_loss_grad", "lp_act_grad", "lp_grad_act", "lp_grad_weight", "lp_update",
-           "lp_advance", "lp_step", "lp_step_index", "lp_sync", "lp_tensor", "lp_profile", "lp_profile_read", "lp_partition"]
+           "lp_advance", "lp_step", "lp_step_index", "lp_sync", "lp_tensor", "lp_profile", "lp_profile_read", "lp_profile_read_layer", "lp_partition", "lp_set_delta_split"]
 
 
 class lp_layer_desc(C.Structure):
@@ -81,6 +81,8 @@ def load_library():
     L.lp_tensor.argtypes = [vp, ip, ip, C.POINTER(vp), C.POINTER(C.c_size_t)]
     dp = C.POINTER(C.c_double)
     L.lp_partition.argtypes = [dp, dp, ip, ip, C.c_double, C.POINTER(ip), C.POINTER(ip), dp, dp, dp]
+    L.lp_set_delta_split.argtypes = [vp, ip, ip]
+    L.lp_profile_read_layer.argtypes = [vp, ip, ip, C.POINTER(C.c_double), C.POINTER(C.c_long), ip]
     L.lp_profile.argtypes = [vp, ip]
     L.lp_profile_read.argtypes = [vp, ip, C.POINTER(C.c_double), C.POINTER(C.c_long), ip]
     for name in EXPORTS:
@@ -216,6 +218,16 @@ def lp_partition(t_fix, t_flex, n_proc: int, alpha: float = 1.01):
     st, dr, bf, tt, tp = (C.c_int * L)(), (C.c_int * L)(), arr(), (C.c_double * n_proc)(), C.c_double()
     _check(None, lib().lp_partition(arr(*t_fix), arr(*t_flex), L, n_proc, alpha, st, dr, bf, tt, C.byref(tp)))
     return dict(stage_fix=list(st), stage_delta_rest=list(dr), borrowed_frac=list(bf), stage_time=list(tt), t_p=tp.value)
+
+
+def lp_set_delta_split(ctx, l: int, cols: int):
+    _check(ctx, lib().lp_set_delta_split(ctx, l, cols))
+
+
+def lp_profile_read_layer(ctx, task: int, l: int, reset: bool = False):
+    ms, n = C.c_double(), C.c_long()
+    _check(ctx, lib().lp_profile_read_layer(ctx, task, l, C.byref(ms), C.byref(n), int(reset)))
+    return ms.value, n.value
 
 
 def lp_profile(ctx, enable: bool):

@@ -29,6 +29,7 @@ struct Layer {
   bool has_A = false, has_Z = false, has_dA = false;
   int ring_slots = 1;
   int delay = 0;       // active d_l
+  int split_cols = 0;  // last columns of dA_{l-1} computed as a second, independent kernel (delta'')
   int cur = 0;         // working-weight buffer F and dX read now
   bool weights_set = false;
 };
@@ -47,16 +48,16 @@ struct lp_ctx {
   long n = 0;
   std::string err;
   bool events_ready = false;
-  std::vector<hipEvent_t> ev_dy, ev_dx, ev_dw;
+  std::vector<hipEvent_t> ev_dy, ev_dx, ev_dw, ev_split;
   hipEvent_t ev_fork = nullptr, ev_join_w = nullptr, ev_join_u = nullptr;
   std::vector<hipStream_t> streams_seen;
   // measurement aid (lp_profile)
-  struct ProfRec { int task; hipEvent_t e0, e1; };
+  struct ProfRec { int task, layer; hipEvent_t e0, e1; };
   bool prof_on = false;
   std::vector<ProfRec> prof_recs;
   std::vector<hipEvent_t> prof_free;
-  double prof_ms[LP_TASK_COUNT] = {0, 0, 0, 0, 0, 0};
-  long prof_n[LP_TASK_COUNT] = {0, 0, 0, 0, 0, 0};
+  std::vector<double> prof_ms;   // [task * (L + 1) + layer], layer 0 = not tied to a layer (loss)
+  std::vector<long> prof_n;
 };
 
 namespace {
@@ -92,7 +93,7 @@ struct ProfScope {
   lp_ctx* c;
   hipStream_t s;
   hipEvent_t e1 = nullptr;
-  ProfScope(lp_ctx* c_, int task, hipStream_t s_) : c(c_), s(s_) {
+  ProfScope(lp_ctx* c_, int task, int layer, hipStream_t s_) : c(c_), s(s_) {
     if (!c->prof_on) return;
     hipEvent_t ev[2] = {nullptr, nullptr};
     for (hipEvent_t& e : ev) {
@@ -105,7 +106,7 @@ struct ProfScope {
     }
     (void)hipEventRecord(ev[0], s);
     e1 = ev[1];
-    c->prof_recs.push_back({task, ev[0], ev[1]});
+    c->prof_recs.push_back({task, layer, ev[0], ev[1]});
   }
   ~ProfScope() {
     if (e1) (void)hipEventRecord(e1, s);
@@ -126,6 +127,7 @@ int need_weights(lp_ctx* c, int l) {
   return LP_OK;
 }
 
+inline int layer_no(const lp_ctx* c, const Layer& ly) { return (int)(&ly - c->layers.data()) + 1; }
 inline void* work_w(lp_ctx* c, Layer& ly) {
   return is_bf16(c) ? (void*)(c->ws + ly.off_work[ly.cur]) : (void*)(c->ws + ly.off_master);
 }
@@ -140,7 +142,7 @@ inline lp::ConvDesc conv_desc(const lp_ctx* c, const Layer& ly) {
 
 // ---- the tasks, shared by the per-layer entry points and lp_step -------------------------------
 hipError_t do_forward(lp_ctx* c, Layer& ly, const void* X, void* Z, void* A, hipStream_t s) {
-  ProfScope prof(c, LP_TASK_F, s);
+  ProfScope prof(c, LP_TASK_F, layer_no(c, ly), s);
   if (ly.d.kind == LP_LINEAR) {
     lp::GemmDesc g;
     g.A = X; g.B = work_w(c, ly);
@@ -160,7 +162,7 @@ hipError_t do_forward(lp_ctx* c, Layer& ly, const void* X, void* Z, void* A, hip
 }
 
 hipError_t do_grad_act(lp_ctx* c, Layer& ly, const void* dY, void* dX, int c0, int c1, hipStream_t s) {
-  ProfScope prof(c, LP_TASK_DX, s);
+  ProfScope prof(c, LP_TASK_DX, layer_no(c, ly), s);
   if (ly.d.kind == LP_LINEAR) {
     lp::GemmDesc g;
     const size_t es = esize(c);
@@ -175,7 +177,7 @@ hipError_t do_grad_act(lp_ctx* c, Layer& ly, const void* dY, void* dX, int c0, i
 }
 
 hipError_t do_grad_weight(lp_ctx* c, Layer& ly, const void* X, const void* dY, float* G, hipStream_t s) {
-  ProfScope prof(c, LP_TASK_DW, s);
+  ProfScope prof(c, LP_TASK_DW, layer_no(c, ly), s);
   if (ly.d.kind == LP_LINEAR) {
     lp::GemmDesc g;
     g.A = X; g.B = dY;
@@ -189,14 +191,14 @@ hipError_t do_grad_weight(lp_ctx* c, Layer& ly, const void* X, const void* dY, f
 }
 
 hipError_t do_act_grad(lp_ctx* c, Layer& ly, const void* dA, const void* S, void* dY, hipStream_t s) {
-  ProfScope prof(c, LP_TASK_HADAMARD, s);
+  ProfScope prof(c, LP_TASK_HADAMARD, layer_no(c, ly), s);
   if (ly.d.kind == LP_CONV3X3 && ly.d.pool == 2)
     return lp::launch_act_grad_pool(is_bf16(c), ly.d.act, dA, S, dY, c->batch, ly.d.H, ly.d.W, ly.d.out, s);
   return lp::launch_act_grad(is_bf16(c), ly.d.act, dA, S, dY, ly.z_elems, s);
 }
 
 hipError_t do_loss(lp_ctx* c, const void* ZL, const void* target, void* dYL, float* loss_dev, hipStream_t s) {
-  ProfScope prof(c, LP_TASK_LOSS, s);
+  ProfScope prof(c, LP_TASK_LOSS, 0, s);
   const Layer& last = c->layers[c->L - 1];
   float* partials = (float*)(c->ws + c->off_partials);
   if (c->loss == LP_LOSS_SOFTMAX_CE)
@@ -206,7 +208,7 @@ hipError_t do_loss(lp_ctx* c, const void* ZL, const void* target, void* dYL, flo
 
 // Applies W <- W - lr*G; BF16 writes the other working buffer.  Does not flip `cur`.
 hipError_t do_update(lp_ctx* c, Layer& ly, const float* G, hipStream_t s) {
-  ProfScope prof(c, LP_TASK_UPDATE, s);
+  ProfScope prof(c, LP_TASK_UPDATE, layer_no(c, ly), s);
   float* master = (float*)(c->ws + ly.off_master);
   void* work_out = is_bf16(c) ? (void*)(c->ws + ly.off_work[ly.cur ^ 1]) : nullptr;
   return lp::launch_sgd(master, G, work_out, c->lr, ly.n_params, s);
@@ -218,7 +220,9 @@ int ensure_events(lp_ctx* c) {
   c->ev_dy.assign(c->L, nullptr);
   c->ev_dx.assign(c->L, nullptr);
   c->ev_dw.assign(c->L, nullptr);
+  c->ev_split.assign(c->L, nullptr);
   for (int l = 0; l < c->L; ++l) {
+    LP_HIP(c, mk(&c->ev_split[l]));
     LP_HIP(c, mk(&c->ev_dy[l]));
     LP_HIP(c, mk(&c->ev_dx[l]));
     LP_HIP(c, mk(&c->ev_dw[l]));
@@ -329,7 +333,7 @@ int lp_create(const lp_layer_desc* layers, int L, int batch, int dtype, int loss
 int lp_destroy(lp_ctx* c) {
   if (!c) return LP_ERR_NULL;
   if (c->events_ready) {
-    for (auto* v : {&c->ev_dy, &c->ev_dx, &c->ev_dw})
+    for (auto* v : {&c->ev_dy, &c->ev_dx, &c->ev_dw, &c->ev_split})
       for (hipEvent_t e : *v)
         if (e) (void)hipEventDestroy(e);
     for (hipEvent_t e : {c->ev_fork, c->ev_join_w, c->ev_join_u})
@@ -471,6 +475,16 @@ int lp_update(lp_ctx* c, int l, const float* G, void* stream) {
   return LP_OK;
 }
 
+int lp_set_delta_split(lp_ctx* c, int l, int cols) {
+  if (!c) return LP_ERR_NULL;
+  if (int r = check_layer(c, l)) return r;
+  Layer& ly = c->layers[l - 1];
+  if (l == 1 && cols != 0) return fail(c, LP_ERR_LAYER, "lp_set_delta_split: layer 1 has no delta task");
+  if (cols < 0 || cols >= ly.d.in) return fail(c, LP_ERR_SHAPE, "lp_set_delta_split: %d columns outside [0, %d)", cols, ly.d.in);
+  ly.split_cols = cols;
+  return LP_OK;
+}
+
 int lp_advance(lp_ctx* c) {
   if (!c) return LP_ERR_NULL;
   c->n += 1;
@@ -545,7 +559,18 @@ int lp_step(lp_ctx* c, const void* X0, const void* target, const int* delay, flo
     const void* dY = c->ws + ly.off_dY;
     if (i > 0) {
       Layer& pv = c->layers[i - 1];
-      LP_HIP(c, do_grad_act(c, ly, dY, c->ws + pv.off_dA, 0, ly.d.in, sC));
+      if (ly.split_cols > 0) {
+        // delta' on the critical stream, delta'' (the columns the next stage borrowed, Sec. III-B) as an
+        // independent kernel on the stream that otherwise carries the G tasks, ahead of this layer's G
+        const int cut = ly.d.in - ly.split_cols;
+        if (multi && sW != sC) LP_HIP(c, hipStreamWaitEvent(sW, c->ev_dy[i], 0));
+        LP_HIP(c, do_grad_act(c, ly, dY, c->ws + pv.off_dA, cut, ly.d.in, sW));
+        if (multi && sW != sC) LP_HIP(c, hipEventRecord(c->ev_split[i], sW));
+        LP_HIP(c, do_grad_act(c, ly, dY, c->ws + pv.off_dA, 0, cut, sC));
+        if (multi && sW != sC) LP_HIP(c, hipStreamWaitEvent(sC, c->ev_split[i], 0));
+      } else {
+        LP_HIP(c, do_grad_act(c, ly, dY, c->ws + pv.off_dA, 0, ly.d.in, sC));
+      }
       if (multi) LP_HIP(c, hipEventRecord(c->ev_dx[i], sC));
       if (pv.off_dY != pv.off_dA) {
         const void* S = pv.has_Z ? c->ws + pv.off_Z : c->ws + pv.off_A;
@@ -617,24 +642,53 @@ int lp_profile(lp_ctx* c, int enable) {
   return LP_OK;
 }
 
-int lp_profile_read(lp_ctx* c, int task, double* total_ms, long* launches, int reset) {
-  if (!c) return LP_ERR_NULL;
-  if (task < 0 || task >= LP_TASK_COUNT) return fail(c, LP_ERR_DTYPE, "lp_profile_read: unknown task %d", task);
-  std::vector<lp_ctx::ProfRec> keep;
+namespace {
+int profile_collect(lp_ctx* c) {
+  if (c->prof_ms.empty()) {
+    c->prof_ms.assign((size_t)LP_TASK_COUNT * (c->L + 1), 0.0);
+    c->prof_n.assign((size_t)LP_TASK_COUNT * (c->L + 1), 0);
+  }
   for (auto& r : c->prof_recs) {
-    if (r.task != task) { keep.push_back(r); continue; }
     LP_HIP(c, hipEventSynchronize(r.e1));
     float ms = 0.f;
     LP_HIP(c, hipEventElapsedTime(&ms, r.e0, r.e1));
-    c->prof_ms[task] += ms;
-    c->prof_n[task] += 1;
+    const size_t k = (size_t)r.task * (c->L + 1) + r.layer;
+    c->prof_ms[k] += ms;
+    c->prof_n[k] += 1;
     c->prof_free.push_back(r.e0);
     c->prof_free.push_back(r.e1);
   }
-  c->prof_recs.swap(keep);
-  if (total_ms) *total_ms = c->prof_ms[task];
-  if (launches) *launches = c->prof_n[task];
-  if (reset) { c->prof_ms[task] = 0; c->prof_n[task] = 0; }
+  c->prof_recs.clear();
+  return LP_OK;
+}
+}  // namespace
+
+int lp_profile_read(lp_ctx* c, int task, double* total_ms, long* launches, int reset) {
+  if (!c) return LP_ERR_NULL;
+  if (task < 0 || task >= LP_TASK_COUNT) return fail(c, LP_ERR_DTYPE, "lp_profile_read: unknown task %d", task);
+  if (int r = profile_collect(c)) return r;
+  double ms = 0.0;
+  long n = 0;
+  for (int l = 0; l <= c->L; ++l) {
+    const size_t k = (size_t)task * (c->L + 1) + l;
+    ms += c->prof_ms[k];
+    n += c->prof_n[k];
+    if (reset) { c->prof_ms[k] = 0; c->prof_n[k] = 0; }
+  }
+  if (total_ms) *total_ms = ms;
+  if (launches) *launches = n;
+  return LP_OK;
+}
+
+int lp_profile_read_layer(lp_ctx* c, int task, int l, double* total_ms, long* launches, int reset) {
+  if (!c) return LP_ERR_NULL;
+  if (task < 0 || task >= LP_TASK_COUNT) return fail(c, LP_ERR_DTYPE, "lp_profile_read_layer: unknown task %d", task);
+  if (int r = check_layer(c, l)) return r;
+  if (int r = profile_collect(c)) return r;
+  const size_t k = (size_t)task * (c->L + 1) + l;
+  if (total_ms) *total_ms = c->prof_ms[k];
+  if (launches) *launches = c->prof_n[k];
+  if (reset) { c->prof_ms[k] = 0; c->prof_n[k] = 0; }
   return LP_OK;
 }
 

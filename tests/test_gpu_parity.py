@@ -425,3 +425,34 @@ def test_step_delay_override_and_errors():
         assert relerr(net.get_weights(l), ora.W[l - 1]) <= 2e-2
     assert not np.array_equal(net.get_weights(1), W0[0])
     net.close()
+
+
+@pytest.mark.parametrize("n_streams", [1, 3])
+def test_delta_split_inside_step_changes_no_bits(n_streams):
+    """delta' on the critical stream and delta'' as an independent kernel (Sec. III-B): same weights, bit for bit."""
+    wl = WL.mlp_4096().with_(layers=WL._mlp([256, 320, 192, 136, 40], WL.RELU), batch=96, delays=(6, 4, 2, 0))
+    W0 = WL.init_weights(wl)
+    outs = []
+    for splits in (None, {2: 104, 3: 1, 4: 135}):
+        net = lp.Network(wl.layers, wl.batch, wl.dtype, wl.loss, wl.lr, wl.delays, n_streams=n_streams)
+        net.set_weights(W0)
+        if splits:
+            for l, c in splits.items():
+                lp.lp_set_delta_split(net.ctx, l, c)
+        losses = [net.step(WL.batch_input(wl, n), WL.batch_target(wl, n)) for n in range(1, 9)]
+        outs.append((losses, [net.get_weights(l) for l in range(1, wl.L + 1)]))
+        net.close()
+    assert outs[0][0] == outs[1][0]
+    assert all(np.array_equal(a, b) for a, b in zip(outs[0][1], outs[1][1]))
+
+
+def test_delta_split_argument_errors():
+    wl = WL.mlp_4096().with_(layers=WL._mlp([64, 48, 16], WL.RELU), batch=16, delays=(2, 0))
+    net = lp.Network(wl.layers, wl.batch, wl.dtype, wl.loss, wl.lr, wl.delays)
+    for l, c, status in ((1, 8, 4), (2, 48, 2), (2, -1, 2), (3, 1, 4)):
+        with pytest.raises(lp.LpError) as ei:
+            lp.lp_set_delta_split(net.ctx, l, c)
+        assert ei.value.status == status
+    lp.lp_set_delta_split(net.ctx, 2, 47)
+    lp.lp_set_delta_split(net.ctx, 1, 0)
+    net.close()
