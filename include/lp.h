@@ -119,7 +119,11 @@ int lp_get_weights(lp_ctx* ctx, int l, float* dst, int is_device, void* stream);
 /* F (Eq. 1, Eq. 2).  X: A_{l-1}, act type, [batch, in] (conv: [batch,H,W,in]).  Writes Z_l (shape
  * [batch,out] / [batch,H,W,out]) and A_l = f(Z_l) (conv with pool: [batch,H/2,W/2,out]); either
  * may be NULL to skip that output, except that a pooled layer needs Z.  A is computed from the
- * stored (rounded) Z.  Reads the current working weights W_l(n-1). */
+ * stored (rounded) Z.  Reads the current working weights W_l(n-1).
+ * Scratch: products with few output tiles and a long reduction are split over K, with fp32 partial
+ * sums in the workspace.  A context has three such regions: (a) lp_forward and lp_grad_act calls whose
+ * range starts at column 0, (b) lp_grad_act calls whose range starts elsewhere, (c) lp_grad_weight.
+ * Calls that use one region must not overlap in time: enqueue them on one stream, or order them. */
 int lp_forward(lp_ctx* ctx, int l, const void* X, void* Z, void* A, void* stream);
 
 /* Error at the output and delta of the last layer (the paper only says the error is computed from
@@ -139,7 +143,9 @@ int lp_act_grad(lp_ctx* ctx, int l, const void* dA, const void* S, void* dY, voi
 /* dX (Eq. 4): dA_{l-1}[:, col0:col1] = dY_l . W_l[col0:col1, :]^T with the current working weights.
  * dX is the full [batch, in] tensor (conv: [batch,H,W,in]); only columns (channels) [col0, col1)
  * of the previous layer's features are written.  (0, in) computes all of it; two calls with
- * complementary ranges are the delta' / delta'' partition of Sec. III-B and may run concurrently. */
+ * complementary ranges are the delta' / delta'' partition of Sec. III-B and may run concurrently
+ * (one range starting at column 0, one not: see the scratch note at lp_forward).  Every element is
+ * summed in the same order whatever the range: cutting the columns changes no bits. */
 int lp_grad_act(lp_ctx* ctx, int l, const void* dY, void* dX, int col0, int col1, void* stream);
 
 /* dW (Eq. 5): G_l = A_{l-1}^T . dY_l, float, shape of W_l.  G == NULL writes into the ring slot of

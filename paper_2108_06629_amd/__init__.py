@@ -292,7 +292,10 @@ class Network:
         """Host array -> device tensor of the act type (labels: int32).  bf16 is torch's
         round-to-nearest-even cast of the fp32 input."""
         t = self.torch.from_numpy(np.ascontiguousarray(x)).to(self.device)
-        return t.to(self.torch.int32) if is_label else t.to(self.act_dtype).contiguous()
+        t = t.to(self.torch.int32) if is_label else t.to(self.act_dtype).contiguous()
+        # the cast ran on torch's stream; the library's streams are not ordered after it
+        self.torch.cuda.current_stream(self.device).synchronize()
+        return t
 
     def step_device(self, x_dev, t_dev, delay=None):
         """Enqueues one training step; returns nothing.  `self.loss_dev` holds the loss afterwards."""

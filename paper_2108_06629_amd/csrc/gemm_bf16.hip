@@ -26,6 +26,8 @@ struct GemmKArgs {
   int M, N, K, lda, ldb, ldc, act;
   unsigned a_bytes, b_bytes;
   int vec_out;
+  int kt_per_split;     // split-K: K tiles per workgroup in y (0: no split)
+  float* partial;       // split-K: [gridDim.y][M][N] fp32
 };
 
 template <bool KC, int R, int BK, int NT, bool ALIGNED>
@@ -68,8 +70,50 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_bf16_dl_kernel(GemmKArgs p) 
   typename dl::OperandSel<BKC, BN, BK, WM * WN>::type ob;
   oa.init(p.A, p.a_bytes, tm * BM, p.M, p.K, p.lda);
   ob.init(p.B, p.b_bytes, tn * BN, p.N, p.K, p.ldb);
+  const int KT = (p.K + BK - 1) / BK;
+  if (p.kt_per_split > 0) {
+    // split-K: this workgroup multiplies K tiles [kt0, kt1) and writes an fp32 partial
+    const int kt0 = blockIdx.y * p.kt_per_split;
+    const int kt1 = kt0 + p.kt_per_split < KT ? kt0 + p.kt_per_split : KT;
+    const int k_end = kt1 * BK < p.K ? kt1 * BK : p.K;
+    oa.Ktot = k_end;
+    ob.Ktot = k_end;
+    StoreEpilogue epi{nullptr, nullptr, p.partial + (size_t)blockIdx.y * p.M * p.N, p.M, p.N, p.N, 0, tm * BM, tn * BN, (p.N % 4) == 0};   // M*N*4 bytes per split: 16-byte aligned when N % 4 == 0
+    dl::gemm_tile_dl<BM, BN, BK, NSTAGE, WM, WN>(oa, ob, kt0 * BK, kt1 > kt0 ? kt1 - kt0 : 0, smem, epi);
+    return;
+  }
   StoreEpilogue epi{p.out_z, p.out_a, p.out_f32, p.M, p.N, p.ldc, p.act, tm * BM, tn * BN, p.vec_out != 0};
-  dl::gemm_tile_dl<BM, BN, BK, NSTAGE, WM, WN>(oa, ob, (p.K + BK - 1) / BK, smem, epi);
+  dl::gemm_tile_dl<BM, BN, BK, NSTAGE, WM, WN>(oa, ob, 0, KT, smem, epi);
+}
+
+// sums the split-K partials in a fixed order and applies the epilogue (rounding, activation);
+// one thread per group of four columns of a row
+__global__ void __launch_bounds__(256) splitk_reduce_kernel(const float* __restrict__ part, int splits, GemmKArgs p) {
+  const int ng = (p.N + 3) / 4;
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= (size_t)p.M * ng) return;
+  const int row = (int)(i / ng), col = (int)(i % ng) * 4;
+  const size_t mn = (size_t)p.M * p.N, o = (size_t)row * p.N + col;
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  if (p.N % 4 == 0) {
+    acc = *reinterpret_cast<const f32x4*>(part + o);
+    for (int s = 1; s < splits; ++s) {
+      const f32x4 v = *reinterpret_cast<const f32x4*>(part + (size_t)s * mn + o);
+#pragma unroll
+      for (int t = 0; t < 4; ++t) acc[t] += v[t];
+    }
+  } else {
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      if (col + t < p.N) {
+        float a = part[o + t];
+        for (int s = 1; s < splits; ++s) a += part[(size_t)s * mn + o + t];
+        acc[t] = a;
+      }
+    }
+  }
+  StoreEpilogue epi{p.out_z, p.out_a, p.out_f32, p.M, p.N, p.ldc, p.act, 0, 0, p.vec_out != 0};
+  epi(row, col, acc);
 }
 
 template <int BM, int BN, int BK, int NSTAGE, int WM, int WN, bool AKC, bool BKC>
@@ -83,6 +127,17 @@ hipError_t launch_dl(const GemmKArgs& a, hipStream_t s) {
     attr_done = true;
   }
   const int nb = ((a.M + BM - 1) / BM) * ((a.N + BN - 1) / BN);
+  if (a.kt_per_split > 0) {
+    // one K range per workgroup row of the grid, then a reduction that applies the real epilogue
+    const int KT = (a.K + BK - 1) / BK;
+    const int splits = (KT + a.kt_per_split - 1) / a.kt_per_split;
+    hipLaunchKernelGGL(kern, dim3(nb, splits), dim3(WM * WN * 64), lds, s, a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const size_t n4 = (size_t)a.M * ((a.N + 3) / 4);
+    hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, s, (const float*)a.partial, splits, a);
+    return hipGetLastError();
+  }
   hipLaunchKernelGGL(kern, dim3(nb), dim3(WM * WN * 64), lds, s, a);
   return hipGetLastError();
 }
@@ -136,7 +191,25 @@ hipError_t launch_cfg_dl(int cfg, const GemmKArgs& a, hipStream_t s) {
   return hipErrorInvalidValue;
 }
 
+// how many K ranges a product on 128x128 tiles is cut into (1: not split)
+int splitk_factor(int M, int N, int K) {
+  const long t256 = (long)((M + 255) / 256) * ((N + 255) / 256);
+  const long t128 = (long)((M + 127) / 128) * ((N + 127) / 128);
+  if (t256 >= 192 || t128 >= 256 || K < 1024) return 1;
+  long s = 512 / t128;               // two workgroups per CU
+  if (s > K / 256) s = K / 256;      // at least four K steps each
+  if (s > 16) s = 16;
+  return s < 2 ? 1 : (int)s;
+}
+
 }  // namespace
+
+int gemm_bf16_splitk_splits(int M, int N, int K) { return splitk_factor(M, N, K); }
+
+size_t gemm_bf16_splitk_bytes(int M, int N, int K) {
+  const int s = splitk_factor(M, N, K);
+  return s > 1 ? ((size_t)s * M * N * sizeof(float) + 255) / 256 * 256 : 0;
+}
 
 int gemm_bf16_num_cfgs() { return (int)(sizeof(kCfgs) / sizeof(kCfgs[0])); }
 const char* gemm_bf16_cfg_name(int cfg) { return (cfg >= 0 && cfg < gemm_bf16_num_cfgs()) ? kCfgs[cfg].name : "?"; }
@@ -163,6 +236,8 @@ hipError_t launch_gemm_bf16(const GemmDesc& d, hipStream_t s, int tile_cfg) {
   a.b_bytes = (unsigned)(b_elems * 2);
   a.vec_out = (d.N % 4 == 0) && (d.ldc % 4 == 0) && ((uintptr_t)d.out_z % 8 == 0) && ((uintptr_t)d.out_a % 8 == 0) &&
               ((uintptr_t)d.out_f32 % 16 == 0);
+  a.kt_per_split = 0;
+  a.partial = nullptr;
 
   // 16-byte loads need every contiguous run to start on a multiple of 8 elements
   const int a_contig = d.a_kcontig ? d.K : d.M, b_contig = d.b_kcontig ? d.K : d.N;
@@ -186,6 +261,23 @@ hipError_t launch_gemm_bf16(const GemmDesc& d, hipStream_t s, int tile_cfg) {
   if (cfg < 0 || cfg >= gemm_bf16_num_cfgs()) return hipErrorInvalidValue;
   if (kCfgs[cfg].kind == 1) {
     if (!aligned) return hipErrorInvalidValue;
+    if (cfg == 5 && tile_cfg < 0) {
+      // 128x128 tiles that do not fill the chip and a long reduction: split K over workgroups.  A caller
+      // that multiplies a column range of a larger product passes the split count of the whole product,
+      // so that every output element is summed in the same order however the columns are cut.
+      const int splits = d.splitk_splits >= 0 ? d.splitk_splits : splitk_factor(d.M, d.N, d.K);
+      if (splits > 1) {
+        const bool fits = d.splitk_scratch && d.splitk_bytes >= (size_t)splits * d.M * d.N * sizeof(float) &&
+                          (uintptr_t)d.splitk_scratch % 16 == 0;
+        if (fits) {
+          const int KT = (d.K + 63) / 64;
+          a.kt_per_split = (KT + splits - 1) / splits;
+          a.partial = d.splitk_scratch;
+        } else if (d.splitk_splits > 1) {
+          return hipErrorInvalidValue;   // a forced split count must not silently change the summation order
+        }
+      }
+    }
     if (d.a_kcontig && d.b_kcontig) return launch_cfg_dl<true, true>(cfg, a, s);
     if (d.a_kcontig && !d.b_kcontig) return launch_cfg_dl<true, false>(cfg, a, s);
     if (!d.a_kcontig && !d.b_kcontig) return launch_cfg_dl<false, false>(cfg, a, s);

@@ -153,9 +153,10 @@ __device__ __forceinline__ void wait_vmcnt() {
   __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
 }
 
-// smem: NSTAGE * (BM + BN) * BK halves.  KT = number of K tiles.
+// smem: NSTAGE * (BM + BN) * BK halves.  Multiplies the KT K-tiles that start at reduction index k_base
+// (split-K: a workgroup takes a K range and the operands' Ktot is the end of that range).
 template <int BM, int BN, int BK, int NSTAGE, int WM, int WN, class OA, class OB, class Epi>
-__device__ __forceinline__ void gemm_tile_dl(const OA& oa, const OB& ob, int KT, unsigned short* smem, Epi epi) {
+__device__ __forceinline__ void gemm_tile_dl(const OA& oa, const OB& ob, int k_base, int KT, unsigned short* smem, Epi epi) {
   constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
   constexpr int A_ELEMS = BM * BK, B_ELEMS = BN * BK, STAGE = A_ELEMS + B_ELEMS;
   constexpr int LOADS = OA::PER_WAVE + OB::PER_WAVE;        // buffer loads per lane per tile
@@ -188,8 +189,8 @@ __device__ __forceinline__ void gemm_tile_dl(const OA& oa, const OB& ob, int KT,
   // the number of loads in flight stays the same in every iteration, which keeps the vmcnt waits exact
   auto issue = [&](int t) {
     unsigned short* st = smem + (t % NSTAGE) * STAGE;
-    oa.issue(t * BK, st, wave);
-    ob.issue(t * BK, st + A_ELEMS, wave);
+    oa.issue(k_base + t * BK, st, wave);
+    ob.issue(k_base + t * BK, st + A_ELEMS, wave);
   };
 
   // scheduling pattern of one substep: one LDS fragment read after each of the first MFMAs

@@ -44,6 +44,9 @@ struct lp_ctx {
   float lr = 0.f;
   size_t ws_bytes = 0;
   size_t off_partials = 0, off_conv_scratch = 0;
+  // split-K partial sums: [0] F and dX column ranges that start at column 0, [1] dW, [2] dX column
+  // ranges that start elsewhere (delta' next to delta'' on another stream)
+  size_t off_splitk[3] = {0, 0, 0}, splitk_bytes[3] = {0, 0, 0};
   char* ws = nullptr;
   long n = 0;
   std::string err;
@@ -150,6 +153,7 @@ hipError_t do_forward(lp_ctx* c, Layer& ly, const void* X, void* Z, void* A, hip
     g.lda = ly.d.in; g.ldb = ly.d.out; g.ldc = ly.d.out;
     g.a_kcontig = true; g.b_kcontig = false;
     g.out_z = Z; g.out_a = A; g.act = ly.d.act;
+    g.splitk_scratch = (float*)(c->ws + c->off_splitk[0]); g.splitk_bytes = c->splitk_bytes[0];
     return is_bf16(c) ? lp::launch_gemm_bf16(g, s) : lp::launch_gemm_f32(g, s);
   }
   const lp::ConvDesc cd = conv_desc(c, ly);
@@ -171,6 +175,10 @@ hipError_t do_grad_act(lp_ctx* c, Layer& ly, const void* dY, void* dX, int c0, i
     g.lda = ly.d.out; g.ldb = ly.d.out; g.ldc = ly.d.in;
     g.a_kcontig = true; g.b_kcontig = true;
     g.out_z = (char*)dX + (size_t)c0 * es;
+    // K is cut as for the whole product, whatever the column range: the split changes no bits
+    const int sk = c0 == 0 ? 0 : 2;
+    g.splitk_splits = lp::gemm_bf16_splitk_splits(c->batch, ly.d.in, ly.d.out);
+    g.splitk_scratch = (float*)(c->ws + c->off_splitk[sk]); g.splitk_bytes = c->splitk_bytes[sk];
     return is_bf16(c) ? lp::launch_gemm_bf16(g, s) : lp::launch_gemm_f32(g, s);
   }
   return lp::launch_conv_grad_act(conv_desc(c, ly), is_bf16(c), dY, work_w(c, ly), dX, c0, c1, s);
@@ -185,6 +193,7 @@ hipError_t do_grad_weight(lp_ctx* c, Layer& ly, const void* X, const void* dY, f
     g.lda = ly.d.in; g.ldb = ly.d.out; g.ldc = ly.d.out;
     g.a_kcontig = false; g.b_kcontig = false;
     g.out_f32 = G;
+    g.splitk_scratch = (float*)(c->ws + c->off_splitk[1]); g.splitk_bytes = c->splitk_bytes[1];
     return is_bf16(c) ? lp::launch_gemm_bf16(g, s) : lp::launch_gemm_f32(g, s);
   }
   return lp::launch_conv_grad_weight(conv_desc(c, ly), is_bf16(c), X, dY, G, (float*)(c->ws + c->off_conv_scratch), s);
@@ -325,6 +334,19 @@ int lp_create(const lp_layer_desc* layers, int L, int batch, int dtype, int loss
   const Layer& lastl = c->layers[L - 1];
   c->off_partials = take(lp::loss_partials_count(loss == LP_LOSS_MSE, batch, lastl.out_feat) * 4);
   c->off_conv_scratch = take(conv_scratch);
+  if (dtype == LP_BF16) {
+    for (int i = 0; i < L; ++i) {
+      const Layer& ly = c->layers[i];
+      if (ly.d.kind != LP_LINEAR) continue;
+      const size_t f = lp::gemm_bf16_splitk_bytes(batch, ly.d.out, ly.d.in), dx = lp::gemm_bf16_splitk_bytes(batch, ly.d.in, ly.d.out);
+      const size_t dw = lp::gemm_bf16_splitk_bytes(ly.d.in, ly.d.out, batch);
+      if (f > c->splitk_bytes[0]) c->splitk_bytes[0] = f;
+      if (dx > c->splitk_bytes[0]) c->splitk_bytes[0] = dx;
+      if (dx > c->splitk_bytes[2]) c->splitk_bytes[2] = dx;
+      if (dw > c->splitk_bytes[1]) c->splitk_bytes[1] = dw;
+    }
+    for (int k = 0; k < 3; ++k) c->off_splitk[k] = take(c->splitk_bytes[k]);
+  }
   c->ws_bytes = off;
   *out = c;
   return LP_OK;

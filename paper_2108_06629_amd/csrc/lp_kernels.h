@@ -24,7 +24,19 @@ struct GemmDesc {
   void* out_a = nullptr;
   float* out_f32 = nullptr;
   int act = ACT_IDENTITY;
+  // optional scratch for split-K partial sums (fp32); the launcher splits K when the output has too
+  // few tiles to occupy the chip and the scratch is large enough
+  float* splitk_scratch = nullptr;
+  size_t splitk_bytes = 0;
+  // < 0: the launcher decides from this product's shape; >= 1: exactly this many K ranges (1: none).
+  // A column range of a larger product passes the count of the whole product so that the summation
+  // order of an output element does not depend on how the columns are cut.
+  int splitk_splits = -1;
 };
+// K ranges the launcher cuts a product of this shape into (1: not split), and the scratch that takes
+// (0: split-K would not be used)
+int gemm_bf16_splitk_splits(int M, int N, int K);
+size_t gemm_bf16_splitk_bytes(int M, int N, int K);
 
 // tile_cfg < 0: pick by problem size.  Returns hipErrorInvalidValue for impossible shapes.
 hipError_t launch_gemm_bf16(const GemmDesc& d, hipStream_t s, int tile_cfg = -1);

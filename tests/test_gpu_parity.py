@@ -27,7 +27,11 @@ def relerr(got, ref):
 
 
 def dev(x, dtype):
-    return torch.from_numpy(np.ascontiguousarray(x)).to(DEV).to(dtype).contiguous()
+    """Host array -> device tensor.  The cast runs on torch's stream, which the library's streams are
+    not ordered after: wait for it here so that a kernel enqueued next reads finished data."""
+    t = torch.from_numpy(np.ascontiguousarray(x)).to(DEV).to(dtype).contiguous()
+    torch.cuda.synchronize()
+    return t
 
 
 def host(t):
@@ -50,7 +54,7 @@ def one_layer_net(d_in, d_out, batch, act="relu", dtype="bf16", seed=0):
 # degenerate sizes.
 FWD_SHAPES = [(96, 200, 136), (33, 77, 19), (1, 8, 8), (7, 1, 3), (300, 520, 264), (64, 4096, 64),
               (1100, 72, 3000), (2304, 96, 5632), (256, 512, 1000), (1024, 136, 6200), (2300, 100, 5700),
-              (1101, 71, 3001)]
+              (1101, 71, 3001), (256, 2048, 512), (300, 1032, 1160)]     # the last two (and (64, 4096, 64), (1100, 72, 3000) for dW) split K
 
 
 @pytest.mark.parametrize("shape", FWD_SHAPES)
