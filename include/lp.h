@@ -167,6 +167,16 @@ int lp_update(lp_ctx* ctx, int l, const float* G, void* stream);
  * on cols.  0 <= cols < D_{l-1}; layer 1 has no delta task. */
 int lp_set_delta_split(lp_ctx* ctx, int l, int cols);
 
+/* Forward run-ahead across steps (Sec. III-A, the schedule of Fig. 6 on one device): with enable != 0,
+ * lp_step runs the forward chain and the loss on streams[3] and no longer joins the streams between
+ * steps, so F_l(n+1) starts as soon as W_l(n) exists (which needs only G_l(n - d_l)) and overlaps the
+ * backward pass of step n.  Each layer then keeps two stashes (A_l, Z_l of steps n and n+1), so the
+ * workspace grows: call this after lp_create and before lp_workspace_bytes / lp_bind_workspace
+ * (LP_ERR_STATE afterwards).  lp_step then needs n_streams >= 4, all different (LP_ERR_STATE).
+ * Results are those of the serial order, bit for bit.  X0 and target of a step must stay unchanged
+ * until that step has finished.  LP_BF16 contexts only (LP_ERR_DTYPE): F32 updates weights in place. */
+int lp_set_run_ahead(lp_ctx* ctx, int enable);
+
 /* Ends a step driven through the per-layer calls: n <- n + 1. */
 int lp_advance(lp_ctx* ctx);
 

@@ -25,7 +25,8 @@ struct Layer {
   size_t in_elems = 0, z_elems = 0, a_elems = 0;  // whole batch
   int in_feat = 0, out_feat = 0;                  // per-sample flattened sizes
   size_t off_master = 0, off_work[2] = {0, 0}, off_ring = 0;
-  size_t off_A = 0, off_Z = 0, off_dA = 0, off_dY = 0;
+  size_t off_A[2] = {0, 0}, off_Z[2] = {0, 0};   // stashes; [1] differs from [0] only with forward run-ahead
+  size_t off_dA = 0, off_dY = 0;
   bool has_A = false, has_Z = false, has_dA = false;
   int ring_slots = 1;
   int delay = 0;       // active d_l
@@ -45,14 +46,17 @@ struct lp_ctx {
   size_t ws_bytes = 0;
   size_t off_partials = 0, off_conv_scratch = 0;
   // split-K partial sums: [0] F and dX column ranges that start at column 0, [1] dW, [2] dX column
-  // ranges that start elsewhere (delta' next to delta'' on another stream)
-  size_t off_splitk[3] = {0, 0, 0}, splitk_bytes[3] = {0, 0, 0};
+  // ranges that start elsewhere (delta' next to delta'' on another stream), [3] F on the forward
+  // stream of a run-ahead step (next to the dX of the step before)
+  size_t off_splitk[4] = {0, 0, 0, 0}, splitk_bytes[4] = {0, 0, 0, 0};
+  bool run_ahead = false;
   char* ws = nullptr;
   long n = 0;
   std::string err;
   bool events_ready = false;
-  std::vector<hipEvent_t> ev_dy, ev_dx, ev_dw, ev_split;
+  std::vector<hipEvent_t> ev_dy, ev_dx, ev_dw, ev_split, ev_upd;
   hipEvent_t ev_fork = nullptr, ev_join_w = nullptr, ev_join_u = nullptr;
+  hipEvent_t ev_loss[2] = {nullptr, nullptr}, ev_bdone[2] = {nullptr, nullptr};
   std::vector<hipStream_t> streams_seen;
   // measurement aid (lp_profile)
   struct ProfRec { int task, layer; hipEvent_t e0, e1; };
@@ -144,7 +148,8 @@ inline lp::ConvDesc conv_desc(const lp_ctx* c, const Layer& ly) {
 }
 
 // ---- the tasks, shared by the per-layer entry points and lp_step -------------------------------
-hipError_t do_forward(lp_ctx* c, Layer& ly, const void* X, void* Z, void* A, hipStream_t s) {
+// sk: which split-K scratch region a linear layer's product may use
+hipError_t do_forward(lp_ctx* c, Layer& ly, const void* X, void* Z, void* A, hipStream_t s, int sk = 0) {
   ProfScope prof(c, LP_TASK_F, layer_no(c, ly), s);
   if (ly.d.kind == LP_LINEAR) {
     lp::GemmDesc g;
@@ -153,7 +158,7 @@ hipError_t do_forward(lp_ctx* c, Layer& ly, const void* X, void* Z, void* A, hip
     g.lda = ly.d.in; g.ldb = ly.d.out; g.ldc = ly.d.out;
     g.a_kcontig = true; g.b_kcontig = false;
     g.out_z = Z; g.out_a = A; g.act = ly.d.act;
-    g.splitk_scratch = (float*)(c->ws + c->off_splitk[0]); g.splitk_bytes = c->splitk_bytes[0];
+    g.splitk_scratch = (float*)(c->ws + c->off_splitk[sk]); g.splitk_bytes = c->splitk_bytes[sk];
     return is_bf16(c) ? lp::launch_gemm_bf16(g, s) : lp::launch_gemm_f32(g, s);
   }
   const lp::ConvDesc cd = conv_desc(c, ly);
@@ -230,8 +235,10 @@ int ensure_events(lp_ctx* c) {
   c->ev_dx.assign(c->L, nullptr);
   c->ev_dw.assign(c->L, nullptr);
   c->ev_split.assign(c->L, nullptr);
+  c->ev_upd.assign(c->L, nullptr);
   for (int l = 0; l < c->L; ++l) {
     LP_HIP(c, mk(&c->ev_split[l]));
+    LP_HIP(c, mk(&c->ev_upd[l]));
     LP_HIP(c, mk(&c->ev_dy[l]));
     LP_HIP(c, mk(&c->ev_dx[l]));
     LP_HIP(c, mk(&c->ev_dw[l]));
@@ -239,7 +246,162 @@ int ensure_events(lp_ctx* c) {
   LP_HIP(c, mk(&c->ev_fork));
   LP_HIP(c, mk(&c->ev_join_w));
   LP_HIP(c, mk(&c->ev_join_u));
+  for (int p = 0; p < 2; ++p) { LP_HIP(c, mk(&c->ev_loss[p])); LP_HIP(c, mk(&c->ev_bdone[p])); }
   c->events_ready = true;
+  return LP_OK;
+}
+
+// Offsets of everything the context keeps in the caller's workspace.  Depends on the layer table and
+// on whether forward run-ahead is enabled (two stashes per layer then).
+void layout_workspace(lp_ctx* c) {
+  const int L = c->L;
+  const size_t es = esize(c);
+  for (size_t& b : c->splitk_bytes) b = 0;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes); return o; };
+  size_t conv_scratch = 0;
+  for (int i = 0; i < L; ++i) {
+    Layer& ly = c->layers[i];
+    const bool last = i == L - 1;
+    const bool pooled = ly.d.kind == LP_CONV3X3 && ly.d.pool == 2;
+    ly.off_master = take(ly.n_params * 4);
+    if (c->dtype == LP_BF16) { ly.off_work[0] = take(ly.n_params * 2); ly.off_work[1] = take(ly.n_params * 2); }
+    ly.off_ring = take((size_t)ly.ring_slots * ly.n_params * 4);
+    ly.has_A = !last;
+    ly.has_Z = last || pooled || ly.d.act == LP_ACT_GELU;
+    ly.has_dA = !last;
+    for (int p = 0; p < 2; ++p) {
+      if (p == 1 && !c->run_ahead) { ly.off_A[1] = ly.off_A[0]; ly.off_Z[1] = ly.off_Z[0]; break; }
+      if (ly.has_A) ly.off_A[p] = take(ly.a_elems * es);
+      if (ly.has_Z) ly.off_Z[p] = take(ly.z_elems * es);
+    }
+    if (ly.has_dA) ly.off_dA = take(ly.a_elems * es);
+    // identity hidden layer without pool: delta equals dA, share the buffer
+    if (ly.has_dA && ly.d.act == LP_ACT_IDENTITY && !pooled) ly.off_dY = ly.off_dA;
+    else ly.off_dY = take(ly.z_elems * es);
+    if (ly.d.kind == LP_CONV3X3) {
+      size_t sc = lp::conv_grad_weight_scratch_bytes(conv_desc(c, ly));
+      if (sc > conv_scratch) conv_scratch = sc;
+    }
+  }
+  const Layer& lastl = c->layers[L - 1];
+  c->off_partials = take(lp::loss_partials_count(c->loss == LP_LOSS_MSE, c->batch, lastl.out_feat) * 4);
+  c->off_conv_scratch = take(conv_scratch);
+  if (c->dtype == LP_BF16) {
+    for (int i = 0; i < L; ++i) {
+      const Layer& ly = c->layers[i];
+      if (ly.d.kind != LP_LINEAR) continue;
+      const size_t f = lp::gemm_bf16_splitk_bytes(c->batch, ly.d.out, ly.d.in), dx = lp::gemm_bf16_splitk_bytes(c->batch, ly.d.in, ly.d.out);
+      const size_t dw = lp::gemm_bf16_splitk_bytes(ly.d.in, ly.d.out, c->batch);
+      if (f > c->splitk_bytes[0]) c->splitk_bytes[0] = f;
+      if (dx > c->splitk_bytes[0]) c->splitk_bytes[0] = dx;
+      if (dx > c->splitk_bytes[2]) c->splitk_bytes[2] = dx;
+      if (dw > c->splitk_bytes[1]) c->splitk_bytes[1] = dw;
+      if (c->run_ahead && f > c->splitk_bytes[3]) c->splitk_bytes[3] = f;
+    }
+    for (int k = 0; k < 4; ++k) c->off_splitk[k] = take(c->splitk_bytes[k]);
+  }
+  c->ws_bytes = off;
+}
+
+// One training step with the forward pass on a stream of its own, so that F(n+1) overlaps the backward
+// pass of step n wherever the delays allow it (Sec. III-A: the weights F_l(n+1) reads, W_l(n), need only
+// G_l(n - d_l)).  The arithmetic of every task, and so every result, is that of the serial order; only
+// the waits differ.  Streams: sF forward chain and loss, sC delta chain, sW G tasks, sU updates.
+// There is no fork/join per step; each hazard has its own event (an event that was never recorded
+// does not block, which covers the first steps):
+//   stash A_l/Z_l[n&1]  written by F_l(n), read by G_{l+1}(n) and the Hadamard of layer l in B(n):
+//                       F(n+2) waits for the end of B(n) (ev_bdone[n&1])
+//   working weights     F_l(n+1) waits for update_l(n) (ev_upd[l]); update_l(n+1) overwrites the copy
+//                       that F_l(n) and dX_l(n) read: it waits for dX_l(n) (layer 1: for the loss of step n)
+//   gradient ring       update_l(n) waits for the newest G_l (ev_dw[l]); G_l(n) overwrites the slot
+//                       update_l(n-1) read: it waits for ev_upd[l]
+//   dY_L                written by the loss of step n+1: waits for dX_L(n) and G_L(n)
+//   delta chain         B(n) starts at the loss of step n (ev_loss[n&1]); within B(n) as in the serial step,
+//                       and sC ends each step by waiting for that step's G tasks, so dA/dY buffers are free
+int step_run_ahead(lp_ctx* c, const void* X0, const void* target, float* loss_dev, void* const* streams) {
+  hipStream_t sC = (hipStream_t)streams[0], sW = (hipStream_t)streams[1], sU = (hipStream_t)streams[2], sF = (hipStream_t)streams[3];
+  for (hipStream_t s : {sC, sW, sU, sF}) note_stream(c, s);
+  if (int r = ensure_events(c)) return r;
+  const int L = c->L;
+  const long n = c->n + 1;
+  const int p = (int)(n & 1);
+  std::vector<char> updated(L, 0);
+
+  auto issue_update = [&](int i) -> int {
+    Layer& ly = c->layers[i];
+    const long src = n - ly.delay;
+    if (src < 1) return LP_OK;
+    LP_HIP(c, hipStreamWaitEvent(sU, c->ev_dw[i], 0));                       // G_l(src) is in the ring
+    LP_HIP(c, hipStreamWaitEvent(sU, i > 0 ? c->ev_dx[i] : c->ev_loss[p ^ 1], 0));   // readers of the copy being overwritten
+    LP_HIP(c, do_update(c, ly, ring_slot(c, ly, src), sU));
+    LP_HIP(c, hipEventRecord(c->ev_upd[i], sU));
+    updated[i] = 1;
+    return LP_OK;
+  };
+  // forward chain of step n on sF
+  LP_HIP(c, hipStreamWaitEvent(sF, c->ev_bdone[p], 0));
+  const void* a_prev = X0;
+  for (int i = 0; i < L; ++i) {
+    Layer& ly = c->layers[i];
+    void* Z = ly.has_Z ? c->ws + ly.off_Z[p] : nullptr;
+    void* A = ly.has_A ? c->ws + ly.off_A[p] : nullptr;
+    LP_HIP(c, hipStreamWaitEvent(sF, c->ev_upd[i], 0));   // W_l(n-1) is complete (recorded by update_l(n-1) at the latest)
+    LP_HIP(c, do_forward(c, ly, a_prev, Z, A, sF, 3));
+    a_prev = A;
+  }
+  Layer& last = c->layers[L - 1];
+  LP_HIP(c, hipStreamWaitEvent(sF, c->ev_dx[L - 1], 0));
+  LP_HIP(c, hipStreamWaitEvent(sF, c->ev_dw[L - 1], 0));
+  LP_HIP(c, do_loss(c, c->ws + last.off_Z[p], target, c->ws + last.off_dY, loss_dev, sF));
+  LP_HIP(c, hipEventRecord(c->ev_loss[p], sF));
+
+  // Updates that need no gradient of this step (their G tasks ran in earlier steps).  Enqueued after
+  // the forward chain so that F_l(n) above waited for update_l(n-1), not for these.
+  for (int i = L - 1; i >= 0; --i)
+    if (c->layers[i].delay > 0)
+      if (int r = issue_update(i)) return r;
+
+  // backward pass of step n
+  LP_HIP(c, hipStreamWaitEvent(sC, c->ev_loss[p], 0));
+  LP_HIP(c, hipEventRecord(c->ev_dy[L - 1], sC));
+  for (int i = L - 1; i >= 0; --i) {
+    Layer& ly = c->layers[i];
+    const void* x_in = i == 0 ? X0 : (const void*)(c->ws + c->layers[i - 1].off_A[p]);
+    const void* dY = c->ws + ly.off_dY;
+    if (i > 0) {
+      Layer& pv = c->layers[i - 1];
+      if (ly.split_cols > 0) {
+        const int cut = ly.d.in - ly.split_cols;
+        LP_HIP(c, hipStreamWaitEvent(sW, c->ev_dy[i], 0));
+        LP_HIP(c, do_grad_act(c, ly, dY, c->ws + pv.off_dA, cut, ly.d.in, sW));
+        LP_HIP(c, hipEventRecord(c->ev_split[i], sW));
+        LP_HIP(c, do_grad_act(c, ly, dY, c->ws + pv.off_dA, 0, cut, sC));
+        LP_HIP(c, hipStreamWaitEvent(sC, c->ev_split[i], 0));
+      } else {
+        LP_HIP(c, do_grad_act(c, ly, dY, c->ws + pv.off_dA, 0, ly.d.in, sC));
+      }
+      LP_HIP(c, hipEventRecord(c->ev_dx[i], sC));
+      if (pv.off_dY != pv.off_dA) {
+        const void* S = pv.has_Z ? c->ws + pv.off_Z[p] : c->ws + pv.off_A[p];
+        LP_HIP(c, do_act_grad(c, pv, c->ws + pv.off_dA, S, c->ws + pv.off_dY, sC));
+      }
+      LP_HIP(c, hipEventRecord(c->ev_dy[i - 1], sC));
+    }
+    LP_HIP(c, hipStreamWaitEvent(sW, c->ev_dy[i], 0));
+    LP_HIP(c, hipStreamWaitEvent(sW, c->ev_upd[i], 0));   // the ring slot's previous gradient has been applied
+    LP_HIP(c, do_grad_weight(c, ly, x_in, dY, ring_slot(c, ly, n), sW));
+    LP_HIP(c, hipEventRecord(c->ev_dw[i], sW));
+    if (!updated[i])
+      if (int r = issue_update(i)) return r;
+  }
+  LP_HIP(c, hipEventRecord(c->ev_join_w, sW));
+  LP_HIP(c, hipStreamWaitEvent(sC, c->ev_join_w, 0));
+  LP_HIP(c, hipEventRecord(c->ev_bdone[p], sC));
+
+  for (int i = 0; i < L; ++i)
+    if (updated[i]) c->layers[i].cur ^= 1;
+  c->n = n;
   return LP_OK;
 }
 
@@ -257,7 +419,6 @@ int lp_create(const lp_layer_desc* layers, int L, int batch, int dtype, int loss
   if (!c) return fail(nullptr, LP_ERR_STATE, "lp_create: out of host memory");
   c->L = L; c->batch = batch; c->dtype = dtype; c->loss = loss; c->lr = lr;
   c->layers.resize(L);
-  const size_t es = dtype == LP_BF16 ? 2 : 4;
   int prev_out_feat = -1, prevH = 0, prevW = 0, prevC = 0;
   bool prev_conv = false;
   for (int i = 0; i < L; ++i) {
@@ -306,48 +467,7 @@ int lp_create(const lp_layer_desc* layers, int L, int batch, int dtype, int loss
     ly.delay = d.delay;
     ly.ring_slots = d.delay + 1;
   }
-  // workspace layout
-  size_t off = 0;
-  auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes); return o; };
-  size_t conv_scratch = 0;
-  for (int i = 0; i < L; ++i) {
-    Layer& ly = c->layers[i];
-    const bool last = i == L - 1;
-    const bool pooled = ly.d.kind == LP_CONV3X3 && ly.d.pool == 2;
-    ly.off_master = take(ly.n_params * 4);
-    if (dtype == LP_BF16) { ly.off_work[0] = take(ly.n_params * 2); ly.off_work[1] = take(ly.n_params * 2); }
-    ly.off_ring = take((size_t)ly.ring_slots * ly.n_params * 4);
-    ly.has_A = !last;
-    ly.has_Z = last || pooled || ly.d.act == LP_ACT_GELU;
-    ly.has_dA = !last;
-    if (ly.has_A) ly.off_A = take(ly.a_elems * es);
-    if (ly.has_Z) ly.off_Z = take(ly.z_elems * es);
-    if (ly.has_dA) ly.off_dA = take(ly.a_elems * es);
-    // identity hidden layer without pool: delta equals dA, share the buffer
-    if (ly.has_dA && ly.d.act == LP_ACT_IDENTITY && !pooled) ly.off_dY = ly.off_dA;
-    else ly.off_dY = take(ly.z_elems * es);
-    if (ly.d.kind == LP_CONV3X3) {
-      size_t sc = lp::conv_grad_weight_scratch_bytes(conv_desc(c, ly));
-      if (sc > conv_scratch) conv_scratch = sc;
-    }
-  }
-  const Layer& lastl = c->layers[L - 1];
-  c->off_partials = take(lp::loss_partials_count(loss == LP_LOSS_MSE, batch, lastl.out_feat) * 4);
-  c->off_conv_scratch = take(conv_scratch);
-  if (dtype == LP_BF16) {
-    for (int i = 0; i < L; ++i) {
-      const Layer& ly = c->layers[i];
-      if (ly.d.kind != LP_LINEAR) continue;
-      const size_t f = lp::gemm_bf16_splitk_bytes(batch, ly.d.out, ly.d.in), dx = lp::gemm_bf16_splitk_bytes(batch, ly.d.in, ly.d.out);
-      const size_t dw = lp::gemm_bf16_splitk_bytes(ly.d.in, ly.d.out, batch);
-      if (f > c->splitk_bytes[0]) c->splitk_bytes[0] = f;
-      if (dx > c->splitk_bytes[0]) c->splitk_bytes[0] = dx;
-      if (dx > c->splitk_bytes[2]) c->splitk_bytes[2] = dx;
-      if (dw > c->splitk_bytes[1]) c->splitk_bytes[1] = dw;
-    }
-    for (int k = 0; k < 3; ++k) c->off_splitk[k] = take(c->splitk_bytes[k]);
-  }
-  c->ws_bytes = off;
+  layout_workspace(c);
   *out = c;
   return LP_OK;
 }
@@ -355,10 +475,10 @@ int lp_create(const lp_layer_desc* layers, int L, int batch, int dtype, int loss
 int lp_destroy(lp_ctx* c) {
   if (!c) return LP_ERR_NULL;
   if (c->events_ready) {
-    for (auto* v : {&c->ev_dy, &c->ev_dx, &c->ev_dw, &c->ev_split})
+    for (auto* v : {&c->ev_dy, &c->ev_dx, &c->ev_dw, &c->ev_split, &c->ev_upd})
       for (hipEvent_t e : *v)
         if (e) (void)hipEventDestroy(e);
-    for (hipEvent_t e : {c->ev_fork, c->ev_join_w, c->ev_join_u})
+    for (hipEvent_t e : {c->ev_fork, c->ev_join_w, c->ev_join_u, c->ev_loss[0], c->ev_loss[1], c->ev_bdone[0], c->ev_bdone[1]})
       if (e) (void)hipEventDestroy(e);
   }
   for (auto& r : c->prof_recs) { (void)hipEventDestroy(r.e0); (void)hipEventDestroy(r.e1); }
@@ -415,6 +535,8 @@ int lp_get_weights(lp_ctx* c, int l, float* dst, int is_device, void* stream) {
   const float* master = (const float*)(c->ws + ly.off_master);
   if (is_device) LP_HIP(c, hipMemcpyAsync(dst, master, ly.n_params * 4, hipMemcpyDeviceToDevice, s));
   else {
+    // run-ahead steps do not join the update stream into any other: wait for all of them
+    if (c->run_ahead) for (hipStream_t t : c->streams_seen) LP_HIP(c, hipStreamSynchronize(t));
     LP_HIP(c, hipStreamSynchronize(s));
     LP_HIP(c, hipMemcpy(dst, master, ly.n_params * 4, hipMemcpyDeviceToHost));
   }
@@ -507,6 +629,15 @@ int lp_set_delta_split(lp_ctx* c, int l, int cols) {
   return LP_OK;
 }
 
+int lp_set_run_ahead(lp_ctx* c, int enable) {
+  if (!c) return LP_ERR_NULL;
+  if (c->ws) return fail(c, LP_ERR_STATE, "lp_set_run_ahead: call it before lp_bind_workspace (it changes the workspace size)");
+  if (enable && !is_bf16(c)) return fail(c, LP_ERR_DTYPE, "lp_set_run_ahead: needs an LP_BF16 context (F32 updates the weights in place)");
+  c->run_ahead = enable != 0;
+  layout_workspace(c);
+  return LP_OK;
+}
+
 int lp_advance(lp_ctx* c) {
   if (!c) return LP_ERR_NULL;
   c->n += 1;
@@ -525,6 +656,13 @@ int lp_step(lp_ctx* c, const void* X0, const void* target, const int* delay, flo
       if (delay[l] < 0 || delay[l] > c->layers[l].d.delay)
         return fail(c, LP_ERR_DELAY, "lp_step: delay[%d] = %d outside [0, %d]", l, delay[l], c->layers[l].d.delay);
     for (int l = 0; l < c->L; ++l) c->layers[l].delay = delay[l];
+  }
+  if (c->run_ahead) {
+    if (n_streams < 4) return fail(c, LP_ERR_STATE, "lp_step: forward run-ahead needs 4 streams, %d given", n_streams);
+    for (int a = 0; a < 4; ++a)
+      for (int b = a + 1; b < 4; ++b)
+        if (streams[a] == streams[b]) return fail(c, LP_ERR_STATE, "lp_step: forward run-ahead needs 4 different streams");
+    return step_run_ahead(c, X0, target, loss_dev, streams);
   }
   const bool multi = n_streams > 1;
   hipStream_t sC = (hipStream_t)streams[0];
@@ -565,19 +703,19 @@ int lp_step(lp_ctx* c, const void* X0, const void* target, const int* delay, flo
   const void* a_prev = X0;
   for (int i = 0; i < L; ++i) {
     Layer& ly = c->layers[i];
-    void* Z = ly.has_Z ? c->ws + ly.off_Z : nullptr;
-    void* A = ly.has_A ? c->ws + ly.off_A : nullptr;
+    void* Z = ly.has_Z ? c->ws + ly.off_Z[0] : nullptr;
+    void* A = ly.has_A ? c->ws + ly.off_A[0] : nullptr;
     LP_HIP(c, do_forward(c, ly, a_prev, Z, A, sC));
     a_prev = A;
   }
   Layer& last = c->layers[L - 1];
-  LP_HIP(c, do_loss(c, c->ws + last.off_Z, target, c->ws + last.off_dY, loss_dev, sC));
+  LP_HIP(c, do_loss(c, c->ws + last.off_Z[0], target, c->ws + last.off_dY, loss_dev, sC));
   if (multi) LP_HIP(c, hipEventRecord(c->ev_dy[L - 1], sC));
 
   // backward: the delta chain on sC first (critical loop), G on sW, updates on sU
   for (int i = L - 1; i >= 0; --i) {
     Layer& ly = c->layers[i];
-    const void* x_in = i == 0 ? X0 : (const void*)(c->ws + c->layers[i - 1].off_A);
+    const void* x_in = i == 0 ? X0 : (const void*)(c->ws + c->layers[i - 1].off_A[0]);
     const void* dY = c->ws + ly.off_dY;
     if (i > 0) {
       Layer& pv = c->layers[i - 1];
@@ -595,7 +733,7 @@ int lp_step(lp_ctx* c, const void* X0, const void* target, const int* delay, flo
       }
       if (multi) LP_HIP(c, hipEventRecord(c->ev_dx[i], sC));
       if (pv.off_dY != pv.off_dA) {
-        const void* S = pv.has_Z ? c->ws + pv.off_Z : c->ws + pv.off_A;
+        const void* S = pv.has_Z ? c->ws + pv.off_Z[0] : c->ws + pv.off_A[0];
         LP_HIP(c, do_act_grad(c, pv, c->ws + pv.off_dA, S, c->ws + pv.off_dY, sC));
       }
       if (multi) LP_HIP(c, hipEventRecord(c->ev_dy[i - 1], sC));
@@ -648,8 +786,8 @@ int lp_tensor(lp_ctx* c, int l, int which, void** dev_ptr, size_t* bytes) {
   switch (which) {
     case LP_T_MASTER_W: *dev_ptr = c->ws + ly.off_master; *bytes = ly.n_params * 4; break;
     case LP_T_WORK_W: *dev_ptr = work_w(c, ly); *bytes = ly.n_params * es; break;
-    case LP_T_A: if (ly.has_A) { *dev_ptr = c->ws + ly.off_A; *bytes = ly.a_elems * es; } break;
-    case LP_T_Z: if (ly.has_Z) { *dev_ptr = c->ws + ly.off_Z; *bytes = ly.z_elems * es; } break;
+    case LP_T_A: if (ly.has_A) { *dev_ptr = c->ws + ly.off_A[c->n & 1]; *bytes = ly.a_elems * es; } break;
+    case LP_T_Z: if (ly.has_Z) { *dev_ptr = c->ws + ly.off_Z[c->n & 1]; *bytes = ly.z_elems * es; } break;
     case LP_T_DA: if (ly.has_dA) { *dev_ptr = c->ws + ly.off_dA; *bytes = ly.a_elems * es; } break;
     case LP_T_DY: *dev_ptr = c->ws + ly.off_dY; *bytes = ly.z_elems * es; break;
     case LP_T_G_LAST: if (c->n >= 1) { *dev_ptr = ring_slot(c, ly, c->n); *bytes = ly.n_params * 4; } break;

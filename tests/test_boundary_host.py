@@ -116,3 +116,25 @@ def test_state_and_argument_errors_before_any_launch():
     assert L.lp_destroy(None) == 1
     with pytest.raises(lp.LpError):
         lp.lp_create(descs(wl), wl.L, -3, lp.LP_F32, 0, 0.1)
+
+
+def test_run_ahead_is_a_layout_decision_made_before_binding():
+    wl = WL.mlp_4096()
+    ctx = lp.lp_create(descs(wl), wl.L, wl.batch, lp.LP_BF16, lp.LP_LOSS_SOFTMAX_CE, 1e-3)
+    L = lp.lib()
+    n0 = lp.lp_workspace_bytes(ctx)
+    assert L.lp_set_run_ahead(ctx, 1) == 0
+    n1 = lp.lp_workspace_bytes(ctx)
+    # a second stash per layer: A_l for l < L (ReLU layers stash A only), Z_L for the last layer
+    stash = sum(wl.batch * ly.d_out * 2 for ly in wl.layers)
+    assert n1 % 256 == 0 and n0 + stash <= n1 <= n0 + stash + 64 * 2 ** 20
+    assert L.lp_set_run_ahead(ctx, 0) == 0 and lp.lp_workspace_bytes(ctx) == n0
+    assert L.lp_bind_workspace(ctx, 0x10000, 1 << 40) == 0                    # host bookkeeping only
+    assert L.lp_set_run_ahead(ctx, 1) == 6                                    # LP_ERR_STATE: workspace already bound
+    assert b"lp_bind_workspace" in L.lp_last_error(ctx)
+    lp.lp_destroy(ctx)
+    small = WL.mlp_small()
+    ctx = lp.lp_create(descs(small), small.L, small.batch, lp.LP_F32, lp.LP_LOSS_SOFTMAX_CE, 0.01)
+    assert L.lp_set_run_ahead(ctx, 1) == 3                                    # LP_ERR_DTYPE: F32 updates in place
+    assert L.lp_set_run_ahead(None, 1) == 1
+    lp.lp_destroy(ctx)

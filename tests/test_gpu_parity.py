@@ -280,7 +280,7 @@ def check_tasks_of_last_step(net, wl, x, target, W_before, G_hist, n):
             assert np.array_equal(work, O.round_bf16(w_new)), ("working copy", l, n)
 
 
-def run_trajectory(wl, steps, n_streams=3, taskwise=True):
+def run_trajectory(wl, steps, n_streams=3, taskwise=True, run_ahead=False):
     """Free-running comparison with the oracle: loss, Z_L and every W_l(n) in max-norm; every G_l in
     max-norm for fp32.  For bf16 the free-running G_l is compared in Frobenius norm against
     max(2e-2, the bf16 oracle's own distance from the unrounded float64 oracle): two correct
@@ -291,7 +291,7 @@ def run_trajectory(wl, steps, n_streams=3, taskwise=True):
     bf = wl.dtype == "bf16"
     storage = "bf16" if bf else "f32"
     W0 = WL.init_weights(wl)
-    net = lp.Network(wl.layers, wl.batch, wl.dtype, wl.loss, wl.lr, wl.delays, n_streams=n_streams)
+    net = lp.Network(wl.layers, wl.batch, wl.dtype, wl.loss, wl.lr, wl.delays, n_streams=n_streams, run_ahead=run_ahead)
     net.set_weights(W0)
     ora = O.DelayedGradientTrainer(wl.layers, W0, wl.delays, wl.lr, wl.loss, storage)
     exact = O.DelayedGradientTrainer(wl.layers, W0, wl.delays, wl.lr, wl.loss, "f64") if bf else None
