@@ -177,6 +177,22 @@ int lp_set_delta_split(lp_ctx* ctx, int l, int cols);
  * until that step has finished.  LP_BF16 contexts only (LP_ERR_DTYPE): F32 updates weights in place. */
 int lp_set_run_ahead(lp_ctx* ctx, int enable);
 
+/* Graph replay of whole steps: with enable != 0, lp_step captures the tasks of a step into a HIP graph
+ * the first time it sees that step's combination of buffers (ring slots, working-weight copies, the
+ * caller's X0 / target / loss_dev pointers and streams) and afterwards replays it with one launch on
+ * streams[0]; this removes the host cost of the 5-7 launches per layer, which bounds small networks.
+ * Gradient rings get a power-of-two number of slots (>= d_l + 1) so that the combinations repeat after
+ * max_l ring_l steps: the workspace grows, so call this after lp_create and before lp_workspace_bytes /
+ * lp_bind_workspace (LP_ERR_STATE afterwards).  Steps up to max d_l + 2 and steps run under lp_profile
+ * are enqueued as usual.  Feed lp_step from a small, repeating set of input buffers: each new pointer
+ * combination is a new capture (at most 512 are kept, further ones run uncaptured).  Results are those
+ * of the uncaptured step, bit for bit.  Not together with lp_set_run_ahead (LP_ERR_STATE). */
+int lp_set_graphs(lp_ctx* ctx, int enable);
+
+/* Counters of lp_step calls since lp_create on a context with graph replay: steps captured (and run),
+ * steps replayed from a captured graph, steps enqueued uncaptured.  Any pointer may be NULL. */
+int lp_graph_stats(const lp_ctx* ctx, long* captured, long* replayed, long* eager);
+
 /* Ends a step driven through the per-layer calls: n <- n + 1. */
 int lp_advance(lp_ctx* ctx);
 

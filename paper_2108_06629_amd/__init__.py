@@ -34,7 +34,7 @@ STATUS_NAMES = ["LP_OK", "LP_ERR_NULL", "LP_ERR_SHAPE", "LP_ERR_DTYPE", "LP_ERR_
 
 EXPORTS = ["lp_create", "lp_destroy", "lp_last_error", "lp_workspace_bytes", "lp_bind_workspace", "lp_set_weights",
            "lp_get_weights", "lp_forward", "lp_loss_grad", "lp_act_grad", "lp_grad_act", "lp_grad_weight", "lp_update",
-           "lp_advance", "lp_step", "lp_step_index", "lp_sync", "lp_tensor", "lp_profile", "lp_profile_read", "lp_profile_read_layer", "lp_partition", "lp_set_delta_split", "lp_set_run_ahead"]
+           "lp_advance", "lp_step", "lp_step_index", "lp_sync", "lp_tensor", "lp_profile", "lp_profile_read", "lp_profile_read_layer", "lp_partition", "lp_set_delta_split", "lp_set_run_ahead", "lp_set_graphs", "lp_graph_stats"]
 
 
 class lp_layer_desc(C.Structure):
@@ -83,6 +83,8 @@ def load_library():
     L.lp_partition.argtypes = [dp, dp, ip, ip, C.c_double, C.POINTER(ip), C.POINTER(ip), dp, dp, dp]
     L.lp_set_delta_split.argtypes = [vp, ip, ip]
     L.lp_set_run_ahead.argtypes = [vp, ip]
+    L.lp_set_graphs.argtypes = [vp, ip]
+    L.lp_graph_stats.argtypes = [vp, C.POINTER(C.c_long), C.POINTER(C.c_long), C.POINTER(C.c_long)]
     L.lp_profile_read_layer.argtypes = [vp, ip, ip, C.POINTER(C.c_double), C.POINTER(C.c_long), ip]
     L.lp_profile.argtypes = [vp, ip]
     L.lp_profile_read.argtypes = [vp, ip, C.POINTER(C.c_double), C.POINTER(C.c_long), ip]
@@ -225,6 +227,17 @@ def lp_set_delta_split(ctx, l: int, cols: int):
     _check(ctx, lib().lp_set_delta_split(ctx, l, cols))
 
 
+def lp_set_graphs(ctx, enable: bool):
+    _check(ctx, lib().lp_set_graphs(ctx, int(enable)))
+
+
+def lp_graph_stats(ctx):
+    """(captured, replayed, eager) step counts."""
+    a, b, c = C.c_long(), C.c_long(), C.c_long()
+    _check(ctx, lib().lp_graph_stats(ctx, C.byref(a), C.byref(b), C.byref(c)))
+    return a.value, b.value, c.value
+
+
 def lp_set_run_ahead(ctx, enable: bool):
     _check(ctx, lib().lp_set_run_ahead(ctx, int(enable)))
 
@@ -251,13 +264,15 @@ class Network:
     objects (kind, d_in, d_out, act, H, W, pool)."""
 
     def __init__(self, layers, batch: int, dtype: str, loss: str, lr: float, delays, device: str = "cuda:0", n_streams: int = 3,
-                 run_ahead: bool = False):
+                 run_ahead: bool = False, graphs: bool = False):
         import torch
         self.torch = torch
         self.layers, self.batch, self.dtype, self.loss = list(layers), batch, dtype, loss
         self.device = torch.device(device)
         self.ctx = lp_create(make_descs(layers, delays), len(layers), batch, _DTYPE[dtype], _LOSS[loss], float(lr))
         self.act_dtype = torch.bfloat16 if dtype == "bf16" else torch.float32
+        if graphs:
+            lp_set_graphs(self.ctx, True)
         if run_ahead:
             lp_set_run_ahead(self.ctx, True)
             n_streams = max(4, n_streams)

@@ -195,9 +195,9 @@ hipError_t launch_cfg_dl(int cfg, const GemmKArgs& a, hipStream_t s) {
 int splitk_factor(int M, int N, int K) {
   const long t256 = (long)((M + 255) / 256) * ((N + 255) / 256);
   const long t128 = (long)((M + 127) / 128) * ((N + 127) / 128);
-  if (t256 >= 192 || t128 >= 256 || K < 1024) return 1;
+  if (t256 >= 192 || t128 >= 256 || K < 2048) return 1;
   long s = 512 / t128;               // two workgroups per CU
-  if (s > K / 256) s = K / 256;      // at least four K steps each
+  if (s > K / 1024) s = K / 1024;    // at least sixteen K steps each: shorter ranges cost more in partial-sum traffic than they gain
   if (s > 16) s = 16;
   return s < 2 ? 1 : (int)s;
 }

@@ -50,6 +50,12 @@ struct lp_ctx {
   // stream of a run-ahead step (next to the dX of the step before)
   size_t off_splitk[4] = {0, 0, 0, 0}, splitk_bytes[4] = {0, 0, 0, 0};
   bool run_ahead = false;
+  // HIP-graph replay of whole steps (lp_set_graphs)
+  struct GraphEntry { std::string key; hipGraph_t graph; hipGraphExec_t exec; };
+  bool graphs = false;
+  int graph_period = 2;              // steps after which every buffer choice of a step repeats
+  std::vector<GraphEntry> graph_cache;
+  long graph_captured = 0, graph_replayed = 0, graph_eager = 0;
   char* ws = nullptr;
   long n = 0;
   std::string err;
@@ -257,6 +263,7 @@ void layout_workspace(lp_ctx* c) {
   const int L = c->L;
   const size_t es = esize(c);
   for (size_t& b : c->splitk_bytes) b = 0;
+  c->graph_period = 2;
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes); return o; };
   size_t conv_scratch = 0;
@@ -266,6 +273,11 @@ void layout_workspace(lp_ctx* c) {
     const bool pooled = ly.d.kind == LP_CONV3X3 && ly.d.pool == 2;
     ly.off_master = take(ly.n_params * 4);
     if (c->dtype == LP_BF16) { ly.off_work[0] = take(ly.n_params * 2); ly.off_work[1] = take(ly.n_params * 2); }
+    // d_l + 1 slots; with graph replay rounded up to a power of two, so that the slot a step uses repeats
+    // with a short common period
+    ly.ring_slots = ly.d.delay + 1;
+    if (c->graphs) { int r = 1; while (r < ly.ring_slots) r *= 2; ly.ring_slots = r; }
+    if (ly.ring_slots > c->graph_period) c->graph_period = ly.ring_slots;
     ly.off_ring = take((size_t)ly.ring_slots * ly.n_params * 4);
     ly.has_A = !last;
     ly.has_Z = last || pooled || ly.d.act == LP_ACT_GELU;
@@ -405,6 +417,166 @@ int step_run_ahead(lp_ctx* c, const void* X0, const void* target, float* loss_de
   return LP_OK;
 }
 
+// Enqueues every task of step n = c->n + 1 in the serial-step order: one fork from sC at the start, one
+// join into sC at the end, so the whole step is a single-entry, single-exit piece of work on sC (which
+// is what lets it be captured into a graph).  Changes no host state; `updated` says which layers'
+// working weights were rewritten.
+int enqueue_step(lp_ctx* c, const void* X0, const void* target, float* loss_dev, hipStream_t sC, hipStream_t sW, hipStream_t sU,
+                 bool multi, std::vector<char>& updated) {
+  const int L = c->L;
+  const long n = c->n + 1;  // the step in progress
+  const bool bf = is_bf16(c);
+  updated.assign(L, 0);
+
+  if (multi) {
+    LP_HIP(c, hipEventRecord(c->ev_fork, sC));
+    if (sW != sC) LP_HIP(c, hipStreamWaitEvent(sW, c->ev_fork, 0));
+    if (sU != sC) LP_HIP(c, hipStreamWaitEvent(sU, c->ev_fork, 0));
+  }
+
+  // Delayed updates whose gradient is already in the ring (d_l > 0).  BF16 keeps two versions of
+  // the working weights, so W_l(n) can be produced while this step still reads W_l(n-1).
+  auto issue_update = [&](int i) -> int {
+    Layer& ly = c->layers[i];
+    const long src = n - ly.delay;
+    if (src >= 1) {
+      LP_HIP(c, do_update(c, ly, ring_slot(c, ly, src), sU));
+      updated[i] = 1;
+    }
+    return LP_OK;
+  };
+  if (bf)
+    for (int i = L - 1; i >= 0; --i)
+      if (c->layers[i].delay > 0)
+        if (int r = issue_update(i)) return r;
+
+  // forward chain
+  const void* a_prev = X0;
+  for (int i = 0; i < L; ++i) {
+    Layer& ly = c->layers[i];
+    void* Z = ly.has_Z ? c->ws + ly.off_Z[0] : nullptr;
+    void* A = ly.has_A ? c->ws + ly.off_A[0] : nullptr;
+    LP_HIP(c, do_forward(c, ly, a_prev, Z, A, sC));
+    a_prev = A;
+  }
+  Layer& last = c->layers[L - 1];
+  LP_HIP(c, do_loss(c, c->ws + last.off_Z[0], target, c->ws + last.off_dY, loss_dev, sC));
+  if (multi) LP_HIP(c, hipEventRecord(c->ev_dy[L - 1], sC));
+
+  // backward: the delta chain on sC first (critical loop), G on sW, updates on sU
+  for (int i = L - 1; i >= 0; --i) {
+    Layer& ly = c->layers[i];
+    const void* x_in = i == 0 ? X0 : (const void*)(c->ws + c->layers[i - 1].off_A[0]);
+    const void* dY = c->ws + ly.off_dY;
+    if (i > 0) {
+      Layer& pv = c->layers[i - 1];
+      if (ly.split_cols > 0) {
+        // delta' on the critical stream, delta'' (the columns the next stage borrowed, Sec. III-B) as an
+        // independent kernel on the stream that otherwise carries the G tasks, ahead of this layer's G
+        const int cut = ly.d.in - ly.split_cols;
+        if (multi && sW != sC) LP_HIP(c, hipStreamWaitEvent(sW, c->ev_dy[i], 0));
+        LP_HIP(c, do_grad_act(c, ly, dY, c->ws + pv.off_dA, cut, ly.d.in, sW));
+        if (multi && sW != sC) LP_HIP(c, hipEventRecord(c->ev_split[i], sW));
+        LP_HIP(c, do_grad_act(c, ly, dY, c->ws + pv.off_dA, 0, cut, sC));
+        if (multi && sW != sC) LP_HIP(c, hipStreamWaitEvent(sC, c->ev_split[i], 0));
+      } else {
+        LP_HIP(c, do_grad_act(c, ly, dY, c->ws + pv.off_dA, 0, ly.d.in, sC));
+      }
+      if (multi) LP_HIP(c, hipEventRecord(c->ev_dx[i], sC));
+      if (pv.off_dY != pv.off_dA) {
+        const void* S = pv.has_Z ? c->ws + pv.off_Z[0] : c->ws + pv.off_A[0];
+        LP_HIP(c, do_act_grad(c, pv, c->ws + pv.off_dA, S, c->ws + pv.off_dY, sC));
+      }
+      if (multi) LP_HIP(c, hipEventRecord(c->ev_dy[i - 1], sC));
+    }
+    if (multi && sW != sC) LP_HIP(c, hipStreamWaitEvent(sW, c->ev_dy[i], 0));
+    LP_HIP(c, do_grad_weight(c, ly, x_in, dY, ring_slot(c, ly, n), sW));
+    if (multi) LP_HIP(c, hipEventRecord(c->ev_dw[i], sW));
+    if (!updated[i]) {
+      // d_l = 0 needs this step's G; an F32 context updates in place, so it also has to wait for
+      // the last reader of W_l(n-1), which is dX_l (layer 1: the forward pass, long finished)
+      if (multi) {
+        if (ly.delay == 0 && sU != sW) LP_HIP(c, hipStreamWaitEvent(sU, c->ev_dw[i], 0));
+        if (!bf && sU != sC) LP_HIP(c, hipStreamWaitEvent(sU, i > 0 ? c->ev_dx[i] : c->ev_dy[L - 1], 0));
+      }
+      if (int r = issue_update(i)) return r;
+    }
+  }
+
+  if (multi) {
+    if (sW != sC) { LP_HIP(c, hipEventRecord(c->ev_join_w, sW)); LP_HIP(c, hipStreamWaitEvent(sC, c->ev_join_w, 0)); }
+    if (sU != sC) { LP_HIP(c, hipEventRecord(c->ev_join_u, sU)); LP_HIP(c, hipStreamWaitEvent(sC, c->ev_join_u, 0)); }
+  }
+  return LP_OK;
+}
+
+void drop_graphs(lp_ctx* c) {
+  for (auto& g : c->graph_cache) {
+    (void)hipGraphExecDestroy(g.exec);
+    (void)hipGraphDestroy(g.graph);
+  }
+  c->graph_cache.clear();
+}
+
+constexpr size_t kMaxGraphs = 512;
+
+// Runs step n = c->n + 1: eagerly, or (lp_set_graphs) as one graph launch on sC.  Every pointer a task
+// of the step uses is a function of the key below: the ring slots and the stash-free serial layout
+// repeat with c->graph_period, the working-weight copies with the layers' `cur` bits, the rest is the
+// caller's.  A step is captured the first time its key is seen and replayed afterwards.  Steps inside
+// the warm-up (some update still skipped) and profiled steps run eagerly.
+int run_or_replay_step(lp_ctx* c, const void* X0, const void* target, float* loss_dev, hipStream_t sC, hipStream_t sW, hipStream_t sU,
+                       bool multi, std::vector<char>& updated) {
+  const long n = c->n + 1;
+  long warm = 1;
+  for (const Layer& ly : c->layers)
+    if (ly.delay + 1 > warm) warm = ly.delay + 1;
+  // the step after the warm-up still runs eagerly: by then every kernel has been launched once
+  // outside a capture (first launches set function attributes)
+  if (!c->graphs || c->prof_on || n <= warm + 1) {
+    if (c->graphs) c->graph_eager += 1;
+    return enqueue_step(c, X0, target, loss_dev, sC, sW, sU, multi, updated);
+  }
+  std::string key;
+  auto put = [&](const void* p, size_t bytes) { key.append((const char*)p, bytes); };
+  const long phase = n % c->graph_period;
+  put(&phase, sizeof phase);
+  put(&X0, sizeof X0); put(&target, sizeof target); put(&loss_dev, sizeof loss_dev);
+  put(&sC, sizeof sC); put(&sW, sizeof sW); put(&sU, sizeof sU);
+  for (const Layer& ly : c->layers) { put(&ly.cur, sizeof ly.cur); put(&ly.delay, sizeof ly.delay); put(&ly.split_cols, sizeof ly.split_cols); }
+
+  updated.assign(c->L, 1);   // past the warm-up every layer is updated in every step
+  for (auto& g : c->graph_cache)
+    if (g.key == key) {
+      LP_HIP(c, hipGraphLaunch(g.exec, sC));
+      c->graph_replayed += 1;
+      return LP_OK;
+    }
+  if (c->graph_cache.size() >= kMaxGraphs) {   // a caller that never repeats its buffers: stay eager
+    c->graph_eager += 1;
+    return enqueue_step(c, X0, target, loss_dev, sC, sW, sU, multi, updated);
+  }
+  LP_HIP(c, hipStreamBeginCapture(sC, hipStreamCaptureModeThreadLocal));
+  const int r = enqueue_step(c, X0, target, loss_dev, sC, sW, sU, multi, updated);
+  hipGraph_t graph = nullptr;
+  const hipError_t e = hipStreamEndCapture(sC, &graph);
+  if (r != LP_OK) {
+    if (graph) (void)hipGraphDestroy(graph);
+    return r;
+  }
+  if (e != hipSuccess) return fail_hip(c, e, "hipStreamEndCapture");
+  hipGraphExec_t exec = nullptr;
+  const hipError_t ei = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
+  if (ei != hipSuccess) {
+    (void)hipGraphDestroy(graph);
+    return fail_hip(c, ei, "hipGraphInstantiate");
+  }
+  c->graph_cache.push_back({key, graph, exec});
+  c->graph_captured += 1;
+  LP_HIP(c, hipGraphLaunch(exec, sC));
+  return LP_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -481,6 +653,7 @@ int lp_destroy(lp_ctx* c) {
     for (hipEvent_t e : {c->ev_fork, c->ev_join_w, c->ev_join_u, c->ev_loss[0], c->ev_loss[1], c->ev_bdone[0], c->ev_bdone[1]})
       if (e) (void)hipEventDestroy(e);
   }
+  drop_graphs(c);
   for (auto& r : c->prof_recs) { (void)hipEventDestroy(r.e0); (void)hipEventDestroy(r.e1); }
   for (hipEvent_t e : c->prof_free) (void)hipEventDestroy(e);
   delete c;
@@ -500,6 +673,7 @@ int lp_bind_workspace(lp_ctx* c, void* dev_ptr, size_t bytes) {
   if (!dev_ptr) return fail(c, LP_ERR_NULL, "lp_bind_workspace: dev_ptr is NULL");
   if ((uintptr_t)dev_ptr % kAlign) return fail(c, LP_ERR_WORKSPACE, "lp_bind_workspace: pointer not %zu-byte aligned", kAlign);
   if (bytes < c->ws_bytes) return fail(c, LP_ERR_WORKSPACE, "lp_bind_workspace: %zu bytes given, %zu needed", bytes, c->ws_bytes);
+  drop_graphs(c);
   c->ws = (char*)dev_ptr;
   c->n = 0;
   for (Layer& ly : c->layers) { ly.weights_set = false; ly.cur = 0; }
@@ -629,10 +803,28 @@ int lp_set_delta_split(lp_ctx* c, int l, int cols) {
   return LP_OK;
 }
 
+int lp_set_graphs(lp_ctx* c, int enable) {
+  if (!c) return LP_ERR_NULL;
+  if (c->ws) return fail(c, LP_ERR_STATE, "lp_set_graphs: call it before lp_bind_workspace (it changes the workspace size)");
+  if (enable && c->run_ahead) return fail(c, LP_ERR_STATE, "lp_set_graphs: not together with forward run-ahead");
+  c->graphs = enable != 0;
+  layout_workspace(c);
+  return LP_OK;
+}
+
+int lp_graph_stats(const lp_ctx* c, long* captured, long* replayed, long* eager) {
+  if (!c) return LP_ERR_NULL;
+  if (captured) *captured = c->graph_captured;
+  if (replayed) *replayed = c->graph_replayed;
+  if (eager) *eager = c->graph_eager;
+  return LP_OK;
+}
+
 int lp_set_run_ahead(lp_ctx* c, int enable) {
   if (!c) return LP_ERR_NULL;
   if (c->ws) return fail(c, LP_ERR_STATE, "lp_set_run_ahead: call it before lp_bind_workspace (it changes the workspace size)");
   if (enable && !is_bf16(c)) return fail(c, LP_ERR_DTYPE, "lp_set_run_ahead: needs an LP_BF16 context (F32 updates the weights in place)");
+  if (enable && c->graphs) return fail(c, LP_ERR_STATE, "lp_set_run_ahead: not together with graph replay");
   c->run_ahead = enable != 0;
   layout_workspace(c);
   return LP_OK;
@@ -673,89 +865,10 @@ int lp_step(lp_ctx* c, const void* X0, const void* target, const int* delay, flo
     if (int r = ensure_events(c)) return r;
 
   const int L = c->L;
-  const long n = c->n + 1;  // the step in progress
+  const long n = c->n + 1;
   const bool bf = is_bf16(c);
-  std::vector<char> updated(L, 0);
-
-  if (multi) {
-    LP_HIP(c, hipEventRecord(c->ev_fork, sC));
-    if (sW != sC) LP_HIP(c, hipStreamWaitEvent(sW, c->ev_fork, 0));
-    if (sU != sC) LP_HIP(c, hipStreamWaitEvent(sU, c->ev_fork, 0));
-  }
-
-  // Delayed updates whose gradient is already in the ring (d_l > 0).  BF16 keeps two versions of
-  // the working weights, so W_l(n) can be produced while this step still reads W_l(n-1).
-  auto issue_update = [&](int i) -> int {
-    Layer& ly = c->layers[i];
-    const long src = n - ly.delay;
-    if (src >= 1) {
-      LP_HIP(c, do_update(c, ly, ring_slot(c, ly, src), sU));
-      updated[i] = 1;
-    }
-    return LP_OK;
-  };
-  if (bf)
-    for (int i = L - 1; i >= 0; --i)
-      if (c->layers[i].delay > 0)
-        if (int r = issue_update(i)) return r;
-
-  // forward chain
-  const void* a_prev = X0;
-  for (int i = 0; i < L; ++i) {
-    Layer& ly = c->layers[i];
-    void* Z = ly.has_Z ? c->ws + ly.off_Z[0] : nullptr;
-    void* A = ly.has_A ? c->ws + ly.off_A[0] : nullptr;
-    LP_HIP(c, do_forward(c, ly, a_prev, Z, A, sC));
-    a_prev = A;
-  }
-  Layer& last = c->layers[L - 1];
-  LP_HIP(c, do_loss(c, c->ws + last.off_Z[0], target, c->ws + last.off_dY, loss_dev, sC));
-  if (multi) LP_HIP(c, hipEventRecord(c->ev_dy[L - 1], sC));
-
-  // backward: the delta chain on sC first (critical loop), G on sW, updates on sU
-  for (int i = L - 1; i >= 0; --i) {
-    Layer& ly = c->layers[i];
-    const void* x_in = i == 0 ? X0 : (const void*)(c->ws + c->layers[i - 1].off_A[0]);
-    const void* dY = c->ws + ly.off_dY;
-    if (i > 0) {
-      Layer& pv = c->layers[i - 1];
-      if (ly.split_cols > 0) {
-        // delta' on the critical stream, delta'' (the columns the next stage borrowed, Sec. III-B) as an
-        // independent kernel on the stream that otherwise carries the G tasks, ahead of this layer's G
-        const int cut = ly.d.in - ly.split_cols;
-        if (multi && sW != sC) LP_HIP(c, hipStreamWaitEvent(sW, c->ev_dy[i], 0));
-        LP_HIP(c, do_grad_act(c, ly, dY, c->ws + pv.off_dA, cut, ly.d.in, sW));
-        if (multi && sW != sC) LP_HIP(c, hipEventRecord(c->ev_split[i], sW));
-        LP_HIP(c, do_grad_act(c, ly, dY, c->ws + pv.off_dA, 0, cut, sC));
-        if (multi && sW != sC) LP_HIP(c, hipStreamWaitEvent(sC, c->ev_split[i], 0));
-      } else {
-        LP_HIP(c, do_grad_act(c, ly, dY, c->ws + pv.off_dA, 0, ly.d.in, sC));
-      }
-      if (multi) LP_HIP(c, hipEventRecord(c->ev_dx[i], sC));
-      if (pv.off_dY != pv.off_dA) {
-        const void* S = pv.has_Z ? c->ws + pv.off_Z[0] : c->ws + pv.off_A[0];
-        LP_HIP(c, do_act_grad(c, pv, c->ws + pv.off_dA, S, c->ws + pv.off_dY, sC));
-      }
-      if (multi) LP_HIP(c, hipEventRecord(c->ev_dy[i - 1], sC));
-    }
-    if (multi && sW != sC) LP_HIP(c, hipStreamWaitEvent(sW, c->ev_dy[i], 0));
-    LP_HIP(c, do_grad_weight(c, ly, x_in, dY, ring_slot(c, ly, n), sW));
-    if (multi) LP_HIP(c, hipEventRecord(c->ev_dw[i], sW));
-    if (!updated[i]) {
-      // d_l = 0 needs this step's G; an F32 context updates in place, so it also has to wait for
-      // the last reader of W_l(n-1), which is dX_l (layer 1: the forward pass, long finished)
-      if (multi) {
-        if (ly.delay == 0 && sU != sW) LP_HIP(c, hipStreamWaitEvent(sU, c->ev_dw[i], 0));
-        if (!bf && sU != sC) LP_HIP(c, hipStreamWaitEvent(sU, i > 0 ? c->ev_dx[i] : c->ev_dy[L - 1], 0));
-      }
-      if (int r = issue_update(i)) return r;
-    }
-  }
-
-  if (multi) {
-    if (sW != sC) { LP_HIP(c, hipEventRecord(c->ev_join_w, sW)); LP_HIP(c, hipStreamWaitEvent(sC, c->ev_join_w, 0)); }
-    if (sU != sC) { LP_HIP(c, hipEventRecord(c->ev_join_u, sU)); LP_HIP(c, hipStreamWaitEvent(sC, c->ev_join_u, 0)); }
-  }
+  std::vector<char> updated;
+  if (int r = run_or_replay_step(c, X0, target, loss_dev, sC, sW, sU, multi, updated)) return r;
   if (bf)
     for (int i = 0; i < L; ++i)
       if (updated[i]) c->layers[i].cur ^= 1;

@@ -138,3 +138,22 @@ def test_run_ahead_is_a_layout_decision_made_before_binding():
     assert L.lp_set_run_ahead(ctx, 1) == 3                                    # LP_ERR_DTYPE: F32 updates in place
     assert L.lp_set_run_ahead(None, 1) == 1
     lp.lp_destroy(ctx)
+
+
+def test_graph_replay_is_a_layout_decision_made_before_binding():
+    wl = WL.mlp_4096()
+    ctx = lp.lp_create(descs(wl), wl.L, wl.batch, lp.LP_BF16, lp.LP_LOSS_SOFTMAX_CE, 1e-3)
+    L = lp.lib()
+    n0 = lp.lp_workspace_bytes(ctx)
+    assert L.lp_set_graphs(ctx, 1) == 0
+    # rings of d_l + 1 = 15, 13, 11, 9, 7, 5, 3, 1 slots become 16, 16, 16, 16, 8, 8, 4, 1
+    extra = sum((r - (d + 1)) * ly.n_params * 4 for r, d, ly in zip((16, 16, 16, 16, 8, 8, 4, 1), wl.delays, wl.layers))
+    assert lp.lp_workspace_bytes(ctx) == n0 + extra
+    assert L.lp_set_run_ahead(ctx, 1) == 6                                    # not both
+    assert lp.lp_graph_stats(ctx) == (0, 0, 0)
+    assert L.lp_set_graphs(ctx, 0) == 0 and lp.lp_workspace_bytes(ctx) == n0
+    assert L.lp_set_run_ahead(ctx, 1) == 0 and L.lp_set_graphs(ctx, 1) == 6
+    assert L.lp_bind_workspace(ctx, 0x10000, 1 << 40) == 0
+    assert L.lp_set_graphs(ctx, 1) == 6                                       # LP_ERR_STATE: workspace already bound
+    assert L.lp_set_graphs(None, 1) == 1 and L.lp_graph_stats(None, None, None, None) == 1
+    lp.lp_destroy(ctx)

@@ -54,7 +54,9 @@ def one_layer_net(d_in, d_out, batch, act="relu", dtype="bf16", seed=0):
 # degenerate sizes.
 FWD_SHAPES = [(96, 200, 136), (33, 77, 19), (1, 8, 8), (7, 1, 3), (300, 520, 264), (64, 4096, 64),
               (1100, 72, 3000), (2304, 96, 5632), (256, 512, 1000), (1024, 136, 6200), (2300, 100, 5700),
-              (1101, 71, 3001), (256, 2048, 512), (300, 1032, 1160)]     # the last two (and (64, 4096, 64), (1100, 72, 3000) for dW) split K
+              (1101, 71, 3001), (256, 2048, 512), (300, 2056, 1160), (200, 1160, 3080)]
+# K is split over workgroups for F of (64, 4096, 64), (256, 2048, 512), (300, 2056, 1160) (ragged last range), for dX of
+# (1100, 72, 3000), (200, 1160, 3080) and for dW of (2304, 96, 5632)
 
 
 @pytest.mark.parametrize("shape", FWD_SHAPES)
