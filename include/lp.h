@@ -61,7 +61,9 @@ typedef enum {
 typedef enum { LP_F32 = 0, LP_BF16 = 1 } lp_dtype;
 typedef enum { LP_LOSS_SOFTMAX_CE = 0, LP_LOSS_MSE = 1 } lp_loss;
 typedef enum { LP_LINEAR = 0, LP_CONV3X3 = 1 } lp_kind;
-typedef enum { LP_ACT_IDENTITY = 0, LP_ACT_RELU = 1, LP_ACT_GELU = 2 } lp_act;
+/* f of Eq. 2.  The paper names sigmoid, tanh and ReLU (Sec. II-A); GELU (exact erf form) is added for the
+ * transformer-MLP workload. */
+typedef enum { LP_ACT_IDENTITY = 0, LP_ACT_RELU = 1, LP_ACT_GELU = 2, LP_ACT_TANH = 3, LP_ACT_SIGMOID = 4 } lp_act;
 
 /* One layer.  LINEAR: in/out are feature counts, H = W = pool = 0.  CONV3X3: in/out are channel
  * counts, H x W the (input = output) image size, pool 0 or 2.  `delay` = d_l >= 0, the number of

@@ -17,7 +17,7 @@ import numpy as np
 
 # layer kinds / activations / losses / dtypes: plain strings on the Python side
 LINEAR, CONV3X3 = "linear", "conv3x3"
-IDENTITY, RELU, GELU = "identity", "relu", "gelu"
+IDENTITY, RELU, GELU, TANH, SIGMOID = "identity", "relu", "gelu", "tanh", "sigmoid"
 SOFTMAX_CE, MSE = "softmax_ce", "mse"
 
 # tensor ids inside one (seed, step) stream

@@ -25,7 +25,7 @@ LIB_PATH = os.path.join(_HERE, "liblayerpipe.so")
 LP_F32, LP_BF16 = 0, 1
 LP_LOSS_SOFTMAX_CE, LP_LOSS_MSE = 0, 1
 LP_LINEAR, LP_CONV3X3 = 0, 1
-LP_ACT_IDENTITY, LP_ACT_RELU, LP_ACT_GELU = 0, 1, 2
+LP_ACT_IDENTITY, LP_ACT_RELU, LP_ACT_GELU, LP_ACT_TANH, LP_ACT_SIGMOID = 0, 1, 2, 3, 4
 LP_T_MASTER_W, LP_T_WORK_W, LP_T_A, LP_T_Z, LP_T_DA, LP_T_DY, LP_T_G_LAST = range(7)
 LP_TASK_F, LP_TASK_DX, LP_TASK_DW, LP_TASK_HADAMARD, LP_TASK_LOSS, LP_TASK_UPDATE = range(6)
 TASK_NAMES = ["F", "dX", "dW", "hadamard", "loss", "update"]
@@ -123,7 +123,7 @@ def _stream(s) -> Optional[int]:
 
 
 _KIND = {"linear": LP_LINEAR, "conv3x3": LP_CONV3X3}
-_ACT = {"identity": LP_ACT_IDENTITY, "relu": LP_ACT_RELU, "gelu": LP_ACT_GELU}
+_ACT = {"identity": LP_ACT_IDENTITY, "relu": LP_ACT_RELU, "gelu": LP_ACT_GELU, "tanh": LP_ACT_TANH, "sigmoid": LP_ACT_SIGMOID}
 _LOSS = {"softmax_ce": LP_LOSS_SOFTMAX_CE, "mse": LP_LOSS_MSE}
 _DTYPE = {"f32": LP_F32, "bf16": LP_BF16}
 

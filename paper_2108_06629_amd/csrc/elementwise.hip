@@ -21,6 +21,8 @@ template <int ACT>
 __device__ __forceinline__ float act_f(float z) {
   if (ACT == ACT_RELU) return z > 0.f ? z : 0.f;
   if (ACT == ACT_GELU) return 0.5f * z * (1.f + erff(z * 0.70710678118654752440f));
+  if (ACT == ACT_TANH) return tanhf(z);
+  if (ACT == ACT_SIGMOID) return 1.f / (1.f + expf(-z));
   return z;
 }
 template <int ACT>
@@ -31,6 +33,8 @@ __device__ __forceinline__ float act_df(float z) {
     const float pdf = 0.39894228040143267794f * __expf(-0.5f * z * z);
     return cdf + z * pdf;
   }
+  if (ACT == ACT_TANH) { const float t = tanhf(z); return 1.f - t * t; }
+  if (ACT == ACT_SIGMOID) { const float s = 1.f / (1.f + expf(-z)); return s * (1.f - s); }
   return 1.f;
 }
 
@@ -295,10 +299,16 @@ hipError_t launch_act_grad(bool bf16, int act, const void* dA, const void* S, vo
   const unsigned nb = blocks_for(nvec > 0 ? nvec : 1, 256 * EW_VEC_PER_THREAD);
   if (bf16) {
     if (act == ACT_RELU) hipLaunchKernelGGL(act_grad_bf16_kernel<ACT_RELU>, dim3(nb), dim3(256), 0, s, (const u32x4*)dA, (const u32x4*)S, (u32x4*)dY, nvec, n);
-    else hipLaunchKernelGGL(act_grad_bf16_kernel<ACT_GELU>, dim3(nb), dim3(256), 0, s, (const u32x4*)dA, (const u32x4*)S, (u32x4*)dY, nvec, n);
+    else if (act == ACT_GELU) hipLaunchKernelGGL(act_grad_bf16_kernel<ACT_GELU>, dim3(nb), dim3(256), 0, s, (const u32x4*)dA, (const u32x4*)S, (u32x4*)dY, nvec, n);
+    else if (act == ACT_TANH) hipLaunchKernelGGL(act_grad_bf16_kernel<ACT_TANH>, dim3(nb), dim3(256), 0, s, (const u32x4*)dA, (const u32x4*)S, (u32x4*)dY, nvec, n);
+    else if (act == ACT_SIGMOID) hipLaunchKernelGGL(act_grad_bf16_kernel<ACT_SIGMOID>, dim3(nb), dim3(256), 0, s, (const u32x4*)dA, (const u32x4*)S, (u32x4*)dY, nvec, n);
+    else return hipErrorInvalidValue;
   } else {
     if (act == ACT_RELU) hipLaunchKernelGGL(act_grad_f32_kernel<ACT_RELU>, dim3(nb), dim3(256), 0, s, (const f32x4*)dA, (const f32x4*)S, (f32x4*)dY, nvec, n);
-    else hipLaunchKernelGGL(act_grad_f32_kernel<ACT_GELU>, dim3(nb), dim3(256), 0, s, (const f32x4*)dA, (const f32x4*)S, (f32x4*)dY, nvec, n);
+    else if (act == ACT_GELU) hipLaunchKernelGGL(act_grad_f32_kernel<ACT_GELU>, dim3(nb), dim3(256), 0, s, (const f32x4*)dA, (const f32x4*)S, (f32x4*)dY, nvec, n);
+    else if (act == ACT_TANH) hipLaunchKernelGGL(act_grad_f32_kernel<ACT_TANH>, dim3(nb), dim3(256), 0, s, (const f32x4*)dA, (const f32x4*)S, (f32x4*)dY, nvec, n);
+    else if (act == ACT_SIGMOID) hipLaunchKernelGGL(act_grad_f32_kernel<ACT_SIGMOID>, dim3(nb), dim3(256), 0, s, (const f32x4*)dA, (const f32x4*)S, (f32x4*)dY, nvec, n);
+    else return hipErrorInvalidValue;
   }
   return hipGetLastError();
 }

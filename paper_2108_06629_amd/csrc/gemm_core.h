@@ -35,6 +35,8 @@ __device__ __forceinline__ float bf16_to_f32(unsigned short b) { return __uint_a
 __device__ __forceinline__ float apply_act(float z, int act) {
   if (act == 1) return z > 0.f ? z : 0.f;                                          // ReLU
   if (act == 2) return 0.5f * z * (1.f + erff(z * 0.70710678118654752440f));      // GELU (erf form)
+  if (act == 3) return tanhf(z);
+  if (act == 4) return 1.f / (1.f + expf(-z));                                      // sigmoid
   return z;
 }
 

@@ -20,6 +20,8 @@ struct GemmFArgs {
 __device__ __forceinline__ float apply_act_f(float z, int act) {
   if (act == ACT_RELU) return z > 0.f ? z : 0.f;
   if (act == ACT_GELU) return 0.5f * z * (1.f + erff(z * 0.70710678118654752440f));
+  if (act == ACT_TANH) return tanhf(z);
+  if (act == ACT_SIGMOID) return 1.f / (1.f + expf(-z));
   return z;
 }
 

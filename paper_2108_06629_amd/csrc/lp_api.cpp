@@ -280,7 +280,8 @@ void layout_workspace(lp_ctx* c) {
     if (ly.ring_slots > c->graph_period) c->graph_period = ly.ring_slots;
     ly.off_ring = take((size_t)ly.ring_slots * ly.n_params * 4);
     ly.has_A = !last;
-    ly.has_Z = last || pooled || ly.d.act == LP_ACT_GELU;
+    // the Hadamard factor is computed from Z; only ReLU's can be read off A (same sign)
+    ly.has_Z = last || pooled || (ly.d.act != LP_ACT_RELU && ly.d.act != LP_ACT_IDENTITY);
     ly.has_dA = !last;
     for (int p = 0; p < 2; ++p) {
       if (p == 1 && !c->run_ahead) { ly.off_A[1] = ly.off_A[0]; ly.off_Z[1] = ly.off_Z[0]; break; }
@@ -603,7 +604,9 @@ int lp_create(const lp_layer_desc* layers, int L, int batch, int dtype, int loss
       return r;
     };
     if (d.kind != LP_LINEAR && d.kind != LP_CONV3X3) return bad(LP_ERR_DTYPE, "unknown kind");
-    if (d.act != LP_ACT_IDENTITY && d.act != LP_ACT_RELU && d.act != LP_ACT_GELU) return bad(LP_ERR_DTYPE, "unknown activation");
+    if (d.act < LP_ACT_IDENTITY || d.act > LP_ACT_SIGMOID) return bad(LP_ERR_DTYPE, "unknown activation");
+    if (d.kind == LP_CONV3X3 && d.pool == 2 && (d.act == LP_ACT_TANH || d.act == LP_ACT_SIGMOID))
+      return bad(LP_ERR_DTYPE, "a pooled convolution takes identity, ReLU or GELU");
     if (d.in < 1 || d.out < 1) return bad(LP_ERR_SHAPE, "in/out must be positive");
     if (d.delay < 0) return bad(LP_ERR_DELAY, "negative delay");
     if (i == L - 1 && d.act != LP_ACT_IDENTITY) return bad(LP_ERR_DTYPE, "the last layer must have identity activation");

@@ -7,7 +7,7 @@
 
 namespace lp {
 
-enum Act { ACT_IDENTITY = 0, ACT_RELU = 1, ACT_GELU = 2 };
+enum Act { ACT_IDENTITY = 0, ACT_RELU = 1, ACT_GELU = 2, ACT_TANH = 3, ACT_SIGMOID = 4 };
 
 // C[M,N] = sum_k Aop(m,k) * Bop(n,k), fp32 accumulate.
 //   a_kcontig:  Aop(m,k) = A[m*lda + k]   else  Aop(m,k) = A[k*lda + m]

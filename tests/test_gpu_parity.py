@@ -129,7 +129,8 @@ def test_grad_weight_bf16(shape):
 
 
 @pytest.mark.parametrize("n_feat", [8, 1000, 4099])
-@pytest.mark.parametrize("act,dtype", [("relu", "bf16"), ("gelu", "bf16"), ("relu", "f32"), ("gelu", "f32")])
+@pytest.mark.parametrize("act,dtype", [("relu", "bf16"), ("gelu", "bf16"), ("relu", "f32"), ("gelu", "f32"),
+                                       ("tanh", "bf16"), ("sigmoid", "bf16"), ("tanh", "f32"), ("sigmoid", "f32")])
 def test_act_grad_hadamard(n_feat, act, dtype):
     B = 37
     net, W, rng = one_layer_net(n_feat, n_feat, B, act, dtype)
@@ -331,6 +332,31 @@ def test_trajectory_mlp_small_f32_full_config():
     wl = WL.mlp_small()
     assert wl.delays == (6, 4, 2, 0) and wl.steps == 8
     run_trajectory(wl, wl.steps)
+
+
+@pytest.mark.parametrize("act", ["tanh", "sigmoid"])
+@pytest.mark.parametrize("shape", [(96, 200, 136), (33, 77, 19), (300, 520, 264), (256, 2048, 512)])
+def test_forward_product_saturating_activations(shape, act):
+    """The activations the paper names next to ReLU (Sec. II-A), fused into the product's epilogue like the others."""
+    B, K, N = shape
+    for dtype, td, tol_z, tol_a in (("bf16", torch.bfloat16, 2e-2, 2.0 ** -7), ("f32", torch.float32, 1e-4, 1e-5)):
+        net, W, rng = one_layer_net(K, N, B, act, dtype)
+        x = rng.standard_normal((B, K)).astype(np.float32)
+        Z = torch.empty(B, N, dtype=td, device=DEV)
+        A = torch.empty(B, N, dtype=td, device=DEV)
+        lp.lp_forward(net.ctx, 1, dev(x, td), Z, A, net.streams[0])
+        lp.lp_sync(net.ctx)
+        q = O.round_bf16 if dtype == "bf16" else (lambda v: v)
+        assert relerr(host(Z), O.store(O.forward_product(q(x), q(W[0])), dtype)) <= tol_z
+        assert relerr(host(A), O.store(O.activation(host(Z), act), dtype)) <= tol_a       # defined on the stored Z
+        net.close()
+
+
+@pytest.mark.parametrize("act", ["tanh", "sigmoid"])
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_trajectory_saturating_activations(act, dtype):
+    wl = WL.mlp_4096().with_(layers=WL._mlp([200, 264, 136, 72, 24], act), batch=48, delays=(6, 4, 2, 0), dtype=dtype, lr=0.05)
+    run_trajectory(wl, 12)
 
 
 def test_trajectory_mlp_bf16_scaled():
