@@ -156,7 +156,7 @@ def partition_report(wl, max_stages):
             "partitions": rows, "step_ms_three_streams": times}
 
 
-def run_workload(wl, steps, warmup, n_streams, profile=True, weights=None, run_ahead=False):
+def run_workload(wl, steps, warmup, n_streams, profile=True, weights=None, run_ahead=False, factor_ring=False):
     import numpy as np
     import torch
     import lp_workloads as WL
@@ -164,7 +164,7 @@ def run_workload(wl, steps, warmup, n_streams, profile=True, weights=None, run_a
 
     dev = torch.device("cuda:0")
     net = lp.Network(wl.layers, wl.batch, wl.dtype, wl.loss, wl.lr, wl.delays, device="cuda:0", n_streams=n_streams,
-                     run_ahead=run_ahead)
+                     run_ahead=run_ahead, factor_ring=(True if factor_ring else None))
     net.set_weights(WL.init_weights(wl) if weights is None else weights)
     # a small pool of resident minibatches, reused round-robin
     pool = 4
@@ -211,6 +211,8 @@ def main():
     ap.add_argument("--streams", type=int, default=3)
     ap.add_argument("--run-ahead", action="store_true",
                     help="forward run-ahead across steps (lp_set_run_ahead): F(n+1) on a fourth stream next to the backward pass of step n")
+    ap.add_argument("--factor-ring", action="store_true",
+                    help="keep (A, dY) pairs instead of G in the delay elements and fuse the product into the delayed update (lp_set_factor_ring)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-others", action="store_true", help="skip the short runs of the other workloads")
     ap.add_argument("--partition", type=int, default=0, metavar="NP",
@@ -245,7 +247,7 @@ def main():
         return
     work = task_work(wl)
     weights = WL.init_weights(wl)
-    dt, loss, prof, upd_params = run_workload(wl, args.steps, args.warmup, args.streams, True, weights, args.run_ahead)
+    dt, loss, prof, upd_params = run_workload(wl, args.steps, args.warmup, args.streams, True, weights, args.run_ahead, args.factor_ring)
     del weights
     ms_per_step = dt / args.steps * 1e3
     value = wl.batch * args.steps / dt
@@ -253,6 +255,13 @@ def main():
     tasks = {}
     for name in ("F", "dX", "dW"):
         ms, cnt = prof.get(name, (0.0, 0))
+        if name == "dW" and args.factor_ring:
+            # the G task only copies its factors; the product runs inside the update
+            ums, ucnt = prof.get("update", (0.0, 0))
+            if ucnt:
+                tf = work["dW"] * args.steps / (ums * 1e-3) / 1e12
+                tasks["update+dW"] = {"launches": ucnt, "avg_ms": ums / ucnt, "TFLOP/s": tf, "frac_of_bf16_peak": tf / PEAK_BF16_TFLOPS}
+            continue
         if cnt:
             tf = work[name] * args.steps / (ms * 1e-3) / 1e12
             tasks[name] = {"launches": cnt, "avg_ms": ms / cnt, "TFLOP/s": tf, "frac_of_bf16_peak": tf / PEAK_BF16_TFLOPS}
@@ -262,7 +271,7 @@ def main():
             gbs = work[name] * args.steps / (ms * 1e-3) / 1e9
             tasks[name] = {"launches": cnt, "avg_ms": ms / cnt, "GB/s": gbs, "frac_of_hbm_peak": gbs / PEAK_HBM_GBS}
     ms, cnt = prof.get("update", (0.0, 0))
-    if cnt and ms > 0:
+    if cnt and ms > 0 and not args.factor_ring:
         gbs = upd_params * work["update_per_param"] / (ms * 1e-3) / 1e9
         tasks["update"] = {"launches": cnt, "avg_ms": ms / cnt, "GB/s": gbs, "frac_of_hbm_peak": gbs / PEAK_HBM_GBS}
 
@@ -296,9 +305,11 @@ def main():
                 others[name] = {"samples_per_s": o.batch * o.steps / odt, "ms_per_step": odt / o.steps * 1e3, "steps": o.steps,
                                 "final_loss": oloss}
                 if o.dtype == "bf16" and o.n_params < 5e8:
-                    rdt, rloss, _, _ = run_workload(o, o.steps, 3, 4, False, run_ahead=True)
-                    others[name]["run_ahead"] = {"samples_per_s": o.batch * o.steps / rdt, "ms_per_step": rdt / o.steps * 1e3,
-                                                 "final_loss": rloss}
+                    for label, kw in (("run_ahead", dict(run_ahead=True)), ("factor_ring", dict(factor_ring=True)),
+                                      ("factor_ring+run_ahead", dict(run_ahead=True, factor_ring=True))):
+                        rdt, rloss, _, _ = run_workload(o, o.steps, 3, 4 if "run_ahead" in kw else args.streams, False, **kw)
+                        others[name][label] = {"samples_per_s": o.batch * o.steps / rdt, "ms_per_step": rdt / o.steps * 1e3,
+                                               "final_loss": rloss}
             except Exception as e:  # a workload this build cannot run yet is reported, not hidden
                 others[name] = {"error": str(e)[:200]}
 
@@ -313,7 +324,7 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": "%s: %d layers, batch %d, delays %s, %s loss, lr %g, %d streams" % (
             wl.name, wl.L, wl.batch, list(wl.delays), wl.loss, wl.lr, 4 if args.run_ahead else args.streams) + (
-                ", forward run-ahead" if args.run_ahead else ""),
+                ", forward run-ahead" if args.run_ahead else "") + (", factor ring" if args.factor_ring else ""),
             "params": wl.n_params, "flops_per_step": sum(wl.flops_per_step()),
             "updated_params_per_step": upd_params / args.steps},
         "roofline": roofline, "cpu_baseline": cpu, "tasks": tasks, "other_workloads": others, "final_loss": loss,

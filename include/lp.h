@@ -179,6 +179,18 @@ int lp_set_delta_split(lp_ctx* ctx, int l, int cols);
  * until that step has finished.  LP_BF16 contexts only (LP_ERR_DTYPE): F32 updates weights in place. */
 int lp_set_run_ahead(lp_ctx* ctx, int enable);
 
+/* Factor ring (for layers whose batch is small next to their width): the delay elements of layer l hold
+ * the two factors of the gradient, A_{l-1}(n) and dY_l(n) (batch x (in + out) elements), instead of the
+ * product G_l(n) (in x out floats).  The G task of a step then only copies the factors; the delayed
+ * update of step n forms G_l(n - d_l) tile by tile with the kernel lp_grad_weight uses and applies each
+ * tile to the weights in its epilogue, so G never travels through memory: same arithmetic and same bits
+ * as the product ring, less memory and less traffic (per parameter 10 bytes instead of 4 + 14).
+ * l = 0 selects every linear layer.  Applies to lp_step and to lp_grad_weight / lp_update called with
+ * G = NULL; LP_T_G_LAST of such a layer is NULL.  Call after lp_create and before lp_workspace_bytes /
+ * lp_bind_workspace (LP_ERR_STATE afterwards).  LP_BF16 contexts (LP_ERR_DTYPE), linear layers
+ * (LP_ERR_LAYER). */
+int lp_set_factor_ring(lp_ctx* ctx, int l, int enable);
+
 /* Graph replay of whole steps: with enable != 0, lp_step captures the tasks of a step into a HIP graph
  * the first time it sees that step's combination of buffers (ring slots, working-weight copies, the
  * caller's X0 / target / loss_dev pointers and streams) and afterwards replays it with one launch on

@@ -272,6 +272,24 @@ __global__ void __launch_bounds__(256) sgd_kernel(f32x4* __restrict__ master, co
   }
 }
 
+// Copies two buffers in one launch (the two factors of a gradient, into their ring slot).  16 bytes per
+// lane; a buffer whose size is not a multiple of 16 ends with a byte-wise tail.
+__global__ void __launch_bounds__(256) copy2_kernel(const u32x4* __restrict__ a, u32x4* __restrict__ da, size_t va, size_t a_bytes,
+                                                    const u32x4* __restrict__ b, u32x4* __restrict__ db, size_t vb, size_t b_bytes) {
+  const size_t base = (size_t)blockIdx.x * (256 * EW_VEC_PER_THREAD) + threadIdx.x;
+#pragma unroll
+  for (int u = 0; u < EW_VEC_PER_THREAD; ++u) {
+    size_t i = base + (size_t)u * 256;
+    const u32x4* src = a; u32x4* dst = da; size_t bytes = a_bytes;
+    if (i >= va) { i -= va; src = b; dst = db; bytes = b_bytes; if (i >= vb) continue; }
+    if ((i + 1) * 16 <= bytes) {
+      __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
+    } else {
+      for (size_t k = i * 16; k < bytes; ++k) ((unsigned char*)dst)[k] = ((const unsigned char*)src)[k];
+    }
+  }
+}
+
 __global__ void __launch_bounds__(256) cast_bf16_kernel(const float* __restrict__ src, unsigned short* __restrict__ dst, size_t n) {
   const size_t i = ((size_t)blockIdx.x * 256 + threadIdx.x) * 4;
   if (i + 3 < n) {
@@ -372,6 +390,15 @@ hipError_t launch_sgd(float* master, const float* g, void* work_out_bf16, float 
   const unsigned nb = blocks_for(nvec > 0 ? nvec : 1, 256 * EW_VEC_PER_THREAD);
   if (work_out_bf16) hipLaunchKernelGGL(sgd_kernel<true>, dim3(nb), dim3(256), 0, s, (f32x4*)master, (const f32x4*)g, (u32x2*)work_out_bf16, -lr, nvec, n);
   else hipLaunchKernelGGL(sgd_kernel<false>, dim3(nb), dim3(256), 0, s, (f32x4*)master, (const f32x4*)g, (u32x2*)nullptr, -lr, nvec, n);
+  return hipGetLastError();
+}
+
+hipError_t launch_copy2(const void* a, void* da, size_t a_bytes, const void* b, void* db, size_t b_bytes, hipStream_t s) {
+  // all four pointers 16-byte aligned (workspace blocks and tensors of the library are)
+  const size_t va = (a_bytes + 15) / 16, vb = (b_bytes + 15) / 16;
+  if (va + vb == 0) return hipSuccess;
+  hipLaunchKernelGGL(copy2_kernel, dim3(blocks_for(va + vb, 256 * EW_VEC_PER_THREAD)), dim3(256), 0, s, (const u32x4*)a, (u32x4*)da, va,
+                     a_bytes, (const u32x4*)b, (u32x4*)db, vb, b_bytes);
   return hipGetLastError();
 }
 

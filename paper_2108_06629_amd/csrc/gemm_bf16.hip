@@ -28,6 +28,8 @@ struct GemmKArgs {
   int vec_out;
   int kt_per_split;     // split-K: K tiles per workgroup in y (0: no split)
   float* partial;       // split-K: [gridDim.y][M][N] fp32
+  float* sgd_master;    // SGD variants: fp32 master weights updated in the epilogue
+  float neg_lr;
 };
 
 template <bool KC, int R, int BK, int NT, bool ALIGNED>
@@ -39,7 +41,7 @@ struct StageSel<false, R, BK, NT, ALIGNED> {
   using type = StageKS<R, BK, NT, ALIGNED>;
 };
 
-template <int BM, int BN, int BK, int WM, int WN, bool AKC, bool BKC, bool ALIGNED>
+template <int BM, int BN, int BK, int WM, int WN, bool AKC, bool BKC, bool ALIGNED, bool SGD = false>
 __global__ void __launch_bounds__(WM* WN * 64) gemm_bf16_kernel(GemmKArgs p) {
   constexpr int NT = WM * WN * 64;
   extern __shared__ __attribute__((aligned(16))) unsigned short smem[];
@@ -56,12 +58,17 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_bf16_kernel(GemmKArgs p) {
   sb.r0 = n0; sb.Rtot = p.N; sb.Ktot = p.K; sb.ld = p.ldb;
   sb.tid = BKC ? tid : (tid + NT / 2) % NT;  // when both operands are transposed in registers, start B's blocks on the other waves
 
-  StoreEpilogue epi{p.out_z, p.out_a, p.out_f32, p.M, p.N, p.ldc, p.act, m0, n0, p.vec_out != 0};
-  gemm_tile<BM, BN, BK, WM, WN>(sa, sb, 0, (p.K + BK - 1) / BK, smem, epi);
+  if constexpr (SGD) {
+    SgdEpilogue epi{p.sgd_master, p.out_z, p.neg_lr, p.M, p.N, p.ldc, m0, n0, p.vec_out != 0};
+    gemm_tile<BM, BN, BK, WM, WN>(sa, sb, 0, (p.K + BK - 1) / BK, smem, epi);
+  } else {
+    StoreEpilogue epi{p.out_z, p.out_a, p.out_f32, p.M, p.N, p.ldc, p.act, m0, n0, p.vec_out != 0};
+    gemm_tile<BM, BN, BK, WM, WN>(sa, sb, 0, (p.K + BK - 1) / BK, smem, epi);
+  }
 }
 
 // direct-to-LDS variant (256x256 tile, K step 32, four LDS stages)
-template <int BM, int BN, int BK, int NSTAGE, int WM, int WN, bool AKC, bool BKC>
+template <int BM, int BN, int BK, int NSTAGE, int WM, int WN, bool AKC, bool BKC, bool SGD = false>
 __global__ void __launch_bounds__(WM* WN * 64) gemm_bf16_dl_kernel(GemmKArgs p) {
   extern __shared__ __attribute__((aligned(16))) unsigned short smem[];
   int tm, tn;
@@ -71,6 +78,11 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_bf16_dl_kernel(GemmKArgs p) 
   oa.init(p.A, p.a_bytes, tm * BM, p.M, p.K, p.lda);
   ob.init(p.B, p.b_bytes, tn * BN, p.N, p.K, p.ldb);
   const int KT = (p.K + BK - 1) / BK;
+  if constexpr (SGD) {
+    SgdEpilogue epi{p.sgd_master, p.out_z, p.neg_lr, p.M, p.N, p.ldc, tm * BM, tn * BN, p.vec_out != 0};
+    dl::gemm_tile_dl<BM, BN, BK, NSTAGE, WM, WN>(oa, ob, 0, KT, smem, epi);
+    return;
+  }
   if (p.kt_per_split > 0) {
     // split-K: this workgroup multiplies K tiles [kt0, kt1) and writes an fp32 partial
     const int kt0 = blockIdx.y * p.kt_per_split;
@@ -116,9 +128,9 @@ __global__ void __launch_bounds__(256) splitk_reduce_kernel(const float* __restr
   epi(row, col, acc);
 }
 
-template <int BM, int BN, int BK, int NSTAGE, int WM, int WN, bool AKC, bool BKC>
+template <int BM, int BN, int BK, int NSTAGE, int WM, int WN, bool AKC, bool BKC, bool SGD = false>
 hipError_t launch_dl(const GemmKArgs& a, hipStream_t s) {
-  auto kern = gemm_bf16_dl_kernel<BM, BN, BK, NSTAGE, WM, WN, AKC, BKC>;
+  auto kern = gemm_bf16_dl_kernel<BM, BN, BK, NSTAGE, WM, WN, AKC, BKC, SGD>;
   constexpr size_t lds = (size_t)NSTAGE * (BM + BN) * BK * sizeof(unsigned short);
   static bool attr_done = false;
   if (!attr_done) {
@@ -156,9 +168,9 @@ constexpr TileCfg kCfgs[] = {
     {"128x128x64_dl_w2x2", 128, 128, 1},  // 5
 };
 
-template <int BM, int BN, int BK, int WM, int WN, bool AKC, bool BKC, bool ALIGNED>
+template <int BM, int BN, int BK, int WM, int WN, bool AKC, bool BKC, bool ALIGNED, bool SGD = false>
 hipError_t launch_one(const GemmKArgs& a, hipStream_t s) {
-  auto kern = gemm_bf16_kernel<BM, BN, BK, WM, WN, AKC, BKC, ALIGNED>;
+  auto kern = gemm_bf16_kernel<BM, BN, BK, WM, WN, AKC, BKC, ALIGNED, SGD>;
   constexpr size_t lds = 2ull * (BM + BN) * BK * sizeof(unsigned short);
   static bool attr_done = false;
   if (!attr_done) {
@@ -178,6 +190,25 @@ hipError_t launch_cfg(int cfg, const GemmKArgs& a, hipStream_t s) {
     case 1: return launch_one<128, 128, 64, 2, 2, AKC, BKC, ALIGNED>(a, s);
     case 2: return launch_one<64, 64, 64, 2, 2, AKC, BKC, ALIGNED>(a, s);
     case 3: return launch_one<256, 256, 64, 2, 2, AKC, BKC, ALIGNED>(a, s);
+  }
+  return hipErrorInvalidValue;
+}
+
+// the G product with the update fused into its epilogue (both operands k-strided)
+template <bool ALIGNED>
+hipError_t launch_cfg_sgd(int cfg, const GemmKArgs& a, hipStream_t s) {
+  switch (cfg) {
+    case 0: return launch_one<256, 256, 64, 2, 4, false, false, ALIGNED, true>(a, s);
+    case 1: return launch_one<128, 128, 64, 2, 2, false, false, ALIGNED, true>(a, s);
+    case 2: return launch_one<64, 64, 64, 2, 2, false, false, ALIGNED, true>(a, s);
+    case 3: return launch_one<256, 256, 64, 2, 2, false, false, ALIGNED, true>(a, s);
+  }
+  return hipErrorInvalidValue;
+}
+hipError_t launch_cfg_dl_sgd(int cfg, const GemmKArgs& a, hipStream_t s) {
+  switch (cfg) {
+    case 4: return launch_dl<256, 256, 64, 2, 2, 4, false, false, true>(a, s);
+    case 5: return launch_dl<128, 128, 64, 2, 2, 2, false, false, true>(a, s);
   }
   return hipErrorInvalidValue;
 }
@@ -238,6 +269,14 @@ hipError_t launch_gemm_bf16(const GemmDesc& d, hipStream_t s, int tile_cfg) {
               ((uintptr_t)d.out_f32 % 16 == 0);
   a.kt_per_split = 0;
   a.partial = nullptr;
+  a.sgd_master = d.sgd_master;
+  a.neg_lr = -d.sgd_lr;
+  const bool sgd = d.sgd_master != nullptr;
+  if (sgd) {
+    if (d.a_kcontig || d.b_kcontig || !d.out_z) return hipErrorInvalidValue;
+    a.out_a = nullptr; a.out_f32 = nullptr; a.act = 0;
+    a.vec_out = (d.N % 4 == 0) && (d.ldc % 4 == 0) && ((uintptr_t)d.out_z % 8 == 0) && ((uintptr_t)d.sgd_master % 16 == 0);
+  }
 
   // 16-byte loads need every contiguous run to start on a multiple of 8 elements
   const int a_contig = d.a_kcontig ? d.K : d.M, b_contig = d.b_kcontig ? d.K : d.N;
@@ -261,6 +300,7 @@ hipError_t launch_gemm_bf16(const GemmDesc& d, hipStream_t s, int tile_cfg) {
   if (cfg < 0 || cfg >= gemm_bf16_num_cfgs()) return hipErrorInvalidValue;
   if (kCfgs[cfg].kind == 1) {
     if (!aligned) return hipErrorInvalidValue;
+    if (sgd) return launch_cfg_dl_sgd(cfg, a, s);
     if (cfg == 5 && tile_cfg < 0) {
       // 128x128 tiles that do not fill the chip and a long reduction: split K over workgroups.  A caller
       // that multiplies a column range of a larger product passes the split count of the whole product,
@@ -283,6 +323,7 @@ hipError_t launch_gemm_bf16(const GemmDesc& d, hipStream_t s, int tile_cfg) {
     if (!d.a_kcontig && !d.b_kcontig) return launch_cfg_dl<false, false>(cfg, a, s);
     return launch_cfg_dl<false, true>(cfg, a, s);
   }
+  if (sgd) return aligned ? launch_cfg_sgd<true>(cfg, a, s) : launch_cfg_sgd<false>(cfg, a, s);
   if (aligned) {
     if (d.a_kcontig && d.b_kcontig) return launch_cfg<true, true, true>(cfg, a, s);
     if (d.a_kcontig && !d.b_kcontig) return launch_cfg<true, false, true>(cfg, a, s);

@@ -352,5 +352,39 @@ struct StoreEpilogue {
   }
 };
 
+// Epilogue of a weight-gradient product that is consumed on the spot (Eq. 6 fused into Eq. 5): the
+// tile of G never goes to memory; W <- W - lr * G on the fp32 master, and the bf16 working copy of the
+// new weights is written next to it.  Same arithmetic as the stand-alone update kernel: one fma per
+// weight, then round-to-nearest-even.
+struct SgdEpilogue {
+  float* master;
+  unsigned short* work_out;
+  float neg_lr;
+  int M, N, ldc, m0, n0;
+  bool vec;
+  __device__ __forceinline__ void operator()(int r, int c, const f32x4& g) const {
+    const int row = m0 + r, col = n0 + c;
+    if (row >= M || col >= N) return;
+    const size_t o = (size_t)row * ldc + col;
+    if (vec) {  // col + 3 < N follows from N % 4 == 0
+      f32x4 w = *reinterpret_cast<const f32x4*>(master + o);
+#pragma unroll
+      for (int t = 0; t < 4; ++t) w[t] = fmaf(neg_lr, g[t], w[t]);
+      *reinterpret_cast<f32x4*>(master + o) = w;
+      *reinterpret_cast<u32x2*>(work_out + o) = u32x2{(unsigned)bf16_bits(w[0]) | ((unsigned)bf16_bits(w[1]) << 16),
+                                                      (unsigned)bf16_bits(w[2]) | ((unsigned)bf16_bits(w[3]) << 16)};
+    } else {
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        if (col + t < N) {
+          const float w = fmaf(neg_lr, g[t], master[o + t]);
+          master[o + t] = w;
+          work_out[o + t] = bf16_bits(w);
+        }
+      }
+    }
+  }
+};
+
 }  // namespace core
 }  // namespace lp

@@ -30,6 +30,8 @@ struct Layer {
   bool has_A = false, has_Z = false, has_dA = false;
   int ring_slots = 1;
   int delay = 0;       // active d_l
+  bool factor_ring = false;   // the ring holds (A_{l-1}, dY_l) pairs instead of G_l; the update multiplies them itself
+  size_t ring_x_bytes = 0, ring_slot_bytes = 0;
   int split_cols = 0;  // last columns of dA_{l-1} computed as a second, independent kernel (delta'')
   int cur = 0;         // working-weight buffer F and dX read now
   bool weights_set = false;
@@ -226,6 +228,34 @@ hipError_t do_loss(lp_ctx* c, const void* ZL, const void* target, void* dYL, flo
   return lp::launch_mse(is_bf16(c), ZL, target, dYL, loss_dev, partials, c->batch, last.out_feat, s);
 }
 
+// The G task of step `step` as lp_step runs it: the product into its ring slot, or, for a layer with a
+// factor ring, only a copy of the two factors (the product is left to the delayed update).
+hipError_t enqueue_G(lp_ctx* c, Layer& ly, const void* X, const void* dY, long step, hipStream_t s) {
+  if (!ly.factor_ring) return do_grad_weight(c, ly, X, dY, ring_slot(c, ly, step), s);
+  ProfScope prof(c, LP_TASK_DW, layer_no(c, ly), s);
+  char* slot = c->ws + ly.off_ring + (size_t)(step % ly.ring_slots) * ly.ring_slot_bytes;
+  return lp::launch_copy2(X, slot, ly.in_elems * esize(c), dY, slot + ly.ring_x_bytes, ly.z_elems * esize(c), s);
+}
+
+// The delayed update with the gradient of step `src` (Eq. 6).  Factor ring: G_l(src) = A_{l-1}(src)^T . dY_l(src)
+// is formed tile by tile from the stored factors by the same kernel that lp_grad_weight runs, and each
+// tile is applied to the weights in its epilogue instead of being stored (same bits as the two-kernel path).
+hipError_t do_update(lp_ctx* c, Layer& ly, const float* G, hipStream_t s);
+hipError_t enqueue_update(lp_ctx* c, Layer& ly, long src, hipStream_t s) {
+  if (!ly.factor_ring) return do_update(c, ly, ring_slot(c, ly, src), s);
+  ProfScope prof(c, LP_TASK_UPDATE, layer_no(c, ly), s);
+  const char* slot = c->ws + ly.off_ring + (size_t)(src % ly.ring_slots) * ly.ring_slot_bytes;
+  lp::GemmDesc g;
+  g.A = slot; g.B = slot + ly.ring_x_bytes;
+  g.M = ly.d.in; g.N = ly.d.out; g.K = c->batch;
+  g.lda = ly.d.in; g.ldb = ly.d.out; g.ldc = ly.d.out;
+  g.a_kcontig = false; g.b_kcontig = false;
+  g.out_z = c->ws + ly.off_work[ly.cur ^ 1];
+  g.sgd_master = (float*)(c->ws + ly.off_master);
+  g.sgd_lr = c->lr;
+  return lp::launch_gemm_bf16(g, s);
+}
+
 // Applies W <- W - lr*G; BF16 writes the other working buffer.  Does not flip `cur`.
 hipError_t do_update(lp_ctx* c, Layer& ly, const float* G, hipStream_t s) {
   ProfScope prof(c, LP_TASK_UPDATE, layer_no(c, ly), s);
@@ -278,7 +308,13 @@ void layout_workspace(lp_ctx* c) {
     ly.ring_slots = ly.d.delay + 1;
     if (c->graphs) { int r = 1; while (r < ly.ring_slots) r *= 2; ly.ring_slots = r; }
     if (ly.ring_slots > c->graph_period) c->graph_period = ly.ring_slots;
-    ly.off_ring = take((size_t)ly.ring_slots * ly.n_params * 4);
+    if (ly.factor_ring) {
+      ly.ring_x_bytes = align_up(ly.in_elems * es);
+      ly.ring_slot_bytes = ly.ring_x_bytes + align_up(ly.z_elems * es);
+      ly.off_ring = take((size_t)ly.ring_slots * ly.ring_slot_bytes);
+    } else {
+      ly.off_ring = take((size_t)ly.ring_slots * ly.n_params * 4);
+    }
     ly.has_A = !last;
     // the Hadamard factor is computed from Z; only ReLU's can be read off A (same sign)
     ly.has_Z = last || pooled || (ly.d.act != LP_ACT_RELU && ly.d.act != LP_ACT_IDENTITY);
@@ -347,7 +383,7 @@ int step_run_ahead(lp_ctx* c, const void* X0, const void* target, float* loss_de
     if (src < 1) return LP_OK;
     LP_HIP(c, hipStreamWaitEvent(sU, c->ev_dw[i], 0));                       // G_l(src) is in the ring
     LP_HIP(c, hipStreamWaitEvent(sU, i > 0 ? c->ev_dx[i] : c->ev_loss[p ^ 1], 0));   // readers of the copy being overwritten
-    LP_HIP(c, do_update(c, ly, ring_slot(c, ly, src), sU));
+    LP_HIP(c, enqueue_update(c, ly, src, sU));
     LP_HIP(c, hipEventRecord(c->ev_upd[i], sU));
     updated[i] = 1;
     return LP_OK;
@@ -403,7 +439,7 @@ int step_run_ahead(lp_ctx* c, const void* X0, const void* target, float* loss_de
     }
     LP_HIP(c, hipStreamWaitEvent(sW, c->ev_dy[i], 0));
     LP_HIP(c, hipStreamWaitEvent(sW, c->ev_upd[i], 0));   // the ring slot's previous gradient has been applied
-    LP_HIP(c, do_grad_weight(c, ly, x_in, dY, ring_slot(c, ly, n), sW));
+    LP_HIP(c, enqueue_G(c, ly, x_in, dY, n, sW));
     LP_HIP(c, hipEventRecord(c->ev_dw[i], sW));
     if (!updated[i])
       if (int r = issue_update(i)) return r;
@@ -441,7 +477,7 @@ int enqueue_step(lp_ctx* c, const void* X0, const void* target, float* loss_dev,
     Layer& ly = c->layers[i];
     const long src = n - ly.delay;
     if (src >= 1) {
-      LP_HIP(c, do_update(c, ly, ring_slot(c, ly, src), sU));
+      LP_HIP(c, enqueue_update(c, ly, src, sU));
       updated[i] = 1;
     }
     return LP_OK;
@@ -491,7 +527,7 @@ int enqueue_step(lp_ctx* c, const void* X0, const void* target, float* loss_dev,
       if (multi) LP_HIP(c, hipEventRecord(c->ev_dy[i - 1], sC));
     }
     if (multi && sW != sC) LP_HIP(c, hipStreamWaitEvent(sW, c->ev_dy[i], 0));
-    LP_HIP(c, do_grad_weight(c, ly, x_in, dY, ring_slot(c, ly, n), sW));
+    LP_HIP(c, enqueue_G(c, ly, x_in, dY, n, sW));
     if (multi) LP_HIP(c, hipEventRecord(c->ev_dw[i], sW));
     if (!updated[i]) {
       // d_l = 0 needs this step's G; an F32 context updates in place, so it also has to wait for
@@ -774,8 +810,11 @@ int lp_grad_weight(lp_ctx* c, int l, const void* X, const void* dY, float* G, vo
   if (!X || !dY) return fail(c, LP_ERR_NULL, "lp_grad_weight: X/dY is NULL");
   if (int r = need_ws(c)) return r;
   Layer& ly = c->layers[l - 1];
-  if (!G) G = ring_slot(c, ly, c->n + 1);
   note_stream(c, (hipStream_t)stream);
+  if (!G) {
+    LP_HIP(c, enqueue_G(c, ly, X, dY, c->n + 1, (hipStream_t)stream));
+    return LP_OK;
+  }
   LP_HIP(c, do_grad_weight(c, ly, X, dY, G, (hipStream_t)stream));
   return LP_OK;
 }
@@ -788,7 +827,10 @@ int lp_update(lp_ctx* c, int l, const float* G, void* stream) {
   if (!G) {
     const long src = c->n + 1 - ly.delay;
     if (src < 1) return LP_OK;  // the delay elements are still empty
-    G = ring_slot(c, ly, src);
+    note_stream(c, (hipStream_t)stream);
+    LP_HIP(c, enqueue_update(c, ly, src, (hipStream_t)stream));
+    if (is_bf16(c)) ly.cur ^= 1;
+    return LP_OK;
   }
   note_stream(c, (hipStream_t)stream);
   LP_HIP(c, do_update(c, ly, G, (hipStream_t)stream));
@@ -803,6 +845,19 @@ int lp_set_delta_split(lp_ctx* c, int l, int cols) {
   if (l == 1 && cols != 0) return fail(c, LP_ERR_LAYER, "lp_set_delta_split: layer 1 has no delta task");
   if (cols < 0 || cols >= ly.d.in) return fail(c, LP_ERR_SHAPE, "lp_set_delta_split: %d columns outside [0, %d)", cols, ly.d.in);
   ly.split_cols = cols;
+  return LP_OK;
+}
+
+int lp_set_factor_ring(lp_ctx* c, int l, int enable) {
+  if (!c) return LP_ERR_NULL;
+  if (c->ws) return fail(c, LP_ERR_STATE, "lp_set_factor_ring: call it before lp_bind_workspace (it changes the workspace size)");
+  if (!is_bf16(c)) return fail(c, LP_ERR_DTYPE, "lp_set_factor_ring: needs an LP_BF16 context");
+  if (l != 0)
+    if (int r = check_layer(c, l)) return r;
+  if (l != 0 && c->layers[l - 1].d.kind != LP_LINEAR) return fail(c, LP_ERR_LAYER, "lp_set_factor_ring: layer %d is not a linear layer", l);
+  for (int i = 0; i < c->L; ++i)
+    if ((l == 0 || i == l - 1) && c->layers[i].d.kind == LP_LINEAR) c->layers[i].factor_ring = enable != 0;
+  layout_workspace(c);
   return LP_OK;
 }
 
@@ -906,7 +961,7 @@ int lp_tensor(lp_ctx* c, int l, int which, void** dev_ptr, size_t* bytes) {
     case LP_T_Z: if (ly.has_Z) { *dev_ptr = c->ws + ly.off_Z[c->n & 1]; *bytes = ly.z_elems * es; } break;
     case LP_T_DA: if (ly.has_dA) { *dev_ptr = c->ws + ly.off_dA; *bytes = ly.a_elems * es; } break;
     case LP_T_DY: *dev_ptr = c->ws + ly.off_dY; *bytes = ly.z_elems * es; break;
-    case LP_T_G_LAST: if (c->n >= 1) { *dev_ptr = ring_slot(c, ly, c->n); *bytes = ly.n_params * 4; } break;
+    case LP_T_G_LAST: if (c->n >= 1 && !ly.factor_ring) { *dev_ptr = ring_slot(c, ly, c->n); *bytes = ly.n_params * 4; } break;
     default: return fail(c, LP_ERR_DTYPE, "lp_tensor: unknown tensor id %d", which);
   }
   return LP_OK;

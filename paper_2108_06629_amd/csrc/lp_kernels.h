@@ -32,6 +32,11 @@ struct GemmDesc {
   // A column range of a larger product passes the count of the whole product so that the summation
   // order of an output element does not depend on how the columns are cut.
   int splitk_splits = -1;
+  // fused delayed update (only with a_kcontig == b_kcontig == false, the G product): instead of storing
+  // G, apply W <- W - lr G to sgd_master (fp32, [M][N] with ldc) and write the bf16 copy of the result
+  // to out_z.  out_a, out_f32 and act are ignored; K is never split.
+  float* sgd_master = nullptr;
+  float sgd_lr = 0.f;
 };
 // K ranges the launcher cuts a product of this shape into (1: not split), and the scratch that takes
 // (0: split-K would not be used)
@@ -78,5 +83,7 @@ hipError_t launch_mse(bool bf16, const void* Z, const void* T, void* dY, float* 
 hipError_t launch_sgd(float* master, const float* g, void* work_out_bf16, float lr, size_t n, hipStream_t s);
 // dst_bf16 <- round(src)
 hipError_t launch_cast_bf16(const float* src, void* dst_bf16, size_t n, hipStream_t s);
+// two device-to-device copies in one launch; every pointer 16-byte aligned
+hipError_t launch_copy2(const void* a, void* da, size_t a_bytes, const void* b, void* db, size_t b_bytes, hipStream_t s);
 
 }  // namespace lp

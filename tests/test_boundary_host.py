@@ -157,3 +157,28 @@ def test_graph_replay_is_a_layout_decision_made_before_binding():
     assert L.lp_set_graphs(ctx, 1) == 6                                       # LP_ERR_STATE: workspace already bound
     assert L.lp_set_graphs(None, 1) == 1 and L.lp_graph_stats(None, None, None, None) == 1
     lp.lp_destroy(ctx)
+
+
+def test_factor_ring_shrinks_the_delay_elements():
+    wl = WL.mlp_4096()
+    ctx = lp.lp_create(descs(wl), wl.L, wl.batch, lp.LP_BF16, lp.LP_LOSS_SOFTMAX_CE, 1e-3)
+    L = lp.lib()
+    n0 = lp.lp_workspace_bytes(ctx)
+    assert L.lp_set_factor_ring(ctx, 0, 1) == 0
+    n1 = lp.lp_workspace_bytes(ctx)
+    ring_g = sum((d + 1) * ly.n_params * 4 for d, ly in zip(wl.delays, wl.layers))
+    ring_f = sum((d + 1) * wl.batch * (ly.d_in + ly.d_out) * 2 for d, ly in zip(wl.delays, wl.layers))
+    assert abs((n0 - n1) - (ring_g - ring_f)) < 2 ** 20 and n1 < n0 / 4
+    assert L.lp_set_factor_ring(ctx, 9, 1) == 4 and L.lp_set_factor_ring(ctx, 3, 0) == 0        # LP_ERR_LAYER; one layer back to products
+    assert lp.lp_workspace_bytes(ctx) == n1 + (wl.delays[2] + 1) * (wl.layers[2].n_params * 4 - wl.batch * (4096 + 4096) * 2)
+    assert L.lp_bind_workspace(ctx, 0x10000, 1 << 40) == 0
+    assert L.lp_set_factor_ring(ctx, 0, 1) == 6                                                   # LP_ERR_STATE: already bound
+    lp.lp_destroy(ctx)
+    small = WL.mlp_small()
+    ctx = lp.lp_create(descs(small), small.L, small.batch, lp.LP_F32, lp.LP_LOSS_SOFTMAX_CE, 0.01)
+    assert L.lp_set_factor_ring(ctx, 0, 1) == 3                                                   # LP_ERR_DTYPE
+    lp.lp_destroy(ctx)
+    cnn = WL.vgg_small(batch=2, hw=8, chans=(8, 8))
+    ctx = lp.lp_create(descs(cnn), cnn.L, 2, lp.LP_BF16, lp.LP_LOSS_SOFTMAX_CE, 0.01)
+    assert L.lp_set_factor_ring(ctx, 1, 1) == 4 and L.lp_set_factor_ring(ctx, cnn.L, 1) == 0      # conv: LP_ERR_LAYER; the FC layer: fine
+    lp.lp_destroy(ctx)
