@@ -11,6 +11,7 @@
 // into a small [9*C_in, C_out] result, so it is split over K across workgroups; the fp32 partials are
 // summed by a second kernel in a fixed order.
 #include "gemm_core.h"
+#include "gemm_dl.h"
 #include "lp_kernels.h"
 
 namespace lp {
@@ -19,6 +20,19 @@ namespace {
 using namespace core;
 
 constexpr int BM = 128, BN = 64, BK = 64, WM = 2, WN = 2, NT = WM * WN * 64;
+
+// Division by a divisor fixed per launch: q = (n * m) >> 32 with m = floor(2^32 / d) + 1, exact while
+// n * d < 2^32 (the host checks the largest n it will see); otherwise, and for d = 1, plain division.
+struct FastDiv {
+  unsigned d, m;
+  __host__ static FastDiv make(unsigned d, unsigned long long max_n) {
+    FastDiv f;
+    f.d = d;
+    f.m = (d > 1 && max_n * d < (1ull << 32)) ? (unsigned)((1ull << 32) / d) + 1u : 0u;
+    return f;
+  }
+  __device__ __forceinline__ unsigned div(unsigned n) const { return m ? __umulhi(n, m) : n / d; }
+};
 
 struct ConvKArgs {
   const unsigned short* img;   // F: x, dX: dy, dW: x
@@ -34,6 +48,7 @@ struct ConvKArgs {
   unsigned img_bytes, mat_bytes;
   int kt_per_split;            // dW: K tiles per workgroup in y
   int vec_out;
+  FastDiv divW, divH, divC;    // by W, by H, by the gathered image's channel count
 };
 
 __device__ __forceinline__ void tap_offsets(int tap, bool flip, int& dy, int& dx) {
@@ -51,25 +66,27 @@ struct StagePixelsKC {
   __amdgpu_buffer_rsrc_t rs;
   int Ktot, C, H, W, tid;
   bool flip;
+  FastDiv divC;
   int pix[CH], yx[CH];   // pixel index and (y << 16 | x) of this thread's rows; pix < 0: row past M
   u32x4 v[CH];
   __device__ __forceinline__ void init(const ConvKArgs& p, int m0, bool flip_) {
     rs = make_rsrc(p.img, p.img_bytes);
-    Ktot = p.K; C = p.Cimg; H = p.H; W = p.W; tid = threadIdx.x; flip = flip_;
+    Ktot = p.K; C = p.Cimg; H = p.H; W = p.W; tid = threadIdx.x; flip = flip_; divC = p.divC;
 #pragma unroll
     for (int it = 0; it < CH; ++it) {
       const int row = (it * NT + tid) / (BK / 8);
       const int m = m0 + row;
       if (m < p.M) {
-        const int x = m % W, t = m / W;
-        pix[it] = m; yx[it] = ((t % H) << 16) | x;
+        const int t = (int)p.divW.div((unsigned)m), x = m - t * W;
+        const int y = t - (int)p.divH.div((unsigned)t) * H;
+        pix[it] = m; yx[it] = (y << 16) | x;
       } else {
         pix[it] = -1; yx[it] = 0;
       }
     }
   }
   __device__ __forceinline__ unsigned elem_off(int it, int k, bool& ok) const {
-    const int tap = k / C, c = k - tap * C;
+    const int tap = (int)divC.div((unsigned)k), c = k - tap * C;
     int dy, dx;
     tap_offsets(tap, flip, dy, dx);
     const int yy = (yx[it] >> 16) + dy, xx = (yx[it] & 0xffff) + dx;
@@ -146,45 +163,63 @@ struct StagePixelsKS {
   static constexpr int IT = (NB + NT - 1) / NT;
   __amdgpu_buffer_rsrc_t rs;
   int m0, Mtot, Ktot, C, H, W, tid;
+  FastDiv divW, divH;
+  // per row of this thread's 8-row group (ALIGNED: one entry, the rows share a tap): tap offsets and channel,
+  // packed as (dy + 1) | (dx + 1) << 2 | c << 4; -1: row past M
+  static constexpr int NQ = ALIGNED ? 1 : 8;
+  int rowinfo[IT][NQ];
   u32x4 v[IT][8];
   __device__ __forceinline__ void init(const ConvKArgs& p, int m0_) {
     rs = make_rsrc(p.img, p.img_bytes);
     m0 = m0_; Mtot = p.M; Ktot = p.K; C = p.Cimg; H = p.H; W = p.W; tid = threadIdx.x;
+    divW = p.divW; divH = p.divH;
+#pragma unroll
+    for (int it = 0; it < IT; ++it) {
+      const int rc = (it * NT + tid) % (BM / 8);
+#pragma unroll
+      for (int q = 0; q < NQ; ++q) {
+        const int mm = m0 + rc * 8 + q;
+        const int tap = (int)p.divC.div((unsigned)mm), c = mm - tap * C;
+        int dy, dx;
+        tap_offsets(tap, false, dy, dx);
+        rowinfo[it][q] = mm < Mtot ? ((dy + 1) | ((dx + 1) << 2) | (c << 4)) : -1;
+      }
+    }
   }
   __device__ __forceinline__ void gload(int k0) {
 #pragma unroll
     for (int it = 0; it < IT; ++it) {
       const int id = it * NT + tid;
       if (NB % NT == 0 || id < NB) {
-        const int rc = id % (BM / 8), kg = id / (BM / 8);
-        const int m = m0 + rc * 8;
+        const int kg = id / (BM / 8);
+        const int p0 = k0 + kg * 8;
+        // (x, y) of the first of this thread's 8 consecutive pixels; the others by stepping
+        const int t = (int)divW.div((unsigned)p0);
+        int x = p0 - t * W, y = t - (int)divH.div((unsigned)t) * H;
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-          const int pxl = k0 + kg * 8 + j;
-          const int x = pxl % W, t = pxl / W, y = t % H;
+          const int pxl = p0 + j;
           if constexpr (ALIGNED) {   // C % 8 == 0: the 8 rows share one tap
-            const int tap = m / C, c = m - tap * C;
-            int dy, dx;
-            tap_offsets(tap, false, dy, dx);
+            const int ri = rowinfo[it][0];
+            const int dy = (ri & 3) - 1, dx = ((ri >> 2) & 3) - 1, c = ri >> 4;
             const int yy = y + dy, xx = x + dx;
-            const bool ok = m < Mtot && pxl < Ktot && yy >= 0 && yy < H && xx >= 0 && xx < W;
+            const bool ok = ri >= 0 && pxl < Ktot && yy >= 0 && yy < H && xx >= 0 && xx < W;
             const unsigned e = (unsigned)((pxl + dy * W + dx) * C + c);
             v[it][j] = __builtin_amdgcn_raw_buffer_load_b128(rs, ok ? e * 2u : kOOB, 0, 0);
           } else {
             unsigned h[8];
 #pragma unroll
             for (int q = 0; q < 8; ++q) {
-              const int mm = m + q;
-              const int tap = mm / C, c = mm - tap * C;
-              int dy, dx;
-              tap_offsets(tap, false, dy, dx);
+              const int ri = rowinfo[it][q];
+              const int dy = (ri & 3) - 1, dx = ((ri >> 2) & 3) - 1, c = ri >> 4;
               const int yy = y + dy, xx = x + dx;
-              const bool ok = mm < Mtot && pxl < Ktot && yy >= 0 && yy < H && xx >= 0 && xx < W;
+              const bool ok = ri >= 0 && pxl < Ktot && yy >= 0 && yy < H && xx >= 0 && xx < W;
               const unsigned e = (unsigned)((pxl + dy * W + dx) * C + c);
               h[q] = (unsigned short)__builtin_amdgcn_raw_buffer_load_b16(rs, ok ? e * 2u : kOOB, 0, 0);
             }
             v[it][j] = u32x4{h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16)};
           }
+          if (++x == W) { x = 0; if (++y == H) y = 0; }
         }
       }
     }
@@ -203,6 +238,194 @@ struct StagePixelsKS {
     }
   }
 };
+
+
+// ---- direct-to-LDS forms (channel counts that are multiples of 8) ----------------------------------
+// Same products on the main loop of gemm_dl.h: 128 x 64 tiles, K step 32, four LDS stages (48 KB, three
+// workgroups per CU), so about three K steps of gather latency are covered -- these layers have short
+// reductions (9 C_in) and little arithmetic per step, and what bounds them is how many loads are in
+// flight.  A buffer_load ... lds takes its global address per lane, so the gather costs nothing extra:
+// the lane that fills LDS chunk p of a row computes the address of the shifted pixel (or an out-of-range
+// offset for the zero padding).
+namespace cdl {
+
+constexpr int DBM = 128, DBN = 64, DBK = 32, DSTAGES = 4, DWM = 2, DWN = 2, DNW = DWM * DWN, DNT = DNW * 64;
+
+// A operand of F and dX: rows are pixels, k = (tap, c), c contiguous in memory.  LDS layout and fragment
+// reads are those of dl::OperandKC.
+struct PixelsKC : dl::OperandKC<DBM, DBK, DNW> {
+  using Base = dl::OperandKC<DBM, DBK, DNW>;
+  int C, H, W;
+  bool flip;
+  FastDiv divC;
+  bool tap_uniform;   // C is a multiple of the K step: a whole K step lies inside one tap
+  int pix[Base::PER_WAVE], yx[Base::PER_WAVE], kofs[Base::PER_WAVE];
+  __device__ __forceinline__ void init(const ConvKArgs& p, int m0, bool flip_, int wave_u) {
+    Base::init(p.img, p.img_bytes, m0, p.M, p.K, 0);
+    C = p.Cimg; H = p.H; W = p.W; flip = flip_; divC = p.divC;
+    tap_uniform = C % DBK == 0;
+#pragma unroll
+    for (int i = 0; i < Base::PER_WAVE; ++i) {
+      const int g = wave_u * Base::PER_WAVE + i;
+      const int trow = g * Base::ROWS_PER_LOAD + this->lrow;
+      kofs[i] = (this->lpos ^ ((trow / Base::RP) % Base::CPR)) * 8;
+      const int m = m0 + trow;
+      if (m < p.M) {
+        const int t = (int)p.divW.div((unsigned)m), x = m - t * W;
+        const int y = t - (int)p.divH.div((unsigned)t) * H;
+        pix[i] = m; yx[i] = (y << 16) | x;
+      } else {
+        pix[i] = -1; yx[i] = 0;
+      }
+    }
+  }
+  __device__ __forceinline__ void issue(int k0, unsigned short* stage, int wave_u) const {
+    if (tap_uniform) {
+      // k0 is the same for the whole workgroup: tap, its offsets and the shift in memory on the scalar unit
+      const int tap = (int)divC.div((unsigned)k0);
+      int dy, dx;
+      tap_offsets(tap, flip, dy, dx);
+      const int shift = (dy * W + dx) * C + (k0 - tap * C);
+      const bool k_ok = k0 < this->Ktot;   // Ktot = 9 C is a multiple of the K step too
+#pragma unroll
+      for (int i = 0; i < Base::PER_WAVE; ++i) {
+        const int g = wave_u * Base::PER_WAVE + i;
+        const int yy = (yx[i] >> 16) + dy, xx = (yx[i] & 0xffff) + dx;
+        const bool ok = k_ok && pix[i] >= 0 && yy >= 0 && yy < H && xx >= 0 && xx < W;
+        const unsigned off = ok ? (unsigned)(pix[i] * C + shift + kofs[i]) * 2u : kOOB;
+        dl::load_to_lds_16(this->rs, off, stage + g * 512);
+      }
+      return;
+    }
+#pragma unroll
+    for (int i = 0; i < Base::PER_WAVE; ++i) {
+      const int g = wave_u * Base::PER_WAVE + i;
+      const int k = k0 + kofs[i];
+      const int tap = (int)divC.div((unsigned)k), c = k - tap * C;
+      int dy, dx;
+      tap_offsets(tap, flip, dy, dx);
+      const int yy = (yx[i] >> 16) + dy, xx = (yx[i] & 0xffff) + dx;
+      const bool ok = pix[i] >= 0 && k < this->Ktot && yy >= 0 && yy < H && xx >= 0 && xx < W;
+      const unsigned off = ok ? (unsigned)((pix[i] + dy * W + dx) * C + c) * 2u : kOOB;
+      dl::load_to_lds_16(this->rs, off, stage + g * 512);
+    }
+  }
+};
+
+// B operand of dX: rows are input channels n (of the range that starts at c0), k = (tap, o), o contiguous:
+// w[(tap * Cin + c0 + n) * Cout + o]
+struct WeightsDX : dl::OperandKC<DBN, DBK, DNW> {
+  using Base = dl::OperandKC<DBN, DBK, DNW>;
+  int Cin, Cout, c0;
+  FastDiv divC;   // by Cout
+  __device__ __forceinline__ void init(const ConvKArgs& p, int n0) {
+    Base::init(p.mat, p.mat_bytes, n0, p.N, p.K, 0);
+    Cin = p.Cin; Cout = p.Cout; c0 = p.c0; divC = p.divC;
+  }
+  __device__ __forceinline__ void issue(int k0, unsigned short* stage, int wave_u) const {
+    const bool tap_uniform = Cout % DBK == 0;
+    const int tap_u = (int)divC.div((unsigned)k0);   // scalar
+#pragma unroll
+    for (int i = 0; i < Base::PER_WAVE; ++i) {
+      const int g = wave_u * Base::PER_WAVE + i;
+      const int trow = g * Base::ROWS_PER_LOAD + this->lrow;
+      const int chunk = this->lpos ^ ((trow / Base::RP) % Base::CPR);
+      const int n = this->r0 + trow, k = k0 + chunk * 8;
+      const int tap = tap_uniform ? tap_u : (int)divC.div((unsigned)k), o = k - tap * Cout;
+      const unsigned off = (n < this->Rtot && k < this->Ktot) ? (unsigned)((tap * Cin + c0 + n) * Cout + o) * 2u : kOOB;
+      dl::load_to_lds_16(this->rs, off, stage + g * 512);
+    }
+  }
+};
+
+// A operand of dW: rows are (tap, c), k runs over pixels; memory order [pixel][c] is kept in LDS and
+// transposed by the LDS read, as in dl::OperandKS.
+struct PixelsKS : dl::OperandKS<DBM, DBK, DNW> {
+  using Base = dl::OperandKS<DBM, DBK, DNW>;
+  int C, H, W;
+  FastDiv divW, divH;
+  int rowinfo[Base::PER_WAVE];   // (dy + 1) | (dx + 1) << 2 | c << 4 of the 8 rows this lane fetches; -1: past M
+  __device__ __forceinline__ void init(const ConvKArgs& p, int m0, int wave_u) {
+    Base::init(p.img, p.img_bytes, m0, p.M, p.K, 0);
+    C = p.Cimg; H = p.H; W = p.W; divW = p.divW; divH = p.divH;
+#pragma unroll
+    for (int i = 0; i < Base::PER_WAVE; ++i) {
+      const int g = wave_u * Base::PER_WAVE + i;
+      const int kr = g * Base::ROWS_PER_LOAD + this->lk;
+      const int m = m0 + (this->lpos ^ Base::swz(kr)) * 8;
+      const int tap = (int)p.divC.div((unsigned)m), c = m - tap * C;
+      int dy, dx;
+      tap_offsets(tap, false, dy, dx);
+      rowinfo[i] = m < p.M ? ((dy + 1) | ((dx + 1) << 2) | (c << 4)) : -1;
+    }
+  }
+  __device__ __forceinline__ void issue(int k0, unsigned short* stage, int wave_u) const {
+#pragma unroll
+    for (int i = 0; i < Base::PER_WAVE; ++i) {
+      const int g = wave_u * Base::PER_WAVE + i;
+      const int pxl = k0 + g * Base::ROWS_PER_LOAD + this->lk;
+      const int t = (int)divW.div((unsigned)pxl), x = pxl - t * W;
+      const int y = t - (int)divH.div((unsigned)t) * H;
+      const int ri = rowinfo[i];
+      const int dy = (ri & 3) - 1, dx = ((ri >> 2) & 3) - 1, c = ri >> 4;
+      const int yy = y + dy, xx = x + dx;
+      const bool ok = ri >= 0 && pxl < this->Ktot && yy >= 0 && yy < H && xx >= 0 && xx < W;
+      const unsigned off = ok ? (unsigned)((pxl + dy * W + dx) * C + c) * 2u : kOOB;
+      dl::load_to_lds_16(this->rs, off, stage + g * 512);
+    }
+  }
+};
+
+using MatKS = dl::OperandKS<DBN, DBK, DNW>;   // W of F ([9 C_in][C_out]) and dY of dW ([pixels][C_out])
+
+__global__ void __launch_bounds__(DNT) conv_fwd_dl_kernel(ConvKArgs p) {
+  extern __shared__ __attribute__((aligned(16))) unsigned short smem[];
+  int tm, tn;
+  tile_of_block<false>(blockIdx.x, (p.M + DBM - 1) / DBM, (p.N + DBN - 1) / DBN, tm, tn);
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  PixelsKC oa;
+  oa.init(p, tm * DBM, false, wave);
+  MatKS ob;
+  ob.init(p.mat, p.mat_bytes, tn * DBN, p.N, p.K, p.Cout);
+  StoreEpilogue epi{p.out_z, p.out_a, nullptr, p.M, p.N, p.ldc, p.act, tm * DBM, tn * DBN, p.vec_out != 0};
+  dl::gemm_tile_dl<DBM, DBN, DBK, DSTAGES, DWM, DWN>(oa, ob, 0, (p.K + DBK - 1) / DBK, smem, epi);
+}
+
+__global__ void __launch_bounds__(DNT) conv_dx_dl_kernel(ConvKArgs p) {
+  extern __shared__ __attribute__((aligned(16))) unsigned short smem[];
+  int tm, tn;
+  tile_of_block<false>(blockIdx.x, (p.M + DBM - 1) / DBM, (p.N + DBN - 1) / DBN, tm, tn);
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  PixelsKC oa;
+  oa.init(p, tm * DBM, true, wave);
+  WeightsDX ob;
+  ob.init(p, tn * DBN);
+  StoreEpilogue epi{p.out_z, nullptr, nullptr, p.M, p.N, p.ldc, 0, tm * DBM, tn * DBN, p.vec_out != 0};
+  dl::gemm_tile_dl<DBM, DBN, DBK, DSTAGES, DWM, DWN>(oa, ob, 0, (p.K + DBK - 1) / DBK, smem, epi);
+}
+
+__global__ void __launch_bounds__(DNT) conv_dw_dl_kernel(ConvKArgs p) {
+  extern __shared__ __attribute__((aligned(16))) unsigned short smem[];
+  const int nbn = (p.N + DBN - 1) / DBN;
+  const int tm = blockIdx.x / nbn, tn = blockIdx.x % nbn;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int KT = (p.K + DBK - 1) / DBK;
+  const int kt0 = blockIdx.y * p.kt_per_split;
+  const int kt1 = kt0 + p.kt_per_split < KT ? kt0 + p.kt_per_split : KT;
+  const int k_end = kt1 * DBK < p.K ? kt1 * DBK : p.K;   // this workgroup's pixel range ends here: later tiles load zeros
+  PixelsKS oa;
+  oa.init(p, tm * DBM, wave);
+  oa.Ktot = k_end;
+  MatKS ob;
+  ob.init(p.mat, p.mat_bytes, tn * DBN, p.N, k_end, p.Cout);
+  float* out = p.out_f32 + (size_t)blockIdx.y * p.M * p.N;   // split s writes partial s (gridDim.y == 1: the result)
+  StoreEpilogue epi{nullptr, nullptr, out, p.M, p.N, p.ldc, 0, tm * DBM, tn * DBN, p.vec_out != 0};
+  dl::gemm_tile_dl<DBM, DBN, DBK, DSTAGES, DWM, DWN>(oa, ob, kt0 * DBK, kt1 > kt0 ? kt1 - kt0 : 0, smem, epi);
+}
+
+constexpr size_t kLdsDl = (size_t)DSTAGES * (DBM + DBN) * DBK * sizeof(unsigned short);
+
+}  // namespace cdl
 
 template <bool ALIGNED_A, bool ALIGNED_B>
 __global__ void __launch_bounds__(NT) conv_fwd_kernel(ConvKArgs p) {
@@ -252,7 +475,14 @@ __global__ void __launch_bounds__(256) reduce_partials_kernel(const float* __res
   const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
   if (i >= n) return;
   float acc = 0.f;
-  for (int s = 0; s < splits; ++s) acc += part[(size_t)s * n + i];
+  for (int s0 = 0; s0 < splits; s0 += 8) {   // eight loads in flight at a time; summed in split order
+    float v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = s0 + u < splits ? part[(size_t)(s0 + u) * n + i] : 0.f;
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+      if (s0 + u < splits) acc += v[u];
+  }
   g[i] = acc;
 }
 
@@ -263,15 +493,36 @@ hipError_t set_lds(K kern) {
   return hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLds);
 }
 
+// both loops use 128 x 64 tiles; a split covers at least 512 pixels
 int dw_splits(const ConvDesc& c) {
   const long M = 9L * c.Cin, N = c.Cout, K = (long)c.B * c.H * c.W;
   const long tiles = ((M + BM - 1) / BM) * ((N + BN - 1) / BN);
-  const long KT = (K + BK - 1) / BK;
-  long s = (512 + tiles - 1) / tiles;   // aim at about two workgroups per CU
-  if (s > KT) s = KT;
-  if (s > 64) s = 64;
+  long s = (768 + tiles - 1) / tiles;   // aim at about three workgroups per CU
+  if (s > K / 512) s = K / 512;
+  if (s > 128) s = 128;
   if (s < 1) s = 1;
   return (int)s;
+}
+
+// the direct-to-LDS kernels need 16-byte chunks of 8 channels everywhere
+bool dl_ok(const ConvDesc& c, const void* a, const void* b) {
+  return c.Cin % 8 == 0 && c.Cout % 8 == 0 && (uintptr_t)a % 16 == 0 && (uintptr_t)b % 16 == 0;
+}
+
+template <class K>
+hipError_t set_lds_dl(K kern, bool& done) {
+  if (done) return hipSuccess;
+  hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)cdl::kLdsDl);
+  done = e == hipSuccess;
+  return e;
+}
+
+// largest dividends: a pixel index (+ one K tile of overshoot) for W and H, a (tap, channel) index (+ a tile) for C
+void set_divs(ConvKArgs& p, const ConvDesc& c) {
+  const unsigned long long pix = (unsigned long long)c.B * c.H * c.W + 256;
+  p.divW = FastDiv::make((unsigned)c.W, pix);
+  p.divH = FastDiv::make((unsigned)c.H, pix);
+  p.divC = FastDiv::make((unsigned)p.Cimg, 9ull * p.Cimg + 256);
 }
 
 bool fits32(const ConvDesc& c) {
@@ -297,8 +548,15 @@ hipError_t launch_conv_fwd(const ConvDesc& c, bool bf16, const void* x, const vo
   p.ldc = c.Cout; p.act = act;
   p.img_bytes = (unsigned)((size_t)p.M * c.Cin * 2); p.mat_bytes = (unsigned)((size_t)p.K * c.Cout * 2);
   p.vec_out = (c.Cout % 4 == 0) && ((uintptr_t)out_z % 8 == 0) && ((uintptr_t)out_a % 8 == 0);
+  set_divs(p, c);
   const bool al_a = c.Cin % 8 == 0 && (uintptr_t)x % 16 == 0, al_b = c.Cout % 8 == 0 && (uintptr_t)w % 16 == 0;
   const int nb = ((p.M + BM - 1) / BM) * ((p.N + BN - 1) / BN);
+  if (dl_ok(c, x, w)) {
+    static bool attr_dl = false;
+    if (hipError_t e = set_lds_dl(cdl::conv_fwd_dl_kernel, attr_dl)) return e;
+    hipLaunchKernelGGL(cdl::conv_fwd_dl_kernel, dim3(nb), dim3(cdl::DNT), cdl::kLdsDl, s, p);
+    return hipGetLastError();
+  }
   static bool attr = false;
   if (!attr) {
     hipError_t e = set_lds(conv_fwd_kernel<true, true>);
@@ -328,7 +586,14 @@ hipError_t launch_conv_grad_act(const ConvDesc& c, bool bf16, const void* dy, co
   p.ldc = c.Cin; p.act = 0;
   p.img_bytes = (unsigned)((size_t)p.M * c.Cout * 2); p.mat_bytes = (unsigned)((size_t)9 * c.Cin * c.Cout * 2);
   p.vec_out = (p.N % 4 == 0) && (c.Cin % 4 == 0) && ((uintptr_t)p.out_z % 8 == 0);
+  set_divs(p, c);
   const int nb = ((p.M + BM - 1) / BM) * ((p.N + BN - 1) / BN);
+  if (dl_ok(c, dy, w) && c0 % 8 == 0) {
+    static bool attr_dl = false;
+    if (hipError_t e = set_lds_dl(cdl::conv_dx_dl_kernel, attr_dl)) return e;
+    hipLaunchKernelGGL(cdl::conv_dx_dl_kernel, dim3(nb), dim3(cdl::DNT), cdl::kLdsDl, s, p);
+    return hipGetLastError();
+  }
   static bool attr = false;
   if (!attr) {
     hipError_t e = set_lds(conv_dx_kernel);
@@ -351,9 +616,12 @@ hipError_t launch_conv_grad_weight(const ConvDesc& c, bool bf16, const void* x, 
   p.M = 9 * c.Cin; p.N = c.Cout; p.K = c.B * c.H * c.W;
   p.ldc = c.Cout; p.act = 0;
   p.img_bytes = (unsigned)((size_t)p.K * c.Cin * 2); p.mat_bytes = (unsigned)((size_t)p.K * c.Cout * 2);
-  const int KT = (p.K + BK - 1) / BK;
+  const bool use_dl = dl_ok(c, x, dy);
+  const int bk = use_dl ? cdl::DBK : BK;
+  const int KT = (p.K + bk - 1) / bk;
   p.kt_per_split = (KT + splits - 1) / splits;
   p.vec_out = (c.Cout % 4 == 0) && ((uintptr_t)p.out_f32 % 16 == 0) && (((size_t)p.M * p.N) % 4 == 0);
+  set_divs(p, c);
   const bool al_a = c.Cin % 8 == 0 && (uintptr_t)x % 16 == 0, al_b = c.Cout % 8 == 0 && (uintptr_t)dy % 16 == 0;
   const int nb = ((p.M + BM - 1) / BM) * ((p.N + BN - 1) / BN);
   static bool attr = false;
@@ -366,7 +634,11 @@ hipError_t launch_conv_grad_weight(const ConvDesc& c, bool bf16, const void* x, 
     attr = true;
   }
   const dim3 grid(nb, splits);
-  if (al_a && al_b) hipLaunchKernelGGL((conv_dw_kernel<true, true>), grid, dim3(NT), kLds, s, p);
+  if (use_dl) {
+    static bool attr_dl = false;
+    if (hipError_t e = set_lds_dl(cdl::conv_dw_dl_kernel, attr_dl)) return e;
+    hipLaunchKernelGGL(cdl::conv_dw_dl_kernel, grid, dim3(cdl::DNT), cdl::kLdsDl, s, p);
+  } else if (al_a && al_b) hipLaunchKernelGGL((conv_dw_kernel<true, true>), grid, dim3(NT), kLds, s, p);
   else if (!al_a && al_b) hipLaunchKernelGGL((conv_dw_kernel<false, true>), grid, dim3(NT), kLds, s, p);
   else if (al_a && !al_b) hipLaunchKernelGGL((conv_dw_kernel<true, false>), grid, dim3(NT), kLds, s, p);
   else hipLaunchKernelGGL((conv_dw_kernel<false, false>), grid, dim3(NT), kLds, s, p);

@@ -61,6 +61,13 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_bf16_kernel(GemmKArgs p) {
   if constexpr (SGD) {
     SgdEpilogue epi{p.sgd_master, p.out_z, p.neg_lr, p.M, p.N, p.ldc, m0, n0, p.vec_out != 0};
     gemm_tile<BM, BN, BK, WM, WN>(sa, sb, 0, (p.K + BK - 1) / BK, smem, epi);
+  } else if (p.kt_per_split > 0) {
+    // split-K: K tiles [kt0, kt1) into an fp32 partial, as in the direct-to-LDS kernel
+    const int KT = (p.K + BK - 1) / BK;
+    const int kt0 = blockIdx.y * p.kt_per_split;
+    const int kt1 = kt0 + p.kt_per_split < KT ? kt0 + p.kt_per_split : KT;
+    StoreEpilogue epi{nullptr, nullptr, p.partial + (size_t)blockIdx.y * p.M * p.N, p.M, p.N, p.N, 0, m0, n0, (p.N % 4) == 0};
+    gemm_tile<BM, BN, BK, WM, WN>(sa, sb, kt0, kt1, smem, epi);
   } else {
     StoreEpilogue epi{p.out_z, p.out_a, p.out_f32, p.M, p.N, p.ldc, p.act, m0, n0, p.vec_out != 0};
     gemm_tile<BM, BN, BK, WM, WN>(sa, sb, 0, (p.K + BK - 1) / BK, smem, epi);
@@ -108,11 +115,18 @@ __global__ void __launch_bounds__(256) splitk_reduce_kernel(const float* __restr
   const size_t mn = (size_t)p.M * p.N, o = (size_t)row * p.N + col;
   f32x4 acc = {0.f, 0.f, 0.f, 0.f};
   if (p.N % 4 == 0) {
-    acc = *reinterpret_cast<const f32x4*>(part + o);
-    for (int s = 1; s < splits; ++s) {
-      const f32x4 v = *reinterpret_cast<const f32x4*>(part + (size_t)s * mn + o);
+    // eight loads in flight at a time (a partial is one cache miss each); summed in split order
+    for (int s0 = 0; s0 < splits; s0 += 8) {
+      f32x4 v[8];
 #pragma unroll
-      for (int t = 0; t < 4; ++t) acc[t] += v[t];
+      for (int u = 0; u < 8; ++u)
+        v[u] = s0 + u < splits ? __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(part + (size_t)(s0 + u) * mn + o)) : f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+        if (s0 + u < splits) {
+#pragma unroll
+          for (int t = 0; t < 4; ++t) acc[t] += v[u][t];
+        }
     }
   } else {
 #pragma unroll
@@ -179,6 +193,16 @@ hipError_t launch_one(const GemmKArgs& a, hipStream_t s) {
     attr_done = true;
   }
   const int nb = ((a.M + BM - 1) / BM) * ((a.N + BN - 1) / BN);
+  if (a.kt_per_split > 0 && !SGD) {
+    const int KT = (a.K + BK - 1) / BK;
+    const int splits = (KT + a.kt_per_split - 1) / a.kt_per_split;
+    hipLaunchKernelGGL(kern, dim3(nb, splits), dim3(WM * WN * 64), lds, s, a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const size_t n4 = (size_t)a.M * ((a.N + 3) / 4);
+    hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, s, (const float*)a.partial, splits, a);
+    return hipGetLastError();
+  }
   hipLaunchKernelGGL(kern, dim3(nb), dim3(WM * WN * 64), lds, s, a);
   return hipGetLastError();
 }
@@ -228,7 +252,10 @@ int splitk_factor(int M, int N, int K) {
   const long t128 = (long)((M + 127) / 128) * ((N + 127) / 128);
   if (t256 >= 192 || t128 >= 256 || K < 2048) return 1;
   long s = 512 / t128;               // two workgroups per CU
-  if (s > K / 1024) s = K / 1024;    // at least sixteen K steps each: shorter ranges cost more in partial-sum traffic than they gain
+  // at least sixteen K steps each (shorter ranges cost more in partial-sum traffic than they gain), four
+  // when the whole output is so small (64 K elements) that its partials do not matter
+  const long min_k = (long)M * N <= 65536 ? 256 : 1024;
+  if (s > K / min_k) s = K / min_k;
   if (s > 16) s = 16;
   return s < 2 ? 1 : (int)s;
 }
@@ -298,26 +325,26 @@ hipError_t launch_gemm_bf16(const GemmDesc& d, hipStream_t s, int tile_cfg) {
     else cfg = t128 >= 64 ? 1 : 2;
   }
   if (cfg < 0 || cfg >= gemm_bf16_num_cfgs()) return hipErrorInvalidValue;
+  if (tile_cfg < 0 && !sgd && (cfg == 5 || cfg == 1 || cfg == 2)) {
+    // small tiles that do not fill the chip and a long reduction: split K over workgroups.  A caller
+    // that multiplies a column range of a larger product passes the split count of the whole product,
+    // so that every output element is summed in the same order however the columns are cut.
+    const int splits = d.splitk_splits >= 0 ? d.splitk_splits : splitk_factor(d.M, d.N, d.K);
+    if (splits > 1) {
+      const bool fits = d.splitk_scratch && d.splitk_bytes >= (size_t)splits * d.M * d.N * sizeof(float) &&
+                        (uintptr_t)d.splitk_scratch % 16 == 0;
+      if (fits) {
+        const int KT = (d.K + 63) / 64;
+        a.kt_per_split = (KT + splits - 1) / splits;
+        a.partial = d.splitk_scratch;
+      } else if (d.splitk_splits > 1) {
+        return hipErrorInvalidValue;   // a forced split count must not silently change the summation order
+      }
+    }
+  }
   if (kCfgs[cfg].kind == 1) {
     if (!aligned) return hipErrorInvalidValue;
     if (sgd) return launch_cfg_dl_sgd(cfg, a, s);
-    if (cfg == 5 && tile_cfg < 0) {
-      // 128x128 tiles that do not fill the chip and a long reduction: split K over workgroups.  A caller
-      // that multiplies a column range of a larger product passes the split count of the whole product,
-      // so that every output element is summed in the same order however the columns are cut.
-      const int splits = d.splitk_splits >= 0 ? d.splitk_splits : splitk_factor(d.M, d.N, d.K);
-      if (splits > 1) {
-        const bool fits = d.splitk_scratch && d.splitk_bytes >= (size_t)splits * d.M * d.N * sizeof(float) &&
-                          (uintptr_t)d.splitk_scratch % 16 == 0;
-        if (fits) {
-          const int KT = (d.K + 63) / 64;
-          a.kt_per_split = (KT + splits - 1) / splits;
-          a.partial = d.splitk_scratch;
-        } else if (d.splitk_splits > 1) {
-          return hipErrorInvalidValue;   // a forced split count must not silently change the summation order
-        }
-      }
-    }
     if (d.a_kcontig && d.b_kcontig) return launch_cfg_dl<true, true>(cfg, a, s);
     if (d.a_kcontig && !d.b_kcontig) return launch_cfg_dl<true, false>(cfg, a, s);
     if (!d.a_kcontig && !d.b_kcontig) return launch_cfg_dl<false, false>(cfg, a, s);

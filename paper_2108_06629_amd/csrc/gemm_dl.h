@@ -92,10 +92,15 @@ struct OperandKC {
 };
 
 // ---- operand with k strided in memory: element (r,k) at base[k*ld + r] ---------------------------
-// LDS stage: [BK][R] halves, chunk p of k-row k holds global chunk p ^ ((k&3)<<2).
+// LDS stage: [BK][R] halves, chunk p of k-row k holds global chunk p ^ swz(k).  A transposing read of
+// half a wave touches four consecutive k-rows, 64 bytes of each; swz moves those four segments onto
+// different quarters of the 256-byte bank line: rows of 256 or 512 bytes (R = 128, 256) all start on the
+// same quarter, so row k moves by k & 3 quarters; rows of 128 bytes (R = 64) alternate between two
+// quarters by themselves, so rows 2 and 3 of a group move by one.
 template <int R, int BK, int NWAVES>
 struct OperandKS {
-  static_assert(R == 128 || R == 256, "row length of 16 or 32 chunks");
+  static_assert(R == 64 || R == 128 || R == 256, "row length of 8, 16 or 32 chunks");
+  static __device__ __forceinline__ int swz(int k) { return R == 64 ? ((k >> 1) & 1) << 2 : (k & 3) << 2; }
   static constexpr int STAGE_ELEMS = R * BK;
   static constexpr int CPR = R / 8;                          // chunks per k-row
   static constexpr int ROWS_PER_LOAD = 64 / CPR;             // k-rows per 1 KB wave load
@@ -117,7 +122,7 @@ struct OperandKS {
     for (int i = 0; i < PER_WAVE; ++i) {
       const int g = wave_u * PER_WAVE + i;
       const int kr = g * ROWS_PER_LOAD + lk;                 // k-row inside the tile
-      const int chunk = lpos ^ ((kr & 3) << 2);
+      const int chunk = lpos ^ swz(kr);
       const int k = k0 + kr, r = r0 + chunk * 8;
       const unsigned off = (k < Ktot && r < Rtot) ? ((unsigned)k * (unsigned)ld + (unsigned)r) * 2u : kOOB;
       load_to_lds_16(rs, off, stage + g * 512);
@@ -128,7 +133,7 @@ struct OperandKS {
     const int l16 = lane & 15, j = l16 >> 2, a = l16 & 3;
     const int col = row0 + ((lane >> 4) & 1) * 16 + a * 4;  // first of the four elements this lane points at
     const int k = kk * 16 + (lane >> 5) * 8 + j;             // k & 3 == j for both halves
-    const int chunk = (col >> 3) ^ (j << 2);
+    const int chunk = (col >> 3) ^ swz(j);
     const unsigned short* p = stage + k * R + chunk * 8 + (col & 7);
     const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)p);
     const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p + 4 * R));
