@@ -10,6 +10,7 @@
 #include <cstring>
 #include <new>
 #include <string>
+#include <unordered_map>
 #include <vector>
 
 #include "lp_kernels.h"
@@ -66,6 +67,14 @@ struct lp_ctx {
   hipEvent_t ev_fork = nullptr, ev_join_w = nullptr, ev_join_u = nullptr;
   hipEvent_t ev_loss[2] = {nullptr, nullptr}, ev_bdone[2] = {nullptr, nullptr};
   std::vector<hipStream_t> streams_seen;
+  // Bookkeeping that lets lp_step drop waits that earlier waits already imply (a wait that is followed
+  // by a launch costs the host several times what the launch costs).  Every record on a stream gets that
+  // stream's next sequence number; a stream that has waited for record q of stream s has thereby waited
+  // for every earlier record of s.
+  struct EvInfo { int src = -1; long seq = 0; };
+  std::unordered_map<hipEvent_t, EvInfo> ev_info;
+  std::vector<long> rec_count;                 // [stream index]: records so far
+  std::vector<std::vector<long>> waited_seq;   // [waiting stream][recording stream]: newest record waited for
   // measurement aid (lp_profile)
   struct ProfRec { int task, layer; hipEvent_t e0, e1; };
   bool prof_on = false;
@@ -101,6 +110,35 @@ inline void note_stream(lp_ctx* c, hipStream_t s) {
   for (hipStream_t t : c->streams_seen)
     if (t == s) return;
   c->streams_seen.push_back(s);
+}
+
+inline int stream_index(lp_ctx* c, hipStream_t s) {
+  for (size_t i = 0; i < c->streams_seen.size(); ++i)
+    if (c->streams_seen[i] == s) return (int)i;
+  c->streams_seen.push_back(s);
+  return (int)c->streams_seen.size() - 1;
+}
+hipError_t record_on(lp_ctx* c, hipEvent_t e, hipStream_t s) {
+  const int si = stream_index(c, s);
+  if ((int)c->rec_count.size() <= si) c->rec_count.resize(si + 1, 0);
+  lp_ctx::EvInfo& info = c->ev_info[e];
+  info.src = si;
+  info.seq = ++c->rec_count[si];
+  return hipEventRecord(e, s);
+}
+// s waits for the latest record of e, unless that is implied: e was never recorded, was recorded on s
+// itself (a stream runs in order), or s has already waited for that record or a later one of the same stream.
+hipError_t wait_on(lp_ctx* c, hipStream_t s, hipEvent_t e) {
+  auto it = c->ev_info.find(e);
+  if (it == c->ev_info.end() || it->second.src < 0) return hipSuccess;
+  const int di = stream_index(c, s), si = it->second.src;
+  if (di == si) return hipSuccess;
+  if ((int)c->waited_seq.size() <= di) c->waited_seq.resize(di + 1);
+  std::vector<long>& w = c->waited_seq[di];
+  if ((int)w.size() <= si) w.resize(si + 1, 0);
+  if (w[si] >= it->second.seq) return hipSuccess;
+  w[si] = it->second.seq;
+  return hipStreamWaitEvent(s, e, 0);
 }
 
 // Brackets one task launch with timing events on its stream when profiling is on.
@@ -381,29 +419,29 @@ int step_run_ahead(lp_ctx* c, const void* X0, const void* target, float* loss_de
     Layer& ly = c->layers[i];
     const long src = n - ly.delay;
     if (src < 1) return LP_OK;
-    LP_HIP(c, hipStreamWaitEvent(sU, c->ev_dw[i], 0));                       // G_l(src) is in the ring
-    LP_HIP(c, hipStreamWaitEvent(sU, i > 0 ? c->ev_dx[i] : c->ev_loss[p ^ 1], 0));   // readers of the copy being overwritten
+    LP_HIP(c, wait_on(c, sU, c->ev_dw[i]));                       // G_l(src) is in the ring
+    LP_HIP(c, wait_on(c, sU, i > 0 ? c->ev_dx[i] : c->ev_loss[p ^ 1]));   // readers of the copy being overwritten
     LP_HIP(c, enqueue_update(c, ly, src, sU));
-    LP_HIP(c, hipEventRecord(c->ev_upd[i], sU));
+    LP_HIP(c, record_on(c, c->ev_upd[i], sU));
     updated[i] = 1;
     return LP_OK;
   };
   // forward chain of step n on sF
-  LP_HIP(c, hipStreamWaitEvent(sF, c->ev_bdone[p], 0));
+  LP_HIP(c, wait_on(c, sF, c->ev_bdone[p]));
   const void* a_prev = X0;
   for (int i = 0; i < L; ++i) {
     Layer& ly = c->layers[i];
     void* Z = ly.has_Z ? c->ws + ly.off_Z[p] : nullptr;
     void* A = ly.has_A ? c->ws + ly.off_A[p] : nullptr;
-    LP_HIP(c, hipStreamWaitEvent(sF, c->ev_upd[i], 0));   // W_l(n-1) is complete (recorded by update_l(n-1) at the latest)
+    LP_HIP(c, wait_on(c, sF, c->ev_upd[i]));   // W_l(n-1) is complete (recorded by update_l(n-1) at the latest)
     LP_HIP(c, do_forward(c, ly, a_prev, Z, A, sF, 3));
     a_prev = A;
   }
   Layer& last = c->layers[L - 1];
-  LP_HIP(c, hipStreamWaitEvent(sF, c->ev_dx[L - 1], 0));
-  LP_HIP(c, hipStreamWaitEvent(sF, c->ev_dw[L - 1], 0));
+  LP_HIP(c, wait_on(c, sF, c->ev_dx[L - 1]));
+  LP_HIP(c, wait_on(c, sF, c->ev_dw[L - 1]));
   LP_HIP(c, do_loss(c, c->ws + last.off_Z[p], target, c->ws + last.off_dY, loss_dev, sF));
-  LP_HIP(c, hipEventRecord(c->ev_loss[p], sF));
+  LP_HIP(c, record_on(c, c->ev_loss[p], sF));
 
   // Updates that need no gradient of this step (their G tasks ran in earlier steps).  Enqueued after
   // the forward chain so that F_l(n) above waited for update_l(n-1), not for these.
@@ -412,8 +450,8 @@ int step_run_ahead(lp_ctx* c, const void* X0, const void* target, float* loss_de
       if (int r = issue_update(i)) return r;
 
   // backward pass of step n
-  LP_HIP(c, hipStreamWaitEvent(sC, c->ev_loss[p], 0));
-  LP_HIP(c, hipEventRecord(c->ev_dy[L - 1], sC));
+  LP_HIP(c, wait_on(c, sC, c->ev_loss[p]));
+  LP_HIP(c, record_on(c, c->ev_dy[L - 1], sC));
   for (int i = L - 1; i >= 0; --i) {
     Layer& ly = c->layers[i];
     const void* x_in = i == 0 ? X0 : (const void*)(c->ws + c->layers[i - 1].off_A[p]);
@@ -422,31 +460,31 @@ int step_run_ahead(lp_ctx* c, const void* X0, const void* target, float* loss_de
       Layer& pv = c->layers[i - 1];
       if (ly.split_cols > 0) {
         const int cut = ly.d.in - ly.split_cols;
-        LP_HIP(c, hipStreamWaitEvent(sW, c->ev_dy[i], 0));
+        LP_HIP(c, wait_on(c, sW, c->ev_dy[i]));
         LP_HIP(c, do_grad_act(c, ly, dY, c->ws + pv.off_dA, cut, ly.d.in, sW));
-        LP_HIP(c, hipEventRecord(c->ev_split[i], sW));
+        LP_HIP(c, record_on(c, c->ev_split[i], sW));
         LP_HIP(c, do_grad_act(c, ly, dY, c->ws + pv.off_dA, 0, cut, sC));
-        LP_HIP(c, hipStreamWaitEvent(sC, c->ev_split[i], 0));
+        LP_HIP(c, wait_on(c, sC, c->ev_split[i]));
       } else {
         LP_HIP(c, do_grad_act(c, ly, dY, c->ws + pv.off_dA, 0, ly.d.in, sC));
       }
-      LP_HIP(c, hipEventRecord(c->ev_dx[i], sC));
+      LP_HIP(c, record_on(c, c->ev_dx[i], sC));
       if (pv.off_dY != pv.off_dA) {
         const void* S = pv.has_Z ? c->ws + pv.off_Z[p] : c->ws + pv.off_A[p];
         LP_HIP(c, do_act_grad(c, pv, c->ws + pv.off_dA, S, c->ws + pv.off_dY, sC));
       }
-      LP_HIP(c, hipEventRecord(c->ev_dy[i - 1], sC));
+      LP_HIP(c, record_on(c, c->ev_dy[i - 1], sC));
     }
-    LP_HIP(c, hipStreamWaitEvent(sW, c->ev_dy[i], 0));
-    LP_HIP(c, hipStreamWaitEvent(sW, c->ev_upd[i], 0));   // the ring slot's previous gradient has been applied
+    LP_HIP(c, wait_on(c, sW, c->ev_dy[i]));
+    LP_HIP(c, wait_on(c, sW, c->ev_upd[i]));   // the ring slot's previous gradient has been applied
     LP_HIP(c, enqueue_G(c, ly, x_in, dY, n, sW));
-    LP_HIP(c, hipEventRecord(c->ev_dw[i], sW));
+    LP_HIP(c, record_on(c, c->ev_dw[i], sW));
     if (!updated[i])
       if (int r = issue_update(i)) return r;
   }
-  LP_HIP(c, hipEventRecord(c->ev_join_w, sW));
-  LP_HIP(c, hipStreamWaitEvent(sC, c->ev_join_w, 0));
-  LP_HIP(c, hipEventRecord(c->ev_bdone[p], sC));
+  LP_HIP(c, record_on(c, c->ev_join_w, sW));
+  LP_HIP(c, wait_on(c, sC, c->ev_join_w));
+  LP_HIP(c, record_on(c, c->ev_bdone[p], sC));
 
   for (int i = 0; i < L; ++i)
     if (updated[i]) c->layers[i].cur ^= 1;
@@ -466,9 +504,9 @@ int enqueue_step(lp_ctx* c, const void* X0, const void* target, float* loss_dev,
   updated.assign(L, 0);
 
   if (multi) {
-    LP_HIP(c, hipEventRecord(c->ev_fork, sC));
-    if (sW != sC) LP_HIP(c, hipStreamWaitEvent(sW, c->ev_fork, 0));
-    if (sU != sC) LP_HIP(c, hipStreamWaitEvent(sU, c->ev_fork, 0));
+    LP_HIP(c, record_on(c, c->ev_fork, sC));
+    if (sW != sC) LP_HIP(c, wait_on(c, sW, c->ev_fork));
+    if (sU != sC) LP_HIP(c, wait_on(c, sU, c->ev_fork));
   }
 
   // Delayed updates whose gradient is already in the ring (d_l > 0).  BF16 keeps two versions of
@@ -498,7 +536,7 @@ int enqueue_step(lp_ctx* c, const void* X0, const void* target, float* loss_dev,
   }
   Layer& last = c->layers[L - 1];
   LP_HIP(c, do_loss(c, c->ws + last.off_Z[0], target, c->ws + last.off_dY, loss_dev, sC));
-  if (multi) LP_HIP(c, hipEventRecord(c->ev_dy[L - 1], sC));
+  if (multi) LP_HIP(c, record_on(c, c->ev_dy[L - 1], sC));
 
   // backward: the delta chain on sC first (critical loop), G on sW, updates on sU
   for (int i = L - 1; i >= 0; --i) {
@@ -511,38 +549,38 @@ int enqueue_step(lp_ctx* c, const void* X0, const void* target, float* loss_dev,
         // delta' on the critical stream, delta'' (the columns the next stage borrowed, Sec. III-B) as an
         // independent kernel on the stream that otherwise carries the G tasks, ahead of this layer's G
         const int cut = ly.d.in - ly.split_cols;
-        if (multi && sW != sC) LP_HIP(c, hipStreamWaitEvent(sW, c->ev_dy[i], 0));
+        if (multi && sW != sC) LP_HIP(c, wait_on(c, sW, c->ev_dy[i]));
         LP_HIP(c, do_grad_act(c, ly, dY, c->ws + pv.off_dA, cut, ly.d.in, sW));
-        if (multi && sW != sC) LP_HIP(c, hipEventRecord(c->ev_split[i], sW));
+        if (multi && sW != sC) LP_HIP(c, record_on(c, c->ev_split[i], sW));
         LP_HIP(c, do_grad_act(c, ly, dY, c->ws + pv.off_dA, 0, cut, sC));
-        if (multi && sW != sC) LP_HIP(c, hipStreamWaitEvent(sC, c->ev_split[i], 0));
+        if (multi && sW != sC) LP_HIP(c, wait_on(c, sC, c->ev_split[i]));
       } else {
         LP_HIP(c, do_grad_act(c, ly, dY, c->ws + pv.off_dA, 0, ly.d.in, sC));
       }
-      if (multi) LP_HIP(c, hipEventRecord(c->ev_dx[i], sC));
+      if (multi && !bf) LP_HIP(c, record_on(c, c->ev_dx[i], sC));   // only an in-place (F32) update waits for it
       if (pv.off_dY != pv.off_dA) {
         const void* S = pv.has_Z ? c->ws + pv.off_Z[0] : c->ws + pv.off_A[0];
         LP_HIP(c, do_act_grad(c, pv, c->ws + pv.off_dA, S, c->ws + pv.off_dY, sC));
       }
-      if (multi) LP_HIP(c, hipEventRecord(c->ev_dy[i - 1], sC));
+      if (multi) LP_HIP(c, record_on(c, c->ev_dy[i - 1], sC));
     }
-    if (multi && sW != sC) LP_HIP(c, hipStreamWaitEvent(sW, c->ev_dy[i], 0));
+    if (multi && sW != sC) LP_HIP(c, wait_on(c, sW, c->ev_dy[i]));
     LP_HIP(c, enqueue_G(c, ly, x_in, dY, n, sW));
-    if (multi) LP_HIP(c, hipEventRecord(c->ev_dw[i], sW));
+    if (multi && !updated[i]) LP_HIP(c, record_on(c, c->ev_dw[i], sW));   // only this step's own update waits for it
     if (!updated[i]) {
       // d_l = 0 needs this step's G; an F32 context updates in place, so it also has to wait for
       // the last reader of W_l(n-1), which is dX_l (layer 1: the forward pass, long finished)
       if (multi) {
-        if (ly.delay == 0 && sU != sW) LP_HIP(c, hipStreamWaitEvent(sU, c->ev_dw[i], 0));
-        if (!bf && sU != sC) LP_HIP(c, hipStreamWaitEvent(sU, i > 0 ? c->ev_dx[i] : c->ev_dy[L - 1], 0));
+        if (ly.delay == 0 && sU != sW) LP_HIP(c, wait_on(c, sU, c->ev_dw[i]));
+        if (!bf && sU != sC) LP_HIP(c, wait_on(c, sU, i > 0 ? c->ev_dx[i] : c->ev_dy[L - 1]));
       }
       if (int r = issue_update(i)) return r;
     }
   }
 
   if (multi) {
-    if (sW != sC) { LP_HIP(c, hipEventRecord(c->ev_join_w, sW)); LP_HIP(c, hipStreamWaitEvent(sC, c->ev_join_w, 0)); }
-    if (sU != sC) { LP_HIP(c, hipEventRecord(c->ev_join_u, sU)); LP_HIP(c, hipStreamWaitEvent(sC, c->ev_join_u, 0)); }
+    if (sW != sC) { LP_HIP(c, record_on(c, c->ev_join_w, sW)); LP_HIP(c, wait_on(c, sC, c->ev_join_w)); }
+    if (sU != sC) { LP_HIP(c, record_on(c, c->ev_join_u, sU)); LP_HIP(c, wait_on(c, sC, c->ev_join_u)); }
   }
   return LP_OK;
 }
