@@ -110,3 +110,49 @@ def test_ffn_stack_full_size_sampled():
     assert abs(loss - loss_ref) <= 1e-5 * loss_ref
     assert relerr(f64(view(L, lp.LP_T_DY, wl.layers[-1].d_out)), O.store(dy_ref, "bf16")) <= 2.0 ** -7
     net.close()
+
+
+def _run_schedule(wl, W0, steps, **kw):
+    """`steps` training steps enqueued back to back from a pool of three resident minibatches; returns the
+    losses and a checksum-free copy of every layer's master weights."""
+    net = lp.Network(wl.layers, wl.batch, wl.dtype, wl.loss, wl.lr, wl.delays, **kw)
+    net.set_weights(W0)
+    xs = [net.to_device(WL.batch_input(wl, n)) for n in range(1, 4)]
+    ts = [net.to_device(WL.batch_target(wl, n), is_label=(wl.loss == WL.SOFTMAX_CE)) for n in range(1, 4)]
+    losses = torch.zeros(steps, dtype=torch.float32, device="cuda:0")
+    slot = torch.zeros(1, dtype=torch.float32, device="cuda:0")
+    torch.cuda.synchronize()
+    for n in range(steps):
+        if kw.get("graphs"):
+            # a captured step needs the same loss address every time; streams[0] carries the whole step
+            lp.lp_step(net.ctx, xs[n % 3], ts[n % 3], None, slot, net.streams)
+            with torch.cuda.stream(net.streams[0]):
+                losses[n:n + 1].copy_(slot)
+        else:
+            # with run-ahead the loss of step n+1 may be written while step n still runs: one slot per step
+            lp.lp_step(net.ctx, xs[n % 3], ts[n % 3], None, losses[n:n + 1], net.streams)
+    lp.lp_sync(net.ctx)
+    torch.cuda.synchronize()
+    out = (losses.cpu().numpy().copy(), [net.get_weights(l) for l in range(1, wl.L + 1)])
+    stats = lp.lp_graph_stats(net.ctx)
+    net.close()
+    return out, stats
+
+
+@pytest.mark.parametrize("name", ["mlp_4096_bf16", "vgg_small_bf16"])
+def test_full_size_schedules_and_ring_kinds_agree_bit_for_bit(name):
+    """At the benchmark's shapes: serial, run-ahead, graph replay, and the factor ring on top of each give
+    the same losses and weights.  (The serial product-ring run of these workloads is the one the tests
+    above compare with the oracle.)"""
+    wl = WL.CONFIGS[name]()
+    W0 = WL.init_weights(wl)
+    steps = max(wl.delays) + 22
+    ref, _ = _run_schedule(wl, W0, steps)
+    assert np.all(np.isfinite(ref[0]))
+    for kw in (dict(run_ahead=True), dict(graphs=True), dict(factor_ring=True), dict(factor_ring=True, run_ahead=True)):
+        got, stats = _run_schedule(wl, W0, steps, **kw)
+        assert np.array_equal(got[0].view(np.uint32), ref[0].view(np.uint32)), (kw, got[0][-4:], ref[0][-4:])
+        for l, (a, b) in enumerate(zip(got[1], ref[1]), start=1):
+            assert np.array_equal(a.view(np.uint32), b.view(np.uint32)), (kw, "W_%d" % l)
+        if kw.get("graphs"):
+            assert stats[0] > 0
