@@ -283,7 +283,7 @@ def main():
         avg_s = tasks["F"]["avg_ms"] * 1e-3
         ach = flops_per_launch / avg_s / 1e12
         roofline = {"bound": "mfma", "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS,
-                    "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name), "kernel": ("gemm_bf16_dl_kernel<256,256,64,2,2,4,true,false> (forward product F)" if wl.name == "ffn_stack_bf16"
+                    "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name), "kernel": ("gemm_bf16_dl_kernel<256,256,64,2,2,4,true,false,false> (forward product F)" if wl.name == "ffn_stack_bf16"
                                else "bf16 MFMA GEMM of the forward product F (tile and K split chosen per layer shape)"),
                     "flops_per_launch": flops_per_launch,
                     "avg_launch_ms": tasks["F"]["avg_ms"]}
