@@ -304,6 +304,11 @@ def main():
                 odt, oloss, _, _ = run_workload(o, o.steps, 3, args.streams, False)
                 others[name] = {"samples_per_s": o.batch * o.steps / odt, "ms_per_step": odt / o.steps * 1e3, "steps": o.steps,
                                 "final_loss": oloss}
+                if o.n_params < 5e8:
+                    # one stream: a third of the host's enqueue time (no cross-stream waits), best for launch-bound networks
+                    sdt, sloss, _, _ = run_workload(o, o.steps, 3, 1, False)
+                    others[name]["one_stream"] = {"samples_per_s": o.batch * o.steps / sdt, "ms_per_step": sdt / o.steps * 1e3,
+                                                  "final_loss": sloss}
                 if o.dtype == "bf16" and o.n_params < 5e8:
                     for label, kw in (("run_ahead", dict(run_ahead=True)), ("factor_ring", dict(factor_ring=True)),
                                       ("factor_ring+run_ahead", dict(run_ahead=True, factor_ring=True))):
