@@ -488,3 +488,38 @@ def test_delta_split_argument_errors():
     lp.lp_set_delta_split(net.ctx, 2, 47)
     lp.lp_set_delta_split(net.ctx, 1, 0)
     net.close()
+
+
+# ---- degenerate networks and the size guard ---------------------------------------------------------
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_trajectory_single_layer_network(dtype):
+    """L = 1: no dX task, no Hadamard, the only layer feeds the loss (multinomial logistic regression)."""
+    wl = WL.mlp_4096().with_(layers=WL._mlp([72, 10], WL.RELU), batch=40, delays=(0,), dtype=dtype, lr=0.1)
+    run_trajectory(wl, 6)
+
+
+def test_trajectory_batch_of_one_and_delayed_last_layer():
+    """One sample per step (every product degenerates to a row), and a last layer whose own update is delayed too."""
+    wl = WL.mlp_4096().with_(layers=WL._mlp([40, 24, 16, 8], WL.RELU), batch=1, delays=(5, 3, 2), dtype="f32", lr=0.05)
+    run_trajectory(wl, 10)
+    wl = WL.mlp_4096().with_(layers=WL._mlp([136, 72, 24], WL.GELU), batch=1, delays=(1, 1), dtype="bf16", lr=0.05)
+    run_trajectory(wl, 6)
+
+
+def test_operand_beyond_32_bit_offsets_is_rejected_not_launched():
+    """Byte offsets inside the kernels are 32-bit; a weight matrix of 2 GiB must come back as an error."""
+    n = 32768
+    layers = (WL.Layer(WL.LINEAR, n, n, WL.IDENTITY),)
+    net = lp.Network(layers, 8, "bf16", WL.MSE, 0.01, (0,))
+    w = torch.zeros(n, n, dtype=torch.float32, device=DEV)
+    lp.lp_set_weights(net.ctx, 1, w, True, net.streams[0])
+    lp.lp_sync(net.ctx)
+    del w
+    x = torch.zeros(8, n, dtype=torch.bfloat16, device=DEV)
+    z = torch.empty(8, n, dtype=torch.bfloat16, device=DEV)
+    with pytest.raises(lp.LpError) as e:
+        lp.lp_forward(net.ctx, 1, x, z, None, net.streams[0])
+    assert e.value.status == 8          # LP_ERR_HIP: the launcher refused the shape
+    with pytest.raises(lp.LpError):
+        lp.lp_grad_act(net.ctx, 1, z, x, 0, n, net.streams[0])
+    net.close()
