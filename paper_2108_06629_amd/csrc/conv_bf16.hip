@@ -744,19 +744,34 @@ __global__ void __launch_bounds__(NT) conv_dw_kernel(ConvKArgs p) {
   gemm_tile<BM, BN, BK, WM, WN>(sa, sb, kt0, kt1, smem, epi);
 }
 
+// Sums the split-K partials of dW in a fixed order.  A block handles 32 consecutive outputs; its eight
+// waves-halves each add up one eighth of the splits (a contiguous range, in order, eight loads in flight),
+// and the eight sub-sums are added in order through LDS: short dependent chains even for 128 splits.
 __global__ void __launch_bounds__(256) reduce_partials_kernel(const float* __restrict__ part, float* __restrict__ g, size_t n, int splits) {
-  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-  if (i >= n) return;
+  __shared__ float sub[8][32];
+  const int o = threadIdx.x & 31, grp = threadIdx.x >> 5;
+  const size_t i = (size_t)blockIdx.x * 32 + o;
+  const int per = (splits + 7) / 8;
+  const int s_begin = grp * per, s_end = s_begin + per < splits ? s_begin + per : splits;
   float acc = 0.f;
-  for (int s0 = 0; s0 < splits; s0 += 8) {   // eight loads in flight at a time; summed in split order
-    float v[8];
+  if (i < n) {
+    for (int s0 = s_begin; s0 < s_end; s0 += 8) {
+      float v[8];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) v[u] = s0 + u < splits ? part[(size_t)(s0 + u) * n + i] : 0.f;
+      for (int u = 0; u < 8; ++u) v[u] = s0 + u < s_end ? part[(size_t)(s0 + u) * n + i] : 0.f;
 #pragma unroll
-    for (int u = 0; u < 8; ++u)
-      if (s0 + u < splits) acc += v[u];
+      for (int u = 0; u < 8; ++u)
+        if (s0 + u < s_end) acc += v[u];
+    }
   }
-  g[i] = acc;
+  sub[grp][o] = acc;
+  __syncthreads();
+  if (grp == 0 && i < n) {
+    float t = sub[0][o];
+#pragma unroll
+    for (int k = 1; k < 8; ++k) t += sub[k][o];
+    g[i] = t;
+  }
 }
 
 constexpr size_t kLds = 2ull * (BM + BN) * BK * sizeof(unsigned short);
@@ -772,7 +787,7 @@ int dw_splits(const ConvDesc& c) {
   const long tiles = ((M + BM - 1) / BM) * ((N + BN - 1) / BN);
   long s = (768 + tiles - 1) / tiles;   // aim at about three workgroups per CU
   if (s > K / 512) s = K / 512;
-  if (s > 128) s = 128;
+  if (s > 256) s = 256;
   if (s < 1) s = 1;
   return (int)s;
 }
@@ -920,7 +935,7 @@ hipError_t launch_conv_grad_weight(const ConvDesc& c, bool bf16, const void* x, 
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || splits == 1) return e;
   const size_t n = (size_t)p.M * p.N;
-  hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, (const float*)partial, g, n, splits);
+  hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)((n + 31) / 32)), dim3(256), 0, s, (const float*)partial, g, n, splits);
   return hipGetLastError();
 }
 

@@ -129,13 +129,18 @@ __global__ void __launch_bounds__(256) splitk_reduce_kernel(const float* __restr
         }
     }
   } else {
+    for (int s0 = 0; s0 < splits; s0 += 8) {   // same order, scalar loads
+      float v[8][4];
 #pragma unroll
-    for (int t = 0; t < 4; ++t) {
-      if (col + t < p.N) {
-        float a = part[o + t];
-        for (int s = 1; s < splits; ++s) a += part[(size_t)s * mn + o + t];
-        acc[t] = a;
-      }
+      for (int u = 0; u < 8; ++u)
+#pragma unroll
+        for (int t = 0; t < 4; ++t) v[u][t] = (s0 + u < splits && col + t < p.N) ? part[(size_t)(s0 + u) * mn + o + t] : 0.f;
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+        if (s0 + u < splits) {
+#pragma unroll
+          for (int t = 0; t < 4; ++t) acc[t] += v[u][t];
+        }
     }
   }
   StoreEpilogue epi{p.out_z, p.out_a, p.out_f32, p.M, p.N, p.ldc, p.act, 0, 0, p.vec_out != 0};
