@@ -177,7 +177,9 @@ int lp_set_delta_split(lp_ctx* ctx, int l, int cols);
  * (LP_ERR_STATE afterwards).  lp_step then needs n_streams >= 4, all different (LP_ERR_STATE).
  * Results are those of the serial order, bit for bit.  X0 and target of a step must stay unchanged
  * until that step has finished, and the loss of step n+1 may be written before step n has finished: give
- * consecutive steps different loss_dev addresses (or read the loss before enqueueing the next step).  LP_BF16 contexts only (LP_ERR_DTYPE): F32 updates weights in place. */
+ * consecutive steps different loss_dev addresses (or read the loss before enqueueing the next step).  No stream
+ * is joined into another at the end of a step: call lp_sync before reading weights, tensors or the loss from
+ * another stream (lp_get_weights to host memory does so itself).  LP_BF16 contexts only (LP_ERR_DTYPE): F32 updates weights in place. */
 int lp_set_run_ahead(lp_ctx* ctx, int enable);
 
 /* Factor ring (for layers whose batch is small next to their width): the delay elements of layer l hold
