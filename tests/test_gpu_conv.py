@@ -25,7 +25,10 @@ def conv_net(B, H, W, cin, cout, pool=0, act="relu"):
 
 # (B, H, W, C_in, C_out): first-layer shape (3 channels: unaligned gather), aligned shapes spanning
 # several 128x64 tiles and K tiles, ragged pixel counts, the smallest image
-CONV_SHAPES = [(2, 8, 8, 3, 16), (3, 6, 10, 8, 24), (2, 16, 16, 64, 64), (5, 8, 8, 16, 136), (1, 2, 2, 8, 8), (4, 32, 32, 3, 64)]
+CONV_SHAPES = [(2, 8, 8, 3, 16), (3, 6, 10, 8, 24), (2, 16, 16, 64, 64), (5, 8, 8, 16, 136), (1, 2, 2, 8, 8), (4, 32, 32, 3, 64),
+               # the halo kernels (channels % 16 == 0, rows of at most 32 pixels): 128-pixel tiles with a ragged last tile and a
+               # ragged last column tile; enough tiles for the 256-pixel form; odd image sizes; a row too long for the halo
+               (3, 32, 32, 32, 48), (7, 5, 7, 16, 32), (20, 32, 32, 16, 208), (2, 4, 33, 16, 16)]
 
 
 @pytest.mark.parametrize("shape", CONV_SHAPES)
