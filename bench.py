@@ -252,28 +252,38 @@ def main():
     ms_per_step = dt / args.steps * 1e3
     value = wl.batch * args.steps / dt
 
-    tasks = {}
-    for name in ("F", "dX", "dW"):
-        ms, cnt = prof.get(name, (0.0, 0))
-        if name == "dW" and args.factor_ring:
-            # the G task only copies its factors; the product runs inside the update
-            ums, ucnt = prof.get("update", (0.0, 0))
-            if ucnt:
-                tf = work["dW"] * args.steps / (ums * 1e-3) / 1e12
-                tasks["update+dW"] = {"launches": ucnt, "avg_ms": ums / ucnt, "TFLOP/s": tf, "frac_of_bf16_peak": tf / PEAK_BF16_TFLOPS}
-            continue
-        if cnt:
-            tf = work[name] * args.steps / (ms * 1e-3) / 1e12
-            tasks[name] = {"launches": cnt, "avg_ms": ms / cnt, "TFLOP/s": tf, "frac_of_bf16_peak": tf / PEAK_BF16_TFLOPS}
-    for name in ("hadamard", "loss"):
-        ms, cnt = prof.get(name, (0.0, 0))
-        if cnt and ms > 0:
-            gbs = work[name] * args.steps / (ms * 1e-3) / 1e9
-            tasks[name] = {"launches": cnt, "avg_ms": ms / cnt, "GB/s": gbs, "frac_of_hbm_peak": gbs / PEAK_HBM_GBS}
-    ms, cnt = prof.get("update", (0.0, 0))
-    if cnt and ms > 0 and not args.factor_ring:
-        gbs = upd_params * work["update_per_param"] / (ms * 1e-3) / 1e9
-        tasks["update"] = {"launches": cnt, "avg_ms": ms / cnt, "GB/s": gbs, "frac_of_hbm_peak": gbs / PEAK_HBM_GBS}
+    def task_rates(prof, steps, upd_params, factor_ring):
+        out = {}
+        for name in ("F", "dX", "dW"):
+            ms, cnt = prof.get(name, (0.0, 0))
+            if name == "dW" and factor_ring:
+                # the G task only copies its factors; the product runs inside the update
+                ums, ucnt = prof.get("update", (0.0, 0))
+                if ucnt:
+                    tf = work["dW"] * steps / (ums * 1e-3) / 1e12
+                    out["update+dW"] = {"launches": ucnt, "avg_ms": ums / ucnt, "TFLOP/s": tf, "frac_of_bf16_peak": tf / PEAK_BF16_TFLOPS}
+                continue
+            if cnt:
+                tf = work[name] * steps / (ms * 1e-3) / 1e12
+                out[name] = {"launches": cnt, "avg_ms": ms / cnt, "TFLOP/s": tf, "frac_of_bf16_peak": tf / PEAK_BF16_TFLOPS}
+        for name in ("hadamard", "loss"):
+            ms, cnt = prof.get(name, (0.0, 0))
+            if cnt and ms > 0:
+                gbs = work[name] * steps / (ms * 1e-3) / 1e9
+                out[name] = {"launches": cnt, "avg_ms": ms / cnt, "GB/s": gbs, "frac_of_hbm_peak": gbs / PEAK_HBM_GBS}
+        ms, cnt = prof.get("update", (0.0, 0))
+        if cnt and ms > 0 and not factor_ring:
+            gbs = upd_params * work["update_per_param"] / (ms * 1e-3) / 1e9
+            out["update"] = {"launches": cnt, "avg_ms": ms / cnt, "GB/s": gbs, "frac_of_hbm_peak": gbs / PEAK_HBM_GBS}
+        return out
+
+    tasks = task_rates(prof, args.steps, upd_params, args.factor_ring)
+    # The same tasks with nothing running next to them (one stream, 4 steps): each kernel's own rate.  In the timed
+    # region above dX and dW share the GPU and the updates run next to F, so those durations include the sharing.
+    tasks_alone = None
+    if not args.no_others and not args.run_ahead and args.streams > 1:
+        _, _, prof1, upd1 = run_workload(wl, 4, args.warmup, 1, True, None, False, args.factor_ring)
+        tasks_alone = task_rates(prof1, 4, upd1, args.factor_ring)
 
     # dominant kernel: the bf16 MFMA GEMM of the forward products (same instantiation for all layers
     # of the default workload)
@@ -332,7 +342,8 @@ def main():
                 ", forward run-ahead" if args.run_ahead else "") + (", factor ring" if args.factor_ring else ""),
             "params": wl.n_params, "flops_per_step": sum(wl.flops_per_step()),
             "updated_params_per_step": upd_params / args.steps},
-        "roofline": roofline, "cpu_baseline": cpu, "tasks": tasks, "other_workloads": others, "final_loss": loss,
+        "roofline": roofline, "cpu_baseline": cpu, "tasks": tasks, "tasks_one_stream": tasks_alone, "other_workloads": others,
+        "final_loss": loss,
     }
     print(json.dumps(out))
 
