@@ -178,17 +178,21 @@ __device__ __forceinline__ void gemm_tile_dl(const OA& oa, const OB& ob, int k_b
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
   bf16x8 fa[2][TM], fb[2][TN];
+  // Fragments are read in the order the MFMAs consume them (b[0], a[0..TM-1], b[1], ...: the MFMAs walk
+  // down a column of the wave's tile before moving to the next), one read after each MFMA of the
+  // previous substep, so every fragment has the same head start of about NMFMA - 1 matrix instructions.
   auto read_frags = [&](const unsigned short* st, int kk, bf16x8 (&a)[TM], bf16x8 (&b)[TN]) {
+    b[0] = ob.frag(st + A_ELEMS, wn * (TN * 32), kk);
 #pragma unroll
     for (int i = 0; i < TM; ++i) a[i] = oa.frag(st, wm * (TM * 32) + i * 32, kk);
 #pragma unroll
-    for (int j = 0; j < TN; ++j) b[j] = ob.frag(st + A_ELEMS, wn * (TN * 32) + j * 32, kk);
+    for (int j = 1; j < TN; ++j) b[j] = ob.frag(st + A_ELEMS, wn * (TN * 32) + j * 32, kk);
   };
   auto mfmas = [&](bf16x8 (&a)[TM], bf16x8 (&b)[TN]) {
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+    for (int j = 0; j < TN; ++j)
 #pragma unroll
-      for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+      for (int i = 0; i < TM; ++i) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
   };
   // tiles past the end are "loaded" too (every chunk out of range, so zeros and no memory traffic):
   // the number of loads in flight stays the same in every iteration, which keeps the vmcnt waits exact
