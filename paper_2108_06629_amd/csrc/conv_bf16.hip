@@ -254,6 +254,7 @@ constexpr int DBM = 128, DBN = 64, DBK = 32, DSTAGES = 4, DWM = 2, DWN = 2, DNW 
 // A operand of F and dX: rows are pixels, k = (tap, c), c contiguous in memory.  LDS layout and fragment
 // reads are those of dl::OperandKC.
 struct PixelsKC : dl::OperandKC<DBM, DBK, DNW> {
+  static constexpr bool SPLIT_ISSUE = false;   // gathers: addresses are not affine in the tile index
   using Base = dl::OperandKC<DBM, DBK, DNW>;
   int C, H, W;
   bool flip;
@@ -315,6 +316,7 @@ struct PixelsKC : dl::OperandKC<DBM, DBK, DNW> {
 // B operand of dX: rows are input channels n (of the range that starts at c0), k = (tap, o), o contiguous:
 // w[(tap * Cin + c0 + n) * Cout + o]
 struct WeightsDX : dl::OperandKC<DBN, DBK, DNW> {
+  static constexpr bool SPLIT_ISSUE = false;   // gathers: addresses are not affine in the tile index
   using Base = dl::OperandKC<DBN, DBK, DNW>;
   int Cin, Cout, c0;
   FastDiv divC;   // by Cout
@@ -341,6 +343,7 @@ struct WeightsDX : dl::OperandKC<DBN, DBK, DNW> {
 // A operand of dW: rows are (tap, c), k runs over pixels; memory order [pixel][c] is kept in LDS and
 // transposed by the LDS read, as in dl::OperandKS.
 struct PixelsKS : dl::OperandKS<DBM, DBK, DNW> {
+  static constexpr bool SPLIT_ISSUE = false;   // gathers: addresses are not affine in the tile index
   using Base = dl::OperandKS<DBM, DBK, DNW>;
   int C, H, W;
   FastDiv divW, divH;

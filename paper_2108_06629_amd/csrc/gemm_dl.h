@@ -71,17 +71,36 @@ struct OperandKC {
     lrow = lane / CPR;
     lpos = lane % CPR;
   }
+  // load i of this wave (of PER_WAVE) for the tile that starts at reduction index k0
+  __device__ __forceinline__ void issue_one(int i, int k0, unsigned short* stage, int wave_u) const {
+    const int g = wave_u * PER_WAVE + i;                    // group of ROWS_PER_LOAD rows
+    const int trow = g * ROWS_PER_LOAD + lrow;             // row inside the tile
+    const int chunk = lpos ^ ((trow / RP) % CPR);           // the swizzle of core::lds_off, applied on the global side
+    const int row = r0 + trow, k = k0 + chunk * 8;
+    const unsigned off = (row < Rtot && k < Ktot) ? ((unsigned)row * (unsigned)ld + (unsigned)k) * 2u : kOOB;
+    load_to_lds_16(rs, off, stage + g * 512);
+  }
   // all waves together fill one stage with the tile that starts at reduction index k0
   __device__ __forceinline__ void issue(int k0, unsigned short* stage, int wave_u) const {
 #pragma unroll
+    for (int i = 0; i < PER_WAVE; ++i) issue_one(i, k0, stage, wave_u);
+  }
+  // The same loads for a tile whose BK reduction indices all exist: the byte offset is a per-lane
+  // constant (row part, kOOB for a row past the end: adding koff keeps it out of range) plus koff(k0).
+  static constexpr bool SPLIT_ISSUE = true;
+  unsigned base[PER_WAVE];
+  __device__ __forceinline__ void prepare(int wave_u) {
+#pragma unroll
     for (int i = 0; i < PER_WAVE; ++i) {
-      const int g = wave_u * PER_WAVE + i;                  // group of ROWS_PER_LOAD rows
-      const int trow = g * ROWS_PER_LOAD + lrow;           // row inside the tile
-      const int chunk = lpos ^ ((trow / RP) % CPR);         // the swizzle of core::lds_off, applied on the global side
-      const int row = r0 + trow, k = k0 + chunk * 8;
-      const unsigned off = (row < Rtot && k < Ktot) ? ((unsigned)row * (unsigned)ld + (unsigned)k) * 2u : kOOB;
-      load_to_lds_16(rs, off, stage + g * 512);
+      const int trow = (wave_u * PER_WAVE + i) * ROWS_PER_LOAD + lrow;
+      const int chunk = lpos ^ ((trow / RP) % CPR);
+      const int row = r0 + trow;
+      base[i] = row < Rtot ? ((unsigned)row * (unsigned)ld + (unsigned)(chunk * 8)) * 2u : kOOB;
     }
+  }
+  __device__ __forceinline__ unsigned koff(int k0) const { return (unsigned)k0 * 2u; }
+  __device__ __forceinline__ void issue_one_full(int i, unsigned koff_, unsigned short* stage, int wave_u) const {
+    load_to_lds_16(rs, base[i] + koff_, stage + (wave_u * PER_WAVE + i) * 512);
   }
   // fragment of MFMA tile rows [row0, row0+32), k substep kk: lane (r = lane&31, g = lane>>5) gets k = 16kk + 8g + 0..7
   __device__ __forceinline__ bf16x8 frag(const unsigned short* stage, int row0, int kk) const {
@@ -117,16 +136,33 @@ struct OperandKS {
     lk = lane / CPR;
     lpos = lane % CPR;
   }
+  __device__ __forceinline__ void issue_one(int i, int k0, unsigned short* stage, int wave_u) const {
+    const int g = wave_u * PER_WAVE + i;
+    const int kr = g * ROWS_PER_LOAD + lk;                   // k-row inside the tile
+    const int chunk = lpos ^ swz(kr);
+    const int k = k0 + kr, r = r0 + chunk * 8;
+    const unsigned off = (k < Ktot && r < Rtot) ? ((unsigned)k * (unsigned)ld + (unsigned)r) * 2u : kOOB;
+    load_to_lds_16(rs, off, stage + g * 512);
+  }
   __device__ __forceinline__ void issue(int k0, unsigned short* stage, int wave_u) const {
 #pragma unroll
+    for (int i = 0; i < PER_WAVE; ++i) issue_one(i, k0, stage, wave_u);
+  }
+  // full tiles: per-lane constant (k-row inside the tile and column part) plus koff(k0), as in OperandKC
+  static constexpr bool SPLIT_ISSUE = true;
+  unsigned base[PER_WAVE];
+  __device__ __forceinline__ void prepare(int wave_u) {
+#pragma unroll
     for (int i = 0; i < PER_WAVE; ++i) {
-      const int g = wave_u * PER_WAVE + i;
-      const int kr = g * ROWS_PER_LOAD + lk;                 // k-row inside the tile
+      const int kr = (wave_u * PER_WAVE + i) * ROWS_PER_LOAD + lk;
       const int chunk = lpos ^ swz(kr);
-      const int k = k0 + kr, r = r0 + chunk * 8;
-      const unsigned off = (k < Ktot && r < Rtot) ? ((unsigned)k * (unsigned)ld + (unsigned)r) * 2u : kOOB;
-      load_to_lds_16(rs, off, stage + g * 512);
+      const int r = r0 + chunk * 8;
+      base[i] = r < Rtot ? ((unsigned)kr * (unsigned)ld + (unsigned)r) * 2u : kOOB;
     }
+  }
+  __device__ __forceinline__ unsigned koff(int k0) const { return (unsigned)k0 * (unsigned)ld * 2u; }
+  __device__ __forceinline__ void issue_one_full(int i, unsigned koff_, unsigned short* stage, int wave_u) const {
+    load_to_lds_16(rs, base[i] + koff_, stage + (wave_u * PER_WAVE + i) * 512);
   }
   __device__ __forceinline__ bf16x8 frag(const unsigned short* stage, int row0, int kk) const {
     const int lane = threadIdx.x & 63;
@@ -161,7 +197,9 @@ __device__ __forceinline__ void wait_vmcnt() {
 // smem: NSTAGE * (BM + BN) * BK halves.  Multiplies the KT K-tiles that start at reduction index k_base
 // (split-K: a workgroup takes a K range and the operands' Ktot is the end of that range).
 template <int BM, int BN, int BK, int NSTAGE, int WM, int WN, class OA, class OB, class Epi>
-__device__ __forceinline__ void gemm_tile_dl(const OA& oa, const OB& ob, int k_base, int KT, unsigned short* smem, Epi epi) {
+__device__ __forceinline__ void gemm_tile_dl(const OA& oa_in, const OB& ob_in, int k_base, int KT, unsigned short* smem, Epi epi) {
+  OA oa = oa_in;
+  OB ob = ob_in;
   constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
   constexpr int A_ELEMS = BM * BK, B_ELEMS = BN * BK, STAGE = A_ELEMS + B_ELEMS;
   constexpr int LOADS = OA::PER_WAVE + OB::PER_WAVE;        // buffer loads per lane per tile
@@ -216,9 +254,8 @@ __device__ __forceinline__ void gemm_tile_dl(const OA& oa, const OB& ob, int k_b
   read_frags(smem, 0, fa[0], fb[0]);
 
   constexpr int KS = BK / 16;   // MFMA substeps per K step
-  for (int t = 0; t < KT; ++t) {
+  auto substeps = [&](int t) {  // all but the last substep of tile t
     const unsigned short* cur = smem + (t % NSTAGE) * STAGE;
-    const unsigned short* nxt = smem + ((t + 1) % NSTAGE) * STAGE;
 #pragma unroll
     for (int kk = 0; kk + 1 < KS; ++kk) {
       read_frags(cur, kk + 1, fa[(kk + 1) & 1], fb[(kk + 1) & 1]);
@@ -226,13 +263,76 @@ __device__ __forceinline__ void gemm_tile_dl(const OA& oa, const OB& ob, int k_b
       interleave_reads();
       __builtin_amdgcn_sched_barrier(0);
     }
-    wait_vmcnt<(NSTAGE - 2) * LOADS>();   // this wave's part of tile t+1 has landed
-    __syncthreads();                      // ... and everyone's; nobody reads tile t's stage any more
-    issue(t + NSTAGE);
-    read_frags(nxt, 0, fa[KS & 1], fb[KS & 1]);
-    mfmas(fa[(KS - 1) & 1], fb[(KS - 1) & 1]);
-    interleave_reads();
-    __builtin_amdgcn_sched_barrier(0);
+  };
+  if constexpr (OA::SPLIT_ISSUE && OB::SPLIT_ISSUE) {
+    // The refill of the freed stage and the first fragment reads of tile t+1 are dealt out over the
+    // MFMAs of the last substep, one slot per MFMA with the MFMA first, so that the matrix pipe has
+    // work from the first cycle after the barrier while the addresses of the loads are formed.
+    constexpr int NFRAG = TM + TN;
+    oa.prepare(wave);
+    ob.prepare(wave);
+    auto last_substep = [&](int t, auto full) {
+      unsigned short* st = smem + (t % NSTAGE) * STAGE;
+      const unsigned short* nxt = smem + ((t + 1) % NSTAGE) * STAGE;
+      const int k0 = k_base + (t + NSTAGE) * BK;
+      const unsigned koa = oa.koff(k0), kob = ob.koff(k0);
+      bf16x8(&ca)[TM] = fa[(KS - 1) & 1];
+      bf16x8(&cb)[TN] = fb[(KS - 1) & 1];
+      bf16x8(&na)[TM] = fa[KS & 1];
+      bf16x8(&nb)[TN] = fb[KS & 1];
+#pragma unroll
+      for (int q = 0; q < NMFMA; ++q) {
+        const int i = q % TM, j = q / TM;
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ca[i], cb[j], acc[i][j], 0, 0, 0);
+#pragma unroll
+        for (int f = 0; f < NFRAG; ++f) {   // consumption order: b[0], a[0..TM-1], b[1..]
+          if ((NFRAG <= NMFMA ? f : f * NMFMA / NFRAG) != q) continue;
+          if (f == 0) nb[0] = ob.frag(nxt + A_ELEMS, wn * (TN * 32), 0);
+          else if (f <= TM) na[f - 1] = oa.frag(nxt, wm * (TM * 32) + (f - 1) * 32, 0);
+          else nb[f - TM] = ob.frag(nxt + A_ELEMS, wn * (TN * 32) + (f - TM) * 32, 0);
+        }
+#pragma unroll
+        for (int l = 0; l < LOADS; ++l) {
+          if ((LOADS <= NMFMA ? l : l * NMFMA / LOADS) != q) continue;
+          if (l < OA::PER_WAVE) {
+            if constexpr (decltype(full)::value) oa.issue_one_full(l, koa, st, wave);
+            else oa.issue_one(l, k0, st, wave);
+          } else {
+            if constexpr (decltype(full)::value) ob.issue_one_full(l - OA::PER_WAVE, kob, st + A_ELEMS, wave);
+            else ob.issue_one(l - OA::PER_WAVE, k0, st + A_ELEMS, wave);
+          }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    };
+    // tiles [0, full_tiles) have all BK reduction indices; iteration t refills with tile t + NSTAGE
+    const int full_tiles = (oa.Ktot - k_base) / BK;
+    const int t_full = full_tiles - NSTAGE < KT ? full_tiles - NSTAGE : KT;
+    int t = 0;
+    for (; t < t_full; ++t) {
+      substeps(t);
+      wait_vmcnt<(NSTAGE - 2) * LOADS>();   // this wave's part of tile t+1 has landed
+      __syncthreads();                      // ... and everyone's; nobody reads tile t's stage any more
+      last_substep(t, std::true_type{});
+    }
+    for (; t < KT; ++t) {
+      substeps(t);
+      wait_vmcnt<(NSTAGE - 2) * LOADS>();
+      __syncthreads();
+      last_substep(t, std::false_type{});
+    }
+  } else {
+    for (int t = 0; t < KT; ++t) {
+      const unsigned short* nxt = smem + ((t + 1) % NSTAGE) * STAGE;
+      substeps(t);
+      wait_vmcnt<(NSTAGE - 2) * LOADS>();   // this wave's part of tile t+1 has landed
+      __syncthreads();                      // ... and everyone's; nobody reads tile t's stage any more
+      issue(t + NSTAGE);
+      read_frags(nxt, 0, fa[KS & 1], fb[KS & 1]);
+      mfmas(fa[(KS - 1) & 1], fb[(KS - 1) & 1]);
+      interleave_reads();
+      __builtin_amdgcn_sched_barrier(0);
+    }
   }
   wait_vmcnt<0>();   // the trailing (empty) tiles still write LDS
   __syncthreads();
