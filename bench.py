@@ -27,7 +27,7 @@ PEAK_HBM_GBS = 8000.0
 # bytes the L2s request from the fabric (Infinity Cache + HBM) plus bytes written, per launch of the F
 # kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script, scaled by a 1 GiB copy
 # (profiles/hbm_traffic_ffn_stack.md)
-MEASURED_TRAFFIC_BYTES = {"ffn_stack_bf16": 1.6115e9 + 3.020e8}
+MEASURED_TRAFFIC_BYTES = {"ffn_stack_bf16": 1.6323e9 + 3.020e8}
 
 
 def task_work(wl):
