@@ -209,6 +209,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=32)
     ap.add_argument("--workload", default="ffn_stack_bf16")
     ap.add_argument("--streams", type=int, default=3)
+    ap.add_argument("--no-task-timing", action="store_true", help="no per-task events in the timed steps (they cost host time; roofline and tasks are then empty)")
+    ap.add_argument("--ra-streams", type=int, default=4, help="distinct streams of the run-ahead schedule (2, 3 or 4)")
     ap.add_argument("--run-ahead", action="store_true",
                     help="forward run-ahead across steps (lp_set_run_ahead): F(n+1) on a fourth stream next to the backward pass of step n")
     ap.add_argument("--factor-ring", action="store_true",
@@ -247,7 +249,7 @@ def main():
         return
     work = task_work(wl)
     weights = WL.init_weights(wl)
-    dt, loss, prof, upd_params = run_workload(wl, args.steps, args.warmup, args.streams, True, weights, args.run_ahead, args.factor_ring)
+    dt, loss, prof, upd_params = run_workload(wl, args.steps, args.warmup, args.ra_streams if args.run_ahead else args.streams, not args.no_task_timing, weights, args.run_ahead, args.factor_ring)
     del weights
     ms_per_step = dt / args.steps * 1e3
     value = wl.batch * args.steps / dt
@@ -321,8 +323,10 @@ def main():
                                                   "final_loss": sloss}
                 if o.dtype == "bf16" and o.n_params < 5e8:
                     for label, kw in (("run_ahead", dict(run_ahead=True)), ("factor_ring", dict(factor_ring=True)),
-                                      ("factor_ring+run_ahead", dict(run_ahead=True, factor_ring=True))):
-                        rdt, rloss, _, _ = run_workload(o, o.steps, 3, 4 if "run_ahead" in kw else args.streams, False, **kw)
+                                      ("factor_ring+run_ahead", dict(run_ahead=True, factor_ring=True)),
+                                      ("factor_ring+run_ahead_3_streams", dict(run_ahead=True, factor_ring=True, ns=3))):
+                        ns = kw.pop("ns", args.ra_streams if "run_ahead" in kw else args.streams)
+                        rdt, rloss, _, _ = run_workload(o, o.steps, 3, ns, False, **kw)
                         others[name][label] = {"samples_per_s": o.batch * o.steps / rdt, "ms_per_step": rdt / o.steps * 1e3,
                                                "final_loss": rloss}
             except Exception as e:  # a workload this build cannot run yet is reported, not hidden
@@ -338,7 +342,7 @@ def main():
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": "%s: %d layers, batch %d, delays %s, %s loss, lr %g, %d streams" % (
-            wl.name, wl.L, wl.batch, list(wl.delays), wl.loss, wl.lr, 4 if args.run_ahead else args.streams) + (
+            wl.name, wl.L, wl.batch, list(wl.delays), wl.loss, wl.lr, args.ra_streams if args.run_ahead else args.streams) + (
                 ", forward run-ahead" if args.run_ahead else "") + (", factor ring" if args.factor_ring else ""),
             "params": wl.n_params, "flops_per_step": sum(wl.flops_per_step()),
             "updated_params_per_step": upd_params / args.steps},

@@ -174,7 +174,10 @@ int lp_set_delta_split(lp_ctx* ctx, int l, int cols);
  * steps, so F_l(n+1) starts as soon as W_l(n) exists (which needs only G_l(n - d_l)) and overlaps the
  * backward pass of step n.  Each layer then keeps two stashes (A_l, Z_l of steps n and n+1), so the
  * workspace grows: call this after lp_create and before lp_workspace_bytes / lp_bind_workspace
- * (LP_ERR_STATE afterwards).  lp_step then needs n_streams >= 4, all different (LP_ERR_STATE).
+ * (LP_ERR_STATE afterwards).  lp_step then needs n_streams >= 4 handles (LP_ERR_STATE): streams[0] critical
+ * backward chain, [1] G tasks, [2] updates, [3] forward chain and loss.  streams[3] must differ from streams[0];
+ * [1] and [2] may repeat another handle (tasks that share a stream run in the order they are enqueued: fewer
+ * cross-stream waits for the host to enqueue, less overlap on the device).
  * Results are those of the serial order, bit for bit.  X0 and target of a step must stay unchanged
  * until that step has finished, and the loss of step n+1 may be written before step n has finished: give
  * consecutive steps different loss_dev addresses (or read the loss before enqueueing the next step).  No stream

@@ -268,10 +268,12 @@ class Network:
     """A context bound to a torch workspace tensor on one GPU.  `layers` are lp_workloads.Layer-like
     objects (kind, d_in, d_out, act, H, W, pool)."""
 
-    def __init__(self, layers, batch: int, dtype: str, loss: str, lr: float, delays, device: str = "cuda:0", n_streams: int = 3,
+    def __init__(self, layers, batch: int, dtype: str, loss: str, lr: float, delays, device: str = "cuda:0", n_streams: int = None,
                  run_ahead: bool = False, graphs: bool = False, factor_ring=None):
         import torch
         self.torch = torch
+        if n_streams is None:
+            n_streams = 4 if run_ahead else 3
         self.layers, self.batch, self.dtype, self.loss = list(layers), batch, dtype, loss
         self.device = torch.device(device)
         self.ctx = lp_create(make_descs(layers, delays), len(layers), batch, _DTYPE[dtype], _LOSS[loss], float(lr))
@@ -282,13 +284,18 @@ class Network:
             lp_set_graphs(self.ctx, True)
         if run_ahead:
             lp_set_run_ahead(self.ctx, True)
-            n_streams = max(4, n_streams)
+            n_streams = max(2, n_streams)
         nbytes = lp_workspace_bytes(self.ctx)
         self.ws = torch.empty(nbytes + 256, dtype=torch.uint8, device=self.device)
         self._ws_off = (-self.ws.data_ptr()) % 256
         lp_bind_workspace(self.ctx, self.ws.data_ptr() + self._ws_off, nbytes)
         with torch.cuda.device(self.device):
             self.streams = [torch.cuda.Stream(device=self.device) for _ in range(max(1, n_streams))]
+        if run_ahead and n_streams < 4:
+            # roles [critical chain, G tasks, updates, forward]: with 3 streams the updates share the G tasks'
+            # stream, with 2 the whole backward pass runs on one stream and the forward chain on the other
+            s = self.streams
+            self.streams = [s[0], s[1], s[1], s[2]] if n_streams == 3 else [s[0], s[0], s[0], s[1]]
         self.loss_dev = torch.zeros(1, dtype=torch.float32, device=self.device)
 
     def close(self):

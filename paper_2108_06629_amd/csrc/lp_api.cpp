@@ -946,10 +946,8 @@ int lp_step(lp_ctx* c, const void* X0, const void* target, const int* delay, flo
     for (int l = 0; l < c->L; ++l) c->layers[l].delay = delay[l];
   }
   if (c->run_ahead) {
-    if (n_streams < 4) return fail(c, LP_ERR_STATE, "lp_step: forward run-ahead needs 4 streams, %d given", n_streams);
-    for (int a = 0; a < 4; ++a)
-      for (int b = a + 1; b < 4; ++b)
-        if (streams[a] == streams[b]) return fail(c, LP_ERR_STATE, "lp_step: forward run-ahead needs 4 different streams");
+    if (n_streams < 4) return fail(c, LP_ERR_STATE, "lp_step: forward run-ahead needs 4 stream handles, %d given", n_streams);
+    if (streams[3] == streams[0]) return fail(c, LP_ERR_STATE, "lp_step: forward run-ahead needs a forward stream (streams[3]) other than streams[0]");
     return step_run_ahead(c, X0, target, loss_dev, streams);
   }
   const bool multi = n_streams > 1;

@@ -149,7 +149,8 @@ def test_full_size_schedules_and_ring_kinds_agree_bit_for_bit(name):
     steps = max(wl.delays) + 22
     ref, _ = _run_schedule(wl, W0, steps)
     assert np.all(np.isfinite(ref[0]))
-    for kw in (dict(run_ahead=True), dict(graphs=True), dict(factor_ring=True), dict(factor_ring=True, run_ahead=True)):
+    for kw in (dict(run_ahead=True), dict(graphs=True), dict(factor_ring=True), dict(factor_ring=True, run_ahead=True),
+               dict(factor_ring=True, run_ahead=True, n_streams=3)):
         got, stats = _run_schedule(wl, W0, steps, **kw)
         assert np.array_equal(got[0].view(np.uint32), ref[0].view(np.uint32)), (kw, got[0][-4:], ref[0][-4:])
         for l, (a, b) in enumerate(zip(got[1], ref[1]), start=1):

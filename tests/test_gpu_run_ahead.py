@@ -14,9 +14,10 @@ from test_gpu_parity import DEV, run_trajectory
 pytestmark = pytest.mark.gpu
 
 
-def enqueue_steps(wl, W0, steps, run_ahead, split=None, delays_now=None):
+def enqueue_steps(wl, W0, steps, run_ahead, split=None, delays_now=None, n_streams=None):
     """All `steps` training steps enqueued without waiting; returns (losses, weights, last gradients)."""
-    net = lp.Network(wl.layers, wl.batch, wl.dtype, wl.loss, wl.lr, wl.delays, n_streams=3, run_ahead=run_ahead)
+    net = lp.Network(wl.layers, wl.batch, wl.dtype, wl.loss, wl.lr, wl.delays,
+                     n_streams=n_streams or (4 if run_ahead else 3), run_ahead=run_ahead)
     net.set_weights(W0)
     if split:
         for l, cols in split.items():
@@ -79,18 +80,28 @@ def test_run_ahead_against_oracle():
     run_trajectory(wl, 12, n_streams=4, run_ahead=True)
 
 
-def test_run_ahead_needs_four_distinct_streams():
+def test_run_ahead_stream_handles():
     wl = WL.mlp_4096().with_(layers=WL._mlp([64, 64, 16], WL.RELU), batch=16, delays=(2, 0))
-    net = lp.Network(wl.layers, wl.batch, wl.dtype, wl.loss, wl.lr, wl.delays, run_ahead=True)
+    net = lp.Network(wl.layers, wl.batch, wl.dtype, wl.loss, wl.lr, wl.delays, n_streams=4, run_ahead=True)
     net.set_weights(WL.init_weights(wl))
     x, t = net.to_device(WL.batch_input(wl, 1)), net.to_device(WL.batch_target(wl, 1), True)
     with pytest.raises(lp.LpError) as e:
         lp.lp_step(net.ctx, x, t, None, net.loss_dev, net.streams[:3])
-    assert e.value.status == 6     # LP_ERR_STATE
+    assert e.value.status == 6     # LP_ERR_STATE: four handles are needed
     with pytest.raises(lp.LpError) as e:
         lp.lp_step(net.ctx, x, t, None, net.loss_dev, [net.streams[0], net.streams[1], net.streams[2], net.streams[0]])
-    assert e.value.status == 6     # LP_ERR_STATE
+    assert e.value.status == 6     # LP_ERR_STATE: the forward chain needs a stream of its own
     lp.lp_step(net.ctx, x, t, None, net.loss_dev, net.streams)
     lp.lp_sync(net.ctx)
     assert np.isfinite(float(net.loss_dev.item()))
     net.close()
+
+
+@pytest.mark.parametrize("n_streams", [2, 3])
+def test_run_ahead_with_shared_streams_bits_equal_serial_schedule(n_streams):
+    # the G tasks and/or the updates share a stream with another role: stronger ordering, same arithmetic
+    wl = WL.mlp_4096().with_(layers=WL._mlp([256, 320, 192, 136, 40], WL.RELU), batch=96, delays=(3, 0, 1, 0))
+    W0 = WL.init_weights(wl)
+    serial = enqueue_steps(wl, W0, 9, False)
+    shared = enqueue_steps(wl, W0, 9, True, split={2: 64}, n_streams=n_streams)
+    assert_same_bits(serial, shared)
