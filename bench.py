@@ -317,6 +317,10 @@ def main():
                 others[name] = {"samples_per_s": o.batch * o.steps / odt, "ms_per_step": odt / o.steps * 1e3, "steps": o.steps,
                                 "final_loss": oloss}
                 if o.n_params < 5e8:
+                    # steady state: every layer's delayed update is active (n > max d_l) in all timed steps
+                    ydt, _, _, _ = run_workload(o, 100, max(o.delays) + 2, args.streams, False)
+                    others[name]["steady_state_ms_per_step"] = ydt / 100 * 1e3
+                if o.n_params < 5e8:
                     # one stream: a third of the host's enqueue time (no cross-stream waits), best for launch-bound networks
                     sdt, sloss, _, _ = run_workload(o, o.steps, 3, 1, False)
                     others[name]["one_stream"] = {"samples_per_s": o.batch * o.steps / sdt, "ms_per_step": sdt / o.steps * 1e3,
@@ -327,8 +331,9 @@ def main():
                                       ("factor_ring+run_ahead_3_streams", dict(run_ahead=True, factor_ring=True, ns=3))):
                         ns = kw.pop("ns", args.ra_streams if "run_ahead" in kw else args.streams)
                         rdt, rloss, _, _ = run_workload(o, o.steps, 3, ns, False, **kw)
+                        ydt, _, _, _ = run_workload(o, 100, max(o.delays) + 2, ns, False, **kw)
                         others[name][label] = {"samples_per_s": o.batch * o.steps / rdt, "ms_per_step": rdt / o.steps * 1e3,
-                                               "final_loss": rloss}
+                                               "steady_state_ms_per_step": ydt / 100 * 1e3, "final_loss": rloss}
             except Exception as e:  # a workload this build cannot run yet is reported, not hidden
                 others[name] = {"error": str(e)[:200]}
 
