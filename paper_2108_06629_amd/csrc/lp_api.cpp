@@ -496,6 +496,9 @@ int step_run_ahead(lp_ctx* c, const void* X0, const void* target, float* loss_de
 // join into sC at the end, so the whole step is a single-entry, single-exit piece of work on sC (which
 // is what lets it be captured into a graph).  Changes no host state; `updated` says which layers'
 // working weights were rewritten.
+constexpr long kChipTiles = 256;   // one 256 x 256 tile per CU
+inline long tiles_256(int m, int n) { return (long)((m + 255) / 256) * ((n + 255) / 256); }
+
 int enqueue_step(lp_ctx* c, const void* X0, const void* target, float* loss_dev, hipStream_t sC, hipStream_t sW, hipStream_t sU,
                  bool multi, std::vector<char>& updated) {
   const int L = c->L;
@@ -564,14 +567,20 @@ int enqueue_step(lp_ctx* c, const void* X0, const void* target, float* loss_dev,
       }
       if (multi) LP_HIP(c, record_on(c, c->ev_dy[i - 1], sC));
     }
-    if (multi && sW != sC) LP_HIP(c, wait_on(c, sW, c->ev_dy[i]));
-    LP_HIP(c, enqueue_G(c, ly, x_in, dY, n, sW));
-    if (multi && !updated[i]) LP_HIP(c, record_on(c, c->ev_dw[i], sW));   // only this step's own update waits for it
+    // A G product that fills every CU with 256 x 256 tiles, next to a delta product that does so too, gains
+    // nothing from a stream of its own: the two kernels only take turns on the CUs and break up each other's
+    // L2 tile blocks.  It then follows dX_l on the critical stream; smaller products overlap on sW.
+    const bool fills_chip = ly.d.kind == LP_LINEAR && !ly.factor_ring && tiles_256(ly.d.in, ly.d.out) >= kChipTiles &&
+                            (i == 0 || tiles_256(c->batch, ly.d.in) >= kChipTiles);
+    hipStream_t sG = fills_chip ? sC : sW;
+    if (multi && sG != sC) LP_HIP(c, wait_on(c, sG, c->ev_dy[i]));
+    LP_HIP(c, enqueue_G(c, ly, x_in, dY, n, sG));
+    if (multi && !updated[i]) LP_HIP(c, record_on(c, c->ev_dw[i], sG));   // only this step's own update waits for it
     if (!updated[i]) {
       // d_l = 0 needs this step's G; an F32 context updates in place, so it also has to wait for
       // the last reader of W_l(n-1), which is dX_l (layer 1: the forward pass, long finished)
       if (multi) {
-        if (ly.delay == 0 && sU != sW) LP_HIP(c, wait_on(c, sU, c->ev_dw[i]));
+        if (ly.delay == 0 && sU != sG) LP_HIP(c, wait_on(c, sU, c->ev_dw[i]));
         if (!bf && sU != sC) LP_HIP(c, wait_on(c, sU, i > 0 ? c->ev_dx[i] : c->ev_dy[L - 1]));
       }
       if (int r = issue_update(i)) return r;
