@@ -157,3 +157,18 @@ def test_full_size_schedules_and_ring_kinds_agree_bit_for_bit(name):
             assert np.array_equal(a.view(np.uint32), b.view(np.uint32)), (kw, "W_%d" % l)
         if kw.get("graphs"):
             assert stats[0] > 0
+
+
+def test_chip_filling_gradient_products_keep_the_serial_bits():
+    """A layer whose G product and delta product each fill every CU with 256 x 256 tiles runs its G task behind
+    dX on the critical stream instead of next to it (layers 1 and 2 here; layer 3 keeps its own stream).  The
+    placement changes no arithmetic: one stream, three streams and graph replay give the same bits."""
+    wl = WL.mlp_4096().with_(layers=WL._mlp([4096, 4096, 4096, 1000], WL.RELU), batch=4096, delays=(4, 2, 0))
+    W0 = WL.init_weights(wl)
+    ref, _ = _run_schedule(wl, W0, 9, n_streams=1)
+    assert np.all(np.isfinite(ref[0])) and ref[0][0] != ref[0][-1]
+    for kw in (dict(n_streams=3), dict(n_streams=3, graphs=True)):
+        got, _ = _run_schedule(wl, W0, 9, **kw)
+        assert np.array_equal(got[0].view(np.uint32), ref[0].view(np.uint32)), kw
+        for l, (a, b) in enumerate(zip(got[1], ref[1]), start=1):
+            assert np.array_equal(a.view(np.uint32), b.view(np.uint32)), (kw, "W_%d" % l)

@@ -128,6 +128,44 @@ def test_grad_weight_bf16(shape):
     net.close()
 
 
+# The direct-to-LDS loop refills its ring with per-lane affine offsets while whole K tiles remain and
+# with bounds-checked offsets for the last (partial or empty) ones: reduction lengths around one, two,
+# three and four K steps of 64, with and without a partial last step, on the 128 x 128 tiles
+# (264 x 136 outputs) and on the 256 x 256 tiles (4096 x 4096 outputs).
+@pytest.mark.parametrize("red", [8, 64, 72, 128, 136, 192, 200, 264])
+@pytest.mark.parametrize("big", [False, True])
+def test_reduction_lengths_around_the_k_step(red, big):
+    if big and red not in (64, 136, 192, 264):
+        pytest.skip("the large outputs take four of the lengths")
+    m, n = (4096, 4096) if big else (264, 136)
+    rng = np.random.default_rng(red + 1000 * big)
+    # F: reduction over the layer's inputs
+    net, W, _ = one_layer_net(red, n, m)
+    x = rng.standard_normal((m, red)).astype(np.float32)
+    Z = torch.empty(m, n, dtype=torch.bfloat16, device=DEV)
+    lp.lp_forward(net.ctx, 1, dev(x, torch.bfloat16), Z, None, net.streams[0])
+    lp.lp_sync(net.ctx)
+    assert relerr(host(Z), O.store(O.forward_product(O.round_bf16(x), O.round_bf16(W[0])), "bf16")) <= 2e-2
+    net.close()
+    # dX: reduction over the layer's outputs
+    net, W, _ = one_layer_net(n, red, m)
+    dy = (rng.standard_normal((m, red)) / np.sqrt(red)).astype(np.float32)
+    dX = torch.full((m, n), float("nan"), dtype=torch.bfloat16, device=DEV)
+    lp.lp_grad_act(net.ctx, 1, dev(dy, torch.bfloat16), dX, 0, n, net.streams[0])
+    lp.lp_sync(net.ctx)
+    assert relerr(host(dX), O.store(O.grad_act(O.round_bf16(dy), O.round_bf16(W[0])), "bf16")) <= 2e-2
+    net.close()
+    # dW: reduction over the batch
+    net, W, _ = one_layer_net(m, n, red)
+    x = rng.standard_normal((red, m)).astype(np.float32)
+    dy = (rng.standard_normal((red, n)) / red).astype(np.float32)
+    G = torch.full((m, n), float("nan"), dtype=torch.float32, device=DEV)
+    lp.lp_grad_weight(net.ctx, 1, dev(x, torch.bfloat16), dev(dy, torch.bfloat16), G, net.streams[0])
+    lp.lp_sync(net.ctx)
+    assert relerr(host(G), O.grad_weight(O.round_bf16(x), O.round_bf16(dy))) <= 2e-4
+    net.close()
+
+
 @pytest.mark.parametrize("n_feat", [8, 1000, 4099])
 @pytest.mark.parametrize("act,dtype", [("relu", "bf16"), ("gelu", "bf16"), ("relu", "f32"), ("gelu", "f32"),
                                        ("tanh", "bf16"), ("sigmoid", "bf16"), ("tanh", "f32"), ("sigmoid", "f32")])
