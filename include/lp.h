@@ -97,6 +97,8 @@ typedef enum {
  * l's output size equals layer l+1's input size (a conv output feeding a linear layer is flattened
  * in NHWC order).  lr is eta of Eq. 6.  *out is set only on LP_OK. */
 int lp_create(const lp_layer_desc* layers, int L, int batch, int dtype, int loss, float lr, lp_ctx** out);
+/* Frees the context, its events and its captured graphs.  Work that earlier calls enqueued must have
+ * finished (lp_sync, or the caller's own stream synchronisation): the library does not wait here. */
 int lp_destroy(lp_ctx* ctx);
 /* Message of the last failing call on ctx (owned by ctx; valid until the next call).  ctx == NULL
  * returns the message of the last failing lp_create. */
