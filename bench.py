@@ -56,12 +56,13 @@ def task_work(wl):
 
 def cpu_baseline(wl, threads):
     """The oracle as it stands, timed on a bounded sample: one training step on at most 256 samples;
-    for networks above 5e8 parameters only the first two layers (one up/down block) on 512 samples,
+    for networks above 5e8 parameters only the first two layers (one up/down block) on up to 8192 samples
+    (about ten seconds of work),
     scaled to the whole network by the ratio of per-sample flops."""
     import lp_workloads as WL
     from oracle import layerpipe_oracle as O
     if wl.n_params > 5e8:
-        sub = wl.with_(layers=wl.layers[:2], batch=512, delays=wl.delays[-2:])
+        sub = wl.with_(layers=wl.layers[:2], batch=min(wl.batch, 8192), delays=wl.delays[-2:])
         what = "the first 2 of %d layers" % wl.L
     else:
         sub = wl.with_(batch=min(wl.batch, 256))
