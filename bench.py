@@ -223,6 +223,9 @@ def main():
                          "print the balanced stage times next to the best whole-layer (PipeDream-style) assignment")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run five 1 GiB device-to-device copy kernels (reference for the FETCH_SIZE / WRITE_SIZE counters)")
+    ap.add_argument("--calibrate-mfma", action="store_true",
+                    help="only run the matrix-instruction-only kernel (lp_probe_mfma) with one and with two workgroups per CU and "
+                         "print what it sustains: the practical ceiling of the bf16 MFMA roofline on this machine")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (one MI355X per box, no collectives); --gpus %d is not supported" % args.gpus,
@@ -242,6 +245,28 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         print(json.dumps({"calibrate_copy": {"bytes_read": src.numel() * 2, "bytes_written": src.numel() * 2, "copies": 5}}))
+        return
+
+    if args.calibrate_mfma:
+        cus = torch.cuda.get_device_properties(0).multi_processor_count
+        rows = []
+        for per_cu, uniform in ((1, False), (2, False), (1, True)):     # 1: two waves per SIMD, as in the 256 x 256 GEMM; 2: four
+            wgs, iters, reps = cus * per_cu, 20000 // per_cu, 8
+            out = torch.empty(wgs * 512, dtype=torch.float32, device="cuda:0")
+            s = torch.cuda.Stream()
+            lp.lp_probe_mfma(out, wgs, 200, uniform, s)
+            s.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(s)
+            for _ in range(reps):
+                lp.lp_probe_mfma(out, wgs, iters, uniform, s)
+            e1.record(s)
+            s.synchronize()
+            ms = e0.elapsed_time(e1) / reps
+            flops = wgs * 8 * iters * 8 * 32768.0
+            rows.append({"workgroups": wgs, "iters": iters, "operands": "uniform small values" if uniform else "pseudo-random in [-1, 1)", "ms_per_launch": ms, "TFLOP/s": flops / (ms * 1e-3) / 1e12,
+                         "frac_of_bf16_peak": flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, "checksum": float(out[0].item())})
+        print(json.dumps({"calibrate_mfma": rows}))
         return
 
     wl = WL.CONFIGS[args.workload]()

@@ -275,6 +275,15 @@ int lp_profile_read(lp_ctx* ctx, int task, double* total_ms, long* launches, int
 /* The same for one layer l = 1..L (the loss task belongs to no layer and is only in the totals). */
 int lp_profile_read_layer(lp_ctx* ctx, int task, int l, double* total_ms, long* launches, int reset);
 
+/* Calibration of the matrix-core roofline (no context needed): launches `workgroups` workgroups of eight
+ * waves that each issue iters * 8 v_mfma_f32_32x32x16_bf16 on operands held in registers, nothing else --
+ * 2 * 32 * 32 * 16 flop per instruction, so workgroups * 8 * iters * 8 * 32768 flop per launch.  out_dev
+ * (device, out_elems >= workgroups * 512 floats, LP_ERR_SHAPE otherwise) receives one checksum per lane.
+ * uniform_values = 0: pseudo-random operands in [-1, 1), as a real product has; != 0: the same few small
+ * values in every lane (few bits toggle, so the chip's power limit allows a higher clock: the two differ).
+ * Asynchronous on `stream`; returns LP_ERR_NULL / LP_ERR_SHAPE / LP_ERR_HIP without a message. */
+int lp_probe_mfma(float* out_dev, size_t out_elems, int workgroups, int iters, int uniform_values, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -34,7 +34,7 @@ STATUS_NAMES = ["LP_OK", "LP_ERR_NULL", "LP_ERR_SHAPE", "LP_ERR_DTYPE", "LP_ERR_
 
 EXPORTS = ["lp_create", "lp_destroy", "lp_last_error", "lp_workspace_bytes", "lp_bind_workspace", "lp_set_weights",
            "lp_get_weights", "lp_forward", "lp_loss_grad", "lp_act_grad", "lp_grad_act", "lp_grad_weight", "lp_update",
-           "lp_advance", "lp_step", "lp_step_index", "lp_sync", "lp_tensor", "lp_profile", "lp_profile_read", "lp_profile_read_layer", "lp_partition", "lp_set_delta_split", "lp_set_run_ahead", "lp_set_graphs", "lp_graph_stats", "lp_set_factor_ring"]
+           "lp_advance", "lp_step", "lp_step_index", "lp_sync", "lp_tensor", "lp_profile", "lp_profile_read", "lp_profile_read_layer", "lp_partition", "lp_set_delta_split", "lp_set_run_ahead", "lp_set_graphs", "lp_graph_stats", "lp_set_factor_ring", "lp_probe_mfma"]
 
 
 class lp_layer_desc(C.Structure):
@@ -82,6 +82,7 @@ def load_library():
     dp = C.POINTER(C.c_double)
     L.lp_partition.argtypes = [dp, dp, ip, ip, C.c_double, C.POINTER(ip), C.POINTER(ip), dp, dp, dp]
     L.lp_set_delta_split.argtypes = [vp, ip, ip]
+    L.lp_probe_mfma.argtypes = [vp, C.c_size_t, ip, ip, ip, vp]
     L.lp_set_run_ahead.argtypes = [vp, ip]
     L.lp_set_graphs.argtypes = [vp, ip]
     L.lp_set_factor_ring.argtypes = [vp, ip, ip]
@@ -241,6 +242,13 @@ def lp_graph_stats(ctx):
     a, b, c = C.c_long(), C.c_long(), C.c_long()
     _check(ctx, lib().lp_graph_stats(ctx, C.byref(a), C.byref(b), C.byref(c)))
     return a.value, b.value, c.value
+
+
+def lp_probe_mfma(out_dev, workgroups: int, iters: int, uniform_values: bool = False, stream=None):
+    """out_dev: float32 device tensor of at least workgroups * 512 elements."""
+    r = lib().lp_probe_mfma(_ptr(out_dev), out_dev.numel(), int(workgroups), int(iters), int(uniform_values), _stream(stream))
+    if r != 0:
+        raise LpError(r, "lp_probe_mfma failed with status %d" % r)
 
 
 def lp_set_run_ahead(ctx, enable: bool):

@@ -274,6 +274,60 @@ size_t gemm_bf16_splitk_bytes(int M, int N, int K) {
   return s > 1 ? ((size_t)s * M * N * sizeof(float) + 255) / 256 * 256 : 0;
 }
 
+// Measurement aid: nothing but the GEMM's matrix instruction.  Each of the eight waves of a workgroup keeps the
+// 4 x 2 accumulator tiles of the 256 x 256 GEMM tile (128 registers) and fixed fragments in registers and
+// issues `iters` rounds of eight independent v_mfma_f32_32x32x16_bf16: what the matrix pipes sustain with no
+// LDS, cache or memory activity to feed them.
+namespace {
+__global__ void __launch_bounds__(512) mfma_only_kernel(float* __restrict__ out, int iters, int uniform) {
+  // operands: pseudo-random values in [-1, 1) (random sign, exponent and mantissa bits, as real activations
+  // and weights have: what the multipliers draw depends on how many bits toggle); `uniform` = 1: all lanes
+  // hold the same few small values instead
+  auto value = [&](unsigned k) -> __bf16 {
+    if (uniform) return (__bf16)(0.0009765625f * (float)(1 + (k & 3)));
+    unsigned h = (k + 0x9e3779b9u * (blockIdx.x * 512u + threadIdx.x + 1u)) * 2654435761u;
+    h ^= h >> 15; h *= 2246822519u; h ^= h >> 13;
+    return (__bf16)((float)(h & 0xffff) * (1.f / 32768.f) - 1.f);
+  };
+  bf16x8 a[4], b[2];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) a[i][e] = value(i * 8 + e);
+#pragma unroll
+  for (int j = 0; j < 2; ++j)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) b[j][e] = value(32 + j * 8 + e);
+  f32x16 acc[4][2];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+  }
+  float sum = 0.f;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) sum += acc[i][j][r];
+  out[(size_t)blockIdx.x * 512 + threadIdx.x] = sum;
+}
+}  // namespace
+
+hipError_t launch_mfma_only(float* out, int workgroups, int iters, bool uniform_values, hipStream_t s) {
+  if (workgroups <= 0 || iters < 0 || !out) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(mfma_only_kernel, dim3((unsigned)workgroups), dim3(512), 0, s, out, iters, uniform_values ? 1 : 0);
+  return hipGetLastError();
+}
+
 int gemm_bf16_num_cfgs() { return (int)(sizeof(kCfgs) / sizeof(kCfgs[0])); }
 const char* gemm_bf16_cfg_name(int cfg) { return (cfg >= 0 && cfg < gemm_bf16_num_cfgs()) ? kCfgs[cfg].name : "?"; }
 

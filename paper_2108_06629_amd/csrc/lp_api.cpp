@@ -1012,6 +1012,12 @@ int lp_tensor(lp_ctx* c, int l, int which, void** dev_ptr, size_t* bytes) {
   return LP_OK;
 }
 
+int lp_probe_mfma(float* out_dev, size_t out_elems, int workgroups, int iters, int uniform_values, void* stream) {
+  if (!out_dev) return LP_ERR_NULL;
+  if (workgroups < 1 || iters < 0 || out_elems < (size_t)workgroups * 512) return LP_ERR_SHAPE;
+  return lp::launch_mfma_only(out_dev, workgroups, iters, uniform_values != 0, (hipStream_t)stream) == hipSuccess ? LP_OK : LP_ERR_HIP;
+}
+
 int lp_profile(lp_ctx* c, int enable) {
   if (!c) return LP_ERR_NULL;
   c->prof_on = enable != 0;

@@ -82,6 +82,8 @@ hipError_t launch_mse(bool bf16, const void* Z, const void* T, void* dY, float* 
 // master <- master - lr * g;  work_out (bf16, may be null) <- round(master)
 hipError_t launch_sgd(float* master, const float* g, void* work_out_bf16, float lr, size_t n, hipStream_t s);
 // dst_bf16 <- round(src)
+// measurement aid: workgroups x 8 waves x iters x 8 MFMAs of 32 x 32 x 16 (65536 flop each wave-wide); out: workgroups * 512 floats
+hipError_t launch_mfma_only(float* out, int workgroups, int iters, bool uniform_values, hipStream_t s);
 hipError_t launch_cast_bf16(const float* src, void* dst_bf16, size_t n, hipStream_t s);
 // two device-to-device copies in one launch; every pointer 16-byte aligned
 hipError_t launch_copy2(const void* a, void* da, size_t a_bytes, const void* b, void* db, size_t b_bytes, hipStream_t s);

@@ -182,3 +182,12 @@ def test_factor_ring_shrinks_the_delay_elements():
     ctx = lp.lp_create(descs(cnn), cnn.L, 2, lp.LP_BF16, lp.LP_LOSS_SOFTMAX_CE, 0.01)
     assert L.lp_set_factor_ring(ctx, 1, 1) == 4 and L.lp_set_factor_ring(ctx, cnn.L, 1) == 0      # conv: LP_ERR_LAYER; the FC layer: fine
     lp.lp_destroy(ctx)
+
+
+def test_mfma_probe_checks_its_arguments_before_launching():
+    L = lp.lib()
+    assert L.lp_probe_mfma(None, 0, 1, 1, 0, None) == 1          # LP_ERR_NULL
+    fake = 4096                                                  # never dereferenced: the checks below fail first
+    assert L.lp_probe_mfma(fake, 511, 1, 1, 0, None) == 2        # LP_ERR_SHAPE: one workgroup writes 512 floats
+    assert L.lp_probe_mfma(fake, 1 << 20, 0, 1, 0, None) == 2    # no workgroups
+    assert L.lp_probe_mfma(fake, 1 << 20, 1, -1, 0, None) == 2   # negative round count

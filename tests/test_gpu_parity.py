@@ -561,3 +561,21 @@ def test_operand_beyond_32_bit_offsets_is_rejected_not_launched():
     with pytest.raises(lp.LpError):
         lp.lp_grad_act(net.ctx, 1, z, x, 0, n, net.streams[0])
     net.close()
+
+
+def test_mfma_probe_runs_the_rounds_it_is_asked_for():
+    """The calibration kernel of the matrix-core roofline: with the uniform operands every product and every
+    partial sum is a small multiple of 2^-20, so the checksums are exact and linear in the number of rounds."""
+    out1 = torch.zeros(4 * 512, dtype=torch.float32, device=DEV)
+    out2 = torch.zeros(4 * 512, dtype=torch.float32, device=DEV)
+    s = torch.cuda.Stream()
+    lp.lp_probe_mfma(out1, 4, 100, True, s)
+    lp.lp_probe_mfma(out2, 4, 200, True, s)
+    s.synchronize()
+    a, b = out1.cpu().numpy(), out2.cpu().numpy()
+    assert np.all(a > 0) and np.array_equal(b, 2 * a)
+    assert np.array_equal(a[:512], a[512:1024])                  # every workgroup holds the same uniform operands
+    lp.lp_probe_mfma(out1, 4, 100, False, s)
+    s.synchronize()
+    r = out1.cpu().numpy()
+    assert np.all(np.isfinite(r)) and not np.array_equal(r[:512], r[512:1024])   # random operands differ by workgroup
