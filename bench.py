@@ -247,25 +247,29 @@ def main():
         print(json.dumps({"calibrate_copy": {"bytes_read": src.numel() * 2, "bytes_written": src.numel() * 2, "copies": 5}}))
         return
 
-    if args.calibrate_mfma:
+    def mfma_only(per_cu, uniform, reps):
+        """lp_probe_mfma with `per_cu` workgroups per CU: (workgroups, rounds, ms per launch, TFLOP/s, a checksum)."""
         cus = torch.cuda.get_device_properties(0).multi_processor_count
+        wgs, iters = cus * per_cu, 20000 // per_cu
+        out = torch.empty(wgs * 512, dtype=torch.float32, device="cuda:0")
+        s = torch.cuda.Stream()
+        lp.lp_probe_mfma(out, wgs, 200, uniform, s)
+        s.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(s)
+        for _ in range(reps):
+            lp.lp_probe_mfma(out, wgs, iters, uniform, s)
+        e1.record(s)
+        s.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        return wgs, iters, ms, wgs * 8 * iters * 8 * 32768.0 / (ms * 1e-3) / 1e12, float(out[0].item())
+
+    if args.calibrate_mfma:
         rows = []
         for per_cu, uniform in ((1, False), (2, False), (1, True)):     # 1: two waves per SIMD, as in the 256 x 256 GEMM; 2: four
-            wgs, iters, reps = cus * per_cu, 20000 // per_cu, 8
-            out = torch.empty(wgs * 512, dtype=torch.float32, device="cuda:0")
-            s = torch.cuda.Stream()
-            lp.lp_probe_mfma(out, wgs, 200, uniform, s)
-            s.synchronize()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record(s)
-            for _ in range(reps):
-                lp.lp_probe_mfma(out, wgs, iters, uniform, s)
-            e1.record(s)
-            s.synchronize()
-            ms = e0.elapsed_time(e1) / reps
-            flops = wgs * 8 * iters * 8 * 32768.0
-            rows.append({"workgroups": wgs, "iters": iters, "operands": "uniform small values" if uniform else "pseudo-random in [-1, 1)", "ms_per_launch": ms, "TFLOP/s": flops / (ms * 1e-3) / 1e12,
-                         "frac_of_bf16_peak": flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, "checksum": float(out[0].item())})
+            wgs, iters, ms, tf, chk = mfma_only(per_cu, uniform, 8)
+            rows.append({"workgroups": wgs, "iters": iters, "operands": "uniform small values" if uniform else "pseudo-random in [-1, 1)",
+                         "ms_per_launch": ms, "TFLOP/s": tf, "frac_of_bf16_peak": tf / PEAK_BF16_TFLOPS, "checksum": chk})
         print(json.dumps({"calibrate_mfma": rows}))
         return
 
@@ -325,6 +329,9 @@ def main():
                                else "bf16 MFMA GEMM of the forward product F (tile and K split chosen per layer shape)"),
                     "flops_per_launch": flops_per_launch,
                     "avg_launch_ms": tasks["F"]["avg_ms"]}
+        # context, measured now on this machine: the matrix instruction alone on random register operands (the chip lowers
+        # its clock with the energy the work draws, so this, not the nominal peak, is what dense bf16 work can reach)
+        roofline["mfma_only_TFLOP/s_on_random_operands"] = mfma_only(1, False, 4)[3]
     elif "F" in tasks:
         flops_per_launch = work["F"] / wl.L
         ach = flops_per_launch / (tasks["F"]["avg_ms"] * 1e-3) / 1e12
