@@ -331,7 +331,8 @@ def main():
                     "avg_launch_ms": tasks["F"]["avg_ms"]}
         # context, measured now on this machine: the matrix instruction alone on random register operands (the chip lowers
         # its clock with the energy the work draws, so this, not the nominal peak, is what dense bf16 work can reach)
-        roofline["mfma_only_TFLOP/s_on_random_operands"] = mfma_only(1, False, 4)[3]
+        if not args.no_others:
+            roofline["mfma_only_TFLOP/s_on_random_operands"] = mfma_only(1, False, 4)[3]
     elif "F" in tasks:
         flops_per_launch = work["F"] / wl.L
         ach = flops_per_launch / (tasks["F"]["avg_ms"] * 1e-3) / 1e12
