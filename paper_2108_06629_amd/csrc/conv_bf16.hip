@@ -562,8 +562,7 @@ struct Tile {
 };
 
 // Main loop: the pipeline of dl::gemm_tile_dl (loads of step t + HSTAGES issued while step t is multiplied, one
-// barrier per step before its last substep) with nine substeps per step, one per tap.  Nine is odd, so the two
-// fragment buffers change roles from one step to the next: the loop is unrolled by two.
+// barrier per step, before its last two substeps) with nine substeps per step, one per tap.
 template <int PBM, int WM, int WN, bool DX, class Epi>
 __device__ __forceinline__ void run(const Tile<PBM, WM, WN, DX>& tl, unsigned short* smem, Epi epi) {
   using T = Tile<PBM, WM, WN, DX>;
@@ -579,7 +578,10 @@ __device__ __forceinline__ void run(const Tile<PBM, WM, WN, DX>& tl, unsigned sh
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  bf16x8 fa[2][TM], fb[2][TN];
+  // Fragments are fetched two taps ahead into three register buffers (a tap has only TM * TN MFMAs to cover
+  // an LDS read with, and the small tile runs one wave per SIMD); nine taps per step keep the buffers' roles
+  // the same in every step.
+  bf16x8 fa[3][TM], fb[3][TN];
   auto read_frags = [&](const unsigned short* st, auto tap_tag, bf16x8 (&a)[TM], bf16x8 (&b)[TN]) {
     constexpr int TAP = decltype(tap_tag)::value;
 #pragma unroll
@@ -600,33 +602,30 @@ __device__ __forceinline__ void run(const Tile<PBM, WM, WN, DX>& tl, unsigned sh
   dl::wait_vmcnt<(HSTAGES - 1) * LOADS>();
   __syncthreads();
   read_frags(smem, std::integral_constant<int, 0>{}, fa[0], fb[0]);
+  read_frags(smem, std::integral_constant<int, 1>{}, fa[1], fb[1]);
 
-  auto step = [&](int t, auto par_tag) {
-    constexpr int P = decltype(par_tag)::value;   // which fragment buffer holds tap 0 of this step
+  auto step = [&](int t) {
     const unsigned short* cur = smem + (t % HSTAGES) * STAGE;
     const unsigned short* nxt = smem + ((t + 1) % HSTAGES) * STAGE;
     auto taps = [&](auto self, auto tap_tag) -> void {
       constexpr int TAP = decltype(tap_tag)::value;
-      if constexpr (TAP < 8) {
-        read_frags(cur, std::integral_constant<int, TAP + 1>{}, fa[(TAP + 1 + P) & 1], fb[(TAP + 1 + P) & 1]);
-        mfmas(fa[(TAP + P) & 1], fb[(TAP + P) & 1]);
+      if constexpr (TAP < 7) {   // taps 0..6 fetch taps 2..8 of this step
+        read_frags(cur, std::integral_constant<int, TAP + 2>{}, fa[(TAP + 2) % 3], fb[(TAP + 2) % 3]);
+        mfmas(fa[TAP % 3], fb[TAP % 3]);
         self(self, std::integral_constant<int, TAP + 1>{});
       }
     };
     taps(taps, std::integral_constant<int, 0>{});
     dl::wait_vmcnt<(HSTAGES - 2) * LOADS>();   // this wave's part of step t+1 has landed
-    __syncthreads();                            // ... and everyone's; nobody reads step t's stage any more
+    __syncthreads();                            // ... and everyone's; every tap of step t is in registers by now
     issue(t + HSTAGES);
-    read_frags(nxt, std::integral_constant<int, 0>{}, fa[(9 + P) & 1], fb[(9 + P) & 1]);
-    mfmas(fa[(8 + P) & 1], fb[(8 + P) & 1]);
+    read_frags(nxt, std::integral_constant<int, 0>{}, fa[0], fb[0]);
+    mfmas(fa[1], fb[1]);                        // tap 7
+    read_frags(nxt, std::integral_constant<int, 1>{}, fa[1], fb[1]);
+    mfmas(fa[2], fb[2]);                        // tap 8
   };
   const int KT = tl.KT;
-  int t = 0;
-  for (; t + 1 < KT; t += 2) {
-    step(t, std::integral_constant<int, 0>{});
-    step(t + 1, std::integral_constant<int, 1>{});
-  }
-  if (t < KT) step(t, std::integral_constant<int, 0>{});
+  for (int t = 0; t < KT; ++t) step(t);
   dl::wait_vmcnt<0>();   // the trailing (empty) steps still write LDS
   __syncthreads();
 
@@ -687,8 +686,8 @@ hipError_t launch(const ConvKArgs& p, hipStream_t s) {
     }
     hipLaunchKernelGGL(kern, dim3((unsigned)t256), dim3(512), T::LDS_BYTES, s, p);
   } else {
-    using T = Tile<128, 2, 2, DX>;
-    auto kern = conv_halo_kernel<128, 2, 2, DX>;
+    using T = Tile<128, 4, 2, DX>;
+    auto kern = conv_halo_kernel<128, 4, 2, DX>;
     static bool attr = false;
     if (!attr) {
       hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)T::LDS_BYTES);
@@ -696,7 +695,7 @@ hipError_t launch(const ConvKArgs& p, hipStream_t s) {
       attr = true;
     }
     const long t128 = (long)((p.M + 127) / 128) * nbn;
-    hipLaunchKernelGGL(kern, dim3((unsigned)t128), dim3(256), T::LDS_BYTES, s, p);
+    hipLaunchKernelGGL(kern, dim3((unsigned)t128), dim3(512), T::LDS_BYTES, s, p);
   }
   return hipGetLastError();
 }
