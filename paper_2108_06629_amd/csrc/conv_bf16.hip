@@ -10,6 +10,7 @@
 // offset), and everything after that is the main loop of gemm_core.h.  dW reduces over B*H*W pixels
 // into a small [9*C_in, C_out] result, so it is split over K across workgroups; the fp32 partials are
 // summed by a second kernel in a fixed order.
+#include "conv_thin.h"
 #include "gemm_core.h"
 #include "gemm_dl.h"
 #include "lp_kernels.h"
@@ -841,6 +842,7 @@ hipError_t launch_conv_fwd(const ConvDesc& c, bool bf16, const void* x, const vo
   set_divs(p, c);
   const bool al_a = c.Cin % 8 == 0 && (uintptr_t)x % 16 == 0, al_b = c.Cout % 8 == 0 && (uintptr_t)w % 16 == 0;
   const int nb = ((p.M + BM - 1) / BM) * ((p.N + BN - 1) / BN);
+  if (conv_thin_ok(c, x, w)) return launch_conv_thin_fwd(c, x, w, out_z, out_a, act, s);
   if (halo::ok(c, c.Cin, x, w)) return halo::launch<false>(p, s);
   if (dl_ok(c, x, w)) {
     static bool attr_dl = false;
@@ -901,6 +903,13 @@ hipError_t launch_conv_grad_weight(const ConvDesc& c, bool bf16, const void* x, 
   if (!fits32(c) || !x || !dy || !g) return hipErrorInvalidValue;
   const int splits = dw_splits(c);
   if (splits > 1 && !partial) return hipErrorInvalidValue;
+  if (splits > 1 && conv_thin_ok(c, x, dy)) {
+    const int chunks = conv_thin_dw_chunks(c), groups = chunks < splits ? chunks : splits;   // the scratch holds `splits` partials
+    if (hipError_t e = launch_conv_thin_dw(c, x, dy, partial, groups, s)) return e;
+    const size_t n = (size_t)9 * c.Cin * c.Cout;
+    hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)((n + 31) / 32)), dim3(256), 0, s, (const float*)partial, g, n, groups);
+    return hipGetLastError();
+  }
   ConvKArgs p{};
   p.img = (const unsigned short*)x; p.mat = (const unsigned short*)dy;
   p.out_f32 = splits > 1 ? partial : g;

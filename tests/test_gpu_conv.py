@@ -28,7 +28,10 @@ def conv_net(B, H, W, cin, cout, pool=0, act="relu"):
 CONV_SHAPES = [(2, 8, 8, 3, 16), (3, 6, 10, 8, 24), (2, 16, 16, 64, 64), (5, 8, 8, 16, 136), (1, 2, 2, 8, 8), (4, 32, 32, 3, 64),
                # the halo kernels (channels % 16 == 0, rows of at most 32 pixels): 128-pixel tiles with a ragged last tile and a
                # ragged last column tile; enough tiles for the 256-pixel form; odd image sizes; a row too long for the halo
-               (3, 32, 32, 32, 48), (7, 5, 7, 16, 32), (20, 32, 32, 16, 208), (2, 4, 33, 16, 16)]
+               (3, 32, 32, 32, 48), (7, 5, 7, 16, 32), (20, 32, 32, 16, 208), (2, 4, 33, 16, 16),
+               # the three-channel image layer: ragged chunks and the longest row its halo takes, a row that is too long (general
+               # kernels), a 1 x 1 image (only the centre tap), more 512-pixel chunks than workgroups in dW
+               (3, 7, 39, 3, 8), (2, 5, 40, 3, 16), (5, 1, 1, 3, 64), (130, 32, 32, 3, 16)]
 
 
 @pytest.mark.parametrize("shape", CONV_SHAPES)
