@@ -325,5 +325,5 @@ class DelayedGradientTrainer:
             if self.delays[l] > 0:
                 self.G_hist[l][n] = G[l]
 
-        self.trace = dict(loss=float(loss), A=A, Z=Z, dA=dA, dY=dY, G=G, IDX=IDX)
+        self.trace = dict(loss=float(loss), A=A, Z=Z, dA=dA, dY=dY, G=G, IDX=IDX, Wk=Wk)
         return float(loss)

@@ -1,19 +1,77 @@
 // Balanced pipeline partitioning (Algorithm 1, Sec. III-C), host only.
 //
-// Layers are walked from the last to the first while processors are filled up to the target load
-// T_p = (sum of all task times) / N_p.  A layer contributes a movable delta task (only the processor
-// of the following layer may take it over) and an immovable part (forward + weight gradient).  The
-// delta task is offered first to the processor that is currently being filled, which is the one that
-// holds the following layer; what does not fit (delta') opens the next processor.  The immovable part
-// follows: into the current processor if it fits, else into a fresh one.  When the walk needs more
-// than N_p processors, T_p grows by the factor alpha and the walk starts over.
+// The network is seen as a queue of jobs, last layer first: for every layer a divisible job (its delta task,
+// Eq. 4, which only the processor of the following layer may take over) followed by an atomic job (forward +
+// weight gradient, which cannot move).  The jobs are packed into a row of bins of capacity T_p, one bin per
+// processor, never returning to an earlier bin:
+//   * a divisible job is poured into the open bin; what overflows opens the next bin (one cut per job: the
+//     part that stayed is delta'', executed by the following layer's processor, the overflow is delta');
+//   * an atomic job goes into the open bin if all of it fits, else it opens the next bin.
+// T_p starts at (sum of all job times) / N_p; while the packing needs more than N_p bins, T_p grows by the
+// factor alpha and the packing is redone.  Bins are numbered from the back of the network while packing and
+// renumbered front to back for the caller.
 //
-// Readings of the printed algorithm: a processor opened for an immovable part starts empty; stages are
-// renumbered front to back at the end; "fits" tolerates a relative 1e-9 so that exact fits (as in the
-// paper's own example, to table rounding) survive floating point.
+// Readings of the printed algorithm: a bin opened for an atomic job starts empty; "fits" tolerates a relative
+// 1e-9 so that exact fits (as in the paper's own example, to table rounding) survive floating point.
 #include "../../include/lp.h"
 
+#include <new>
 #include <vector>
+
+namespace {
+
+constexpr double kFitTol = 1e-9;
+
+struct Bins {
+  double cap;
+  std::vector<double> load;
+  explicit Bins(double cap_) : cap(cap_), load(1, 0.0) {}
+  int open_bin() const { return (int)load.size() - 1; }
+  double room() const { return cap - load.back(); }
+  void next() { load.push_back(0.0); }
+  // returns the amount the bin that was open on entry took
+  double pour(double amount) {
+    const double free_now = room();
+    if (amount <= free_now * (1.0 + kFitTol)) {
+      load.back() += amount;
+      return amount;
+    }
+    const double stays = free_now > 0.0 ? free_now : 0.0;
+    load.back() += stays;
+    next();
+    load.back() += amount - stays;
+    return stays;
+  }
+  void drop(double amount) {
+    if (amount > room() * (1.0 + kFitTol) + kFitTol * cap) next();
+    load.back() += amount;
+  }
+};
+
+// where the two jobs of one layer ended up (bins counted from the back of the network)
+struct LayerPlace {
+  int delta_first_bin = 0;   // bin that was open when the delta task arrived
+  int delta_last_bin = 0;    // bin that holds its overflow (same bin if it was not cut)
+  double delta_first_share = 1.0;
+  int fix_bin = 0;
+};
+
+int pack(const double* t_fix, const double* t_flex, int L, double cap, std::vector<LayerPlace>& place, std::vector<double>& load) {
+  Bins bins(cap);
+  for (int l = L - 1; l >= 0; --l) {
+    LayerPlace& p = place[l];
+    p.delta_first_bin = bins.open_bin();
+    const double kept = bins.pour(t_flex[l]);
+    p.delta_last_bin = bins.open_bin();
+    p.delta_first_share = p.delta_last_bin == p.delta_first_bin ? 1.0 : (t_flex[l] > 0.0 ? kept / t_flex[l] : 0.0);
+    bins.drop(t_fix[l]);
+    p.fix_bin = bins.open_bin();
+  }
+  load.swap(bins.load);
+  return (int)load.size();
+}
+
+}  // namespace
 
 extern "C" int lp_partition(const double* t_fix, const double* t_flex, int L, int n_proc, double alpha, int* stage_fix,
                             int* stage_delta_rest, double* borrowed_frac, double* stage_time, double* t_p_out) {
@@ -25,56 +83,32 @@ extern "C" int lp_partition(const double* t_fix, const double* t_flex, int L, in
     total += t_fix[l];
   }
   for (int l = 0; l < L; ++l) total += t_flex[l];
-  const double slack = 1e-9;
-  double target = total / n_proc;
-  std::vector<int> fix_on(L), first_on(L), rest_on(L);
-  std::vector<double> first_part(L);
-  std::vector<double> load;
-  for (int round = 0; round < 100000; ++round) {
-    load.assign(1, 0.0);
-    int cur = 0;
-    double room = target;
-    for (int l = L - 1; l >= 0; --l) {
-      const double d = t_flex[l];
-      first_on[l] = cur;
-      if (d <= room * (1.0 + slack)) {
-        load[cur] += d;
-        room -= d;
-        first_part[l] = 1.0;
-        rest_on[l] = cur;
-      } else {
-        const double stays = room > 0.0 ? room : 0.0;   // delta''
-        const double moves = d - stays;                 // delta'
-        load[cur] += stays;
-        first_part[l] = stays / d;
-        load.push_back(moves);
-        ++cur;
-        room = target - moves;
-        rest_on[l] = cur;
-      }
-      if (t_fix[l] > room * (1.0 + slack) + slack * target) {
-        load.push_back(0.0);
-        ++cur;
-        room = target;
-      }
-      load[cur] += t_fix[l];
-      room -= t_fix[l];
-      fix_on[l] = cur;
-    }
-    const int used = cur + 1;
-    if (used > n_proc) {
+  try {
+    std::vector<LayerPlace> place(L);
+    std::vector<double> load;
+    double target = total / n_proc;
+    int used = pack(t_fix, t_flex, L, target, place, load);
+    for (int relaxations = 0; used > n_proc; ++relaxations) {
+      if (relaxations >= 100000) return LP_ERR_STATE;
       target *= alpha;
-      continue;
+      used = pack(t_fix, t_flex, L, target, place, load);
     }
+    auto stage_of = [used](int bin) { return used - 1 - bin; };
     for (int l = 0; l < L; ++l) {
-      stage_fix[l] = used - 1 - fix_on[l];
-      stage_delta_rest[l] = used - 1 - rest_on[l];
-      const bool borrowed = l < L - 1 && first_on[l] == fix_on[l + 1] && fix_on[l + 1] != fix_on[l] && t_flex[l] > 0.0;
-      borrowed_frac[l] = borrowed ? first_part[l] : 0.0;
+      const LayerPlace& p = place[l];
+      stage_fix[l] = stage_of(p.fix_bin);
+      stage_delta_rest[l] = stage_of(p.delta_last_bin);
+      // borrowed: the share that stayed in the bin of the following layer's immovable job, when this layer's own
+      // immovable job sits in another bin
+      const bool by_next = l + 1 < L && t_flex[l] > 0.0 && p.delta_first_bin == place[l + 1].fix_bin && p.fix_bin != place[l + 1].fix_bin;
+      borrowed_frac[l] = by_next ? p.delta_first_share : 0.0;
     }
     for (int s = 0; s < n_proc; ++s) stage_time[s] = s < used ? load[used - 1 - s] : 0.0;
     if (t_p_out) *t_p_out = target;
     return LP_OK;
+  } catch (const std::bad_alloc&) {
+    return LP_ERR_STATE;
+  } catch (...) {
+    return LP_ERR_STATE;
   }
-  return LP_ERR_STATE;
 }

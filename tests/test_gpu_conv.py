@@ -7,7 +7,7 @@ import torch
 import lp_workloads as WL
 import paper_2108_06629_amd as lp
 from oracle import layerpipe_oracle as O
-from test_gpu_parity import DEV, dev, host, relerr, frob
+from test_gpu_parity import DEV, dev, host, relerr, frob, check_g_free_running, relu_flips, run_key, RECORDS, _dump_records
 
 pytestmark = pytest.mark.gpu
 
@@ -111,19 +111,28 @@ def test_pool_forward_and_routing_with_ties():
     net.close()
 
 
-def run_cnn(wl, steps):
+def run_cnn(wl, steps, exact=True, product_steps=None):
+    """As run_trajectory of test_gpu_parity.py, for networks with convolution layers: free-running loss, Z_L, W_l and
+    G_l (max-norm) against the oracle trajectory, and every task on the tensors it actually read on the GPU.
+    `product_steps` (None = all) limits the recomputation of the products; the Hadamard / pool routing, the update
+    from the ring and the frozen prefix are checked in every step."""
     W0 = WL.init_weights(wl)
     net = lp.Network(wl.layers, wl.batch, wl.dtype, wl.loss, wl.lr, wl.delays)
     net.set_weights(W0)
     ora = O.DelayedGradientTrainer(wl.layers, W0, wl.delays, wl.lr, wl.loss, "bf16")
-    exact = O.DelayedGradientTrainer(wl.layers, W0, wl.delays, wl.lr, wl.loss, "f64")
+    exact = O.DelayedGradientTrainer(wl.layers, W0, wl.delays, wl.lr, wl.loss, "f64") if exact else None
     G_hist = [dict() for _ in range(wl.L)]
+    rec = RECORDS.setdefault(run_key(wl), [])
+    del rec[:]
     for n in range(1, steps + 1):
+        print("run_cnn %s step %d of %d" % (wl.name, n, steps), flush=True)
+        products = product_steps is None or n in product_steps
         x, t = WL.batch_input(wl, n), WL.batch_target(wl, n)
         W_before = [net.get_weights(l) for l in range(1, wl.L + 1)]
         loss = net.step(x, t)
         ref = ora.step(x, t)
-        exact.step(x, t)
+        if exact is not None:
+            exact.step(x, t)
         assert abs(loss - ref) <= 2e-2 * max(abs(ref), 1e-3), (n, loss, ref)
         zl = net.tensor_np(wl.L, lp.LP_T_Z).reshape(ora.trace["Z"][-1].shape)
         assert relerr(zl, ora.trace["Z"][-1]) <= 2e-2
@@ -135,19 +144,21 @@ def run_cnn(wl, steps):
             a_in = A[-1]
             if ly.kind == WL.LINEAR and a_in.ndim == 4:
                 a_in = a_in.reshape(a_in.shape[0], -1)
-            z_ref = O.store(O.forward_product(a_in, Wk[l - 1]), "bf16")
             z_gpu = net.tensor_np(l, lp.LP_T_Z)
+            z_ref = O.store(O.forward_product(a_in, Wk[l - 1]), "bf16") if products else None
             if z_gpu is not None:
-                z_gpu = z_gpu.reshape(z_ref.shape)
-                assert relerr(z_gpu, z_ref) <= 2e-2, ("F/Z", l, n)
+                z_gpu = z_gpu.reshape(ly.z_shape(wl.batch))
+                if products:
+                    assert relerr(z_gpu, z_ref) <= 2e-2, ("F/Z", l, n)
             if l < wl.L:
                 a_gpu = net.tensor_np(l, lp.LP_T_A).reshape(ly.out_shape(wl.batch))
-                a_ref = O.store(O.activation(z_gpu if z_gpu is not None else z_ref, ly.act), "bf16")
-                if ly.pool == 2:
-                    a_ref, _ = O.maxpool2x2(a_ref)
-                    assert np.array_equal(a_gpu, a_ref), ("pool", l, n)      # computed from the stored Z: exact
-                else:
-                    assert relerr(a_gpu, a_ref) <= 2e-2, ("F/A", l, n)
+                if z_gpu is not None or products:
+                    a_ref = O.store(O.activation(z_gpu if z_gpu is not None else z_ref, ly.act), "bf16")
+                    if ly.pool == 2:
+                        a_ref, _ = O.maxpool2x2(a_ref)
+                        assert np.array_equal(a_gpu, a_ref), ("pool", l, n)      # computed from the stored Z: exact
+                    else:
+                        assert relerr(a_gpu, a_ref) <= 2e-2, ("F/A", l, n)
                 A.append(a_gpu)
         for l in range(wl.L, 0, -1):
             ly = wl.layers[l - 1]
@@ -156,15 +167,18 @@ def run_cnn(wl, steps):
             if ly.kind == WL.LINEAR and a_in.ndim == 4:
                 a_in = a_in.reshape(a_in.shape[0], -1)
             g = net.tensor_np(l, lp.LP_T_G_LAST).reshape(Wk[l - 1].shape)
-            assert relerr(g, O.grad_weight(a_in, dy)) <= 2e-4, ("dW", l, n)
+            if products:
+                assert relerr(g, O.grad_weight(a_in, dy)) <= 2e-4, ("dW", l, n)
             G_hist[l - 1][n] = g
-            floor = frob(ora.trace["G"][l - 1], exact.trace["G"][l - 1])
-            assert frob(g, ora.trace["G"][l - 1]) <= max(2e-2, floor), ("G free-running", l, n)
+            e = check_g_free_running(wl, l, n, g, ora.trace["G"][l - 1], None if exact is None else exact.trace["G"][l - 1])
+            flips, units = relu_flips(net, wl, l, ora.trace["Z"][l - 1])
+            rec.append(dict(n=n, l=l, g_maxnorm=e, relu_flips=flips, relu_units=units))
             if l > 1:
                 prev = wl.layers[l - 2]
                 da = net.tensor_np(l - 1, lp.LP_T_DA).reshape(prev.out_shape(wl.batch))
-                da_ref = O.store(O.grad_act(dy, Wk[l - 1]), "bf16").reshape(da.shape)
-                assert relerr(da, da_ref) <= 2e-2, ("dX", l, n)
+                if products:
+                    da_ref = O.store(O.grad_act(dy, Wk[l - 1]), "bf16").reshape(da.shape)
+                    assert relerr(da, da_ref) <= 2e-2, ("dX", l, n)
                 dyp = net.tensor_np(l - 1, lp.LP_T_DY).reshape(prev.z_shape(wl.batch))
                 if prev.pool == 2:
                     zp = net.tensor_np(l - 1, lp.LP_T_Z).reshape(prev.z_shape(wl.batch))
@@ -182,6 +196,7 @@ def run_cnn(wl, steps):
                 assert np.max(np.abs(w_new - upd)) <= 2.0 ** -22 * np.max(np.abs(upd)), ("update", l, n)
             assert relerr(w_new, ora.W[l - 1]) <= 2e-2, ("W free-running", l, n)
     net.close()
+    _dump_records(run_key(wl))
 
 
 def test_trajectory_cnn_small_unaligned_first_layer():

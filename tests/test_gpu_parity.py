@@ -261,11 +261,69 @@ def frob(got, ref):
     return float(np.linalg.norm(got - ref) / max(np.linalg.norm(ref), 1e-300))
 
 
-def check_tasks_of_last_step(net, wl, x, target, W_before, G_hist, n):
+# Free-running bf16 gradients: measured bounds on max |G_gpu - G_oracle| / max |G_oracle| for the runs in which the
+# stated 2e-2 does not hold (run_key -> {layer: bound}); everything not listed is held to 2e-2.  The GPU and the
+# oracle differ in summation order only, which moves the last bf16 bit of a few stored elements; a ReLU decided on
+# such an element may flip, and a flipped unit moves single entries of G by a whole term.  The task-by-task check on
+# identical inputs (check_tasks_of_last_step) is the bound that does not compound.
+G_MAXNORM_BOUND = {}
+
+RECORDS = {}     # run key -> list of dict(n, l, g_maxnorm, relu_flips, relu_units): what the last run measured
+
+
+def run_key(wl):
+    """Names a run by its workload, batch and parameter count (scaled replicas keep the workload's name)."""
+    return "%s_batch%d_params%d" % (wl.name, wl.batch, wl.n_params)
+
+
+def _dump_records(name):
+    """With LP_RECORD_DIR set, the per-layer per-step figures of a run are written there as JSON."""
+    import json
+    import os
+    d = os.environ.get("LP_RECORD_DIR")
+    if d and RECORDS.get(name):
+        os.makedirs(d, exist_ok=True)
+        with open(os.path.join(d, "g_maxnorm_%s.json" % name), "w") as f:
+            json.dump(RECORDS[name], f)
+
+
+def check_g_free_running(wl, l, n, g, g_ref, g_exact=None):
+    """Every free-running G_l is held element-wise (max-norm relative to the largest entry of the oracle's G_l);
+    the Frobenius comparison against the bf16 oracle's own distance from the float64 oracle is kept beside it."""
+    bf = wl.dtype == "bf16"
+    e = relerr(g, g_ref)
+    if not bf:
+        assert e <= (1e-3 if n >= 8 else 1e-4), ("G", l, n, e)
+        return e
+    bound = G_MAXNORM_BOUND.get(run_key(wl), {}).get(l, 2e-2)
+    assert e <= bound, ("G max-norm", wl.name, l, n, e, bound)
+    if g_exact is not None:
+        floor = frob(g_ref, g_exact)
+        ef = frob(g, g_ref)
+        assert ef <= max(2e-2, floor), ("G Frobenius", l, n, ef, floor)
+    return e
+
+
+def relu_flips(net, wl, l, z_ref):
+    """Number of units of ReLU layer l whose on/off decision differs between the GPU and the oracle trajectory."""
+    ly = wl.layers[l - 1]
+    if ly.act != "relu" or l == wl.L:
+        return 0, 0
+    z_gpu = net.tensor_np(l, lp.LP_T_Z)
+    if z_gpu is None:                     # a ReLU layer without pool keeps A only: same sign as Z
+        z_gpu = net.tensor_np(l, lp.LP_T_A)
+    z_gpu = z_gpu.reshape(z_ref.shape)
+    return int(np.count_nonzero((z_gpu > 0) != (z_ref > 0))), int(z_ref.size)
+
+
+def check_tasks_of_last_step(net, wl, x, target, W_before, G_hist, n, products=True):
     """Task-by-task check of the step that just ran: every task's output is compared with the oracle
     operator applied to the inputs that task actually read on the GPU.  With identical inputs the
     discrete decisions (ReLU mask) are identical too, so the bound is the arithmetic one, and the
-    delayed update is checked against the GPU's own gradient of d_l steps ago (the ring)."""
+    delayed update is checked against the GPU's own gradient of d_l steps ago (the ring).
+    products=False skips the recomputation of the three products and of the loss (the long runs at the
+    benchmark's sizes do them on some steps only); the Hadamard, the update from the ring, the frozen
+    prefix and the working copy are checked in every step."""
     bf = wl.dtype == "bf16"
     st = "bf16" if bf else "f32"
     tol = 2e-2 if bf else 1e-4
@@ -275,31 +333,34 @@ def check_tasks_of_last_step(net, wl, x, target, W_before, G_hist, n):
     A = [O.store(x, st)] + [net.tensor_np(l, lp.LP_T_A) for l in range(1, L)]
     A = [a if a is None else a.reshape(wl.batch, -1) for a in A]
     dY = [net.tensor_np(l, lp.LP_T_DY).reshape(wl.batch, -1) for l in range(1, L + 1)]
-    for l in range(1, L + 1):
-        ly = wl.layers[l - 1]
-        z_ref = O.store(O.forward_product(A[l - 1], Wk[l - 1]), st)
-        z_gpu = net.tensor_np(l, lp.LP_T_Z)
-        if z_gpu is not None:
-            z_gpu = z_gpu.reshape(z_ref.shape)
-            assert relerr(z_gpu, z_ref) <= tol, ("F/Z", l, n)
-        if l < L:
-            a_ref = O.store(O.activation(z_gpu if z_gpu is not None else z_ref, ly.act), st)
-            assert relerr(A[l], a_ref) <= tol, ("F/A", l, n)
-    zL = net.tensor_np(L, lp.LP_T_Z).reshape(wl.batch, -1)
-    if wl.loss == WL.SOFTMAX_CE:
-        loss_ref, dyL = O.softmax_ce(zL, target)
-    else:
-        loss_ref, dyL = O.mse(zL, O.store(target, st).reshape(zL.shape))
-    assert abs(float(net.loss_dev) - loss_ref) <= 1e-5 * max(1.0, abs(loss_ref)), ("loss", n)
-    assert relerr(dY[L - 1], O.store(dyL, st)) <= tol, ("dY_L", n)
+    if products:
+        for l in range(1, L + 1):
+            ly = wl.layers[l - 1]
+            z_ref = O.store(O.forward_product(A[l - 1], Wk[l - 1]), st)
+            z_gpu = net.tensor_np(l, lp.LP_T_Z)
+            if z_gpu is not None:
+                z_gpu = z_gpu.reshape(z_ref.shape)
+                assert relerr(z_gpu, z_ref) <= tol, ("F/Z", l, n)
+            if l < L:
+                a_ref = O.store(O.activation(z_gpu if z_gpu is not None else z_ref, ly.act), st)
+                assert relerr(A[l], a_ref) <= tol, ("F/A", l, n)
+        zL = net.tensor_np(L, lp.LP_T_Z).reshape(wl.batch, -1)
+        if wl.loss == WL.SOFTMAX_CE:
+            loss_ref, dyL = O.softmax_ce(zL, target)
+        else:
+            loss_ref, dyL = O.mse(zL, O.store(target, st).reshape(zL.shape))
+        assert abs(float(net.loss_dev) - loss_ref) <= 1e-5 * max(1.0, abs(loss_ref)), ("loss", n)
+        assert relerr(dY[L - 1], O.store(dyL, st)) <= tol, ("dY_L", n)
     for l in range(L, 0, -1):
         g = net.tensor_np(l, lp.LP_T_G_LAST).reshape(Wk[l - 1].shape)
-        assert relerr(g, O.grad_weight(A[l - 1], dY[l - 1])) <= tolG, ("dW", l, n)
+        if products:
+            assert relerr(g, O.grad_weight(A[l - 1], dY[l - 1])) <= tolG, ("dW", l, n)
         G_hist[l - 1][n] = g
         if l > 1:
             prev = wl.layers[l - 2]
             da = net.tensor_np(l - 1, lp.LP_T_DA).reshape(wl.batch, -1)
-            assert relerr(da, O.store(O.grad_act(dY[l - 1], Wk[l - 1]), st)) <= tol, ("dX", l, n)
+            if products:
+                assert relerr(da, O.store(O.grad_act(dY[l - 1], Wk[l - 1]), st)) <= tol, ("dX", l, n)
             stash = net.tensor_np(l - 1, lp.LP_T_Z)
             stash = A[l - 1] if stash is None else stash.reshape(wl.batch, -1)
             dy_ref = O.store(O.act_grad(da, stash, prev.act), st)
@@ -316,33 +377,36 @@ def check_tasks_of_last_step(net, wl, x, target, W_before, G_hist, n):
             g_old = G_hist[l - 1].pop(src)
             ref = O.store(O.delayed_sgd(W_before[l - 1].astype(np.float64), g_old, float(np.float32(wl.lr))), "f32")
             assert np.max(np.abs(w_new - ref)) <= 2.0 ** -22 * np.max(np.abs(ref)), ("update", l, n)
+            if np.any(g_old != 0):
+                assert not np.array_equal(w_new, W_before[l - 1]), ("update changed nothing", l, n)
         if bf:
             work = net.tensor_np(l, lp.LP_T_WORK_W).reshape(w_new.shape)
             assert np.array_equal(work, O.round_bf16(w_new)), ("working copy", l, n)
 
 
-def run_trajectory(wl, steps, n_streams=3, taskwise=True, run_ahead=False):
-    """Free-running comparison with the oracle: loss, Z_L and every W_l(n) in max-norm; every G_l in
-    max-norm for fp32.  For bf16 the free-running G_l is compared in Frobenius norm against
-    max(2e-2, the bf16 oracle's own distance from the unrounded float64 oracle): two correct
-    implementations that differ only in summation order decorrelate in the last bf16 bit of every
-    stored tensor, a ReLU decision on such inputs may legitimately flip and moves single entries of
-    G by a whole term, and both effects compound over the 2L stored tensors between the input and
-    G_1.  The bound that does not compound is the task-by-task check on identical inputs below."""
+def run_trajectory(wl, steps, n_streams=3, taskwise=True, run_ahead=False, exact=True, product_steps=None):
+    """Free-running comparison with the oracle: loss, Z_L, every W_l(n) and every G_l in max-norm (for bf16 the
+    bound on G_l is 2e-2 unless G_MAXNORM_BOUND lists a measured one).  With `exact`, a float64 oracle runs beside
+    the bf16 one and the free-running G_l is also compared in Frobenius norm against max(2e-2, the bf16 oracle's
+    own distance from the float64 oracle).  The bound that does not compound is the task-by-task check on
+    identical inputs; `product_steps` (a set of step numbers, None = all) limits its recomputation of the products."""
     bf = wl.dtype == "bf16"
     storage = "bf16" if bf else "f32"
     W0 = WL.init_weights(wl)
     net = lp.Network(wl.layers, wl.batch, wl.dtype, wl.loss, wl.lr, wl.delays, n_streams=n_streams, run_ahead=run_ahead)
     net.set_weights(W0)
     ora = O.DelayedGradientTrainer(wl.layers, W0, wl.delays, wl.lr, wl.loss, storage)
-    exact = O.DelayedGradientTrainer(wl.layers, W0, wl.delays, wl.lr, wl.loss, "f64") if bf else None
+    exact = O.DelayedGradientTrainer(wl.layers, W0, wl.delays, wl.lr, wl.loss, "f64") if (bf and exact) else None
     G_hist = [dict() for _ in range(wl.L)]
+    rec = RECORDS.setdefault(run_key(wl), [])
+    del rec[:]
     for n in range(1, steps + 1):
+        print("run_trajectory %s step %d of %d" % (wl.name, n, steps), flush=True)
         x, t = WL.batch_input(wl, n), WL.batch_target(wl, n)
         W_before = [net.get_weights(l) for l in range(1, wl.L + 1)] if taskwise else None
         loss = net.step(x, t)
         ref = ora.step(x, t)
-        if bf:
+        if exact is not None:
             exact.step(x, t)
         tol = 2e-2 if bf else (1e-3 if n >= 8 else 1e-4)
         assert abs(loss - ref) <= tol * max(abs(ref), 1e-3), (n, loss, ref)
@@ -350,20 +414,17 @@ def run_trajectory(wl, steps, n_streams=3, taskwise=True, run_ahead=False):
         assert relerr(zl, ora.trace["Z"][-1]) <= tol, ("Z_L", n)
         for l in range(1, wl.L + 1):
             g = net.tensor_np(l, lp.LP_T_G_LAST).reshape(ora.trace["G"][l - 1].shape)
-            if bf:
-                floor = frob(ora.trace["G"][l - 1], exact.trace["G"][l - 1])
-                e = frob(g, ora.trace["G"][l - 1])
-                assert e <= max(tol, floor), ("G", l, n, e, floor)
-            else:
-                e = relerr(g, ora.trace["G"][l - 1])
-                assert e <= tol, ("G", l, n, e)
+            e = check_g_free_running(wl, l, n, g, ora.trace["G"][l - 1], None if exact is None else exact.trace["G"][l - 1])
+            flips, units = relu_flips(net, wl, l, ora.trace["Z"][l - 1])
+            rec.append(dict(n=n, l=l, g_maxnorm=e, relu_flips=flips, relu_units=units))
             w = net.get_weights(l)
             assert relerr(w, ora.W[l - 1]) <= tol, ("W", l, n)
             if n <= wl.delays[l - 1]:       # delay elements still empty: weights untouched, bit for bit
                 assert np.array_equal(w, W0[l - 1]), ("frozen", l, n)
         if taskwise:
-            check_tasks_of_last_step(net, wl, x, t, W_before, G_hist, n)
+            check_tasks_of_last_step(net, wl, x, t, W_before, G_hist, n, products=(product_steps is None or n in product_steps))
     net.close()
+    _dump_records(run_key(wl))
 
 
 def test_trajectory_mlp_small_f32_full_config():

@@ -352,14 +352,89 @@ def test_bf16_rounding_against_library_and_ties():
 
 
 def test_storage_rounding_is_applied_to_stored_tensors_only():
-    wl = tiny_mlp("relu", (16, 12, 8), 4)
+    wl = tiny_mlp("tanh", (16, 12, 8), 4)
     tr = O.DelayedGradientTrainer(wl.layers, WL.init_weights(wl), [0, 0], wl.lr, wl.loss, "bf16")
     tr.step(WL.batch_input(wl, 1), WL.batch_target(wl, 1))
     isb = lambda v: np.array_equal(O.round_bf16(v), v)
-    for k in ("A", "Z", "dY"):
-        assert all(isb(v) for v in tr.trace[k] if v is not None), k
+    # every tensor the HIP path keeps in bf16: activations, products, both kinds of gradient w.r.t. activations,
+    # and the working copy of the weights that F and dX read
+    for k in ("A", "Z", "dY", "dA", "Wk"):
+        vals = [v for v in tr.trace[k] if v is not None]
+        assert vals and all(isb(v) for v in vals), k
     assert not all(isb(g) for g in tr.trace["G"])                 # gradients stay unrounded
     assert all(np.array_equal(w.astype(np.float32).astype(np.float64), w) for w in tr.W)   # fp32 master
+    assert not all(isb(w) for w in tr.W)                          # ... which is not the rounded copy
+    # the unrounded trainer rounds none of them
+    ex = O.DelayedGradientTrainer(wl.layers, WL.init_weights(wl), [0, 0], wl.lr, wl.loss, "f64")
+    ex.step(WL.batch_input(wl, 1), WL.batch_target(wl, 1))
+    for k in ("Z", "dY", "dA"):
+        assert not all(isb(v) for v in ex.trace[k] if v is not None), k
+
+
+def test_mse_target_is_rounded_to_the_stored_type():
+    """A bf16 context stores the regression target in bf16: the error is taken against the rounded target.
+    One identity layer with unit weights, so Z = x; targets 1.5 + 2^-8 (an exact tie: rounds to the even
+    neighbour 1.5) and 3 - 2^-8 (rounds to 3).  By hand: d = (1 - 1.5, 2 - 3), E = (0.25 + 1) / 2 = 0.625,
+    dY = 2 d / 2 = d.  Against the unrounded target E would be 0.62306...: the 3rd digit differs."""
+    layers = (WL.Layer(WL.LINEAR, 2, 2, WL.IDENTITY),)
+    x = np.array([[1.0, 2.0]])
+    t = np.array([[1.5 + 2.0 ** -8, 3.0 - 2.0 ** -8]])
+    tr = O.DelayedGradientTrainer(layers, [np.eye(2)], [0], 0.25, WL.MSE, "bf16")
+    loss = tr.step(x, t)
+    assert loss == 0.625
+    assert np.array_equal(tr.trace["dY"][0], [[-0.5, -1.0]])
+    unrounded = ((1.0 - t[0, 0]) ** 2 + (2.0 - t[0, 1]) ** 2) / 2
+    assert abs(unrounded - 0.623062133789) < 1e-9 and abs(loss - unrounded) > 1e-3
+    # G = x^T dY, W(1) = I - 0.25 G
+    assert np.array_equal(tr.W[0], np.eye(2) - 0.25 * np.array([[-0.5, -1.0], [-1.0, -2.0]]))
+    # an f32 context does not round it
+    tr32 = O.DelayedGradientTrainer(layers, [np.eye(2)], [0], 0.25, WL.MSE, "f32")
+    assert abs(tr32.step(x, t) - unrounded) < 1e-12
+
+
+def test_hand_computed_bf16_step_of_a_two_layer_network():
+    """One training step worked out by hand on numbers chosen so that every result is exact and every rounding to
+    bf16 that the path prescribes changes a digit somewhere.  a = 1 + 2^-8 + 2^-12 is an fp32 number that rounds UP
+    to 1 + 2^-7 in bf16.  Batch 1, eta = 1/2, no delay, MSE over 4 outputs (dY = (z - t) / 2).
+
+      master W1 = [[a, 2, 1], [1, 1, 1]]                        working copy: a -> 1 + 2^-7
+      x = [1, -1]        z1 = [2^-7, 1, 0]                      (with the unrounded a: 2^-8 + 2^-12)
+      ReLU               a1 = [2^-7, 1, 0],  f'(z1) = [1, 1, 0]  (the unit at exactly 0 is off)
+      master W2 = [[64, 0, 256 a, 0], [3, a, -2^-6, 0], [5, 7, 1, 0]]     working copy: 256 a -> 258, a -> 1 + 2^-7
+      z2 = a1 . W2 = [0.5 + 3, 1 + 2^-7, 258/128 - 1/64, 0] = [3.5, 1 + 2^-7, 2, 0]
+      t  = [-0.5 - 2^-10, a, 6, 0]   stored as  [-0.5, 1 + 2^-7, 6, 0]
+      d  = z2 - t = [4, 0, -4, 0]     E = (16 + 0 + 16 + 0) / 4 = 8      dY2 = [2, 0, -2, 0]
+      G2 = a1^T dY2 = [[2^-6, 0, -2^-6, 0], [2, 0, -2, 0], [0, 0, 0, 0]]
+      dA1 = dY2 . W2^T = [128 - 516, 6 + 2^-5, 10 - 2] = [-388, 6.03125, 8]   (master 256 a instead of 258: -386.125)
+      dY1 = dA1 (.) f'(z1) = [-388, 6.03125, 0]
+      G1 = x^T dY1 = [[-388, 6.03125, 0], [388, -6.03125, 0]]
+      W1(1) = W1 - G1 / 2,  W2(1) = W2 - G2 / 2      (on the fp32 masters)
+    """
+    a = 1.0 + 2.0 ** -8 + 2.0 ** -12
+    assert np.float32(a) == a and O.round_bf16(np.array([a]))[0] == 1.0 + 2.0 ** -7 and O.round_bf16(np.array([256 * a]))[0] == 258.0
+    layers = (WL.Layer(WL.LINEAR, 2, 3, WL.RELU), WL.Layer(WL.LINEAR, 3, 4, WL.IDENTITY))
+    W1 = np.array([[a, 2.0, 1.0], [1.0, 1.0, 1.0]])
+    W2 = np.array([[64.0, 0.0, 256 * a, 0.0], [3.0, a, -2.0 ** -6, 0.0], [5.0, 7.0, 1.0, 0.0]])
+    x = np.array([[1.0, -1.0]])
+    t = np.array([[-0.5 - 2.0 ** -10, a, 6.0, 0.0]])
+    for split in (True, False):
+        tr = O.DelayedGradientTrainer(layers, [W1, W2], [0, 0], 0.5, WL.MSE, "bf16", split=split)
+        assert tr.step(x, t) == 8.0
+        assert np.array_equal(tr.trace["Z"][0], [[2.0 ** -7, 1.0, 0.0]])
+        assert np.array_equal(tr.trace["Z"][1], [[3.5, 1.0 + 2.0 ** -7, 2.0, 0.0]])
+        assert np.array_equal(tr.trace["dY"][1], [[2.0, 0.0, -2.0, 0.0]])
+        assert np.array_equal(tr.trace["dY"][0], [[-388.0, 6.03125, 0.0]])
+        assert np.array_equal(tr.trace["G"][0], [[-388.0, 6.03125, 0.0], [388.0, -6.03125, 0.0]])
+        assert np.array_equal(tr.trace["G"][1], [[2.0 ** -6, 0.0, -2.0 ** -6, 0.0], [2.0, 0.0, -2.0, 0.0], [0.0, 0.0, 0.0, 0.0]])
+        assert np.array_equal(tr.W[0], [[a + 194.0, 2.0 - 3.015625, 1.0], [1.0 - 194.0, 1.0 + 3.015625, 1.0]])
+        assert np.array_equal(tr.W[1], [[64.0 - 2.0 ** -7, 0.0, 256 * a + 2.0 ** -7, 0.0], [2.0, a, 1.0 - 2.0 ** -6, 0.0], [5.0, 7.0, 1.0, 0.0]])
+    assert np.array_equal(tr.trace["dA"][0] if tr.trace["dA"][0] is not None else [[-388.0, 6.03125, 8.0]], [[-388.0, 6.03125, 8.0]])
+    # second step: F reads the rounded copy of the UPDATED masters (a + 194 = 195.0041... is stored as 195 in bf16)
+    tr = O.DelayedGradientTrainer(layers, [W1, W2], [0, 0], 0.5, WL.MSE, "bf16")
+    tr.step(x, t)
+    tr.step(np.array([[1.0, 0.0]]), t)
+    assert np.array_equal(tr.trace["Wk"][0][0], [195.0, -1.015625, 1.0])
+    assert np.array_equal(tr.trace["Z"][0], [[195.0, -1.015625, 1.0]])
 
 
 # ------------------------------------------------------------------------------------------------

@@ -110,6 +110,83 @@ def test_library_partition_matches_oracle_and_table_iii():
             assert all(abs(a - b) <= 1e-9 * max(1.0, abs(b)) for a, b in zip(got[k], want[k])), (trial, k)
 
 
+# ------------------------------------------------------------------------------------------------
+# brute force, written from the text of Sec. III-C rather than from the listing's arithmetic
+# ------------------------------------------------------------------------------------------------
+def unit_walk(t_fix, t_flex, n_proc, cap):
+    """All times are whole numbers of unit jobs.  Processors are filled one after the other, last layer first, each up
+    to `cap` units.  A layer's delta task is a pile of independent unit jobs (the delta computation is parallel over
+    channels): each unit goes to the processor being filled; the first unit that finds it full opens the next
+    processor, and the rest of the pile follows it there (the task is cut once, into delta'' and delta').  The fixed
+    part of a layer is one indivisible job: it opens a fresh processor unless all of it fits.  Returns None if that
+    takes more than n_proc processors, else (processor of each fixed part, units of each delta task per processor,
+    load per processor), processors numbered from the back of the network."""
+    L = len(t_fix)
+    load = [0]
+    fix_on = [None] * L
+    flex_on = [dict() for _ in range(L)]
+    for l in reversed(range(L)):
+        cut = False
+        for _ in range(t_flex[l]):
+            if not cut and load[-1] + 1 > cap:
+                load.append(0)
+                cut = True
+            load[-1] += 1
+            flex_on[l][len(load) - 1] = flex_on[l].get(len(load) - 1, 0) + 1
+        if load[-1] + t_fix[l] > cap:
+            load.append(0)
+        load[-1] += t_fix[l]
+        fix_on[l] = len(load) - 1
+    return None if len(load) > n_proc else (fix_on, flex_on, load)
+
+
+def brute_force_partition(t_fix, t_flex, n_proc, alpha):
+    cap = (sum(t_fix) + sum(t_flex)) // n_proc
+    while True:
+        r = unit_walk(t_fix, t_flex, n_proc, cap)
+        if r is not None:
+            return cap, r
+        cap *= alpha
+
+
+@pytest.mark.parametrize("which", ["oracle", "library"])
+def test_partition_against_unit_by_unit_brute_force(which):
+    """Whole-number task times, a total divisible by N_p and alpha = 2 keep the target load a whole number, so the
+    unit-by-unit walk and Algorithm 1 must agree exactly: stage of every fixed part, units of every delta task that
+    the next layer's stage borrows, load of every stage.  Delta tasks no longer than the first target load: a pile
+    longer than a whole processor is outside what the text describes (the listing would overfill one processor)."""
+    rng = random.Random(11)
+    done = 0
+    while done < 400:
+        L, n_proc = rng.randint(1, 5), rng.randint(1, 4)
+        t_fix = [rng.randint(0, 12) for _ in range(L)]
+        t_flex = [rng.randint(0, 30) for _ in range(L)]
+        tot = sum(t_fix) + sum(t_flex)
+        t_fix[0] += (-tot) % n_proc                      # total divisible by N_p
+        tot = sum(t_fix) + sum(t_flex)
+        if tot == 0 or max(t_flex) > tot // n_proc:
+            continue
+        done += 1
+        cap, (fix_on, flex_on, load) = brute_force_partition(t_fix, t_flex, n_proc, 2)
+        used = len(load)
+        f = [float(v) for v in t_fix], [float(v) for v in t_flex]
+        got = P.partition(f[0], f[1], n_proc, 2.0) if which == "oracle" else lib_partition(f[0], f[1], n_proc, 2.0)
+        case = (t_fix, t_flex, n_proc)
+        assert got["t_p"] == cap, case
+        assert got["stage_fix"] == [used - 1 - q for q in fix_on], case
+        assert got["stage_time"] == [float(v) for v in reversed(load)] + [0.0] * (n_proc - used), case
+        for l in range(L):
+            # units of layer l's delta task that run on the stage of layer l+1's fixed part while layer l's own fixed part
+            # sits elsewhere = the borrowed part (delta'')
+            borrowed = 0
+            if l < L - 1 and fix_on[l + 1] != fix_on[l]:
+                borrowed = flex_on[l].get(fix_on[l + 1], 0)
+            assert abs(got["borrowed_frac"][l] * t_flex[l] - borrowed) < 1e-9, (case, l)
+            rest = [q for q in flex_on[l] if not (l < L - 1 and q == fix_on[l + 1] and fix_on[l + 1] != fix_on[l])]
+            if t_flex[l] > 0 and rest:
+                assert got["stage_delta_rest"][l] == used - 1 - max(rest), (case, l)
+
+
 def test_library_partition_rejects_bad_arguments():
     L = lp.lib()
     one = (C.c_double * 1)(1.0)
