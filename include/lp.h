@@ -32,8 +32,16 @@
  *
  * Execution.  Compute entry points validate their arguments synchronously, then enqueue kernels on
  * the given hipStream_t (passed as void*; NULL = the default stream) and return without waiting.
- * Every function returns an lp_status; on error nothing has been enqueued and lp_last_error gives
- * a message.  No function throws or aborts.  A context is not thread-safe.
+ * Every function returns an lp_status and lp_last_error gives a message.  Shapes, sizes and operand
+ * limits are checked by lp_create (an operand of 2 GiB or more is LP_ERR_SHAPE there: the kernels use
+ * 32-bit byte offsets), pointers and state by each call before its first launch, so an error of these
+ * kinds means nothing has been enqueued; LP_ERR_HIP reports a failure of the HIP runtime itself, after
+ * which earlier launches of the same call may already be running.  No C++ exception leaves the
+ * library (host memory exhaustion inside it is reported as LP_ERR_STATE) and nothing aborts.  A
+ * context is not thread-safe.
+ *
+ * Timing events per task and the matrix-instruction probe used by the benchmark are declared in
+ * lp_measure.h; they are not part of the training path.
  */
 #ifndef LAYERPIPE_LP_H
 #define LAYERPIPE_LP_H
@@ -117,6 +125,11 @@ int lp_bind_workspace(lp_ctx* ctx, void* dev_ptr, size_t bytes);
 int lp_set_weights(lp_ctx* ctx, int l, const float* W, int is_device, void* stream);
 /* Copies the master weights of layer l to dst (host: synchronous after draining `stream`). */
 int lp_get_weights(lp_ctx* ctx, int l, float* dst, int is_device, void* stream);
+/* Converts n floats (device) to the context's act type (device): round-to-nearest-even for LP_BF16, a
+ * copy for LP_F32.  This is how an input batch or a regression target given as float becomes a tensor
+ * lp_step accepts; the storage rounding of Eq. 1's operands is the library's, not the caller's.
+ * src and dst 16-byte aligned, not overlapping.  Asynchronous on `stream`. */
+int lp_cast(lp_ctx* ctx, const float* src, void* dst, size_t n, void* stream);
 
 /* ---- the per-layer tasks ------------------------------------------------------------------- */
 
@@ -133,6 +146,7 @@ int lp_forward(lp_ctx* ctx, int l, const void* X, void* Z, void* A, void* stream
 /* Error at the output and delta of the last layer (the paper only says the error is computed from
  * the ground truth; this library offers two).  ZL: act type [batch, D_L].  SOFTMAX_CE: target =
  * int labels [batch] in [0, D_L); E = -mean_b log softmax(z_b)[y_b]; dYL = (softmax - onehot)/batch.
+ * A label outside [0, D_L) is not dereferenced: that row gets dYL = softmax/batch and makes E NaN.
  * MSE: target = act type [batch, D_L]; E = mean (z - t)^2; dYL = 2 (z - t) / (batch * D_L).
  * loss_dev: device float, may be NULL.  Needs a bound workspace (row partials). */
 int lp_loss_grad(lp_ctx* ctx, const void* ZL, const void* target, void* dYL, float* loss_dev, void* stream);
@@ -193,7 +207,10 @@ int lp_set_run_ahead(lp_ctx* ctx, int enable);
  * update of step n forms G_l(n - d_l) tile by tile with the kernel lp_grad_weight uses and applies each
  * tile to the weights in its epilogue, so G never travels through memory: same arithmetic and same bits
  * as the product ring, less memory and less traffic (per parameter 10 bytes instead of 4 + 14).
- * l = 0 selects every linear layer.  Applies to lp_step and to lp_grad_weight / lp_update called with
+ * A layer whose G product lp_grad_weight splits over K ranges (fewer than 256 output tiles of 128 x 128
+ * and batch >= 2048) would be summed in another order by the fused update, so it is excluded:
+ * l = 0 selects every linear layer but those (they keep the product ring), l > 0 on such a layer is
+ * LP_ERR_LAYER.  Applies to lp_step and to lp_grad_weight / lp_update called with
  * G = NULL; LP_T_G_LAST of such a layer is NULL.  Call after lp_create and before lp_workspace_bytes /
  * lp_bind_workspace (LP_ERR_STATE afterwards).  LP_BF16 contexts (LP_ERR_DTYPE), linear layers
  * (LP_ERR_LAYER). */
@@ -250,39 +267,6 @@ int lp_tensor(lp_ctx* ctx, int l, int which, void** dev_ptr, size_t* bytes);
  * *t_p (may be NULL): the final target load.  Touches no device. */
 int lp_partition(const double* t_fix, const double* t_flex, int L, int n_proc, double alpha, int* stage_fix,
                  int* stage_delta_rest, double* borrowed_frac, double* stage_time, double* t_p);
-
-/* ---- measurement aid ----------------------------------------------------------------------- */
-
-/* Task kinds of Fig. 1(b) as this library launches them. */
-typedef enum {
-  LP_TASK_F = 0,         /* forward product + activation (Eq. 1, Eq. 2)  */
-  LP_TASK_DX = 1,        /* activation-gradient product (Eq. 4)          */
-  LP_TASK_DW = 2,        /* weight-gradient product (Eq. 5)              */
-  LP_TASK_HADAMARD = 3,  /* the moved f' factor (Eq. 3)                  */
-  LP_TASK_LOSS = 4,      /* error and delta of the output layer          */
-  LP_TASK_UPDATE = 5,    /* delayed SGD update (Eq. 6)                   */
-  LP_TASK_COUNT = 6
-} lp_task;
-
-/* enable != 0: from now on every task launch is bracketed by two timing events recorded on the
- * stream the task is launched on (host memory and HIP events only; no device memory).  Tasks that
- * overlap on different streams each report their own begin-to-end time. */
-int lp_profile(lp_ctx* ctx, int enable);
-/* Waits for the recorded launches of `task`, adds their durations and returns the totals gathered
- * since the last reset: *total_ms (milliseconds) and *launches; either may be NULL.  reset != 0
- * clears the totals of this task afterwards. */
-int lp_profile_read(lp_ctx* ctx, int task, double* total_ms, long* launches, int reset);
-/* The same for one layer l = 1..L (the loss task belongs to no layer and is only in the totals). */
-int lp_profile_read_layer(lp_ctx* ctx, int task, int l, double* total_ms, long* launches, int reset);
-
-/* Calibration of the matrix-core roofline (no context needed): launches `workgroups` workgroups of eight
- * waves that each issue iters * 8 v_mfma_f32_32x32x16_bf16 on operands held in registers, nothing else --
- * 2 * 32 * 32 * 16 flop per instruction, so workgroups * 8 * iters * 8 * 32768 flop per launch.  out_dev
- * (device, out_elems >= workgroups * 512 floats, LP_ERR_SHAPE otherwise) receives one checksum per lane.
- * uniform_values = 0: pseudo-random operands in [-1, 1), as a real product has; != 0: the same few small
- * values in every lane (few bits toggle, so the chip's power limit allows a higher clock: the two differ).
- * Asynchronous on `stream`; returns LP_ERR_NULL / LP_ERR_SHAPE / LP_ERR_HIP without a message. */
-int lp_probe_mfma(float* out_dev, size_t out_elems, int workgroups, int iters, int uniform_values, void* stream);
 
 #ifdef __cplusplus
 }

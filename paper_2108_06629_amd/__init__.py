@@ -33,7 +33,7 @@ STATUS_NAMES = ["LP_OK", "LP_ERR_NULL", "LP_ERR_SHAPE", "LP_ERR_DTYPE", "LP_ERR_
                 "LP_ERR_STATE", "LP_ERR_WORKSPACE", "LP_ERR_HIP"]
 
 EXPORTS = ["lp_create", "lp_destroy", "lp_last_error", "lp_workspace_bytes", "lp_bind_workspace", "lp_set_weights",
-           "lp_get_weights", "lp_forward", "lp_loss_grad", "lp_act_grad", "lp_grad_act", "lp_grad_weight", "lp_update",
+           "lp_get_weights", "lp_cast", "lp_forward", "lp_loss_grad", "lp_act_grad", "lp_grad_act", "lp_grad_weight", "lp_update",
            "lp_advance", "lp_step", "lp_step_index", "lp_sync", "lp_tensor", "lp_profile", "lp_profile_read", "lp_profile_read_layer", "lp_partition", "lp_set_delta_split", "lp_set_run_ahead", "lp_set_graphs", "lp_graph_stats", "lp_set_factor_ring", "lp_probe_mfma"]
 
 
@@ -68,6 +68,7 @@ def load_library():
     L.lp_bind_workspace.argtypes = [vp, vp, C.c_size_t]
     L.lp_set_weights.argtypes = [vp, ip, vp, ip, vp]
     L.lp_get_weights.argtypes = [vp, ip, vp, ip, vp]
+    L.lp_cast.argtypes = [vp, vp, vp, C.c_size_t, vp]
     L.lp_forward.argtypes = [vp, ip, vp, vp, vp, vp]
     L.lp_loss_grad.argtypes = [vp, vp, vp, vp, vp, vp]
     L.lp_act_grad.argtypes = [vp, ip, vp, vp, vp, vp]
@@ -164,6 +165,10 @@ def lp_set_weights(ctx, l: int, W, is_device: bool = False, stream=None):
 
 def lp_get_weights(ctx, l: int, dst, is_device: bool = False, stream=None):
     _check(ctx, lib().lp_get_weights(ctx, l, _ptr(dst), int(is_device), _stream(stream)))
+
+
+def lp_cast(ctx, src, dst, n: int, stream=None):
+    _check(ctx, lib().lp_cast(ctx, _ptr(src), _ptr(dst), n, _stream(stream)))
 
 
 def lp_forward(ctx, l: int, X, Z, A, stream=None):
@@ -335,13 +340,20 @@ class Network:
         return out
 
     def to_device(self, x: np.ndarray, is_label: bool = False):
-        """Host array -> device tensor of the act type (labels: int32).  bf16 is torch's
-        round-to-nearest-even cast of the fp32 input."""
-        t = self.torch.from_numpy(np.ascontiguousarray(x)).to(self.device)
-        t = t.to(self.torch.int32) if is_label else t.to(self.act_dtype).contiguous()
-        # the cast ran on torch's stream; the library's streams are not ordered after it
-        self.torch.cuda.current_stream(self.device).synchronize()
-        return t
+        """Host array -> device tensor of the act type (labels: int32).  PyTorch only moves the bytes (float32 or
+        int32 as given); the conversion to the act type is the library's (lp_cast on streams[0])."""
+        torch = self.torch
+        if is_label:
+            t = torch.from_numpy(np.ascontiguousarray(x, dtype=np.int32)).to(self.device)
+            torch.cuda.current_stream(self.device).synchronize()
+            return t
+        src = torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).to(self.device)
+        # the upload ran on torch's stream; the library's streams are not ordered after it
+        torch.cuda.current_stream(self.device).synchronize()
+        out = torch.empty(src.shape, dtype=self.act_dtype, device=self.device)
+        lp_cast(self.ctx, src, out, src.numel(), self.streams[0])
+        self.streams[0].synchronize()
+        return out
 
     def step_device(self, x_dev, t_dev, delay=None):
         """Enqueues one training step; returns nothing.  `self.loss_dev` holds the loss afterwards."""

@@ -177,6 +177,83 @@ __global__ void __launch_bounds__(256) act_grad_pool_kernel(const T* __restrict_
   for (int k = 0; k < 4; ++k) dY[off[k]] = Elem<T>::st(k == arg ? da * act_df<ACT>(zv[k]) : 0.f);
 }
 
+// The same two kernels for bf16 tensors whose channel count is a multiple of 8: one lane handles 8 consecutive
+// channels of one pooled pixel (16-byte loads and stores, consecutive lanes on consecutive channel groups).
+// Element for element the arithmetic of the scalar kernels above.
+__device__ __forceinline__ void unpack8(const u32x4& v, float (&f)[8]) {
+#pragma unroll
+  for (int d = 0; d < 4; ++d) { f[2 * d] = bf2f((unsigned short)(v[d] & 0xffffu)); f[2 * d + 1] = bf2f((unsigned short)(v[d] >> 16)); }
+}
+__device__ __forceinline__ u32x4 pack8(const float (&f)[8]) {
+  u32x4 v;
+#pragma unroll
+  for (int d = 0; d < 4; ++d) v[d] = (unsigned)f2bf(f[2 * d]) | ((unsigned)f2bf(f[2 * d + 1]) << 16);
+  return v;
+}
+
+template <int ACT>
+__global__ void __launch_bounds__(256) relu_pool_vec8_kernel(const u32x4* __restrict__ z, u32x4* __restrict__ a, int B, int H, int W, int C8) {
+  const size_t total = (size_t)B * (H / 2) * (W / 2) * C8;
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= total) return;
+  const int c = (int)(i % C8);
+  size_t t = i / C8;
+  const int x = (int)(t % (W / 2)); t /= (W / 2);
+  const int y = (int)(t % (H / 2));
+  const int b = (int)(t / (H / 2));
+  u32x4 zv[4];
+#pragma unroll
+  for (int k = 0; k < 4; ++k) zv[k] = z[(((size_t)b * H + (2 * y + (k >> 1))) * W + (2 * x + (k & 1))) * C8 + c];
+  float best[8];
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    float f[8];
+    unpack8(zv[k], f);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const float v = bf2f(f2bf(act_f<ACT>(f[e])));
+      if (k == 0 || v > best[e]) best[e] = v;
+    }
+  }
+  a[i] = pack8(best);
+}
+
+template <int ACT>
+__global__ void __launch_bounds__(256) act_grad_pool_vec8_kernel(const u32x4* __restrict__ dA, const u32x4* __restrict__ Z, u32x4* __restrict__ dY,
+                                                                 int B, int H, int W, int C8) {
+  const size_t total = (size_t)B * (H / 2) * (W / 2) * C8;
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= total) return;
+  const int c = (int)(i % C8);
+  size_t t = i / C8;
+  const int x = (int)(t % (W / 2)); t /= (W / 2);
+  const int y = (int)(t % (H / 2));
+  const int b = (int)(t / (H / 2));
+  size_t off[4];
+  float zf[4][8], da[8];
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    off[k] = (((size_t)b * H + (2 * y + (k >> 1))) * W + (2 * x + (k & 1))) * C8 + c;
+    unpack8(Z[off[k]], zf[k]);
+  }
+  unpack8(dA[i], da);
+  float out[4][8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    float best = 0.f;
+    int arg = 0;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const float v = bf2f(f2bf(act_f<ACT>(zf[k][e])));
+      if (k == 0 || v > best) { best = v; arg = k; }   // strict '>' keeps the first maximum
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) out[k][e] = k == arg ? da[e] * act_df<ACT>(zf[k][e]) : 0.f;
+  }
+#pragma unroll
+  for (int k = 0; k < 4; ++k) dY[off[k]] = pack8(out[k]);
+}
+
 // ---- loss + delta of the output layer ------------------------------------------------------------
 // one wavefront per row
 template <typename T>
@@ -193,31 +270,141 @@ __global__ void __launch_bounds__(256) softmax_ce_kernel(const T* __restrict__ Z
   for (int c = lane; c < cols; c += 64) sum += expf(Elem<T>::ld(z[c]) - m);
   sum = wave_sum(sum);
   const int y = labels[row];
+  const bool y_ok = (unsigned)y < (unsigned)cols;   // a label outside the classes is not dereferenced: NaN loss
   const float inv = 1.f / sum, invB = 1.f / (float)rows;
   T* dy = dY + (size_t)row * cols;
   for (int c = lane; c < cols; c += 64) {
     const float p = expf(Elem<T>::ld(z[c]) - m) * inv;
     dy[c] = Elem<T>::st((p - (c == y ? 1.f : 0.f)) * invB);
   }
-  if (lane == 0) row_loss[row] = (m + logf(sum)) - Elem<T>::ld(z[y]);
+  if (lane == 0) row_loss[row] = y_ok ? (m + logf(sum)) - Elem<T>::ld(z[y]) : __builtin_nanf("");
 }
 
-constexpr int MSE_PER_BLOCK = 256 * 16;
+// The same for rows whose length is a multiple of the 16-byte vector (8 bf16 / 4 floats) and that fit the
+// registers of one wavefront (NV vectors per lane): the row is read once, with 16-byte loads, and written once.
+template <typename T>
+struct Vec16;
+template <>
+struct Vec16<unsigned short> {
+  static constexpr int N = 8;
+  static __device__ __forceinline__ void unpack(const u32x4& v, float* f) {
+#pragma unroll
+    for (int d = 0; d < 4; ++d) { f[2 * d] = bf2f((unsigned short)(v[d] & 0xffffu)); f[2 * d + 1] = bf2f((unsigned short)(v[d] >> 16)); }
+  }
+  static __device__ __forceinline__ u32x4 pack(const float* f) {
+    u32x4 v;
+#pragma unroll
+    for (int d = 0; d < 4; ++d) v[d] = (unsigned)f2bf(f[2 * d]) | ((unsigned)f2bf(f[2 * d + 1]) << 16);
+    return v;
+  }
+};
+template <>
+struct Vec16<float> {
+  static constexpr int N = 4;
+  static __device__ __forceinline__ void unpack(const u32x4& v, float* f) {
+#pragma unroll
+    for (int d = 0; d < 4; ++d) f[d] = __uint_as_float(v[d]);
+  }
+  static __device__ __forceinline__ u32x4 pack(const float* f) {
+    u32x4 v;
+#pragma unroll
+    for (int d = 0; d < 4; ++d) v[d] = __float_as_uint(f[d]);
+    return v;
+  }
+};
 
+template <typename T, int NV>
+__global__ void __launch_bounds__(256) softmax_ce_rowreg_kernel(const T* __restrict__ Z, const int* __restrict__ labels, T* __restrict__ dY,
+                                                                float* __restrict__ row_loss, int rows, int cols) {
+  constexpr int VN = Vec16<T>::N;
+  const int lane = threadIdx.x & 63;
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const T* zrow = Z + (size_t)row * cols;
+  const u32x4* z = reinterpret_cast<const u32x4*>(zrow);
+  u32x4* dy = reinterpret_cast<u32x4*>(dY + (size_t)row * cols);
+  const int nvec = cols / VN;
+  float v[NV][VN];
+  float m = -INFINITY;
+#pragma unroll
+  for (int u = 0; u < NV; ++u) {
+    const int i = lane + 64 * u;
+    if (i < nvec) {
+      Vec16<T>::unpack(__builtin_nontemporal_load(z + i), v[u]);
+#pragma unroll
+      for (int e = 0; e < VN; ++e) m = fmaxf(m, v[u][e]);
+    }
+  }
+  m = wave_max(m);
+  float sum = 0.f;
+#pragma unroll
+  for (int u = 0; u < NV; ++u) {
+    if (lane + 64 * u < nvec) {
+#pragma unroll
+      for (int e = 0; e < VN; ++e) { v[u][e] = expf(v[u][e] - m); sum += v[u][e]; }
+    }
+  }
+  sum = wave_sum(sum);
+  const int y = labels[row];
+  const bool y_ok = (unsigned)y < (unsigned)cols;
+  const float inv = 1.f / sum, invB = 1.f / (float)rows;
+#pragma unroll
+  for (int u = 0; u < NV; ++u) {
+    const int i = lane + 64 * u;
+    if (i < nvec) {
+      float o[VN];
+#pragma unroll
+      for (int e = 0; e < VN; ++e) o[e] = (v[u][e] * inv - (i * VN + e == y ? 1.f : 0.f)) * invB;
+      __builtin_nontemporal_store(Vec16<T>::pack(o), dy + i);
+    }
+  }
+  if (lane == 0) row_loss[row] = y_ok ? (m + logf(sum)) - Elem<T>::ld(zrow[y]) : __builtin_nanf("");
+}
+
+constexpr int MSE_PER_BLOCK = 8192;
+
+// Each block handles MSE_PER_BLOCK consecutive elements with 16-byte vectors per lane (the loads of a lane are all
+// issued before its arithmetic) and writes one partial sum of squared differences.
 template <typename T>
 __global__ void __launch_bounds__(256) mse_kernel(const T* __restrict__ Z, const T* __restrict__ Tg, T* __restrict__ dY,
                                                   float* __restrict__ partial, size_t n, float scale) {
+  constexpr int VN = Vec16<T>::N;
+  constexpr int UNROLL = MSE_PER_BLOCK / (256 * VN);
   __shared__ float sh4[4];
+  const u32x4* z = reinterpret_cast<const u32x4*>(Z);
+  const u32x4* tg = reinterpret_cast<const u32x4*>(Tg);
+  u32x4* dy = reinterpret_cast<u32x4*>(dY);
+  const size_t v0 = (size_t)blockIdx.x * (MSE_PER_BLOCK / VN) + threadIdx.x;
+  const size_t nvec = n / VN;
+  u32x4 zv[UNROLL], tv[UNROLL];
+#pragma unroll
+  for (int u = 0; u < UNROLL; ++u) {
+    const size_t i = v0 + (size_t)u * 256;
+    if (i < nvec) { zv[u] = __builtin_nontemporal_load(z + i); tv[u] = __builtin_nontemporal_load(tg + i); }
+  }
   float acc = 0.f;
-  const size_t b0 = (size_t)blockIdx.x * MSE_PER_BLOCK;
-#pragma unroll 4
-  for (int u = 0; u < MSE_PER_BLOCK / 256; ++u) {
-    const size_t i = b0 + (size_t)u * 256 + threadIdx.x;
-    if (i < n) {
-      const float d = Elem<T>::ld(Z[i]) - Elem<T>::ld(Tg[i]);
-      acc += d * d;
-      dY[i] = Elem<T>::st(d * scale);
+#pragma unroll
+  for (int u = 0; u < UNROLL; ++u) {
+    const size_t i = v0 + (size_t)u * 256;
+    if (i < nvec) {
+      float a[VN], b[VN], o[VN];
+      Vec16<T>::unpack(zv[u], a);
+      Vec16<T>::unpack(tv[u], b);
+#pragma unroll
+      for (int e = 0; e < VN; ++e) {
+        const float d = a[e] - b[e];
+        acc += d * d;
+        o[e] = d * scale;
+      }
+      __builtin_nontemporal_store(Vec16<T>::pack(o), dy + i);
     }
+  }
+  // the last elements of a tensor whose size is not a multiple of the vector: the block that owns them, one per lane
+  const size_t tail = nvec * VN + threadIdx.x;
+  if (tail < n && tail / MSE_PER_BLOCK == blockIdx.x) {
+    const float d = Elem<T>::ld(Z[tail]) - Elem<T>::ld(Tg[tail]);
+    acc += d * d;
+    dY[tail] = Elem<T>::st(d * scale);
   }
   acc = block_sum_256(acc, sh4);
   if (threadIdx.x == 0) partial[blockIdx.x] = acc;
@@ -341,6 +528,14 @@ static hipError_t relu_pool_t(const void* z, void* a, int B, int H, int W, int C
   return hipGetLastError();
 }
 hipError_t launch_relu_pool(bool bf16, const void* z, void* a, int B, int H, int W, int C, int act, hipStream_t s) {
+  if (bf16 && C % 8 == 0 && (uintptr_t)z % 16 == 0 && (uintptr_t)a % 16 == 0) {
+    const size_t total = (size_t)B * (H / 2) * (W / 2) * (C / 8);
+    const unsigned nb = blocks_for(total, 256);
+    if (act == ACT_RELU) hipLaunchKernelGGL(relu_pool_vec8_kernel<ACT_RELU>, dim3(nb), dim3(256), 0, s, (const u32x4*)z, (u32x4*)a, B, H, W, C / 8);
+    else if (act == ACT_GELU) hipLaunchKernelGGL(relu_pool_vec8_kernel<ACT_GELU>, dim3(nb), dim3(256), 0, s, (const u32x4*)z, (u32x4*)a, B, H, W, C / 8);
+    else hipLaunchKernelGGL(relu_pool_vec8_kernel<ACT_IDENTITY>, dim3(nb), dim3(256), 0, s, (const u32x4*)z, (u32x4*)a, B, H, W, C / 8);
+    return hipGetLastError();
+  }
   return bf16 ? relu_pool_t<unsigned short>(z, a, B, H, W, C, act, s) : relu_pool_t<float>(z, a, B, H, W, C, act, s);
 }
 
@@ -354,6 +549,14 @@ static hipError_t act_grad_pool_t(int act, const void* dA, const void* Z, void* 
   return hipGetLastError();
 }
 hipError_t launch_act_grad_pool(bool bf16, int act, const void* dA, const void* Z, void* dY, int B, int H, int W, int C, hipStream_t s) {
+  if (bf16 && C % 8 == 0 && (uintptr_t)dA % 16 == 0 && (uintptr_t)Z % 16 == 0 && (uintptr_t)dY % 16 == 0) {
+    const size_t total = (size_t)B * (H / 2) * (W / 2) * (C / 8);
+    const unsigned nb = blocks_for(total, 256);
+    if (act == ACT_RELU) hipLaunchKernelGGL(act_grad_pool_vec8_kernel<ACT_RELU>, dim3(nb), dim3(256), 0, s, (const u32x4*)dA, (const u32x4*)Z, (u32x4*)dY, B, H, W, C / 8);
+    else if (act == ACT_GELU) hipLaunchKernelGGL(act_grad_pool_vec8_kernel<ACT_GELU>, dim3(nb), dim3(256), 0, s, (const u32x4*)dA, (const u32x4*)Z, (u32x4*)dY, B, H, W, C / 8);
+    else hipLaunchKernelGGL(act_grad_pool_vec8_kernel<ACT_IDENTITY>, dim3(nb), dim3(256), 0, s, (const u32x4*)dA, (const u32x4*)Z, (u32x4*)dY, B, H, W, C / 8);
+    return hipGetLastError();
+  }
   return bf16 ? act_grad_pool_t<unsigned short>(act, dA, Z, dY, B, H, W, C, s) : act_grad_pool_t<float>(act, dA, Z, dY, B, H, W, C, s);
 }
 
@@ -362,11 +565,24 @@ size_t loss_partials_count(int loss_is_mse, int rows, int cols) {
   return ((size_t)rows * cols + MSE_PER_BLOCK - 1) / MSE_PER_BLOCK;
 }
 
-hipError_t launch_softmax_ce(bool bf16, const void* Z, const int* labels, void* dY, float* loss, float* partials, int rows, int cols, hipStream_t s) {
+template <typename T>
+static hipError_t softmax_ce_t(const void* Z, const int* labels, void* dY, float* partials, int rows, int cols, hipStream_t s) {
+  constexpr int VN = 16 / (int)sizeof(T);
   const unsigned nb = (unsigned)((rows + 3) / 4);
-  if (bf16) hipLaunchKernelGGL(softmax_ce_kernel<unsigned short>, dim3(nb), dim3(256), 0, s, (const unsigned short*)Z, labels, (unsigned short*)dY, partials, rows, cols);
-  else hipLaunchKernelGGL(softmax_ce_kernel<float>, dim3(nb), dim3(256), 0, s, (const float*)Z, labels, (float*)dY, partials, rows, cols);
-  hipError_t e = hipGetLastError();
+  const bool vec = cols % VN == 0 && cols / VN <= 64 * 8 && (uintptr_t)Z % 16 == 0 && (uintptr_t)dY % 16 == 0;
+  const int nv = vec ? (cols / VN + 63) / 64 : 0;   // vectors per lane
+#define LP_CE(NV) hipLaunchKernelGGL((softmax_ce_rowreg_kernel<T, NV>), dim3(nb), dim3(256), 0, s, (const T*)Z, labels, (T*)dY, partials, rows, cols)
+  if (nv == 1) LP_CE(1);
+  else if (nv == 2) LP_CE(2);
+  else if (nv >= 3 && nv <= 4) LP_CE(4);
+  else if (nv >= 5 && nv <= 8) LP_CE(8);
+  else hipLaunchKernelGGL(softmax_ce_kernel<T>, dim3(nb), dim3(256), 0, s, (const T*)Z, labels, (T*)dY, partials, rows, cols);
+#undef LP_CE
+  return hipGetLastError();
+}
+
+hipError_t launch_softmax_ce(bool bf16, const void* Z, const int* labels, void* dY, float* loss, float* partials, int rows, int cols, hipStream_t s) {
+  hipError_t e = bf16 ? softmax_ce_t<unsigned short>(Z, labels, dY, partials, rows, cols, s) : softmax_ce_t<float>(Z, labels, dY, partials, rows, cols, s);
   if (e != hipSuccess || !loss) return e;
   hipLaunchKernelGGL(finalize_loss_kernel, dim3(1), dim3(256), 0, s, (const float*)partials, (size_t)rows, 1.f / (float)rows, loss);
   return hipGetLastError();

@@ -2,12 +2,14 @@
 // that realise the delay elements of Eq. 6, and the stream/event graph of one training step.
 // All arithmetic lives in the HIP kernels behind lp_kernels.h; nothing here computes on the host.
 #include "../../include/lp.h"
+#include "../../include/lp_measure.h"
 
 #include <hip/hip_runtime.h>
 
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <memory>
 #include <new>
 #include <string>
 #include <unordered_map>
@@ -103,6 +105,22 @@ int fail_hip(lp_ctx* c, hipError_t e, const char* what) {
     hipError_t e__ = (call);                              \
     if (e__ != hipSuccess) return fail_hip(c, e__, #call); \
   } while (0)
+
+// Runs the body of an entry point; a C++ exception (host memory exhausted in a container of the context) ends
+// the call with LP_ERR_STATE instead of crossing the C boundary.
+template <class Body>
+int guarded(lp_ctx* c, const char* where, Body&& body) noexcept {
+  try {
+    return body();
+  } catch (...) {
+    try {
+      if (c) { c->err = where; c->err += ": out of host memory or internal error"; }
+      else { g_create_error = where; g_create_error += ": out of host memory or internal error"; }
+    } catch (...) {
+    }
+    return LP_ERR_STATE;
+  }
+}
 
 inline bool is_bf16(const lp_ctx* c) { return c->dtype == LP_BF16; }
 inline size_t esize(const lp_ctx* c) { return is_bf16(c) ? 2 : 4; }
@@ -665,85 +683,98 @@ int run_or_replay_step(lp_ctx* c, const void* X0, const void* target, float* los
 
 extern "C" {
 
+// Largest operand of a layer's products in bytes, for the kernels' 32-bit byte offsets.
+constexpr unsigned long long kMaxOperandBytes = 0x7fffffffull;
+
 int lp_create(const lp_layer_desc* layers, int L, int batch, int dtype, int loss, float lr, lp_ctx** out) {
-  if (!layers || !out) return fail(nullptr, LP_ERR_NULL, "lp_create: layers/out is NULL");
-  if (L < 1) return fail(nullptr, LP_ERR_SHAPE, "lp_create: L = %d", L);
-  if (batch < 1) return fail(nullptr, LP_ERR_SHAPE, "lp_create: batch = %d", batch);
-  if (dtype != LP_F32 && dtype != LP_BF16) return fail(nullptr, LP_ERR_DTYPE, "lp_create: unknown dtype %d", dtype);
-  if (loss != LP_LOSS_SOFTMAX_CE && loss != LP_LOSS_MSE) return fail(nullptr, LP_ERR_DTYPE, "lp_create: unknown loss %d", loss);
-  lp_ctx* c = new (std::nothrow) lp_ctx;
-  if (!c) return fail(nullptr, LP_ERR_STATE, "lp_create: out of host memory");
-  c->L = L; c->batch = batch; c->dtype = dtype; c->loss = loss; c->lr = lr;
-  c->layers.resize(L);
-  int prev_out_feat = -1, prevH = 0, prevW = 0, prevC = 0;
-  bool prev_conv = false;
-  for (int i = 0; i < L; ++i) {
-    Layer& ly = c->layers[i];
-    ly.d = layers[i];
-    const lp_layer_desc& d = ly.d;
-    auto bad = [&](int code, const char* msg) {
-      int r = fail(nullptr, code, "lp_create: layer %d: %s", i + 1, msg);
-      delete c;
-      return r;
-    };
-    if (d.kind != LP_LINEAR && d.kind != LP_CONV3X3) return bad(LP_ERR_DTYPE, "unknown kind");
-    if (d.act < LP_ACT_IDENTITY || d.act > LP_ACT_SIGMOID) return bad(LP_ERR_DTYPE, "unknown activation");
-    if (d.kind == LP_CONV3X3 && d.pool == 2 && (d.act == LP_ACT_TANH || d.act == LP_ACT_SIGMOID))
-      return bad(LP_ERR_DTYPE, "a pooled convolution takes identity, ReLU or GELU");
-    if (d.in < 1 || d.out < 1) return bad(LP_ERR_SHAPE, "in/out must be positive");
-    if (d.delay < 0) return bad(LP_ERR_DELAY, "negative delay");
-    if (i == L - 1 && d.act != LP_ACT_IDENTITY) return bad(LP_ERR_DTYPE, "the last layer must have identity activation");
-    if (d.kind == LP_LINEAR) {
-      if (d.pool != 0 || d.H != 0 || d.W != 0) return bad(LP_ERR_SHAPE, "H, W, pool must be 0 for a linear layer");
-      ly.in_feat = d.in; ly.out_feat = d.out;
-      ly.n_params = (size_t)d.in * d.out;
-      ly.in_elems = (size_t)batch * d.in;
-      ly.z_elems = ly.a_elems = (size_t)batch * d.out;
-      if (i > 0 && prev_out_feat != d.in) return bad(LP_ERR_LAYER, "input width differs from the previous layer's output");
-      prev_conv = false;
-    } else {
-      if (dtype != LP_BF16) return bad(LP_ERR_DTYPE, "convolution layers need an LP_BF16 context");
-      if (d.H < 1 || d.W < 1) return bad(LP_ERR_SHAPE, "conv needs H, W >= 1");
-      if (i > 0 && d.out % 8 != 0) return bad(LP_ERR_SHAPE, "a conv layer other than the first needs out % 8 == 0 (dX reads 16-byte chunks)");
-      if (d.pool != 0 && d.pool != 2) return bad(LP_ERR_SHAPE, "pool must be 0 or 2");
-      if (d.pool == 2 && (d.H % 2 || d.W % 2)) return bad(LP_ERR_SHAPE, "pool needs even H and W");
-      if (i == L - 1 && d.pool) return bad(LP_ERR_SHAPE, "the last layer cannot pool");
-      if (i > 0) {
-        if (!prev_conv) return bad(LP_ERR_LAYER, "a conv layer cannot follow a linear layer");
-        if (prevH != d.H || prevW != d.W || prevC != d.in) return bad(LP_ERR_LAYER, "conv input shape differs from the previous layer's output");
+  return guarded(nullptr, "lp_create", [&]() -> int {
+    if (!layers || !out) return fail(nullptr, LP_ERR_NULL, "lp_create: layers/out is NULL");
+    if (L < 1) return fail(nullptr, LP_ERR_SHAPE, "lp_create: L = %d", L);
+    if (batch < 1) return fail(nullptr, LP_ERR_SHAPE, "lp_create: batch = %d", batch);
+    if (dtype != LP_F32 && dtype != LP_BF16) return fail(nullptr, LP_ERR_DTYPE, "lp_create: unknown dtype %d", dtype);
+    if (loss != LP_LOSS_SOFTMAX_CE && loss != LP_LOSS_MSE) return fail(nullptr, LP_ERR_DTYPE, "lp_create: unknown loss %d", loss);
+    std::unique_ptr<lp_ctx> c(new lp_ctx);
+    c->L = L; c->batch = batch; c->dtype = dtype; c->loss = loss; c->lr = lr;
+    c->layers.resize(L);
+    int prev_out_feat = -1, prevH = 0, prevW = 0, prevC = 0;
+    bool prev_conv = false;
+    for (int i = 0; i < L; ++i) {
+      Layer& ly = c->layers[i];
+      ly.d = layers[i];
+      const lp_layer_desc& d = ly.d;
+      auto bad = [&](int code, const char* msg) { return fail(nullptr, code, "lp_create: layer %d: %s", i + 1, msg); };
+      if (d.kind != LP_LINEAR && d.kind != LP_CONV3X3) return bad(LP_ERR_DTYPE, "unknown kind");
+      if (d.act < LP_ACT_IDENTITY || d.act > LP_ACT_SIGMOID) return bad(LP_ERR_DTYPE, "unknown activation");
+      if (d.kind == LP_CONV3X3 && d.pool == 2 && (d.act == LP_ACT_TANH || d.act == LP_ACT_SIGMOID))
+        return bad(LP_ERR_DTYPE, "a pooled convolution takes identity, ReLU or GELU");
+      if (d.in < 1 || d.out < 1) return bad(LP_ERR_SHAPE, "in/out must be positive");
+      if (d.delay < 0) return bad(LP_ERR_DELAY, "negative delay");
+      if (i == L - 1 && d.act != LP_ACT_IDENTITY) return bad(LP_ERR_DTYPE, "the last layer must have identity activation");
+      // Everything a task launcher would refuse is refused here, so that lp_step cannot fail on a shape
+      // after its first launch: the kernels address their operands with 32-bit byte offsets.
+      const unsigned long long es = dtype == LP_BF16 ? 2 : 4;
+      if (d.kind == LP_LINEAR) {
+        if (d.pool != 0 || d.H != 0 || d.W != 0) return bad(LP_ERR_SHAPE, "H, W, pool must be 0 for a linear layer");
+        const unsigned long long b = (unsigned long long)batch, in = (unsigned long long)d.in, o = (unsigned long long)d.out;
+        if (dtype == LP_BF16 && (b * in * es >= kMaxOperandBytes || b * o * es >= kMaxOperandBytes || in * o * es >= kMaxOperandBytes))
+          return bad(LP_ERR_SHAPE, "an operand of this layer's products reaches 2 GiB (the kernels use 32-bit byte offsets)");
+        if (dtype == LP_F32 && (batch > 65535 * 32 || d.in > 65535 * 32))
+          return bad(LP_ERR_SHAPE, "more than 2097120 rows in an F32 product");
+        ly.in_feat = d.in; ly.out_feat = d.out;
+        ly.n_params = (size_t)d.in * d.out;
+        ly.in_elems = (size_t)batch * d.in;
+        ly.z_elems = ly.a_elems = (size_t)batch * d.out;
+        if (i > 0 && prev_out_feat != d.in) return bad(LP_ERR_LAYER, "input width differs from the previous layer's output");
+        prev_conv = false;
+      } else {
+        if (dtype != LP_BF16) return bad(LP_ERR_DTYPE, "convolution layers need an LP_BF16 context");
+        if (d.H < 1 || d.W < 1) return bad(LP_ERR_SHAPE, "conv needs H, W >= 1");
+        if (d.H >= 32768 || d.W >= 32768) return bad(LP_ERR_SHAPE, "conv needs H, W < 32768");
+        if ((unsigned long long)batch * d.H * d.W * (d.in > d.out ? d.in : d.out) * es >= kMaxOperandBytes)
+          return bad(LP_ERR_SHAPE, "an image tensor of this layer reaches 2 GiB (the kernels use 32-bit byte offsets)");
+        if (i > 0 && d.out % 8 != 0) return bad(LP_ERR_SHAPE, "a conv layer other than the first needs out % 8 == 0 (dX reads 16-byte chunks)");
+        if (d.pool != 0 && d.pool != 2) return bad(LP_ERR_SHAPE, "pool must be 0 or 2");
+        if (d.pool == 2 && (d.H % 2 || d.W % 2)) return bad(LP_ERR_SHAPE, "pool needs even H and W");
+        if (i == L - 1 && d.pool) return bad(LP_ERR_SHAPE, "the last layer cannot pool");
+        if (i > 0) {
+          if (!prev_conv) return bad(LP_ERR_LAYER, "a conv layer cannot follow a linear layer");
+          if (prevH != d.H || prevW != d.W || prevC != d.in) return bad(LP_ERR_LAYER, "conv input shape differs from the previous layer's output");
+        }
+        const int p = d.pool == 2 ? 2 : 1;
+        ly.in_feat = d.H * d.W * d.in;
+        ly.out_feat = (d.H / p) * (d.W / p) * d.out;
+        ly.n_params = (size_t)9 * d.in * d.out;
+        ly.in_elems = (size_t)batch * ly.in_feat;
+        ly.z_elems = (size_t)batch * d.H * d.W * d.out;
+        ly.a_elems = (size_t)batch * ly.out_feat;
+        prev_conv = true; prevH = d.H / p; prevW = d.W / p; prevC = d.out;
       }
-      const int p = d.pool == 2 ? 2 : 1;
-      ly.in_feat = d.H * d.W * d.in;
-      ly.out_feat = (d.H / p) * (d.W / p) * d.out;
-      ly.n_params = (size_t)9 * d.in * d.out;
-      ly.in_elems = (size_t)batch * ly.in_feat;
-      ly.z_elems = (size_t)batch * d.H * d.W * d.out;
-      ly.a_elems = (size_t)batch * ly.out_feat;
-      prev_conv = true; prevH = d.H / p; prevW = d.W / p; prevC = d.out;
+      prev_out_feat = ly.out_feat;
+      ly.delay = d.delay;
+      ly.ring_slots = d.delay + 1;
     }
-    prev_out_feat = ly.out_feat;
-    ly.delay = d.delay;
-    ly.ring_slots = d.delay + 1;
-  }
-  layout_workspace(c);
-  *out = c;
-  return LP_OK;
+    layout_workspace(c.get());
+    *out = c.release();
+    return LP_OK;
+  });
 }
 
 int lp_destroy(lp_ctx* c) {
-  if (!c) return LP_ERR_NULL;
-  if (c->events_ready) {
-    for (auto* v : {&c->ev_dy, &c->ev_dx, &c->ev_dw, &c->ev_split, &c->ev_upd})
-      for (hipEvent_t e : *v)
+  return guarded(nullptr, "lp_destroy", [&]() -> int {
+    if (!c) return LP_ERR_NULL;
+    if (c->events_ready) {
+      for (auto* v : {&c->ev_dy, &c->ev_dx, &c->ev_dw, &c->ev_split, &c->ev_upd})
+        for (hipEvent_t e : *v)
+          if (e) (void)hipEventDestroy(e);
+      for (hipEvent_t e : {c->ev_fork, c->ev_join_w, c->ev_join_u, c->ev_loss[0], c->ev_loss[1], c->ev_bdone[0], c->ev_bdone[1]})
         if (e) (void)hipEventDestroy(e);
-    for (hipEvent_t e : {c->ev_fork, c->ev_join_w, c->ev_join_u, c->ev_loss[0], c->ev_loss[1], c->ev_bdone[0], c->ev_bdone[1]})
-      if (e) (void)hipEventDestroy(e);
-  }
-  drop_graphs(c);
-  for (auto& r : c->prof_recs) { (void)hipEventDestroy(r.e0); (void)hipEventDestroy(r.e1); }
-  for (hipEvent_t e : c->prof_free) (void)hipEventDestroy(e);
-  delete c;
-  return LP_OK;
+    }
+    drop_graphs(c);
+    for (auto& r : c->prof_recs) { (void)hipEventDestroy(r.e0); (void)hipEventDestroy(r.e1); }
+    for (hipEvent_t e : c->prof_free) (void)hipEventDestroy(e);
+    delete c;
+    return LP_OK;
+  });
 }
 
 const char* lp_last_error(const lp_ctx* c) { return c ? c->err.c_str() : g_create_error.c_str(); }
@@ -755,166 +786,210 @@ int lp_workspace_bytes(const lp_ctx* c, size_t* bytes) {
 }
 
 int lp_bind_workspace(lp_ctx* c, void* dev_ptr, size_t bytes) {
-  if (!c) return LP_ERR_NULL;
-  if (!dev_ptr) return fail(c, LP_ERR_NULL, "lp_bind_workspace: dev_ptr is NULL");
-  if ((uintptr_t)dev_ptr % kAlign) return fail(c, LP_ERR_WORKSPACE, "lp_bind_workspace: pointer not %zu-byte aligned", kAlign);
-  if (bytes < c->ws_bytes) return fail(c, LP_ERR_WORKSPACE, "lp_bind_workspace: %zu bytes given, %zu needed", bytes, c->ws_bytes);
-  drop_graphs(c);
-  c->ws = (char*)dev_ptr;
-  c->n = 0;
-  for (Layer& ly : c->layers) { ly.weights_set = false; ly.cur = 0; }
-  return LP_OK;
+  return guarded(c, "lp_bind_workspace", [&]() -> int {
+    if (!c) return LP_ERR_NULL;
+    if (!dev_ptr) return fail(c, LP_ERR_NULL, "lp_bind_workspace: dev_ptr is NULL");
+    if ((uintptr_t)dev_ptr % kAlign) return fail(c, LP_ERR_WORKSPACE, "lp_bind_workspace: pointer not %zu-byte aligned", kAlign);
+    if (bytes < c->ws_bytes) return fail(c, LP_ERR_WORKSPACE, "lp_bind_workspace: %zu bytes given, %zu needed", bytes, c->ws_bytes);
+    drop_graphs(c);
+    c->ws = (char*)dev_ptr;
+    c->n = 0;
+    for (Layer& ly : c->layers) { ly.weights_set = false; ly.cur = 0; }
+    return LP_OK;
+  });
 }
 
 int lp_set_weights(lp_ctx* c, int l, const float* W, int is_device, void* stream) {
-  if (!c) return LP_ERR_NULL;
-  if (int r = check_layer(c, l)) return r;
-  if (!W) return fail(c, LP_ERR_NULL, "lp_set_weights: W is NULL");
-  if (int r = need_ws(c)) return r;
-  Layer& ly = c->layers[l - 1];
-  hipStream_t s = (hipStream_t)stream;
-  note_stream(c, s);
-  float* master = (float*)(c->ws + ly.off_master);
-  if (is_device) LP_HIP(c, hipMemcpyAsync(master, W, ly.n_params * 4, hipMemcpyDeviceToDevice, s));
-  else {
-    LP_HIP(c, hipStreamSynchronize(s));
-    LP_HIP(c, hipMemcpy(master, W, ly.n_params * 4, hipMemcpyHostToDevice));
-  }
-  if (is_bf16(c)) LP_HIP(c, lp::launch_cast_bf16(master, c->ws + ly.off_work[ly.cur], ly.n_params, s));
-  ly.weights_set = true;
-  return LP_OK;
+  return guarded(c, "lp_set_weights", [&]() -> int {
+    if (!c) return LP_ERR_NULL;
+    if (int r = check_layer(c, l)) return r;
+    if (!W) return fail(c, LP_ERR_NULL, "lp_set_weights: W is NULL");
+    if (int r = need_ws(c)) return r;
+    Layer& ly = c->layers[l - 1];
+    hipStream_t s = (hipStream_t)stream;
+    note_stream(c, s);
+    float* master = (float*)(c->ws + ly.off_master);
+    if (is_device) LP_HIP(c, hipMemcpyAsync(master, W, ly.n_params * 4, hipMemcpyDeviceToDevice, s));
+    else {
+      LP_HIP(c, hipStreamSynchronize(s));
+      LP_HIP(c, hipMemcpy(master, W, ly.n_params * 4, hipMemcpyHostToDevice));
+    }
+    if (is_bf16(c)) LP_HIP(c, lp::launch_cast_bf16(master, c->ws + ly.off_work[ly.cur], ly.n_params, s));
+    ly.weights_set = true;
+    return LP_OK;
+  });
 }
 
 int lp_get_weights(lp_ctx* c, int l, float* dst, int is_device, void* stream) {
-  if (!c) return LP_ERR_NULL;
-  if (int r = check_layer(c, l)) return r;
-  if (!dst) return fail(c, LP_ERR_NULL, "lp_get_weights: dst is NULL");
-  if (int r = need_weights(c, l)) return r;
-  Layer& ly = c->layers[l - 1];
-  hipStream_t s = (hipStream_t)stream;
-  const float* master = (const float*)(c->ws + ly.off_master);
-  if (is_device) LP_HIP(c, hipMemcpyAsync(dst, master, ly.n_params * 4, hipMemcpyDeviceToDevice, s));
-  else {
-    // run-ahead steps do not join the update stream into any other: wait for all of them
-    if (c->run_ahead) for (hipStream_t t : c->streams_seen) LP_HIP(c, hipStreamSynchronize(t));
-    LP_HIP(c, hipStreamSynchronize(s));
-    LP_HIP(c, hipMemcpy(dst, master, ly.n_params * 4, hipMemcpyDeviceToHost));
-  }
-  return LP_OK;
+  return guarded(c, "lp_get_weights", [&]() -> int {
+    if (!c) return LP_ERR_NULL;
+    if (int r = check_layer(c, l)) return r;
+    if (!dst) return fail(c, LP_ERR_NULL, "lp_get_weights: dst is NULL");
+    if (int r = need_weights(c, l)) return r;
+    Layer& ly = c->layers[l - 1];
+    hipStream_t s = (hipStream_t)stream;
+    const float* master = (const float*)(c->ws + ly.off_master);
+    if (is_device) LP_HIP(c, hipMemcpyAsync(dst, master, ly.n_params * 4, hipMemcpyDeviceToDevice, s));
+    else {
+      // run-ahead steps do not join the update stream into any other: wait for all of them
+      if (c->run_ahead) for (hipStream_t t : c->streams_seen) LP_HIP(c, hipStreamSynchronize(t));
+      LP_HIP(c, hipStreamSynchronize(s));
+      LP_HIP(c, hipMemcpy(dst, master, ly.n_params * 4, hipMemcpyDeviceToHost));
+    }
+    return LP_OK;
+  });
+}
+
+int lp_cast(lp_ctx* c, const float* src, void* dst, size_t n, void* stream) {
+  return guarded(c, "lp_cast", [&]() -> int {
+    if (!c) return LP_ERR_NULL;
+    if (!src || !dst) return fail(c, LP_ERR_NULL, "lp_cast: src/dst is NULL");
+    if ((uintptr_t)src % 16 || (uintptr_t)dst % 16) return fail(c, LP_ERR_SHAPE, "lp_cast: src and dst must be 16-byte aligned");
+    if (n == 0) return LP_OK;
+    note_stream(c, (hipStream_t)stream);
+    if (is_bf16(c)) LP_HIP(c, lp::launch_cast_bf16(src, dst, n, (hipStream_t)stream));
+    else LP_HIP(c, hipMemcpyAsync(dst, src, n * 4, hipMemcpyDeviceToDevice, (hipStream_t)stream));
+    return LP_OK;
+  });
 }
 
 int lp_forward(lp_ctx* c, int l, const void* X, void* Z, void* A, void* stream) {
-  if (!c) return LP_ERR_NULL;
-  if (int r = check_layer(c, l)) return r;
-  if (!X) return fail(c, LP_ERR_NULL, "lp_forward: X is NULL");
-  if (!Z && !A) return fail(c, LP_ERR_NULL, "lp_forward: both outputs are NULL");
-  Layer& ly = c->layers[l - 1];
-  if (ly.d.kind == LP_CONV3X3 && ly.d.pool == 2 && !Z) return fail(c, LP_ERR_NULL, "lp_forward: a pooled layer needs Z");
-  if (int r = need_weights(c, l)) return r;
-  note_stream(c, (hipStream_t)stream);
-  LP_HIP(c, do_forward(c, ly, X, Z, A, (hipStream_t)stream));
-  return LP_OK;
+  return guarded(c, "lp_forward", [&]() -> int {
+    if (!c) return LP_ERR_NULL;
+    if (int r = check_layer(c, l)) return r;
+    if (!X) return fail(c, LP_ERR_NULL, "lp_forward: X is NULL");
+    if (!Z && !A) return fail(c, LP_ERR_NULL, "lp_forward: both outputs are NULL");
+    Layer& ly = c->layers[l - 1];
+    if (ly.d.kind == LP_CONV3X3 && ly.d.pool == 2 && !Z) return fail(c, LP_ERR_NULL, "lp_forward: a pooled layer needs Z");
+    if (int r = need_weights(c, l)) return r;
+    note_stream(c, (hipStream_t)stream);
+    LP_HIP(c, do_forward(c, ly, X, Z, A, (hipStream_t)stream));
+    return LP_OK;
+  });
 }
 
 int lp_loss_grad(lp_ctx* c, const void* ZL, const void* target, void* dYL, float* loss_dev, void* stream) {
-  if (!c) return LP_ERR_NULL;
-  if (!ZL || !target || !dYL) return fail(c, LP_ERR_NULL, "lp_loss_grad: ZL/target/dYL is NULL");
-  if (int r = need_ws(c)) return r;
-  note_stream(c, (hipStream_t)stream);
-  LP_HIP(c, do_loss(c, ZL, target, dYL, loss_dev, (hipStream_t)stream));
-  return LP_OK;
+  return guarded(c, "lp_loss_grad", [&]() -> int {
+    if (!c) return LP_ERR_NULL;
+    if (!ZL || !target || !dYL) return fail(c, LP_ERR_NULL, "lp_loss_grad: ZL/target/dYL is NULL");
+    if (int r = need_ws(c)) return r;
+    note_stream(c, (hipStream_t)stream);
+    LP_HIP(c, do_loss(c, ZL, target, dYL, loss_dev, (hipStream_t)stream));
+    return LP_OK;
+  });
 }
 
 int lp_act_grad(lp_ctx* c, int l, const void* dA, const void* S, void* dY, void* stream) {
-  if (!c) return LP_ERR_NULL;
-  if (int r = check_layer(c, l)) return r;
-  Layer& ly = c->layers[l - 1];
-  if (!dA || !dY || (!S && ly.d.act != LP_ACT_IDENTITY)) return fail(c, LP_ERR_NULL, "lp_act_grad: dA/S/dY is NULL");
-  if (ly.d.kind == LP_CONV3X3 && ly.d.pool == 2) {
-    if (!S) return fail(c, LP_ERR_NULL, "lp_act_grad: a pooled layer needs S = Z");
-    if (dA == dY) return fail(c, LP_ERR_SHAPE, "lp_act_grad: dY may not alias dA on a pooled layer");
-  }
-  note_stream(c, (hipStream_t)stream);
-  LP_HIP(c, do_act_grad(c, ly, dA, S, dY, (hipStream_t)stream));
-  return LP_OK;
+  return guarded(c, "lp_act_grad", [&]() -> int {
+    if (!c) return LP_ERR_NULL;
+    if (int r = check_layer(c, l)) return r;
+    Layer& ly = c->layers[l - 1];
+    if (!dA || !dY || (!S && ly.d.act != LP_ACT_IDENTITY)) return fail(c, LP_ERR_NULL, "lp_act_grad: dA/S/dY is NULL");
+    if (ly.d.kind == LP_CONV3X3 && ly.d.pool == 2) {
+      if (!S) return fail(c, LP_ERR_NULL, "lp_act_grad: a pooled layer needs S = Z");
+      if (dA == dY) return fail(c, LP_ERR_SHAPE, "lp_act_grad: dY may not alias dA on a pooled layer");
+    }
+    note_stream(c, (hipStream_t)stream);
+    LP_HIP(c, do_act_grad(c, ly, dA, S, dY, (hipStream_t)stream));
+    return LP_OK;
+  });
 }
 
 int lp_grad_act(lp_ctx* c, int l, const void* dY, void* dX, int col0, int col1, void* stream) {
-  if (!c) return LP_ERR_NULL;
-  if (int r = check_layer(c, l)) return r;
-  if (!dY || !dX) return fail(c, LP_ERR_NULL, "lp_grad_act: dY/dX is NULL");
-  Layer& ly = c->layers[l - 1];
-  if (col0 < 0 || col1 > ly.d.in || col0 >= col1) return fail(c, LP_ERR_SHAPE, "lp_grad_act: column range [%d,%d) outside [0,%d)", col0, col1, ly.d.in);
-  if (int r = need_weights(c, l)) return r;
-  note_stream(c, (hipStream_t)stream);
-  LP_HIP(c, do_grad_act(c, ly, dY, dX, col0, col1, (hipStream_t)stream));
-  return LP_OK;
+  return guarded(c, "lp_grad_act", [&]() -> int {
+    if (!c) return LP_ERR_NULL;
+    if (int r = check_layer(c, l)) return r;
+    if (!dY || !dX) return fail(c, LP_ERR_NULL, "lp_grad_act: dY/dX is NULL");
+    Layer& ly = c->layers[l - 1];
+    if (col0 < 0 || col1 > ly.d.in || col0 >= col1) return fail(c, LP_ERR_SHAPE, "lp_grad_act: column range [%d,%d) outside [0,%d)", col0, col1, ly.d.in);
+    if (int r = need_weights(c, l)) return r;
+    note_stream(c, (hipStream_t)stream);
+    LP_HIP(c, do_grad_act(c, ly, dY, dX, col0, col1, (hipStream_t)stream));
+    return LP_OK;
+  });
 }
 
 int lp_grad_weight(lp_ctx* c, int l, const void* X, const void* dY, float* G, void* stream) {
-  if (!c) return LP_ERR_NULL;
-  if (int r = check_layer(c, l)) return r;
-  if (!X || !dY) return fail(c, LP_ERR_NULL, "lp_grad_weight: X/dY is NULL");
-  if (int r = need_ws(c)) return r;
-  Layer& ly = c->layers[l - 1];
-  note_stream(c, (hipStream_t)stream);
-  if (!G) {
-    LP_HIP(c, enqueue_G(c, ly, X, dY, c->n + 1, (hipStream_t)stream));
+  return guarded(c, "lp_grad_weight", [&]() -> int {
+    if (!c) return LP_ERR_NULL;
+    if (int r = check_layer(c, l)) return r;
+    if (!X || !dY) return fail(c, LP_ERR_NULL, "lp_grad_weight: X/dY is NULL");
+    if (int r = need_ws(c)) return r;
+    Layer& ly = c->layers[l - 1];
+    note_stream(c, (hipStream_t)stream);
+    if (!G) {
+      LP_HIP(c, enqueue_G(c, ly, X, dY, c->n + 1, (hipStream_t)stream));
+      return LP_OK;
+    }
+    LP_HIP(c, do_grad_weight(c, ly, X, dY, G, (hipStream_t)stream));
     return LP_OK;
-  }
-  LP_HIP(c, do_grad_weight(c, ly, X, dY, G, (hipStream_t)stream));
-  return LP_OK;
+  });
 }
 
 int lp_update(lp_ctx* c, int l, const float* G, void* stream) {
-  if (!c) return LP_ERR_NULL;
-  if (int r = check_layer(c, l)) return r;
-  if (int r = need_weights(c, l)) return r;
-  Layer& ly = c->layers[l - 1];
-  if (!G) {
-    const long src = c->n + 1 - ly.delay;
-    if (src < 1) return LP_OK;  // the delay elements are still empty
+  return guarded(c, "lp_update", [&]() -> int {
+    if (!c) return LP_ERR_NULL;
+    if (int r = check_layer(c, l)) return r;
+    if (int r = need_weights(c, l)) return r;
+    Layer& ly = c->layers[l - 1];
+    if (!G) {
+      const long src = c->n + 1 - ly.delay;
+      if (src < 1) return LP_OK;  // the delay elements are still empty
+      note_stream(c, (hipStream_t)stream);
+      LP_HIP(c, enqueue_update(c, ly, src, (hipStream_t)stream));
+      if (is_bf16(c)) ly.cur ^= 1;
+      return LP_OK;
+    }
     note_stream(c, (hipStream_t)stream);
-    LP_HIP(c, enqueue_update(c, ly, src, (hipStream_t)stream));
+    LP_HIP(c, do_update(c, ly, G, (hipStream_t)stream));
     if (is_bf16(c)) ly.cur ^= 1;
     return LP_OK;
-  }
-  note_stream(c, (hipStream_t)stream);
-  LP_HIP(c, do_update(c, ly, G, (hipStream_t)stream));
-  if (is_bf16(c)) ly.cur ^= 1;
-  return LP_OK;
+  });
 }
 
 int lp_set_delta_split(lp_ctx* c, int l, int cols) {
-  if (!c) return LP_ERR_NULL;
-  if (int r = check_layer(c, l)) return r;
-  Layer& ly = c->layers[l - 1];
-  if (l == 1 && cols != 0) return fail(c, LP_ERR_LAYER, "lp_set_delta_split: layer 1 has no delta task");
-  if (cols < 0 || cols >= ly.d.in) return fail(c, LP_ERR_SHAPE, "lp_set_delta_split: %d columns outside [0, %d)", cols, ly.d.in);
-  ly.split_cols = cols;
-  return LP_OK;
+  return guarded(c, "lp_set_delta_split", [&]() -> int {
+    if (!c) return LP_ERR_NULL;
+    if (int r = check_layer(c, l)) return r;
+    Layer& ly = c->layers[l - 1];
+    if (l == 1 && cols != 0) return fail(c, LP_ERR_LAYER, "lp_set_delta_split: layer 1 has no delta task");
+    if (cols < 0 || cols >= ly.d.in) return fail(c, LP_ERR_SHAPE, "lp_set_delta_split: %d columns outside [0, %d)", cols, ly.d.in);
+    ly.split_cols = cols;
+    return LP_OK;
+  });
 }
 
 int lp_set_factor_ring(lp_ctx* c, int l, int enable) {
-  if (!c) return LP_ERR_NULL;
-  if (c->ws) return fail(c, LP_ERR_STATE, "lp_set_factor_ring: call it before lp_bind_workspace (it changes the workspace size)");
-  if (!is_bf16(c)) return fail(c, LP_ERR_DTYPE, "lp_set_factor_ring: needs an LP_BF16 context");
-  if (l != 0)
-    if (int r = check_layer(c, l)) return r;
-  if (l != 0 && c->layers[l - 1].d.kind != LP_LINEAR) return fail(c, LP_ERR_LAYER, "lp_set_factor_ring: layer %d is not a linear layer", l);
-  for (int i = 0; i < c->L; ++i)
-    if ((l == 0 || i == l - 1) && c->layers[i].d.kind == LP_LINEAR) c->layers[i].factor_ring = enable != 0;
-  layout_workspace(c);
-  return LP_OK;
+  return guarded(c, "lp_set_factor_ring", [&]() -> int {
+    if (!c) return LP_ERR_NULL;
+    if (c->ws) return fail(c, LP_ERR_STATE, "lp_set_factor_ring: call it before lp_bind_workspace (it changes the workspace size)");
+    if (!is_bf16(c)) return fail(c, LP_ERR_DTYPE, "lp_set_factor_ring: needs an LP_BF16 context");
+    if (l != 0)
+      if (int r = check_layer(c, l)) return r;
+    if (l != 0 && c->layers[l - 1].d.kind != LP_LINEAR) return fail(c, LP_ERR_LAYER, "lp_set_factor_ring: layer %d is not a linear layer", l);
+    // A G product that lp_grad_weight cuts into K ranges (few output tiles, long batch) is summed in another
+    // order than the fused update, which never cuts K: such a layer keeps its product ring.
+    auto k_is_cut = [&](const Layer& ly) { return lp::gemm_bf16_splitk_splits(ly.d.in, ly.d.out, c->batch) > 1; };
+    if (l != 0 && enable && k_is_cut(c->layers[l - 1]))
+      return fail(c, LP_ERR_LAYER, "lp_set_factor_ring: the G product of layer %d is split over K at this batch size; it keeps the product ring", l);
+    for (int i = 0; i < c->L; ++i) {
+      Layer& ly = c->layers[i];
+      if ((l == 0 || i == l - 1) && ly.d.kind == LP_LINEAR) ly.factor_ring = enable != 0 && !k_is_cut(ly);
+    }
+    layout_workspace(c);
+    return LP_OK;
+  });
 }
 
 int lp_set_graphs(lp_ctx* c, int enable) {
-  if (!c) return LP_ERR_NULL;
-  if (c->ws) return fail(c, LP_ERR_STATE, "lp_set_graphs: call it before lp_bind_workspace (it changes the workspace size)");
-  if (enable && c->run_ahead) return fail(c, LP_ERR_STATE, "lp_set_graphs: not together with forward run-ahead");
-  c->graphs = enable != 0;
-  layout_workspace(c);
-  return LP_OK;
+  return guarded(c, "lp_set_graphs", [&]() -> int {
+    if (!c) return LP_ERR_NULL;
+    if (c->ws) return fail(c, LP_ERR_STATE, "lp_set_graphs: call it before lp_bind_workspace (it changes the workspace size)");
+    if (enable && c->run_ahead) return fail(c, LP_ERR_STATE, "lp_set_graphs: not together with forward run-ahead");
+    c->graphs = enable != 0;
+    layout_workspace(c);
+    return LP_OK;
+  });
 }
 
 int lp_graph_stats(const lp_ctx* c, long* captured, long* replayed, long* eager) {
@@ -926,13 +1001,15 @@ int lp_graph_stats(const lp_ctx* c, long* captured, long* replayed, long* eager)
 }
 
 int lp_set_run_ahead(lp_ctx* c, int enable) {
-  if (!c) return LP_ERR_NULL;
-  if (c->ws) return fail(c, LP_ERR_STATE, "lp_set_run_ahead: call it before lp_bind_workspace (it changes the workspace size)");
-  if (enable && !is_bf16(c)) return fail(c, LP_ERR_DTYPE, "lp_set_run_ahead: needs an LP_BF16 context (F32 updates the weights in place)");
-  if (enable && c->graphs) return fail(c, LP_ERR_STATE, "lp_set_run_ahead: not together with graph replay");
-  c->run_ahead = enable != 0;
-  layout_workspace(c);
-  return LP_OK;
+  return guarded(c, "lp_set_run_ahead", [&]() -> int {
+    if (!c) return LP_ERR_NULL;
+    if (c->ws) return fail(c, LP_ERR_STATE, "lp_set_run_ahead: call it before lp_bind_workspace (it changes the workspace size)");
+    if (enable && !is_bf16(c)) return fail(c, LP_ERR_DTYPE, "lp_set_run_ahead: needs an LP_BF16 context (F32 updates the weights in place)");
+    if (enable && c->graphs) return fail(c, LP_ERR_STATE, "lp_set_run_ahead: not together with graph replay");
+    c->run_ahead = enable != 0;
+    layout_workspace(c);
+    return LP_OK;
+  });
 }
 
 int lp_advance(lp_ctx* c) {
@@ -942,41 +1019,43 @@ int lp_advance(lp_ctx* c) {
 }
 
 int lp_step(lp_ctx* c, const void* X0, const void* target, const int* delay, float* loss_dev, void* const* streams, int n_streams) {
-  if (!c) return LP_ERR_NULL;
-  if (!X0 || !target) return fail(c, LP_ERR_NULL, "lp_step: X0/target is NULL");
-  if (!streams || n_streams < 1) return fail(c, LP_ERR_NULL, "lp_step: needs at least one stream");
-  if (int r = need_ws(c)) return r;
-  for (int l = 1; l <= c->L; ++l)
-    if (int r = need_weights(c, l)) return r;
-  if (delay) {
-    for (int l = 0; l < c->L; ++l)
-      if (delay[l] < 0 || delay[l] > c->layers[l].d.delay)
-        return fail(c, LP_ERR_DELAY, "lp_step: delay[%d] = %d outside [0, %d]", l, delay[l], c->layers[l].d.delay);
-    for (int l = 0; l < c->L; ++l) c->layers[l].delay = delay[l];
-  }
-  if (c->run_ahead) {
-    if (n_streams < 4) return fail(c, LP_ERR_STATE, "lp_step: forward run-ahead needs 4 stream handles, %d given", n_streams);
-    if (streams[3] == streams[0]) return fail(c, LP_ERR_STATE, "lp_step: forward run-ahead needs a forward stream (streams[3]) other than streams[0]");
-    return step_run_ahead(c, X0, target, loss_dev, streams);
-  }
-  const bool multi = n_streams > 1;
-  hipStream_t sC = (hipStream_t)streams[0];
-  hipStream_t sW = multi ? (hipStream_t)streams[1] : sC;
-  hipStream_t sU = multi ? (hipStream_t)streams[2 % n_streams] : sC;
-  note_stream(c, sC); note_stream(c, sW); note_stream(c, sU);
-  if (multi)
-    if (int r = ensure_events(c)) return r;
+  return guarded(c, "lp_step", [&]() -> int {
+    if (!c) return LP_ERR_NULL;
+    if (!X0 || !target) return fail(c, LP_ERR_NULL, "lp_step: X0/target is NULL");
+    if (!streams || n_streams < 1) return fail(c, LP_ERR_NULL, "lp_step: needs at least one stream");
+    if (int r = need_ws(c)) return r;
+    for (int l = 1; l <= c->L; ++l)
+      if (int r = need_weights(c, l)) return r;
+    if (delay) {
+      for (int l = 0; l < c->L; ++l)
+        if (delay[l] < 0 || delay[l] > c->layers[l].d.delay)
+          return fail(c, LP_ERR_DELAY, "lp_step: delay[%d] = %d outside [0, %d]", l, delay[l], c->layers[l].d.delay);
+      for (int l = 0; l < c->L; ++l) c->layers[l].delay = delay[l];
+    }
+    if (c->run_ahead) {
+      if (n_streams < 4) return fail(c, LP_ERR_STATE, "lp_step: forward run-ahead needs 4 stream handles, %d given", n_streams);
+      if (streams[3] == streams[0]) return fail(c, LP_ERR_STATE, "lp_step: forward run-ahead needs a forward stream (streams[3]) other than streams[0]");
+      return step_run_ahead(c, X0, target, loss_dev, streams);
+    }
+    const bool multi = n_streams > 1;
+    hipStream_t sC = (hipStream_t)streams[0];
+    hipStream_t sW = multi ? (hipStream_t)streams[1] : sC;
+    hipStream_t sU = multi ? (hipStream_t)streams[2 % n_streams] : sC;
+    note_stream(c, sC); note_stream(c, sW); note_stream(c, sU);
+    if (multi)
+      if (int r = ensure_events(c)) return r;
 
-  const int L = c->L;
-  const long n = c->n + 1;
-  const bool bf = is_bf16(c);
-  std::vector<char> updated;
-  if (int r = run_or_replay_step(c, X0, target, loss_dev, sC, sW, sU, multi, updated)) return r;
-  if (bf)
-    for (int i = 0; i < L; ++i)
-      if (updated[i]) c->layers[i].cur ^= 1;
-  c->n = n;
-  return LP_OK;
+    const int L = c->L;
+    const long n = c->n + 1;
+    const bool bf = is_bf16(c);
+    std::vector<char> updated;
+    if (int r = run_or_replay_step(c, X0, target, loss_dev, sC, sW, sU, multi, updated)) return r;
+    if (bf)
+      for (int i = 0; i < L; ++i)
+        if (updated[i]) c->layers[i].cur ^= 1;
+    c->n = n;
+    return LP_OK;
+  });
 }
 
 int lp_step_index(const lp_ctx* c, long* n) {
@@ -986,30 +1065,34 @@ int lp_step_index(const lp_ctx* c, long* n) {
 }
 
 int lp_sync(lp_ctx* c) {
-  if (!c) return LP_ERR_NULL;
-  for (hipStream_t s : c->streams_seen) LP_HIP(c, hipStreamSynchronize(s));
-  return LP_OK;
+  return guarded(c, "lp_sync", [&]() -> int {
+    if (!c) return LP_ERR_NULL;
+    for (hipStream_t s : c->streams_seen) LP_HIP(c, hipStreamSynchronize(s));
+    return LP_OK;
+  });
 }
 
 int lp_tensor(lp_ctx* c, int l, int which, void** dev_ptr, size_t* bytes) {
-  if (!c) return LP_ERR_NULL;
-  if (!dev_ptr || !bytes) return fail(c, LP_ERR_NULL, "lp_tensor: dev_ptr/bytes is NULL");
-  if (int r = check_layer(c, l)) return r;
-  if (int r = need_ws(c)) return r;
-  Layer& ly = c->layers[l - 1];
-  const size_t es = esize(c);
-  *dev_ptr = nullptr; *bytes = 0;
-  switch (which) {
-    case LP_T_MASTER_W: *dev_ptr = c->ws + ly.off_master; *bytes = ly.n_params * 4; break;
-    case LP_T_WORK_W: *dev_ptr = work_w(c, ly); *bytes = ly.n_params * es; break;
-    case LP_T_A: if (ly.has_A) { *dev_ptr = c->ws + ly.off_A[c->n & 1]; *bytes = ly.a_elems * es; } break;
-    case LP_T_Z: if (ly.has_Z) { *dev_ptr = c->ws + ly.off_Z[c->n & 1]; *bytes = ly.z_elems * es; } break;
-    case LP_T_DA: if (ly.has_dA) { *dev_ptr = c->ws + ly.off_dA; *bytes = ly.a_elems * es; } break;
-    case LP_T_DY: *dev_ptr = c->ws + ly.off_dY; *bytes = ly.z_elems * es; break;
-    case LP_T_G_LAST: if (c->n >= 1 && !ly.factor_ring) { *dev_ptr = ring_slot(c, ly, c->n); *bytes = ly.n_params * 4; } break;
-    default: return fail(c, LP_ERR_DTYPE, "lp_tensor: unknown tensor id %d", which);
-  }
-  return LP_OK;
+  return guarded(c, "lp_tensor", [&]() -> int {
+    if (!c) return LP_ERR_NULL;
+    if (!dev_ptr || !bytes) return fail(c, LP_ERR_NULL, "lp_tensor: dev_ptr/bytes is NULL");
+    if (int r = check_layer(c, l)) return r;
+    if (int r = need_ws(c)) return r;
+    Layer& ly = c->layers[l - 1];
+    const size_t es = esize(c);
+    *dev_ptr = nullptr; *bytes = 0;
+    switch (which) {
+      case LP_T_MASTER_W: *dev_ptr = c->ws + ly.off_master; *bytes = ly.n_params * 4; break;
+      case LP_T_WORK_W: *dev_ptr = work_w(c, ly); *bytes = ly.n_params * es; break;
+      case LP_T_A: if (ly.has_A) { *dev_ptr = c->ws + ly.off_A[c->n & 1]; *bytes = ly.a_elems * es; } break;
+      case LP_T_Z: if (ly.has_Z) { *dev_ptr = c->ws + ly.off_Z[c->n & 1]; *bytes = ly.z_elems * es; } break;
+      case LP_T_DA: if (ly.has_dA) { *dev_ptr = c->ws + ly.off_dA; *bytes = ly.a_elems * es; } break;
+      case LP_T_DY: *dev_ptr = c->ws + ly.off_dY; *bytes = ly.z_elems * es; break;
+      case LP_T_G_LAST: if (c->n >= 1 && !ly.factor_ring) { *dev_ptr = ring_slot(c, ly, c->n); *bytes = ly.n_params * 4; } break;
+      default: return fail(c, LP_ERR_DTYPE, "lp_tensor: unknown tensor id %d", which);
+    }
+    return LP_OK;
+  });
 }
 
 int lp_probe_mfma(float* out_dev, size_t out_elems, int workgroups, int iters, int uniform_values, void* stream) {
@@ -1046,32 +1129,36 @@ int profile_collect(lp_ctx* c) {
 }  // namespace
 
 int lp_profile_read(lp_ctx* c, int task, double* total_ms, long* launches, int reset) {
-  if (!c) return LP_ERR_NULL;
-  if (task < 0 || task >= LP_TASK_COUNT) return fail(c, LP_ERR_DTYPE, "lp_profile_read: unknown task %d", task);
-  if (int r = profile_collect(c)) return r;
-  double ms = 0.0;
-  long n = 0;
-  for (int l = 0; l <= c->L; ++l) {
-    const size_t k = (size_t)task * (c->L + 1) + l;
-    ms += c->prof_ms[k];
-    n += c->prof_n[k];
-    if (reset) { c->prof_ms[k] = 0; c->prof_n[k] = 0; }
-  }
-  if (total_ms) *total_ms = ms;
-  if (launches) *launches = n;
-  return LP_OK;
+  return guarded(c, "lp_profile_read", [&]() -> int {
+    if (!c) return LP_ERR_NULL;
+    if (task < 0 || task >= LP_TASK_COUNT) return fail(c, LP_ERR_DTYPE, "lp_profile_read: unknown task %d", task);
+    if (int r = profile_collect(c)) return r;
+    double ms = 0.0;
+    long n = 0;
+    for (int l = 0; l <= c->L; ++l) {
+      const size_t k = (size_t)task * (c->L + 1) + l;
+      ms += c->prof_ms[k];
+      n += c->prof_n[k];
+      if (reset) { c->prof_ms[k] = 0; c->prof_n[k] = 0; }
+    }
+    if (total_ms) *total_ms = ms;
+    if (launches) *launches = n;
+    return LP_OK;
+  });
 }
 
 int lp_profile_read_layer(lp_ctx* c, int task, int l, double* total_ms, long* launches, int reset) {
-  if (!c) return LP_ERR_NULL;
-  if (task < 0 || task >= LP_TASK_COUNT) return fail(c, LP_ERR_DTYPE, "lp_profile_read_layer: unknown task %d", task);
-  if (int r = check_layer(c, l)) return r;
-  if (int r = profile_collect(c)) return r;
-  const size_t k = (size_t)task * (c->L + 1) + l;
-  if (total_ms) *total_ms = c->prof_ms[k];
-  if (launches) *launches = c->prof_n[k];
-  if (reset) { c->prof_ms[k] = 0; c->prof_n[k] = 0; }
-  return LP_OK;
+  return guarded(c, "lp_profile_read_layer", [&]() -> int {
+    if (!c) return LP_ERR_NULL;
+    if (task < 0 || task >= LP_TASK_COUNT) return fail(c, LP_ERR_DTYPE, "lp_profile_read_layer: unknown task %d", task);
+    if (int r = check_layer(c, l)) return r;
+    if (int r = profile_collect(c)) return r;
+    const size_t k = (size_t)task * (c->L + 1) + l;
+    if (total_ms) *total_ms = c->prof_ms[k];
+    if (launches) *launches = c->prof_n[k];
+    if (reset) { c->prof_ms[k] = 0; c->prof_n[k] = 0; }
+    return LP_OK;
+  });
 }
 
 }  // extern "C"

@@ -14,9 +14,14 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def declared_functions():
-    text = open(os.path.join(ROOT, "include", "lp.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(lp_[a-z_]+)\s*\(", text)))
+    names = set()
+    for header in sorted(os.listdir(os.path.join(ROOT, "include"))):
+        if not header.endswith(".h"):
+            continue
+        text = open(os.path.join(ROOT, "include", header)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b(lp_[a-z_]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_library_exports_every_declared_symbol():
@@ -64,6 +69,32 @@ def test_create_rejects_bad_arguments():
     assert create_status(bad, cnn.L, 2, lp.LP_BF16, 0) in (2, 4)
     bad = descs(cnn); bad[2].in_ = 100
     assert create_status(bad, cnn.L, 2, lp.LP_BF16, 0) == 4
+
+
+def test_create_rejects_what_a_task_launcher_would_refuse():
+    """Operand limits of the kernels (32-bit byte offsets) are checked when the context is made, so that a step
+    cannot fail on a shape after its first launch."""
+    big = (WL.Layer(WL.LINEAR, 32768, 32768, WL.IDENTITY),)                      # 2 GiB of bf16 weights
+    assert create_status(lp.make_descs(big, (0,)), 1, 8, lp.LP_BF16, lp.LP_LOSS_MSE) == 2
+    assert b"2 GiB" in lp.lib().lp_last_error(None)
+    ok = (WL.Layer(WL.LINEAR, 32768, 32760, WL.IDENTITY),)
+    assert create_status(lp.make_descs(ok, (0,)), 1, 8, lp.LP_BF16, lp.LP_LOSS_MSE) == 0
+    wide = (WL.Layer(WL.LINEAR, 16, 16, WL.IDENTITY),)
+    assert create_status(lp.make_descs(wide, (0,)), 1, 1 << 27, lp.LP_BF16, lp.LP_LOSS_MSE) == 2      # batch x width reaches 2 GiB
+    assert create_status(lp.make_descs(wide, (0,)), 1, 65535 * 32 + 1, lp.LP_F32, lp.LP_LOSS_MSE) == 2
+    img = (WL.Layer(WL.CONV3X3, 8, 64, WL.RELU, H=512, W=512), WL.Layer(WL.LINEAR, 512 * 512 * 64, 8, WL.IDENTITY))
+    assert create_status(lp.make_descs(img, (0, 0)), 2, 64, lp.LP_BF16, lp.LP_LOSS_SOFTMAX_CE) == 2   # 64 x 512 x 512 x 64 bf16 = 2 GiB
+
+
+def test_cast_checks_its_arguments_before_launching():
+    wl = WL.mlp_small()
+    ctx = lp.lp_create(descs(wl), wl.L, wl.batch, lp.LP_BF16, lp.LP_LOSS_SOFTMAX_CE, 0.01)
+    L = lp.lib()
+    assert L.lp_cast(None, 0x10000, 0x20000, 8, None) == 1
+    assert L.lp_cast(ctx, None, 0x20000, 8, None) == 1 and L.lp_cast(ctx, 0x10000, None, 8, None) == 1
+    assert L.lp_cast(ctx, 0x10004, 0x20000, 8, None) == 2 and L.lp_cast(ctx, 0x10000, 0x20008, 8, None) == 2
+    assert L.lp_cast(ctx, 0x10000, 0x20000, 0, None) == 0                     # nothing to do, nothing launched
+    lp.lp_destroy(ctx)
 
 
 def test_workspace_size_accounts_for_rings_and_weight_versions():
@@ -181,6 +212,20 @@ def test_factor_ring_shrinks_the_delay_elements():
     cnn = WL.vgg_small(batch=2, hw=8, chans=(8, 8))
     ctx = lp.lp_create(descs(cnn), cnn.L, 2, lp.LP_BF16, lp.LP_LOSS_SOFTMAX_CE, 0.01)
     assert L.lp_set_factor_ring(ctx, 1, 1) == 4 and L.lp_set_factor_ring(ctx, cnn.L, 1) == 0      # conv: LP_ERR_LAYER; the FC layer: fine
+    lp.lp_destroy(ctx)
+    # A G product that lp_grad_weight splits over K keeps its product ring: the fused update never splits K, so its
+    # bits would differ.  Batch 2048: 512 x 512, 512 x 4096 and 4096 x 16 outputs have fewer than 256 tiles of
+    # 128 x 128 and are split; 4096 x 4096 (1024 tiles) is not.
+    mixed = WL.mlp_4096().with_(layers=WL._mlp([512, 512, 4096, 4096, 16], WL.RELU), batch=2048, delays=(6, 4, 2, 0))
+    ctx = lp.lp_create(descs(mixed), mixed.L, mixed.batch, lp.LP_BF16, lp.LP_LOSS_SOFTMAX_CE, 1e-3)
+    n0 = lp.lp_workspace_bytes(ctx)
+    for l in (1, 2, 4):
+        assert L.lp_set_factor_ring(ctx, l, 1) == 4 and b"split over K" in L.lp_last_error(ctx)
+    assert lp.lp_workspace_bytes(ctx) == n0
+    assert L.lp_set_factor_ring(ctx, 0, 1) == 0                  # "every linear layer": here that is layer 3 alone
+    # layer 3 (d = 2: three slots): a slot of G (4096 x 4096 floats) becomes a slot of factors (2048 x (4096 + 4096) bf16)
+    assert n0 - lp.lp_workspace_bytes(ctx) == 3 * (4096 * 4096 * 4 - 2048 * (4096 + 4096) * 2)
+    assert L.lp_set_factor_ring(ctx, 3, 0) == 0 and lp.lp_workspace_bytes(ctx) == n0
     lp.lp_destroy(ctx)
 
 

@@ -193,7 +193,9 @@ def test_act_grad_hadamard(n_feat, act, dtype):
     net.close()
 
 
-@pytest.mark.parametrize("rows,cols", [(32, 10), (256, 1000), (5, 33), (1, 1), (1024, 1000)])
+# row lengths: not a multiple of the 16-byte vector (scalar kernel), one / two / four / eight vectors per lane of the
+# register-resident kernel, and a row too long for it
+@pytest.mark.parametrize("rows,cols", [(32, 10), (256, 1000), (5, 33), (1, 1), (1024, 1000), (9, 8), (7, 2048), (6, 4096), (3, 4104), (2, 8192)])
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 def test_softmax_ce(rows, cols, dtype):
     layers = (WL.Layer(WL.LINEAR, 16, cols, WL.IDENTITY),)
@@ -216,7 +218,8 @@ def test_softmax_ce(rows, cols, dtype):
     net.close()
 
 
-@pytest.mark.parametrize("rows,cols", [(64, 256), (3, 7), (512, 4096)])
+# sizes: several blocks of 8192 elements, fewer elements than one vector, a ragged tail behind whole vectors
+@pytest.mark.parametrize("rows,cols", [(64, 256), (3, 7), (512, 4096), (1, 3), (5, 1643), (33, 8193)])
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 def test_mse(rows, cols, dtype):
     layers = (WL.Layer(WL.LINEAR, 16, cols, WL.IDENTITY),)
@@ -606,22 +609,35 @@ def test_trajectory_batch_of_one_and_delayed_last_layer():
 
 
 def test_operand_beyond_32_bit_offsets_is_rejected_not_launched():
-    """Byte offsets inside the kernels are 32-bit; a weight matrix of 2 GiB must come back as an error."""
+    """Byte offsets inside the kernels are 32-bit; a weight matrix of 2 GiB is refused when the context is made."""
     n = 32768
     layers = (WL.Layer(WL.LINEAR, n, n, WL.IDENTITY),)
-    net = lp.Network(layers, 8, "bf16", WL.MSE, 0.01, (0,))
-    w = torch.zeros(n, n, dtype=torch.float32, device=DEV)
-    lp.lp_set_weights(net.ctx, 1, w, True, net.streams[0])
-    lp.lp_sync(net.ctx)
-    del w
-    x = torch.zeros(8, n, dtype=torch.bfloat16, device=DEV)
-    z = torch.empty(8, n, dtype=torch.bfloat16, device=DEV)
     with pytest.raises(lp.LpError) as e:
-        lp.lp_forward(net.ctx, 1, x, z, None, net.streams[0])
-    assert e.value.status == 8          # LP_ERR_HIP: the launcher refused the shape
-    with pytest.raises(lp.LpError):
-        lp.lp_grad_act(net.ctx, 1, z, x, 0, n, net.streams[0])
-    net.close()
+        lp.Network(layers, 8, "bf16", WL.MSE, 0.01, (0,))
+    assert e.value.status == 2          # LP_ERR_SHAPE
+
+
+def test_softmax_label_outside_the_classes_is_not_dereferenced():
+    """A bad label gives that row the plain softmax as delta and a NaN loss; the other rows are untouched."""
+    rows, cols = 6, 1000
+    layers = (WL.Layer(WL.LINEAR, 16, cols, WL.IDENTITY),)
+    for dtype, td in (("bf16", torch.bfloat16), ("f32", torch.float32)):
+        net = lp.Network(layers, rows, dtype, WL.SOFTMAX_CE, 0.01, (0,))
+        rng = np.random.default_rng(3)
+        zd = dev(rng.standard_normal((rows, cols)).astype(np.float32), td)
+        y = rng.integers(0, cols, rows).astype(np.int32)
+        bad = y.copy(); bad[2] = cols; bad[4] = -7
+        dY, dYb = torch.empty_like(zd), torch.empty_like(zd)
+        loss, lossb = torch.zeros(1, device=DEV), torch.zeros(1, device=DEV)
+        lp.lp_loss_grad(net.ctx, zd, dev(y, torch.int32), dY, loss, net.streams[0])
+        lp.lp_loss_grad(net.ctx, zd, dev(bad, torch.int32), dYb, lossb, net.streams[0])
+        lp.lp_sync(net.ctx)
+        assert np.isfinite(float(loss)) and np.isnan(float(lossb))
+        good = [0, 1, 3, 5]
+        assert torch.equal(dY[good], dYb[good])
+        p = np.exp(host(zd) - host(zd).max(axis=1, keepdims=True)); p /= p.sum(axis=1, keepdims=True)
+        assert relerr(host(dYb)[[2, 4]], p[[2, 4]] / rows) <= (2e-2 if dtype == "bf16" else 1e-5)
+        net.close()
 
 
 def test_mfma_probe_runs_the_rounds_it_is_asked_for():
