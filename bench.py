@@ -24,10 +24,16 @@ PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 PEAK_FP32_MFMA_TFLOPS = 157.3
 PEAK_HBM_GBS = 8000.0
 
-# bytes the L2s request from the fabric (Infinity Cache + HBM) plus bytes written, per launch of the F
-# kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script, scaled by a 1 GiB copy
-# (profiles/hbm_traffic_ffn_stack.md)
-MEASURED_TRAFFIC_BYTES = {"ffn_stack_bf16": 1.6323e9 + 3.020e8}
+# Bytes the L2s request from the fabric (Infinity Cache + HBM) plus bytes written, per launch, from rocprofv3 --pmc
+# FETCH_SIZE / WRITE_SIZE runs of this script scaled by a 1 GiB copy.  Counters cannot be read from inside this
+# process, so the figure is tied to the exact kernel it was measured on: a kernel whose name differs (any change of
+# its template arguments) has no entry and reports "traffic": null until it is profiled again.
+MEASURED_TRAFFIC = {
+    ("ffn_stack_bf16", "gemm_bf16_dl_kernel<256,256,64,2,2,4,true,false,false>"):
+        {"bytes": 1.6323e9 + 3.020e8, "profile": "profiles/hbm_traffic_ffn_stack.md"},
+}
+# the kernel that runs the forward product of the default workload (every layer of it takes this instantiation)
+F_KERNEL = {"ffn_stack_bf16": "gemm_bf16_dl_kernel<256,256,64,2,2,4,true,false,false>"}
 
 
 def task_work(wl):
@@ -54,13 +60,29 @@ def task_work(wl):
     return {"F": f, "dX": dx, "dW": dw, "hadamard": had, "loss": float(loss), "update_per_param": per_param}
 
 
-def cpu_baseline(wl, threads):
+def blas_threads():
+    """(threads the BLAS behind numpy uses, what the library calls itself); the oracle's products run on them."""
+    try:
+        from threadpoolctl import threadpool_info
+        pools = [p for p in threadpool_info() if p.get("user_api") == "blas"]
+        if pools:
+            return max(int(p.get("num_threads", 1)) for p in pools), ", ".join(sorted(set(str(p.get("internal_api")) for p in pools)))
+    except Exception:
+        pass
+    return None, "unknown"
+
+
+def cpu_baseline(wl):
     """The oracle as it stands, timed on a bounded sample: one training step on at most 256 samples;
     for networks above 5e8 parameters only the first two layers (one up/down block) on up to 8192 samples
     (about ten seconds of work),
     scaled to the whole network by the ratio of per-sample flops."""
+    import numpy  # noqa: F401  (loads the BLAS whose thread pool is reported)
     import lp_workloads as WL
     from oracle import layerpipe_oracle as O
+    threads, blas = blas_threads()
+    if threads is None:
+        threads = int(os.environ.get("OMP_NUM_THREADS", "0")) or (os.cpu_count() or 1)
     if wl.n_params > 5e8:
         sub = wl.with_(layers=wl.layers[:2], batch=min(wl.batch, 8192), delays=wl.delays[-2:])
         what = "the first 2 of %d layers" % wl.L
@@ -75,9 +97,11 @@ def cpu_baseline(wl, threads):
     ora.step(x, t)
     dt = time.perf_counter() - t0
     return {"value": sub.batch / (dt * scale), "unit": "samples/s", "cores": threads, "kind": "oracle",
-            "sample": "one oracle training step (numpy float64, %d BLAS threads) of %s of %s at full widths on %d of the %d samples "
+            "host_cpus": os.cpu_count(), "blas": blas, "omp_num_threads_env": os.environ.get("OMP_NUM_THREADS"),
+            "sample": "one oracle training step (numpy float64; its products ran on %d BLAS threads (%s) of a host that shows %s CPUs) "
+                      "of %s of %s at full widths on %d of the %d samples "
                       "of a minibatch took %.1f s; scaled by the per-sample flop ratio %.2f to the whole network" % (
-                          threads, what, wl.name, sub.batch, wl.batch, dt, scale)}
+                          threads, blas, os.cpu_count(), what, wl.name, sub.batch, wl.batch, dt, scale)}
 
 
 def partition_report(wl, max_stages):
@@ -324,8 +348,12 @@ def main():
         flops_per_launch = work["F"] / wl.L
         avg_s = tasks["F"]["avg_ms"] * 1e-3
         ach = flops_per_launch / avg_s / 1e12
+        kernel = F_KERNEL.get(wl.name)
+        traffic = MEASURED_TRAFFIC.get((wl.name, kernel))
         roofline = {"bound": "mfma", "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS,
-                    "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name), "kernel": ("gemm_bf16_dl_kernel<256,256,64,2,2,4,true,false,false> (forward product F)" if wl.name == "ffn_stack_bf16"
+                    "traffic": traffic["bytes"] if traffic else None,
+                    "traffic_source": traffic["profile"] if traffic else None,
+                    "kernel": ("%s (forward product F)" % kernel if kernel
                                else "bf16 MFMA GEMM of the forward product F (tile and K split chosen per layer shape)"),
                     "flops_per_launch": flops_per_launch,
                     "avg_launch_ms": tasks["F"]["avg_ms"]}
@@ -373,18 +401,31 @@ def main():
 
     cpu = None
     if not args.no_cpu_baseline:
-        threads = int(os.environ.get("OMP_NUM_THREADS", "0")) or min(16, os.cpu_count() or 1)
-        cpu = cpu_baseline(wl, threads)
+        cpu = cpu_baseline(wl)
+
+    # Steady state of the headline workload: a layer is not updated while n <= d_l (Eq. 6 with empty delay elements),
+    # so timed steps that start before step max d_l + 1 carry fewer updates.  When the requested warm-up is that short,
+    # the same number of steps is timed once more behind a warm-up of max d_l + 1 steps.
+    d_max = max(wl.delays)
+    full_steps = sum(1 for n in range(args.warmup + 1, args.warmup + args.steps + 1) if n > d_max)
+    steady = None
+    if full_steps < args.steps and not args.run_ahead:
+        sdt, _, _, supd = run_workload(wl, args.steps, d_max + 1, args.streams, False, None, False, args.factor_ring)
+        steady = {"warmup": d_max + 1, "steps": args.steps, "ms_per_step": sdt / args.steps * 1e3, "value": wl.batch * args.steps / sdt,
+                  "unit": "samples/s", "updated_params_per_step": supd / args.steps}
 
     out = {
         "metric": "training samples/sec (1 GPU)", "value": value, "unit": "samples/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": wl.dtype, "data": "synthetic",
-        "config": {"workload": "%s: %d layers, batch %d, delays %s, %s loss, lr %g, %d streams" % (
-            wl.name, wl.L, wl.batch, list(wl.delays), wl.loss, wl.lr, args.ra_streams if args.run_ahead else args.streams) + (
+        "config": {"workload": "%s: %d layers, batch %d, delays %s, %s loss, lr %g, %d streams; %d of the %d timed steps update every layer "
+                               "(step number > max delay %d)" % (
+            wl.name, wl.L, wl.batch, list(wl.delays), wl.loss, wl.lr, args.ra_streams if args.run_ahead else args.streams,
+            full_steps, args.steps, d_max) + (
                 ", forward run-ahead" if args.run_ahead else "") + (", factor ring" if args.factor_ring else ""),
             "params": wl.n_params, "flops_per_step": sum(wl.flops_per_step()),
             "updated_params_per_step": upd_params / args.steps},
+        "steady_state": steady,
         "roofline": roofline, "cpu_baseline": cpu, "tasks": tasks, "tasks_one_stream": tasks_alone, "other_workloads": others,
         "final_loss": loss,
     }
