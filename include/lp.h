@@ -151,6 +151,19 @@ int lp_forward(lp_ctx* ctx, int l, const void* X, void* Z, void* A, void* stream
  * loss_dev: device float, may be NULL.  Needs a bound workspace (row partials). */
 int lp_loss_grad(lp_ctx* ctx, const void* ZL, const void* target, void* dYL, float* loss_dev, void* stream);
 
+/* lp_loss_grad for callers that cannot allocate device memory and have no workspace to hand over (code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): same kernels, same results bit
+ * for bit, but the partial sums of the loss live in a static device array inside the library (65536 floats =
+ * 256 KiB, held by every GPU the library runs on until the process ends) instead of the workspace.  No
+ * workspace needs to be bound; the call allocates nothing on the device or through any library.
+ * Limit: batch <= 65536 rows (SOFTMAX_CE) or batch * D_L <= 536870912 elements (MSE: one partial per 8192
+ * elements); larger sizes are LP_ERR_SHAPE.  The first call on a device looks up the array's address there
+ * (make that call outside a graph capture).  Every call on one GPU uses the same array: calls that overlap in
+ * time on one GPU race (enqueue them on one stream, or order them); nothing in it has to start at zero, every
+ * partial that is read has been written by the same call.  The stream is not recorded for lp_sync: synchronise
+ * `stream` yourself.  ZL, target, dYL, loss_dev as in lp_loss_grad. */
+int lp_loss_grad_static(lp_ctx* ctx, const void* ZL, const void* target, void* dYL, float* loss_dev, void* stream);
+
 /* The Hadamard part of Eq. 3 for layer l, the piece the inter-layer split moves into the stage that
  * holds Z_l:  dY_l = dA_l (.) f'(Z_l).  S is the stashed Z_l; for a ReLU layer without pool the
  * stashed A_l works as well (same sign).  For a pooled layer dA has the pooled shape and is routed

@@ -33,7 +33,7 @@ STATUS_NAMES = ["LP_OK", "LP_ERR_NULL", "LP_ERR_SHAPE", "LP_ERR_DTYPE", "LP_ERR_
                 "LP_ERR_STATE", "LP_ERR_WORKSPACE", "LP_ERR_HIP"]
 
 EXPORTS = ["lp_create", "lp_destroy", "lp_last_error", "lp_workspace_bytes", "lp_bind_workspace", "lp_set_weights",
-           "lp_get_weights", "lp_cast", "lp_forward", "lp_loss_grad", "lp_act_grad", "lp_grad_act", "lp_grad_weight", "lp_update",
+           "lp_get_weights", "lp_cast", "lp_forward", "lp_loss_grad", "lp_loss_grad_static", "lp_act_grad", "lp_grad_act", "lp_grad_weight", "lp_update",
            "lp_advance", "lp_step", "lp_step_index", "lp_sync", "lp_tensor", "lp_profile", "lp_profile_read", "lp_profile_read_layer", "lp_partition", "lp_set_delta_split", "lp_set_run_ahead", "lp_set_graphs", "lp_graph_stats", "lp_set_factor_ring", "lp_probe_mfma"]
 
 
@@ -71,6 +71,7 @@ def load_library():
     L.lp_cast.argtypes = [vp, vp, vp, C.c_size_t, vp]
     L.lp_forward.argtypes = [vp, ip, vp, vp, vp, vp]
     L.lp_loss_grad.argtypes = [vp, vp, vp, vp, vp, vp]
+    L.lp_loss_grad_static.argtypes = [vp, vp, vp, vp, vp, vp]
     L.lp_act_grad.argtypes = [vp, ip, vp, vp, vp, vp]
     L.lp_grad_act.argtypes = [vp, ip, vp, vp, ip, ip, vp]
     L.lp_grad_weight.argtypes = [vp, ip, vp, vp, vp, vp]
@@ -177,6 +178,10 @@ def lp_forward(ctx, l: int, X, Z, A, stream=None):
 
 def lp_loss_grad(ctx, ZL, target, dYL, loss_dev, stream=None):
     _check(ctx, lib().lp_loss_grad(ctx, _ptr(ZL), _ptr(target), _ptr(dYL), _ptr(loss_dev), _stream(stream)))
+
+
+def lp_loss_grad_static(ctx, ZL, target, dYL, loss_dev, stream=None):
+    _check(ctx, lib().lp_loss_grad_static(ctx, _ptr(ZL), _ptr(target), _ptr(dYL), _ptr(loss_dev), _stream(stream)))
 
 
 def lp_act_grad(ctx, l: int, dA, S, dY, stream=None):

@@ -4,6 +4,8 @@
 // consecutive lanes on consecutive addresses; row reductions stay inside one 64-lane wavefront.
 #include "lp_kernels.h"
 
+#include <mutex>
+
 namespace lp {
 namespace {
 
@@ -598,6 +600,37 @@ hipError_t launch_mse(bool bf16, const void* Z, const void* T, void* dY, float* 
   if (e != hipSuccess || !loss) return e;
   hipLaunchKernelGGL(finalize_loss_kernel, dim3(1), dim3(256), 0, s, (const float*)partials, (size_t)nb, 1.f / (float)n, loss);
   return hipGetLastError();
+}
+
+// ---- loss partials for callers that cannot allocate ------------------------------------------------
+// The partial sums of the loss kernels normally live in the caller's workspace.  This array is the same
+// scratch inside the library's own image: every GPU the library runs on holds one copy (256 KiB) until the
+// process ends.  In host code its name is only a handle; the device address is asked for once per device.
+namespace {
+constexpr size_t kStaticLossPartials = 65536;
+static __device__ __align__(256) float scratch[kStaticLossPartials];
+constexpr int kMaxDevices = 64;
+std::mutex scratch_mutex;
+float* scratch_ptr[kMaxDevices] = {};
+}  // namespace
+
+size_t static_loss_partials_capacity() { return kStaticLossPartials; }
+
+hipError_t static_loss_partials(float** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(scratch_mutex);
+  if (!scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));   // the copy of the device that is current
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    scratch_ptr[dev] = static_cast<float*>(p);
+  }
+  *out = scratch_ptr[dev];
+  return hipSuccess;
 }
 
 hipError_t launch_sgd(float* master, const float* g, void* work_out_bf16, float lr, size_t n, hipStream_t s) {

@@ -879,6 +879,25 @@ int lp_loss_grad(lp_ctx* c, const void* ZL, const void* target, void* dYL, float
   });
 }
 
+int lp_loss_grad_static(lp_ctx* c, const void* ZL, const void* target, void* dYL, float* loss_dev, void* stream) {
+  return guarded(c, "lp_loss_grad_static", [&]() -> int {
+    if (!c) return LP_ERR_NULL;
+    if (!ZL || !target || !dYL) return fail(c, LP_ERR_NULL, "lp_loss_grad_static: ZL/target/dYL is NULL");
+    const Layer& last = c->layers[c->L - 1];
+    const bool mse = c->loss == LP_LOSS_MSE;
+    const size_t need = lp::loss_partials_count(mse, c->batch, last.out_feat), have = lp::static_loss_partials_capacity();
+    if (need > have)
+      return fail(c, LP_ERR_SHAPE, "lp_loss_grad_static: %zu partial sums needed, the static scratch holds %zu (%s); use lp_loss_grad with a workspace",
+                  need, have, mse ? "batch x D_L <= 536870912 elements" : "batch <= 65536 rows");
+    float* partials = nullptr;
+    LP_HIP(c, lp::static_loss_partials(&partials));
+    hipStream_t s = (hipStream_t)stream;
+    if (mse) LP_HIP(c, lp::launch_mse(is_bf16(c), ZL, target, dYL, loss_dev, partials, c->batch, last.out_feat, s));
+    else LP_HIP(c, lp::launch_softmax_ce(is_bf16(c), ZL, (const int*)target, dYL, loss_dev, partials, c->batch, last.out_feat, s));
+    return LP_OK;
+  });
+}
+
 int lp_act_grad(lp_ctx* c, int l, const void* dA, const void* S, void* dY, void* stream) {
   return guarded(c, "lp_act_grad", [&]() -> int {
     if (!c) return LP_ERR_NULL;

@@ -79,6 +79,11 @@ hipError_t launch_softmax_ce(bool bf16, const void* Z, const int* labels, void* 
 hipError_t launch_mse(bool bf16, const void* Z, const void* T, void* dY, float* loss, float* partials, int rows,
                       int cols, hipStream_t s);
 
+// The same scratch as a static device array of the library (one copy per GPU): its device address on the current
+// device (looked up on the first call per device) and its capacity in floats.
+hipError_t static_loss_partials(float** out);
+size_t static_loss_partials_capacity();
+
 // master <- master - lr * g;  work_out (bf16, may be null) <- round(master)
 hipError_t launch_sgd(float* master, const float* g, void* work_out_bf16, float lr, size_t n, hipStream_t s);
 // dst_bf16 <- round(src)
