@@ -7,7 +7,7 @@ import torch
 import lp_workloads as WL
 import paper_2108_06629_amd as lp
 from oracle import layerpipe_oracle as O
-from test_gpu_parity import DEV, dev, host, relerr, frob, check_g_free_running, relu_flips, run_key, RECORDS, _dump_records
+from test_gpu_parity import DEV, dev, host, relerr, frob, check_g_free_running, relu_flips, run_key, RECORDS, RECORDING, ZL_BOUND, _dump_records
 
 pytestmark = pytest.mark.gpu
 
@@ -133,9 +133,11 @@ def run_cnn(wl, steps, exact=True, product_steps=None):
         ref = ora.step(x, t)
         if exact is not None:
             exact.step(x, t)
-        assert abs(loss - ref) <= 2e-2 * max(abs(ref), 1e-3), (n, loss, ref)
         zl = net.tensor_np(wl.L, lp.LP_T_Z).reshape(ora.trace["Z"][-1].shape)
-        assert relerr(zl, ora.trace["Z"][-1]) <= 2e-2
+        e_loss, e_zl = abs(loss - ref) / max(abs(ref), 1e-3), relerr(zl, ora.trace["Z"][-1])
+        if not RECORDING:
+            assert e_loss <= 2e-2, (n, loss, ref)
+            assert e_zl <= ZL_BOUND.get(run_key(wl), 2e-2), ("Z_L", n, e_zl)
         # task by task on the tensors the GPU tasks actually read
         Wk = [O.round_bf16(w) for w in W_before]
         A = [O.round_bf16(x)]
@@ -170,9 +172,8 @@ def run_cnn(wl, steps, exact=True, product_steps=None):
             if products:
                 assert relerr(g, O.grad_weight(a_in, dy)) <= 2e-4, ("dW", l, n)
             G_hist[l - 1][n] = g
-            e = check_g_free_running(wl, l, n, g, ora.trace["G"][l - 1], None if exact is None else exact.trace["G"][l - 1])
+            e, share = check_g_free_running(wl, l, n, g, ora.trace["G"][l - 1], None if exact is None else exact.trace["G"][l - 1])
             flips, units = relu_flips(net, wl, l, ora.trace["Z"][l - 1])
-            rec.append(dict(n=n, l=l, g_maxnorm=e, relu_flips=flips, relu_units=units))
             if l > 1:
                 prev = wl.layers[l - 2]
                 da = net.tensor_np(l - 1, lp.LP_T_DA).reshape(prev.out_shape(wl.batch))
@@ -194,7 +195,11 @@ def run_cnn(wl, steps, exact=True, product_steps=None):
             else:
                 upd = O.store(O.delayed_sgd(W_before[l - 1].astype(np.float64), G_hist[l - 1].pop(src), float(np.float32(wl.lr))), "f32")
                 assert np.max(np.abs(w_new - upd)) <= 2.0 ** -22 * np.max(np.abs(upd)), ("update", l, n)
-            assert relerr(w_new, ora.W[l - 1]) <= 2e-2, ("W free-running", l, n)
+            e_w = relerr(w_new, ora.W[l - 1])
+            rec.append(dict(n=n, l=l, g_maxnorm=e, g_share_over=share, relu_flips=flips, relu_units=units, w_relerr=e_w, zl_relerr=e_zl,
+                            loss_relerr=e_loss))
+            if not RECORDING:
+                assert e_w <= 2e-2, ("W free-running", l, n)
     net.close()
     _dump_records(run_key(wl))
 
