@@ -12,6 +12,8 @@
 #include "gemm_dl.h"
 #include "lp_kernels.h"
 
+#include <mutex>
+
 namespace lp {
 namespace {
 
@@ -30,6 +32,7 @@ struct GemmKArgs {
   float* partial;       // split-K: [gridDim.y][M][N] fp32
   float* sgd_master;    // SGD variants: fp32 master weights updated in the epilogue
   float neg_lr;
+  const unsigned short* act_lut;   // optional table of the activation over all bf16 inputs (GELU)
 };
 
 template <bool KC, int R, int BK, int NT, bool ALIGNED>
@@ -69,7 +72,7 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_bf16_kernel(GemmKArgs p) {
     StoreEpilogue epi{nullptr, nullptr, p.partial + (size_t)blockIdx.y * p.M * p.N, p.M, p.N, p.N, 0, m0, n0, (p.N % 4) == 0};
     gemm_tile<BM, BN, BK, WM, WN>(sa, sb, kt0, kt1, smem, epi);
   } else {
-    StoreEpilogue epi{p.out_z, p.out_a, p.out_f32, p.M, p.N, p.ldc, p.act, m0, n0, p.vec_out != 0};
+    StoreEpilogue epi{p.out_z, p.out_a, p.out_f32, p.M, p.N, p.ldc, p.act, m0, n0, p.vec_out != 0, p.act_lut};
     gemm_tile<BM, BN, BK, WM, WN>(sa, sb, 0, (p.K + BK - 1) / BK, smem, epi);
   }
 }
@@ -101,7 +104,7 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_bf16_dl_kernel(GemmKArgs p) 
     dl::gemm_tile_dl<BM, BN, BK, NSTAGE, WM, WN>(oa, ob, kt0 * BK, kt1 > kt0 ? kt1 - kt0 : 0, smem, epi);
     return;
   }
-  StoreEpilogue epi{p.out_z, p.out_a, p.out_f32, p.M, p.N, p.ldc, p.act, tm * BM, tn * BN, p.vec_out != 0};
+  StoreEpilogue epi{p.out_z, p.out_a, p.out_f32, p.M, p.N, p.ldc, p.act, tm * BM, tn * BN, p.vec_out != 0, p.act_lut};
   dl::gemm_tile_dl<BM, BN, BK, NSTAGE, WM, WN>(oa, ob, 0, KT, smem, epi);
 }
 
@@ -143,8 +146,8 @@ __global__ void __launch_bounds__(256) splitk_reduce_kernel(const float* __restr
         }
     }
   }
-  StoreEpilogue epi{p.out_z, p.out_a, p.out_f32, p.M, p.N, p.ldc, p.act, 0, 0, p.vec_out != 0};
-  epi(row, col, acc);
+  StoreEpilogue epi{p.out_z, p.out_a, p.out_f32, p.M, p.N, p.ldc, p.act, 0, 0, p.vec_out != 0, p.act_lut};
+  epi.with_static_act([&](auto store) { store(row, col, acc); });
 }
 
 template <int BM, int BN, int BK, int NSTAGE, int WM, int WN, bool AKC, bool BKC, bool SGD = false>
@@ -328,6 +331,47 @@ hipError_t launch_mfma_only(float* out, int workgroups, int iters, bool uniform_
   return hipGetLastError();
 }
 
+// ---- GELU over all bfloat16 inputs --------------------------------------------------------------------
+// A bf16 activation has 65536 possible inputs.  In a product's epilogue the exact GELU costs about 28 vector
+// instructions per element, and that arithmetic is exposed (every workgroup of a round reaches its epilogue at the
+// same time); a look-up costs one 2-byte gather from a table whose live part (|z| < 8: some 3000 entries) sits in the
+// CU's L1.  The table is a static device array of the library (128 KiB per GPU, kept until the process ends), filled
+// once per device by a kernel that evaluates z * Phi(z) in fp64 and rounds to nearest even, so an entry is the
+// correctly rounded GELU of the stored z (up to the double rounding through fp32).
+namespace {
+static __device__ __align__(256) unsigned short gelu_table[65536];
+__global__ void __launch_bounds__(256) gelu_table_fill_kernel(unsigned short* __restrict__ t) {
+  const unsigned i = blockIdx.x * 256 + threadIdx.x;
+  const double z = (double)bf16_to_f32((unsigned short)i);
+  t[i] = bf16_bits((float)(0.5 * z * erfc(-z * 0.70710678118654752440)));   // erfc: no cancellation for z << 0
+}
+constexpr int kMaxDevices = 64;
+std::mutex gelu_table_mutex;
+const unsigned short* gelu_table_ptr[kMaxDevices] = {};
+}  // namespace
+
+hipError_t gelu_lut_bf16(const void** out, hipStream_t s) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(gelu_table_mutex);
+  if (!gelu_table_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(gelu_table));   // this device's copy
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    hipLaunchKernelGGL(gelu_table_fill_kernel, dim3(256), dim3(256), 0, s, (unsigned short*)p);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    e = hipStreamSynchronize(s);   // kernels on any other stream may read the table from now on
+    if (e != hipSuccess) return e;
+    gelu_table_ptr[dev] = (const unsigned short*)p;
+  }
+  *out = gelu_table_ptr[dev];
+  return hipSuccess;
+}
+
 int gemm_bf16_num_cfgs() { return (int)(sizeof(kCfgs) / sizeof(kCfgs[0])); }
 const char* gemm_bf16_cfg_name(int cfg) { return (cfg >= 0 && cfg < gemm_bf16_num_cfgs()) ? kCfgs[cfg].name : "?"; }
 
@@ -357,6 +401,7 @@ hipError_t launch_gemm_bf16(const GemmDesc& d, hipStream_t s, int tile_cfg) {
   a.partial = nullptr;
   a.sgd_master = d.sgd_master;
   a.neg_lr = -d.sgd_lr;
+  a.act_lut = (d.act == ACT_GELU && d.out_a) ? (const unsigned short*)d.act_lut : nullptr;
   const bool sgd = d.sgd_master != nullptr;
   if (sgd) {
     if (d.a_kcontig || d.b_kcontig || !d.out_z) return hipErrorInvalidValue;

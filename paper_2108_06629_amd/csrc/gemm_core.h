@@ -353,6 +353,8 @@ struct StoreEpilogue {
   float* out_f32;
   int M, N, ldc, act, m0, n0;
   bool vec;
+  // optional: f(z) for every bfloat16 bit pattern z (65536 entries); when set, A is looked up instead of computed
+  const unsigned short* act_lut;
   // ACT < 0: the activation is read from `act`
   template <int ACT>
   __device__ __forceinline__ void store(int r, int c, const f32x4& v) const {
@@ -368,6 +370,7 @@ struct StoreEpilogue {
         for (int t = 0; t < 4; ++t) {
           if constexpr (ACT < 0) ab[t] = bf16_bits(apply_act(bf16_to_f32(zb[t]), act));
           else if constexpr (ACT == 0) ab[t] = zb[t];
+          else if constexpr (ACT == 5) ab[t] = act_lut[zb[t]];
           else ab[t] = bf16_bits(apply_act_static<ACT>(bf16_to_f32(zb[t])));
         }
       }
@@ -398,7 +401,10 @@ struct StoreEpilogue {
   __device__ __forceinline__ void with_static_act(F&& f) const {
     switch (out_a ? act : 0) {
       case 1: f(StaticAct<1>{*this}); break;
-      case 2: f(StaticAct<2>{*this}); break;
+      case 2:
+        if (act_lut) f(StaticAct<5>{*this});   // 5: table look-up
+        else f(StaticAct<2>{*this});
+        break;
       case 3: f(StaticAct<3>{*this}); break;
       case 4: f(StaticAct<4>{*this}); break;
       default: f(StaticAct<0>{*this}); break;

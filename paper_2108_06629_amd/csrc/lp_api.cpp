@@ -62,6 +62,7 @@ struct lp_ctx {
   std::vector<GraphEntry> graph_cache;
   long graph_captured = 0, graph_replayed = 0, graph_eager = 0;
   char* ws = nullptr;
+  const void* gelu_lut = nullptr;   // GELU over all bf16 inputs (lp::gelu_lut_bf16), looked up by the F epilogue of GELU layers
   long n = 0;
   std::string err;
   bool events_ready = false;
@@ -222,6 +223,7 @@ hipError_t do_forward(lp_ctx* c, Layer& ly, const void* X, void* Z, void* A, hip
     g.lda = ly.d.in; g.ldb = ly.d.out; g.ldc = ly.d.out;
     g.a_kcontig = true; g.b_kcontig = false;
     g.out_z = Z; g.out_a = A; g.act = ly.d.act;
+    g.act_lut = c->gelu_lut;
     g.splitk_scratch = (float*)(c->ws + c->off_splitk[sk]); g.splitk_bytes = c->splitk_bytes[sk];
     return is_bf16(c) ? lp::launch_gemm_bf16(g, s) : lp::launch_gemm_f32(g, s);
   }
@@ -815,6 +817,8 @@ int lp_set_weights(lp_ctx* c, int l, const float* W, int is_device, void* stream
       LP_HIP(c, hipMemcpy(master, W, ly.n_params * 4, hipMemcpyHostToDevice));
     }
     if (is_bf16(c)) LP_HIP(c, lp::launch_cast_bf16(master, c->ws + ly.off_work[ly.cur], ly.n_params, s));
+    // the table the F epilogue of a GELU layer looks its activation up in: made ready here, outside any step
+    if (is_bf16(c) && ly.d.kind == LP_LINEAR && ly.d.act == LP_ACT_GELU && !c->gelu_lut) LP_HIP(c, lp::gelu_lut_bf16(&c->gelu_lut, s));
     ly.weights_set = true;
     return LP_OK;
   });

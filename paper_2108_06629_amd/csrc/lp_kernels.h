@@ -37,7 +37,12 @@ struct GemmDesc {
   // to out_z.  out_a, out_f32 and act are ignored; K is never split.
   float* sgd_master = nullptr;
   float sgd_lr = 0.f;
+  // optional, for act == ACT_GELU with out_a: the table gelu_lut_bf16 returns; A is then looked up, not computed
+  const void* act_lut = nullptr;
 };
+// Device address of GELU(z) for all 65536 bfloat16 bit patterns z (bf16 entries; a static array of the library,
+// one copy per GPU).  The first call on a device fills it with a kernel on `s` and waits for it: not under capture.
+hipError_t gelu_lut_bf16(const void** out, hipStream_t s);
 // K ranges the launcher cuts a product of this shape into (1: not split), and the scratch that takes
 // (0: split-K would not be used)
 int gemm_bf16_splitk_splits(int M, int N, int K);

@@ -91,6 +91,36 @@ def test_forward_product_bf16(shape, act):
     net.close()
 
 
+def test_gelu_of_every_bf16_input_is_the_rounded_exact_value():
+    """Every finite bf16 pattern as the pre-activation of a GELU layer (identity weights, so Z = X): A must be the
+    fp64 GELU of the stored Z rounded to bf16, bit for bit, wherever the oracle's erf form is itself accurate to far
+    below half a bf16 ulp (z > -6; beyond that 1 + erf(z / sqrt 2) cancels in fp64 and both sides are below 1e-7 in
+    magnitude)."""
+    n = 256
+    pats = np.arange(65536, dtype=np.uint32)
+    x = (pats << 16).astype(np.uint32).view(np.float32).copy()
+    x[~np.isfinite(x)] = 0.0
+    x = x.reshape(n, n)
+    layers = (WL.Layer(WL.LINEAR, n, n, WL.GELU), WL.Layer(WL.LINEAR, n, 8, WL.IDENTITY))
+    net = lp.Network(layers, n, "bf16", WL.SOFTMAX_CE, 0.01, (0, 0))
+    net.set_weights([np.eye(n, dtype=np.float32), np.zeros((n, 8), dtype=np.float32)])
+    xd = dev(x, torch.bfloat16)
+    Z = torch.empty(n, n, dtype=torch.bfloat16, device=DEV)
+    A = torch.empty(n, n, dtype=torch.bfloat16, device=DEV)
+    lp.lp_forward(net.ctx, 1, xd, Z, A, net.streams[0])
+    lp.lp_sync(net.ctx)
+    z, a = host(Z), host(A)
+    normal = np.abs(x) >= 2.0 ** -126
+    assert np.array_equal(z[normal], x[normal].astype(np.float64))      # one non-zero term per sum: Z is X
+    assert np.unique(z).size > 65000
+    ref = O.store(O.activation(z, "gelu"), "bf16")
+    accurate = z > -6.0
+    assert np.array_equal(a[accurate], ref[accurate])
+    assert np.all(np.signbit(a[~accurate]) | (a[~accurate] == 0.0))
+    assert np.max(np.abs(a[~accurate] - ref[~accurate])) <= 1e-7
+    net.close()
+
+
 @pytest.mark.parametrize("shape", FWD_SHAPES)
 def test_grad_act_and_column_partition_bf16(shape):
     B, K, N = shape          # layer K -> N;  dX = dY[B,N] . W[K,N]^T
@@ -236,6 +266,35 @@ def test_mse(rows, cols, dtype):
     ref_loss, ref_dy = O.mse(host(zd), host(tg))
     assert abs(float(loss) - ref_loss) <= 1e-5 * ref_loss
     assert relerr(host(dY), O.store(ref_dy, "bf16" if dtype == "bf16" else "f32")) <= (2.0 ** -7 if dtype == "bf16" else 1e-6)
+    net.close()
+
+
+@pytest.mark.parametrize("n", [1, 3, 4, 1000, 4099, 1 << 20])
+def test_cast_rounds_to_nearest_even_like_the_oracle(n):
+    """lp_cast is how a float input becomes an act-type tensor: bit for bit the oracle's storage rounding, including exact
+    ties (both directions), values below the smallest normal and infinities; an F32 context copies."""
+    layers = (WL.Layer(WL.LINEAR, 8, 8, WL.IDENTITY),)
+    rng = np.random.default_rng(n)
+    x = (rng.standard_normal(n) * np.exp(rng.uniform(-30, 30, n))).astype(np.float32)
+    special = np.array([1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, -(1.0 + 2.0 ** -8), 2.0 ** -130, -2.0 ** -140, 0.0, -0.0, np.inf, -np.inf,
+                        3.3895314e38, 1.0 + 2.0 ** -9, 1.0 + 2.0 ** -8 + 2.0 ** -20], dtype=np.float32)
+    x[:min(n, special.size)] = special[:min(n, special.size)]
+    net = lp.Network(layers, 4, "bf16", WL.MSE, 0.01, (0,))
+    src = torch.from_numpy(x).to(DEV)
+    dst = torch.full((n,), float("nan"), dtype=torch.bfloat16, device=DEV)
+    torch.cuda.synchronize()
+    lp.lp_cast(net.ctx, src, dst, n, net.streams[0])
+    lp.lp_sync(net.ctx)
+    got = dst.view(torch.int16).cpu().numpy().view(np.uint16)
+    want = (O.round_bf16(x).astype(np.float32).view(np.uint32) >> 16).astype(np.uint16)
+    assert np.array_equal(got, want)
+    assert torch.equal(net.to_device(x.reshape(1, -1)).view(torch.int16).cpu().view(-1), dst.view(torch.int16).cpu())
+    net.close()
+    net = lp.Network(layers, 4, "f32", WL.MSE, 0.01, (0,))
+    out = torch.zeros(n, dtype=torch.float32, device=DEV)
+    lp.lp_cast(net.ctx, src, out, n, net.streams[0])
+    lp.lp_sync(net.ctx)
+    assert torch.equal(out.view(torch.int32), src.view(torch.int32))
     net.close()
 
 
