@@ -181,6 +181,9 @@ def partition_report(wl, max_stages):
             "partitions": rows, "step_ms_three_streams": times}
 
 
+FUSED_HADAMARD = True   # --separate-hadamard clears it: Eq. 3 then runs as a kernel of its own after every dX product
+
+
 def run_workload(wl, steps, warmup, n_streams, profile=True, weights=None, run_ahead=False, factor_ring=False):
     import numpy as np
     import torch
@@ -189,7 +192,7 @@ def run_workload(wl, steps, warmup, n_streams, profile=True, weights=None, run_a
 
     dev = torch.device("cuda:0")
     net = lp.Network(wl.layers, wl.batch, wl.dtype, wl.loss, wl.lr, wl.delays, device="cuda:0", n_streams=n_streams,
-                     run_ahead=run_ahead, factor_ring=(True if factor_ring else None))
+                     run_ahead=run_ahead, factor_ring=(True if factor_ring else None), fused_hadamard=FUSED_HADAMARD)
     net.set_weights(WL.init_weights(wl) if weights is None else weights)
     # a small pool of resident minibatches, reused round-robin
     pool = 4
@@ -240,6 +243,8 @@ def main():
                     help="forward run-ahead across steps (lp_set_run_ahead): F(n+1) on a fourth stream next to the backward pass of step n")
     ap.add_argument("--factor-ring", action="store_true",
                     help="keep (A, dY) pairs instead of G in the delay elements and fuse the product into the delayed update (lp_set_factor_ring)")
+    ap.add_argument("--separate-hadamard", action="store_true",
+                    help="run the Hadamard products f'(S) (.) dA as kernels of their own instead of inside the dX products (lp_set_fused_hadamard 0)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-others", action="store_true", help="skip the short runs of the other workloads")
     ap.add_argument("--partition", type=int, default=0, metavar="NP",
@@ -255,6 +260,8 @@ def main():
         print("bench.py: this build runs on ONE GPU (one MI355X per box, no collectives); --gpus %d is not supported" % args.gpus,
               file=sys.stderr)
         sys.exit(2)
+    global FUSED_HADAMARD
+    FUSED_HADAMARD = not args.separate_hadamard
 
     import torch
     import lp_workloads as WL
@@ -327,6 +334,8 @@ def main():
             if cnt and ms > 0:
                 gbs = work[name] * steps / (ms * 1e-3) / 1e9
                 out[name] = {"launches": cnt, "avg_ms": ms / cnt, "GB/s": gbs, "frac_of_hbm_peak": gbs / PEAK_HBM_GBS}
+            elif name == "hadamard" and work[name] > 0:
+                out[name] = {"launches": 0, "note": "applied in the epilogue of the dX products (its time is part of dX; --separate-hadamard times it alone)"}
         ms, cnt = prof.get("update", (0.0, 0))
         if cnt and ms > 0 and not factor_ring:
             gbs = upd_params * work["update_per_param"] / (ms * 1e-3) / 1e9
@@ -422,7 +431,8 @@ def main():
                                "(step number > max delay %d)" % (
             wl.name, wl.L, wl.batch, list(wl.delays), wl.loss, wl.lr, args.ra_streams if args.run_ahead else args.streams,
             full_steps, args.steps, d_max) + (
-                ", forward run-ahead" if args.run_ahead else "") + (", factor ring" if args.factor_ring else ""),
+                ", forward run-ahead" if args.run_ahead else "") + (", factor ring" if args.factor_ring else "") + (
+                ", Hadamard products as separate kernels" if args.separate_hadamard else ""),
             "params": wl.n_params, "flops_per_step": sum(wl.flops_per_step()),
             "updated_params_per_step": upd_params / args.steps},
         "steady_state": steady,

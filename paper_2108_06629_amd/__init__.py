@@ -34,7 +34,7 @@ STATUS_NAMES = ["LP_OK", "LP_ERR_NULL", "LP_ERR_SHAPE", "LP_ERR_DTYPE", "LP_ERR_
 
 EXPORTS = ["lp_create", "lp_destroy", "lp_last_error", "lp_workspace_bytes", "lp_bind_workspace", "lp_set_weights",
            "lp_get_weights", "lp_cast", "lp_forward", "lp_loss_grad", "lp_loss_grad_static", "lp_act_grad", "lp_grad_act", "lp_grad_weight", "lp_update",
-           "lp_advance", "lp_step", "lp_step_index", "lp_sync", "lp_tensor", "lp_profile", "lp_profile_read", "lp_profile_read_layer", "lp_partition", "lp_set_delta_split", "lp_set_run_ahead", "lp_set_graphs", "lp_graph_stats", "lp_set_factor_ring", "lp_probe_mfma"]
+           "lp_advance", "lp_step", "lp_step_index", "lp_sync", "lp_tensor", "lp_profile", "lp_profile_read", "lp_profile_read_layer", "lp_partition", "lp_set_delta_split", "lp_set_run_ahead", "lp_set_graphs", "lp_graph_stats", "lp_set_factor_ring", "lp_set_fused_hadamard", "lp_probe_mfma"]
 
 
 class lp_layer_desc(C.Structure):
@@ -86,6 +86,7 @@ def load_library():
     L.lp_set_delta_split.argtypes = [vp, ip, ip]
     L.lp_probe_mfma.argtypes = [vp, C.c_size_t, ip, ip, ip, vp]
     L.lp_set_run_ahead.argtypes = [vp, ip]
+    L.lp_set_fused_hadamard.argtypes = [vp, ip]
     L.lp_set_graphs.argtypes = [vp, ip]
     L.lp_set_factor_ring.argtypes = [vp, ip, ip]
     L.lp_graph_stats.argtypes = [vp, C.POINTER(C.c_long), C.POINTER(C.c_long), C.POINTER(C.c_long)]
@@ -261,6 +262,10 @@ def lp_probe_mfma(out_dev, workgroups: int, iters: int, uniform_values: bool = F
         raise LpError(r, "lp_probe_mfma failed with status %d" % r)
 
 
+def lp_set_fused_hadamard(ctx, enable: bool):
+    _check(ctx, lib().lp_set_fused_hadamard(ctx, int(enable)))
+
+
 def lp_set_run_ahead(ctx, enable: bool):
     _check(ctx, lib().lp_set_run_ahead(ctx, int(enable)))
 
@@ -287,7 +292,7 @@ class Network:
     objects (kind, d_in, d_out, act, H, W, pool)."""
 
     def __init__(self, layers, batch: int, dtype: str, loss: str, lr: float, delays, device: str = "cuda:0", n_streams: int = None,
-                 run_ahead: bool = False, graphs: bool = False, factor_ring=None):
+                 run_ahead: bool = False, graphs: bool = False, factor_ring=None, fused_hadamard: bool = True):
         import torch
         self.torch = torch
         if n_streams is None:
@@ -300,6 +305,8 @@ class Network:
             lp_set_factor_ring(self.ctx, l, True)
         if graphs:
             lp_set_graphs(self.ctx, True)
+        if not fused_hadamard:
+            lp_set_fused_hadamard(self.ctx, False)
         if run_ahead:
             lp_set_run_ahead(self.ctx, True)
             n_streams = max(2, n_streams)

@@ -75,9 +75,17 @@ __device__ __forceinline__ float block_sum_256(float v, float* sh4) {
 // ---- dY = dA (.) f'(S) ---------------------------------------------------------------------------
 constexpr int EW_VEC_PER_THREAD = 4;
 
+// ACT_LUT (not an activation of the library): f' is looked up in `lut`, fp32 entries for all 65536 bf16 patterns of S
+constexpr int ACT_LUT = 100;
+template <int ACT>
+__device__ __forceinline__ float act_df_bf16(unsigned short s, const float* __restrict__ lut) {
+  if constexpr (ACT == ACT_LUT) return lut[s];
+  else return act_df<ACT>(bf2f(s));
+}
+
 template <int ACT>
 __global__ void __launch_bounds__(256) act_grad_bf16_kernel(const u32x4* __restrict__ dA, const u32x4* __restrict__ S,
-                                                            u32x4* __restrict__ dY, size_t nvec, size_t n) {
+                                                            u32x4* __restrict__ dY, size_t nvec, size_t n, const float* __restrict__ lut) {
   const size_t base = (size_t)blockIdx.x * (256 * EW_VEC_PER_THREAD) + threadIdx.x;
   u32x4 a[EW_VEC_PER_THREAD], s[EW_VEC_PER_THREAD];
 #pragma unroll
@@ -93,8 +101,8 @@ __global__ void __launch_bounds__(256) act_grad_bf16_kernel(const u32x4* __restr
 #pragma unroll
       for (int d = 0; d < 4; ++d) {
         const float a0 = bf2f((unsigned short)(a[u][d] & 0xffffu)), a1 = bf2f((unsigned short)(a[u][d] >> 16));
-        const float s0 = bf2f((unsigned short)(s[u][d] & 0xffffu)), s1 = bf2f((unsigned short)(s[u][d] >> 16));
-        o[d] = (unsigned)f2bf(a0 * act_df<ACT>(s0)) | ((unsigned)f2bf(a1 * act_df<ACT>(s1)) << 16);
+        const unsigned short s0 = (unsigned short)(s[u][d] & 0xffffu), s1 = (unsigned short)(s[u][d] >> 16);
+        o[d] = (unsigned)f2bf(a0 * act_df_bf16<ACT>(s0, lut)) | ((unsigned)f2bf(a1 * act_df_bf16<ACT>(s1, lut)) << 16);
       }
       __builtin_nontemporal_store(o, dY + i);
     }
@@ -105,7 +113,7 @@ __global__ void __launch_bounds__(256) act_grad_bf16_kernel(const u32x4* __restr
     if (i < n) {
       const unsigned short* a16 = (const unsigned short*)dA;
       const unsigned short* s16 = (const unsigned short*)S;
-      ((unsigned short*)dY)[i] = f2bf(bf2f(a16[i]) * act_df<ACT>(bf2f(s16[i])));
+      ((unsigned short*)dY)[i] = f2bf(bf2f(a16[i]) * act_df_bf16<ACT>(s16[i], lut));
     }
   }
 }
@@ -496,7 +504,7 @@ inline unsigned blocks_for(size_t items, size_t per_block) { return (unsigned)((
 
 }  // namespace
 
-hipError_t launch_act_grad(bool bf16, int act, const void* dA, const void* S, void* dY, size_t n, hipStream_t s) {
+hipError_t launch_act_grad(bool bf16, int act, const void* dA, const void* S, void* dY, size_t n, hipStream_t s, const float* gelu_grad_lut) {
   if (n == 0) return hipSuccess;
   if (act == ACT_IDENTITY) {
     if (dA == dY) return hipSuccess;
@@ -505,10 +513,12 @@ hipError_t launch_act_grad(bool bf16, int act, const void* dA, const void* S, vo
   const size_t per = bf16 ? 8 : 4, nvec = n / per;
   const unsigned nb = blocks_for(nvec > 0 ? nvec : 1, 256 * EW_VEC_PER_THREAD);
   if (bf16) {
-    if (act == ACT_RELU) hipLaunchKernelGGL(act_grad_bf16_kernel<ACT_RELU>, dim3(nb), dim3(256), 0, s, (const u32x4*)dA, (const u32x4*)S, (u32x4*)dY, nvec, n);
-    else if (act == ACT_GELU) hipLaunchKernelGGL(act_grad_bf16_kernel<ACT_GELU>, dim3(nb), dim3(256), 0, s, (const u32x4*)dA, (const u32x4*)S, (u32x4*)dY, nvec, n);
-    else if (act == ACT_TANH) hipLaunchKernelGGL(act_grad_bf16_kernel<ACT_TANH>, dim3(nb), dim3(256), 0, s, (const u32x4*)dA, (const u32x4*)S, (u32x4*)dY, nvec, n);
-    else if (act == ACT_SIGMOID) hipLaunchKernelGGL(act_grad_bf16_kernel<ACT_SIGMOID>, dim3(nb), dim3(256), 0, s, (const u32x4*)dA, (const u32x4*)S, (u32x4*)dY, nvec, n);
+    const float* no_lut = nullptr;
+    if (act == ACT_RELU) hipLaunchKernelGGL(act_grad_bf16_kernel<ACT_RELU>, dim3(nb), dim3(256), 0, s, (const u32x4*)dA, (const u32x4*)S, (u32x4*)dY, nvec, n, no_lut);
+    else if (act == ACT_GELU && gelu_grad_lut) hipLaunchKernelGGL(act_grad_bf16_kernel<ACT_LUT>, dim3(nb), dim3(256), 0, s, (const u32x4*)dA, (const u32x4*)S, (u32x4*)dY, nvec, n, gelu_grad_lut);
+    else if (act == ACT_GELU) hipLaunchKernelGGL(act_grad_bf16_kernel<ACT_GELU>, dim3(nb), dim3(256), 0, s, (const u32x4*)dA, (const u32x4*)S, (u32x4*)dY, nvec, n, no_lut);
+    else if (act == ACT_TANH) hipLaunchKernelGGL(act_grad_bf16_kernel<ACT_TANH>, dim3(nb), dim3(256), 0, s, (const u32x4*)dA, (const u32x4*)S, (u32x4*)dY, nvec, n, no_lut);
+    else if (act == ACT_SIGMOID) hipLaunchKernelGGL(act_grad_bf16_kernel<ACT_SIGMOID>, dim3(nb), dim3(256), 0, s, (const u32x4*)dA, (const u32x4*)S, (u32x4*)dY, nvec, n, no_lut);
     else return hipErrorInvalidValue;
   } else {
     if (act == ACT_RELU) hipLaunchKernelGGL(act_grad_f32_kernel<ACT_RELU>, dim3(nb), dim3(256), 0, s, (const f32x4*)dA, (const f32x4*)S, (f32x4*)dY, nvec, n);

@@ -33,6 +33,8 @@ struct GemmKArgs {
   float* sgd_master;    // SGD variants: fp32 master weights updated in the epilogue
   float neg_lr;
   const unsigned short* act_lut;   // optional table of the activation over all bf16 inputs (GELU)
+  const unsigned short* had_s;     // dX form only: stash of the preceding layer; the Hadamard product of Eq. 3 is then applied on the way out
+  const float* had_lut;            // ... with f' looked up here (null: the ReLU form)
 };
 
 template <bool KC, int R, int BK, int NT, bool ALIGNED>
@@ -72,7 +74,7 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_bf16_kernel(GemmKArgs p) {
     StoreEpilogue epi{nullptr, nullptr, p.partial + (size_t)blockIdx.y * p.M * p.N, p.M, p.N, p.N, 0, m0, n0, (p.N % 4) == 0};
     gemm_tile<BM, BN, BK, WM, WN>(sa, sb, kt0, kt1, smem, epi);
   } else {
-    StoreEpilogue epi{p.out_z, p.out_a, p.out_f32, p.M, p.N, p.ldc, p.act, m0, n0, p.vec_out != 0, p.act_lut};
+    StoreEpilogueT<AKC && BKC> epi{p.out_z, p.out_a, p.out_f32, p.M, p.N, p.ldc, p.act, m0, n0, p.vec_out != 0, p.act_lut, p.had_s, p.had_lut};
     gemm_tile<BM, BN, BK, WM, WN>(sa, sb, 0, (p.K + BK - 1) / BK, smem, epi);
   }
 }
@@ -104,7 +106,7 @@ __global__ void __launch_bounds__(WM* WN * 64) gemm_bf16_dl_kernel(GemmKArgs p) 
     dl::gemm_tile_dl<BM, BN, BK, NSTAGE, WM, WN>(oa, ob, kt0 * BK, kt1 > kt0 ? kt1 - kt0 : 0, smem, epi);
     return;
   }
-  StoreEpilogue epi{p.out_z, p.out_a, p.out_f32, p.M, p.N, p.ldc, p.act, tm * BM, tn * BN, p.vec_out != 0, p.act_lut};
+  StoreEpilogueT<AKC && BKC> epi{p.out_z, p.out_a, p.out_f32, p.M, p.N, p.ldc, p.act, tm * BM, tn * BN, p.vec_out != 0, p.act_lut, p.had_s, p.had_lut};
   dl::gemm_tile_dl<BM, BN, BK, NSTAGE, WM, WN>(oa, ob, 0, KT, smem, epi);
 }
 
@@ -146,7 +148,7 @@ __global__ void __launch_bounds__(256) splitk_reduce_kernel(const float* __restr
         }
     }
   }
-  StoreEpilogue epi{p.out_z, p.out_a, p.out_f32, p.M, p.N, p.ldc, p.act, 0, 0, p.vec_out != 0, p.act_lut};
+  StoreEpilogueT<true> epi{p.out_z, p.out_a, p.out_f32, p.M, p.N, p.ldc, p.act, 0, 0, p.vec_out != 0, p.act_lut, p.had_s, p.had_lut};
   epi.with_static_act([&](auto store) { store(row, col, acc); });
 }
 
@@ -331,45 +333,65 @@ hipError_t launch_mfma_only(float* out, int workgroups, int iters, bool uniform_
   return hipGetLastError();
 }
 
-// ---- GELU over all bfloat16 inputs --------------------------------------------------------------------
-// A bf16 activation has 65536 possible inputs.  In a product's epilogue the exact GELU costs about 28 vector
+// ---- GELU and its derivative over all bfloat16 inputs ---------------------------------------------------
+// A bf16 pre-activation has 65536 possible values.  In a product's epilogue the exact GELU costs about 28 vector
 // instructions per element, and that arithmetic is exposed (every workgroup of a round reaches its epilogue at the
-// same time); a look-up costs one 2-byte gather from a table whose live part (|z| < 8: some 3000 entries) sits in the
-// CU's L1.  The table is a static device array of the library (128 KiB per GPU, kept until the process ends), filled
-// once per device by a kernel that evaluates z * Phi(z) in fp64 and rounds to nearest even, so an entry is the
-// correctly rounded GELU of the stored z (up to the double rounding through fp32).
+// same time); a look-up costs one gather from a table whose live part (2^-10 <= |z| < 16: some 3300 entries) sits in
+// the CU's L1.  Two tables, static device arrays of the library (128 + 256 KiB per GPU, kept until the process ends),
+// each filled once per device by a kernel that evaluates in fp64 and rounds to nearest even:
+//   gelu_table[z]       z Phi(z) as bf16       (the F epilogue's second output)
+//   gelu_grad_table[z]  Phi(z) + z phi(z) as fp32   (the factor of the Hadamard product, Eq. 3)
+// Phi through erfc, so that nothing cancels for z << 0.
 namespace {
 static __device__ __align__(256) unsigned short gelu_table[65536];
+static __device__ __align__(256) float gelu_grad_table[65536];
 __global__ void __launch_bounds__(256) gelu_table_fill_kernel(unsigned short* __restrict__ t) {
   const unsigned i = blockIdx.x * 256 + threadIdx.x;
   const double z = (double)bf16_to_f32((unsigned short)i);
-  t[i] = bf16_bits((float)(0.5 * z * erfc(-z * 0.70710678118654752440)));   // erfc: no cancellation for z << 0
+  t[i] = bf16_bits((float)(0.5 * z * erfc(-z * 0.70710678118654752440)));
+}
+__global__ void __launch_bounds__(256) gelu_grad_table_fill_kernel(float* __restrict__ t) {
+  const unsigned i = blockIdx.x * 256 + threadIdx.x;
+  const double z = (double)bf16_to_f32((unsigned short)i);
+  const double cdf = 0.5 * erfc(-z * 0.70710678118654752440);
+  const double pdf = 0.39894228040143267794 * exp(-0.5 * z * z);
+  t[i] = (float)(cdf + (pdf > 0.0 ? z * pdf : 0.0));   // +-inf: 1 and 0, not inf * 0
 }
 constexpr int kMaxDevices = 64;
-std::mutex gelu_table_mutex;
-const unsigned short* gelu_table_ptr[kMaxDevices] = {};
-}  // namespace
+std::mutex table_mutex;
+const void* table_ptr[2][kMaxDevices] = {};
 
-hipError_t gelu_lut_bf16(const void** out, hipStream_t s) {
+// which: 0 = gelu_table, 1 = gelu_grad_table
+hipError_t table_of_device(int which, const void** out, hipStream_t s) {
   int dev = -1;
   hipError_t e = hipGetDevice(&dev);
   if (e != hipSuccess) return e;
   if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
-  std::lock_guard<std::mutex> lock(gelu_table_mutex);
-  if (!gelu_table_ptr[dev]) {
+  std::lock_guard<std::mutex> lock(table_mutex);
+  if (!table_ptr[which][dev]) {
     void* p = nullptr;
-    e = hipGetSymbolAddress(&p, HIP_SYMBOL(gelu_table));   // this device's copy
+    e = which == 0 ? hipGetSymbolAddress(&p, HIP_SYMBOL(gelu_table)) : hipGetSymbolAddress(&p, HIP_SYMBOL(gelu_grad_table));   // this device's copy
     if (e != hipSuccess) return e;
     if (!p) return hipErrorInvalidSymbol;
-    hipLaunchKernelGGL(gelu_table_fill_kernel, dim3(256), dim3(256), 0, s, (unsigned short*)p);
+    if (which == 0) hipLaunchKernelGGL(gelu_table_fill_kernel, dim3(256), dim3(256), 0, s, (unsigned short*)p);
+    else hipLaunchKernelGGL(gelu_grad_table_fill_kernel, dim3(256), dim3(256), 0, s, (float*)p);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     e = hipStreamSynchronize(s);   // kernels on any other stream may read the table from now on
     if (e != hipSuccess) return e;
-    gelu_table_ptr[dev] = (const unsigned short*)p;
+    table_ptr[which][dev] = p;
   }
-  *out = gelu_table_ptr[dev];
+  *out = table_ptr[which][dev];
   return hipSuccess;
+}
+}  // namespace
+
+hipError_t gelu_lut_bf16(const void** out, hipStream_t s) { return table_of_device(0, out, s); }
+hipError_t gelu_grad_lut_f32(const float** out, hipStream_t s) {
+  const void* p = nullptr;
+  const hipError_t e = table_of_device(1, &p, s);
+  if (e == hipSuccess) *out = (const float*)p;
+  return e;
 }
 
 int gemm_bf16_num_cfgs() { return (int)(sizeof(kCfgs) / sizeof(kCfgs[0])); }
@@ -402,6 +424,13 @@ hipError_t launch_gemm_bf16(const GemmDesc& d, hipStream_t s, int tile_cfg) {
   a.sgd_master = d.sgd_master;
   a.neg_lr = -d.sgd_lr;
   a.act_lut = (d.act == ACT_GELU && d.out_a) ? (const unsigned short*)d.act_lut : nullptr;
+  a.had_s = (const unsigned short*)d.had_s;
+  a.had_lut = d.had_s ? d.had_lut : nullptr;
+  if (d.had_s) {
+    // the fused Hadamard product exists in the dX form only and writes nothing but out_z
+    if (!d.a_kcontig || !d.b_kcontig || !d.out_z || d.out_a || d.out_f32 || d.sgd_master) return hipErrorInvalidValue;
+    a.vec_out = a.vec_out && ((uintptr_t)d.had_s % 8 == 0);
+  }
   const bool sgd = d.sgd_master != nullptr;
   if (sgd) {
     if (d.a_kcontig || d.b_kcontig || !d.out_z) return hipErrorInvalidValue;

@@ -203,6 +203,67 @@ __device__ __forceinline__ void tile_of_block(int pid, int nbm, int nbn, int& tm
   tn = (lid % width) / gsz;
 }
 
+// Accumulators of one wave (TM x TN blocks of 32 x 32, the layout v_mfma_f32_32x32x16 leaves them in) to memory: band by
+// band of 32 rows through this wave's strip of LDS, so that a lane then owns four consecutive columns of a row and a
+// wavefront writes whole 128-byte lines.  `smem` must be free (all waves past their last fragment read) and hold
+// waves x 32 x (TN*32+8) floats.  epi is asked once for a view with its run-time switches turned into compile-time
+// constants (with_static_act); a view that needs a second operand per output element (kHasSide: the stash of a fused
+// Hadamard product) is asked for it one band ahead, so that those loads are in flight during the trip through LDS.
+struct NoSide {};
+template <int TM, int TN, class Epi>
+__device__ __forceinline__ void epilogue_through_lds(float* smem, const f32x16 (&acc)[TM][TN], int wave, int lane, int row0, int col0,
+                                                     const Epi& epi) {
+  constexpr int EP_LD = TN * 32 + 8;
+  constexpr int NE = 4 * TN;   // 16-byte groups of a band per lane
+  float* ep = smem + wave * (32 * EP_LD);
+  epi.with_static_act([&](auto store) {
+    using Store = decltype(store);
+    using Side = typename Store::Side;
+    Side side[2][NE];
+    auto fetch = [&](int i, Side (&sd)[NE]) {
+#pragma unroll
+      for (int q = 0; q < NE; ++q) {
+        const int e = lane + 64 * q;
+        sd[q] = store.side(row0 + i * 32 + e / (TN * 8), col0 + (e % (TN * 8)) * 4);
+      }
+    };
+    if constexpr (Store::kHasSide) fetch(0, side[0]);
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+      if constexpr (Store::kHasSide) {
+        if (i + 1 < TM) fetch(i + 1, side[(i + 1) & 1]);
+      }
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+          ep[((r >> 2) * 8 + (lane >> 5) * 4 + (r & 3)) * EP_LD + j * 32 + (lane & 31)] = acc[i][j][r];
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+      if constexpr (Store::kHasSide) {
+#pragma unroll
+        for (int q = 0; q < NE; ++q) {
+          const int e = lane + 64 * q;
+          const int row = e / (TN * 8), c4 = e % (TN * 8);
+          const f32x4 v = *reinterpret_cast<const f32x4*>(ep + row * EP_LD + c4 * 4);
+          store(row0 + i * 32 + row, col0 + c4 * 4, v, side[i & 1][q]);
+        }
+      } else {
+#pragma unroll 4
+        for (int e = lane; e < 32 * TN * 8; e += 64) {
+          const int row = e / (TN * 8), c4 = e % (TN * 8);
+          const f32x4 v = *reinterpret_cast<const f32x4*>(ep + row * EP_LD + c4 * 4);
+          store(row0 + i * 32 + row, col0 + c4 * 4, v);
+        }
+      }
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    }
+  });
+}
+
 // Accumulates K tiles [kt0, kt1) of the BM x BN tile and hands the result to epi(row_in_tile,
 // col_in_tile, four consecutive columns).  smem: 2 * (BM + BN) * BK halves.
 //
@@ -308,30 +369,7 @@ __device__ __forceinline__ void gemm_tile(SA& sa, SB& sb, int kt0, int kt1, unsi
   if (kt0 < kt1) step(kt1 - 1, std::false_type{});
   __syncthreads();
 
-  constexpr int EP_LD = TN * 32 + 8;
-  float* ep = reinterpret_cast<float*>(smem) + wave * (32 * EP_LD);
-  epi.with_static_act([&](auto store) {
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-#pragma unroll
-      for (int j = 0; j < TN; ++j)
-#pragma unroll
-        for (int r = 0; r < 16; ++r)
-          ep[((r >> 2) * 8 + (lane >> 5) * 4 + (r & 3)) * EP_LD + j * 32 + (lane & 31)] = acc[i][j][r];
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-      __builtin_amdgcn_wave_barrier();
-      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-#pragma unroll 4
-      for (int e = lane; e < 32 * TN * 8; e += 64) {
-        const int row = e / (TN * 8), c4 = e % (TN * 8);
-        const f32x4 v = *reinterpret_cast<const f32x4*>(ep + row * EP_LD + c4 * 4);
-        store(wm * (TM * 32) + i * 32 + row, wn * (TN * 32) + c4 * 4, v);
-      }
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-      __builtin_amdgcn_wave_barrier();
-      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    }
-  });
+  epilogue_through_lds<TM, TN>(reinterpret_cast<float*>(smem), acc, wave, lane, wm * (TM * 32), wn * (TN * 32), epi);
 }
 
 template <int ACT>
@@ -347,7 +385,12 @@ __device__ __forceinline__ float apply_act_static(float z) {
 // vec: N, ldc and the output pointers allow 8-/16-byte stores.
 // The activation is a run-time field; an epilogue that handles many elements per lane asks for a view with the
 // activation as a compile-time constant once (with_static_act) instead of deciding it per element.
-struct StoreEpilogue {
+// HAD (the dX form only, to keep the other kernels small): the product is dA of the preceding layer and had_s that
+// layer's stash S; what goes to out_z is then dY = q(q(dA) * f'(S)) (Eq. 3 moved into the product that feeds it,
+// Sec. III-B), the arithmetic of the stand-alone Hadamard kernel element for element: dA is rounded to bf16 first,
+// exactly as if it had been stored and read back.
+template <bool HAD>
+struct StoreEpilogueT {
   unsigned short* out_z;
   unsigned short* out_a;
   float* out_f32;
@@ -355,7 +398,12 @@ struct StoreEpilogue {
   bool vec;
   // optional: f(z) for every bfloat16 bit pattern z (65536 entries); when set, A is looked up instead of computed
   const unsigned short* act_lut;
-  // ACT < 0: the activation is read from `act`
+  // HAD: stash of the preceding layer (indexed like out_z; 8-byte aligned rows when vec), and f'(z) for every bfloat16
+  // bit pattern z as fp32 (null: f' = [S > 0], the ReLU form)
+  const unsigned short* had_s;
+  const float* had_lut;
+
+  // ACT < 0: the activation is read from `act`; 5: table look-up
   template <int ACT>
   __device__ __forceinline__ void store(int r, int c, const f32x4& v) const {
     const int row = m0 + r, col = n0 + c;
@@ -391,18 +439,67 @@ struct StoreEpilogue {
     }
   }
   __device__ __forceinline__ void operator()(int r, int c, const f32x4& v) const { store<-1>(r, c, v); }
+
+  // the four stash values that belong to store_had(r, c, ...); zeros where they are not read ahead
+  __device__ __forceinline__ u32x2 had_side(int r, int c) const {
+    const int row = m0 + r, col = n0 + c;
+    if (!vec || row >= M || col >= N) return u32x2{0u, 0u};
+    return *reinterpret_cast<const u32x2*>(had_s + (size_t)row * ldc + col);
+  }
+  template <bool LUT>
+  __device__ __forceinline__ unsigned short had_one(float v, unsigned short s) const {
+    const float da = bf16_to_f32(bf16_bits(v));
+    const float df = LUT ? had_lut[s] : (bf16_to_f32(s) > 0.f ? 1.f : 0.f);
+    return bf16_bits(da * df);
+  }
+  template <bool LUT>
+  __device__ __forceinline__ void store_had(int r, int c, const f32x4& v, const u32x2& sd) const {
+    const int row = m0 + r, col = n0 + c;
+    if (row >= M || col >= N) return;
+    const size_t o = (size_t)row * ldc + col;
+    if (vec) {
+      const unsigned short y0 = had_one<LUT>(v[0], (unsigned short)(sd[0] & 0xffffu)), y1 = had_one<LUT>(v[1], (unsigned short)(sd[0] >> 16));
+      const unsigned short y2 = had_one<LUT>(v[2], (unsigned short)(sd[1] & 0xffffu)), y3 = had_one<LUT>(v[3], (unsigned short)(sd[1] >> 16));
+      *reinterpret_cast<u32x2*>(out_z + o) = u32x2{(unsigned)y0 | ((unsigned)y1 << 16), (unsigned)y2 | ((unsigned)y3 << 16)};
+    } else {
+#pragma unroll
+      for (int t = 0; t < 4; ++t)
+        if (col + t < N) out_z[o + t] = had_one<LUT>(v[t], had_s[o + t]);
+    }
+  }
+
   template <int ACT>
   struct StaticAct {
-    const StoreEpilogue& e;
+    const StoreEpilogueT& e;
+    static constexpr bool kHasSide = false;
+    using Side = NoSide;
+    __device__ __forceinline__ NoSide side(int, int) const { return NoSide{}; }
     __device__ __forceinline__ void operator()(int r, int c, const f32x4& v) const { e.template store<ACT>(r, c, v); }
+    __device__ __forceinline__ void operator()(int r, int c, const f32x4& v, NoSide) const { e.template store<ACT>(r, c, v); }
+  };
+  template <bool LUT>
+  struct Hadamard {
+    const StoreEpilogueT& e;
+    static constexpr bool kHasSide = true;
+    using Side = u32x2;
+    __device__ __forceinline__ u32x2 side(int r, int c) const { return e.had_side(r, c); }
+    __device__ __forceinline__ void operator()(int r, int c, const f32x4& v, const u32x2& sd) const { e.template store_had<LUT>(r, c, v, sd); }
+    __device__ __forceinline__ void operator()(int r, int c, const f32x4& v) const { e.template store_had<LUT>(r, c, v, e.had_side(r, c)); }
   };
   // calls f with a view of this epilogue whose activation is a compile-time constant (same arithmetic, element for element)
   template <class F>
   __device__ __forceinline__ void with_static_act(F&& f) const {
+    if constexpr (HAD) {
+      if (had_s) {
+        if (had_lut) f(Hadamard<true>{*this});
+        else f(Hadamard<false>{*this});
+        return;
+      }
+    }
     switch (out_a ? act : 0) {
       case 1: f(StaticAct<1>{*this}); break;
       case 2:
-        if (act_lut) f(StaticAct<5>{*this});   // 5: table look-up
+        if (act_lut) f(StaticAct<5>{*this});
         else f(StaticAct<2>{*this});
         break;
       case 3: f(StaticAct<3>{*this}); break;
@@ -411,6 +508,7 @@ struct StoreEpilogue {
     }
   }
 };
+using StoreEpilogue = StoreEpilogueT<false>;
 
 // Epilogue of a weight-gradient product that is consumed on the spot (Eq. 6 fused into Eq. 5): the
 // tile of G never goes to memory; W <- W - lr * G on the fp32 master, and the bf16 working copy of the
@@ -444,6 +542,10 @@ struct SgdEpilogue {
       }
     }
   }
+  static constexpr bool kHasSide = false;
+  using Side = NoSide;
+  __device__ __forceinline__ NoSide side(int, int) const { return NoSide{}; }
+  __device__ __forceinline__ void operator()(int r, int c, const f32x4& g, NoSide) const { (*this)(r, c, g); }
   template <class F>
   __device__ __forceinline__ void with_static_act(F&& f) const { f(*this); }
 };

@@ -337,32 +337,8 @@ __device__ __forceinline__ void gemm_tile_dl(const OA& oa_in, const OB& ob_in, i
   wait_vmcnt<0>();   // the trailing (empty) tiles still write LDS
   __syncthreads();
 
-  // epilogue through LDS, as in gemm_core.h
-  constexpr int EP_LD = TN * 32 + 8;
-  static_assert(WM * WN * 32 * EP_LD * 4 <= NSTAGE * STAGE * 2, "epilogue band does not fit the ring");
-  float* ep = reinterpret_cast<float*>(smem) + wave * (32 * EP_LD);
-  epi.with_static_act([&](auto store) {
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-#pragma unroll
-      for (int j = 0; j < TN; ++j)
-#pragma unroll
-        for (int r = 0; r < 16; ++r)
-          ep[((r >> 2) * 8 + (lane >> 5) * 4 + (r & 3)) * EP_LD + j * 32 + (lane & 31)] = acc[i][j][r];
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-      __builtin_amdgcn_wave_barrier();
-      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-#pragma unroll 4
-      for (int e = lane; e < 32 * TN * 8; e += 64) {
-        const int row = e / (TN * 8), c4 = e % (TN * 8);
-        const f32x4 v = *reinterpret_cast<const f32x4*>(ep + row * EP_LD + c4 * 4);
-        store(wm * (TM * 32) + i * 32 + row, wn * (TN * 32) + c4 * 4, v);
-      }
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-      __builtin_amdgcn_wave_barrier();
-      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    }
-  });
+  static_assert(WM * WN * 32 * (TN * 32 + 8) * 4 <= NSTAGE * STAGE * 2, "epilogue band does not fit the ring");
+  core::epilogue_through_lds<TM, TN>(reinterpret_cast<float*>(smem), acc, wave, lane, wm * (TM * 32), wn * (TN * 32), epi);
 }
 
 }  // namespace dl

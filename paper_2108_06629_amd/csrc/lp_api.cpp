@@ -63,6 +63,8 @@ struct lp_ctx {
   long graph_captured = 0, graph_replayed = 0, graph_eager = 0;
   char* ws = nullptr;
   const void* gelu_lut = nullptr;   // GELU over all bf16 inputs (lp::gelu_lut_bf16), looked up by the F epilogue of GELU layers
+  const float* gelu_grad_lut = nullptr;   // its derivative (lp::gelu_grad_lut_f32), looked up by the Hadamard product
+  bool fuse_hadamard = true;        // lp_step folds f'(S_{l-1}) (.) into the epilogue of dX_l where the pair of layers allows it
   long n = 0;
   std::string err;
   bool events_ready = false;
@@ -236,8 +238,12 @@ hipError_t do_forward(lp_ctx* c, Layer& ly, const void* X, void* Z, void* A, hip
   return lp::launch_conv_fwd(cd, is_bf16(c), X, work_w(c, ly), Z, A, ly.d.act, s);
 }
 
-hipError_t do_grad_act(lp_ctx* c, Layer& ly, const void* dY, void* dX, int c0, int c1, hipStream_t s) {
+// had_of/S: the preceding layer and its stash when its Hadamard product (Eq. 3) rides in this product's epilogue
+// (hadamard_fused); dX then receives dY_{l-1} and dA_{l-1} is never stored.
+hipError_t do_grad_act(lp_ctx* c, Layer& ly, const void* dY, void* dX, int c0, int c1, hipStream_t s, const Layer* had_of = nullptr,
+                       const void* S = nullptr) {
   ProfScope prof(c, LP_TASK_DX, layer_no(c, ly), s);
+  if (had_of && (ly.d.kind != LP_LINEAR || !is_bf16(c) || !S)) return hipErrorInvalidValue;
   if (ly.d.kind == LP_LINEAR) {
     lp::GemmDesc g;
     const size_t es = esize(c);
@@ -246,6 +252,10 @@ hipError_t do_grad_act(lp_ctx* c, Layer& ly, const void* dY, void* dX, int c0, i
     g.lda = ly.d.out; g.ldb = ly.d.out; g.ldc = ly.d.in;
     g.a_kcontig = true; g.b_kcontig = true;
     g.out_z = (char*)dX + (size_t)c0 * es;
+    if (had_of) {
+      g.had_s = (const char*)S + (size_t)c0 * es;
+      g.had_lut = had_of->d.act == LP_ACT_GELU ? c->gelu_grad_lut : nullptr;
+    }
     // K is cut as for the whole product, whatever the column range: the split changes no bits
     const int sk = c0 == 0 ? 0 : 2;
     g.splitk_splits = lp::gemm_bf16_splitk_splits(c->batch, ly.d.in, ly.d.out);
@@ -274,7 +284,18 @@ hipError_t do_act_grad(lp_ctx* c, Layer& ly, const void* dA, const void* S, void
   ProfScope prof(c, LP_TASK_HADAMARD, layer_no(c, ly), s);
   if (ly.d.kind == LP_CONV3X3 && ly.d.pool == 2)
     return lp::launch_act_grad_pool(is_bf16(c), ly.d.act, dA, S, dY, c->batch, ly.d.H, ly.d.W, ly.d.out, s);
-  return lp::launch_act_grad(is_bf16(c), ly.d.act, dA, S, dY, ly.z_elems, s);
+  return lp::launch_act_grad(is_bf16(c), ly.d.act, dA, S, dY, ly.z_elems, s, is_bf16(c) ? c->gelu_grad_lut : nullptr);
+}
+
+// Whether lp_step applies the Hadamard product of layer `pv` inside the dX product of the layer `ly` above it
+// (Sec. III-B moves that product next to the task that feeds it; here it shares its kernel): a fully connected `ly`
+// of a bf16 context, an element-wise ReLU or GELU below it (a pooled layer routes its gradient, tanh / sigmoid keep
+// the stand-alone kernel).  Same bits either way.
+bool hadamard_fused(const lp_ctx* c, const Layer& ly, const Layer& pv) {
+  if (!c->fuse_hadamard || !is_bf16(c) || ly.d.kind != LP_LINEAR) return false;
+  if (pv.off_dY == pv.off_dA) return false;   // identity: there is no product
+  if (pv.d.kind == LP_CONV3X3 && pv.d.pool == 2) return false;
+  return pv.d.act == LP_ACT_RELU || (pv.d.act == LP_ACT_GELU && c->gelu_grad_lut != nullptr);
 }
 
 hipError_t do_loss(lp_ctx* c, const void* ZL, const void* target, void* dYL, float* loss_dev, hipStream_t s) {
@@ -478,21 +499,22 @@ int step_run_ahead(lp_ctx* c, const void* X0, const void* target, float* loss_de
     const void* dY = c->ws + ly.off_dY;
     if (i > 0) {
       Layer& pv = c->layers[i - 1];
+      const void* S = pv.has_Z ? c->ws + pv.off_Z[p] : c->ws + pv.off_A[p];
+      const bool fused = hadamard_fused(c, ly, pv);
+      void* dX = c->ws + (fused ? pv.off_dY : pv.off_dA);
+      const Layer* had = fused ? &pv : nullptr;
       if (ly.split_cols > 0) {
         const int cut = ly.d.in - ly.split_cols;
         LP_HIP(c, wait_on(c, sW, c->ev_dy[i]));
-        LP_HIP(c, do_grad_act(c, ly, dY, c->ws + pv.off_dA, cut, ly.d.in, sW));
+        LP_HIP(c, do_grad_act(c, ly, dY, dX, cut, ly.d.in, sW, had, S));
         LP_HIP(c, record_on(c, c->ev_split[i], sW));
-        LP_HIP(c, do_grad_act(c, ly, dY, c->ws + pv.off_dA, 0, cut, sC));
+        LP_HIP(c, do_grad_act(c, ly, dY, dX, 0, cut, sC, had, S));
         LP_HIP(c, wait_on(c, sC, c->ev_split[i]));
       } else {
-        LP_HIP(c, do_grad_act(c, ly, dY, c->ws + pv.off_dA, 0, ly.d.in, sC));
+        LP_HIP(c, do_grad_act(c, ly, dY, dX, 0, ly.d.in, sC, had, S));
       }
       LP_HIP(c, record_on(c, c->ev_dx[i], sC));
-      if (pv.off_dY != pv.off_dA) {
-        const void* S = pv.has_Z ? c->ws + pv.off_Z[p] : c->ws + pv.off_A[p];
-        LP_HIP(c, do_act_grad(c, pv, c->ws + pv.off_dA, S, c->ws + pv.off_dY, sC));
-      }
+      if (pv.off_dY != pv.off_dA && !fused) LP_HIP(c, do_act_grad(c, pv, c->ws + pv.off_dA, S, c->ws + pv.off_dY, sC));
       LP_HIP(c, record_on(c, c->ev_dy[i - 1], sC));
     }
     LP_HIP(c, wait_on(c, sW, c->ev_dy[i]));
@@ -568,23 +590,24 @@ int enqueue_step(lp_ctx* c, const void* X0, const void* target, float* loss_dev,
     const void* dY = c->ws + ly.off_dY;
     if (i > 0) {
       Layer& pv = c->layers[i - 1];
+      const void* S = pv.has_Z ? c->ws + pv.off_Z[0] : c->ws + pv.off_A[0];
+      const bool fused = hadamard_fused(c, ly, pv);   // then dX_l writes dY_{l-1} itself
+      void* dX = c->ws + (fused ? pv.off_dY : pv.off_dA);
+      const Layer* had = fused ? &pv : nullptr;
       if (ly.split_cols > 0) {
         // delta' on the critical stream, delta'' (the columns the next stage borrowed, Sec. III-B) as an
         // independent kernel on the stream that otherwise carries the G tasks, ahead of this layer's G
         const int cut = ly.d.in - ly.split_cols;
         if (multi && sW != sC) LP_HIP(c, wait_on(c, sW, c->ev_dy[i]));
-        LP_HIP(c, do_grad_act(c, ly, dY, c->ws + pv.off_dA, cut, ly.d.in, sW));
+        LP_HIP(c, do_grad_act(c, ly, dY, dX, cut, ly.d.in, sW, had, S));
         if (multi && sW != sC) LP_HIP(c, record_on(c, c->ev_split[i], sW));
-        LP_HIP(c, do_grad_act(c, ly, dY, c->ws + pv.off_dA, 0, cut, sC));
+        LP_HIP(c, do_grad_act(c, ly, dY, dX, 0, cut, sC, had, S));
         if (multi && sW != sC) LP_HIP(c, wait_on(c, sC, c->ev_split[i]));
       } else {
-        LP_HIP(c, do_grad_act(c, ly, dY, c->ws + pv.off_dA, 0, ly.d.in, sC));
+        LP_HIP(c, do_grad_act(c, ly, dY, dX, 0, ly.d.in, sC, had, S));
       }
       if (multi && !bf) LP_HIP(c, record_on(c, c->ev_dx[i], sC));   // only an in-place (F32) update waits for it
-      if (pv.off_dY != pv.off_dA) {
-        const void* S = pv.has_Z ? c->ws + pv.off_Z[0] : c->ws + pv.off_A[0];
-        LP_HIP(c, do_act_grad(c, pv, c->ws + pv.off_dA, S, c->ws + pv.off_dY, sC));
-      }
+      if (pv.off_dY != pv.off_dA && !fused) LP_HIP(c, do_act_grad(c, pv, c->ws + pv.off_dA, S, c->ws + pv.off_dY, sC));
       if (multi) LP_HIP(c, record_on(c, c->ev_dy[i - 1], sC));
     }
     // A G product that fills every CU with 256 x 256 tiles, next to a delta product that does so too, gains
@@ -819,6 +842,7 @@ int lp_set_weights(lp_ctx* c, int l, const float* W, int is_device, void* stream
     if (is_bf16(c)) LP_HIP(c, lp::launch_cast_bf16(master, c->ws + ly.off_work[ly.cur], ly.n_params, s));
     // the table the F epilogue of a GELU layer looks its activation up in: made ready here, outside any step
     if (is_bf16(c) && ly.d.kind == LP_LINEAR && ly.d.act == LP_ACT_GELU && !c->gelu_lut) LP_HIP(c, lp::gelu_lut_bf16(&c->gelu_lut, s));
+    if (is_bf16(c) && ly.d.act == LP_ACT_GELU && !c->gelu_grad_lut) LP_HIP(c, lp::gelu_grad_lut_f32(&c->gelu_grad_lut, s));
     ly.weights_set = true;
     return LP_OK;
   });
@@ -1035,6 +1059,15 @@ int lp_set_run_ahead(lp_ctx* c, int enable) {
   });
 }
 
+int lp_set_fused_hadamard(lp_ctx* c, int enable) {
+  return guarded(c, "lp_set_fused_hadamard", [&]() -> int {
+    if (!c) return LP_ERR_NULL;
+    if ((enable != 0) != c->fuse_hadamard) drop_graphs(c);   // captured steps hold the other kernel sequence
+    c->fuse_hadamard = enable != 0;
+    return LP_OK;
+  });
+}
+
 int lp_advance(lp_ctx* c) {
   if (!c) return LP_ERR_NULL;
   c->n += 1;
@@ -1109,7 +1142,9 @@ int lp_tensor(lp_ctx* c, int l, int which, void** dev_ptr, size_t* bytes) {
       case LP_T_WORK_W: *dev_ptr = work_w(c, ly); *bytes = ly.n_params * es; break;
       case LP_T_A: if (ly.has_A) { *dev_ptr = c->ws + ly.off_A[c->n & 1]; *bytes = ly.a_elems * es; } break;
       case LP_T_Z: if (ly.has_Z) { *dev_ptr = c->ws + ly.off_Z[c->n & 1]; *bytes = ly.z_elems * es; } break;
-      case LP_T_DA: if (ly.has_dA) { *dev_ptr = c->ws + ly.off_dA; *bytes = ly.a_elems * es; } break;
+      case LP_T_DA:   // not materialised when the layer above applies the Hadamard product in its dX epilogue
+        if (ly.has_dA && !(l < c->L && hadamard_fused(c, c->layers[l], ly))) { *dev_ptr = c->ws + ly.off_dA; *bytes = ly.a_elems * es; }
+        break;
       case LP_T_DY: *dev_ptr = c->ws + ly.off_dY; *bytes = ly.z_elems * es; break;
       case LP_T_G_LAST: if (c->n >= 1 && !ly.factor_ring) { *dev_ptr = ring_slot(c, ly, c->n); *bytes = ly.n_params * 4; } break;
       default: return fail(c, LP_ERR_DTYPE, "lp_tensor: unknown tensor id %d", which);

@@ -39,10 +39,18 @@ struct GemmDesc {
   float sgd_lr = 0.f;
   // optional, for act == ACT_GELU with out_a: the table gelu_lut_bf16 returns; A is then looked up, not computed
   const void* act_lut = nullptr;
+  // optional, dX form (both operands k contiguous) with out_z only: the product is dA of the preceding layer and
+  // had_s that layer's stash, laid out like out_z (same ldc); out_z then receives dY = q(q(dA) * f'(S)) (Eq. 3),
+  // bit for bit what launch_act_grad makes of the stored dA.  f' = [S > 0] (ReLU; S may be A or Z), or, with
+  // had_lut (the table gelu_grad_lut_f32 returns), the GELU derivative of S = Z.
+  const void* had_s = nullptr;
+  const float* had_lut = nullptr;
 };
 // Device address of GELU(z) for all 65536 bfloat16 bit patterns z (bf16 entries; a static array of the library,
 // one copy per GPU).  The first call on a device fills it with a kernel on `s` and waits for it: not under capture.
 hipError_t gelu_lut_bf16(const void** out, hipStream_t s);
+// The same for the derivative: Phi(z) + z phi(z) as fp32, the factor of the Hadamard product of a GELU layer.
+hipError_t gelu_grad_lut_f32(const float** out, hipStream_t s);
 // K ranges the launcher cuts a product of this shape into (1: not split), and the scratch that takes
 // (0: split-K would not be used)
 int gemm_bf16_splitk_splits(int M, int N, int K);
@@ -70,7 +78,8 @@ hipError_t launch_conv_grad_weight(const ConvDesc& c, bool bf16, const void* x, 
 size_t conv_grad_weight_scratch_bytes(const ConvDesc& c);
 
 // dY = dA (.) f'(S), n elements.
-hipError_t launch_act_grad(bool bf16, int act, const void* dA, const void* S, void* dY, size_t n, hipStream_t s);
+// gelu_grad_lut (bf16 GELU only, optional): the table gelu_grad_lut_f32 returns; f' is then looked up, not computed
+hipError_t launch_act_grad(bool bf16, int act, const void* dA, const void* S, void* dY, size_t n, hipStream_t s, const float* gelu_grad_lut = nullptr);
 // pooled conv layer: a[b,y/2,x/2,c] = max over window of relu(z)
 hipError_t launch_relu_pool(bool bf16, const void* z, void* a, int B, int H, int W, int C, int act, hipStream_t s);
 // pooled conv layer backward: dy (full res) from da (pooled) and z (full res)

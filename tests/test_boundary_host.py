@@ -236,3 +236,23 @@ def test_mfma_probe_checks_its_arguments_before_launching():
     assert L.lp_probe_mfma(fake, 511, 1, 1, 0, None) == 2        # LP_ERR_SHAPE: one workgroup writes 512 floats
     assert L.lp_probe_mfma(fake, 1 << 20, 0, 1, 0, None) == 2    # no workgroups
     assert L.lp_probe_mfma(fake, 1 << 20, 1, -1, 0, None) == 2   # negative round count
+
+
+def test_fused_hadamard_switch_decides_whether_dA_is_materialised():
+    """Host bookkeeping only: with the Hadamard product of a ReLU layer inside the dX product above it (the default), that
+    layer's dA has no address; with the switch off it has one.  An F32 context never fuses."""
+    wl = WL.mlp_4096()
+    L = lp.lib()
+    ctx = lp.lp_create(descs(wl), wl.L, wl.batch, lp.LP_BF16, lp.LP_LOSS_SOFTMAX_CE, 1e-3)
+    assert L.lp_bind_workspace(ctx, 0x10000, 1 << 40) == 0
+    assert all(not lp.lp_tensor(ctx, l, lp.LP_T_DA)[0] for l in range(1, wl.L))
+    assert L.lp_set_fused_hadamard(ctx, 0) == 0
+    assert all(lp.lp_tensor(ctx, l, lp.LP_T_DA)[0] for l in range(1, wl.L))
+    assert L.lp_set_fused_hadamard(ctx, 1) == 0 and not lp.lp_tensor(ctx, 1, lp.LP_T_DA)[0]
+    assert L.lp_set_fused_hadamard(None, 1) == 1
+    lp.lp_destroy(ctx)
+    small = WL.mlp_small()
+    ctx = lp.lp_create(descs(small), small.L, small.batch, lp.LP_F32, lp.LP_LOSS_SOFTMAX_CE, 0.01)
+    assert L.lp_bind_workspace(ctx, 0x10000, 1 << 40) == 0
+    assert all(lp.lp_tensor(ctx, l, lp.LP_T_DA)[0] for l in range(1, small.L))
+    lp.lp_destroy(ctx)

@@ -48,8 +48,10 @@ def f64(t):
 
 
 @pytest.mark.timeout(900)
-def test_ffn_stack_full_size_sampled():
-    """The largest workload for its configured 10 steps.  Layers with d_l <= 9 (the last five) receive delayed updates
+@pytest.mark.parametrize("fused", [True, False])
+def test_ffn_stack_full_size_sampled(fused):
+    """`fused`: the Hadamard products inside the dX products (lp_step's default) or as kernels of their own, which keeps dA.
+    The largest workload for its configured 10 steps.  Layers with d_l <= 9 (the last five) receive delayed updates
     in that time; the others must stay bit-identical to their initial weights.  Every step: the update of every layer
     on a sampled 48 x 48 block of its weights against Eq. 6 with the GPU's own sampled gradient of d_l steps ago, and
     the working copy against the rounded master.  Steps 1 and 10: every task's output on sampled rows and columns,
@@ -58,7 +60,7 @@ def test_ffn_stack_full_size_sampled():
     assert wl.batch == 8192 and wl.L == 16 and wl.n_params == 16 * 4096 * 16384 and wl.steps == 10
     rng = np.random.default_rng(7)
     W0 = WL.init_weights(wl)
-    net = lp.Network(wl.layers, wl.batch, wl.dtype, wl.loss, wl.lr, wl.delays)
+    net = lp.Network(wl.layers, wl.batch, wl.dtype, wl.loss, wl.lr, wl.delays, fused_hadamard=fused)
     net.set_weights(W0)
     B, L = wl.batch, wl.L
     rows = np.sort(rng.choice(B, 12, replace=False))
@@ -129,16 +131,22 @@ def test_ffn_stack_full_size_sampled():
                     # dX (Eq. 4): dA_{l-1}[rows, kin] = dY[rows] . W[kin, :]^T
                     da_ref = O.store(f64(dY[rt]) @ Wr[l - 1].T, "bf16")
                     dAg = view(l - 1, lp.LP_T_DA, prev.d_out)
-                    assert relerr(f64(dAg[rt][:, kt]), da_ref) <= 2e-2, ("dX", l, n)
-                    # the moved Hadamard (Eq. 3) on whole sampled rows
                     stash = view(l - 1, lp.LP_T_Z, prev.d_out)
                     stash = A[l - 1] if stash is None else stash
-                    dy_prev_ref = O.store(O.act_grad(f64(dAg[rt]), f64(stash[rt]), prev.act), "bf16")
                     dy_prev = f64(view(l - 1, lp.LP_T_DY, prev.d_out)[rt])
-                    if prev.act == WL.GELU:
-                        assert relerr(dy_prev, dy_prev_ref) <= 2.0 ** -7, ("Hadamard", l - 1, n)
+                    if dAg is None:
+                        # Eq. 3 was applied in the epilogue of dX_l and dA_{l-1} never stored: the two tasks together
+                        assert fused and prev.act == WL.GELU, ("dA missing", l - 1, n)
+                        dy_prev_ref = O.store(O.act_grad(da_ref, f64(stash[rt][:, kt]), prev.act), "bf16")
+                        assert relerr(dy_prev[:, kin], dy_prev_ref) <= 2e-2, ("dX + Hadamard", l, n)
                     else:
-                        assert np.array_equal(dy_prev, dy_prev_ref), ("Hadamard", l - 1, n)
+                        assert relerr(f64(dAg[rt][:, kt]), da_ref) <= 2e-2, ("dX", l, n)
+                        # the moved Hadamard (Eq. 3) on whole sampled rows
+                        dy_prev_ref = O.store(O.act_grad(f64(dAg[rt]), f64(stash[rt]), prev.act), "bf16")
+                        if prev.act == WL.GELU:
+                            assert relerr(dy_prev, dy_prev_ref) <= 2.0 ** -7, ("Hadamard", l - 1, n)
+                        else:
+                            assert np.array_equal(dy_prev, dy_prev_ref), ("Hadamard", l - 1, n)
             # Eq. 6: W_l(n) = W_l(n-1) - eta G_l(n - d_l) with the GPU's own gradient of d_l steps ago
             w_gpu = wsample(l, lp.LP_T_MASTER_W)
             src = n - wl.delays[l - 1]
