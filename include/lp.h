@@ -198,13 +198,13 @@ int lp_update(lp_ctx* ctx, int l, const float* G, void* stream);
  * on cols.  0 <= cols < D_{l-1}; layer 1 has no delta task. */
 int lp_set_delta_split(lp_ctx* ctx, int l, int cols);
 
-/* The moved Hadamard product inside lp_step (Eq. 3, placement of Sec. III-B): where layer l is fully connected,
- * the context is LP_BF16 and layer l-1 applies ReLU or GELU element-wise (not pooled), the dX task of layer l
- * multiplies by f'(S_{l-1}) in its own epilogue and writes dY_{l-1} directly; dA_{l-1} is then never stored
- * (LP_T_DA of layer l-1 is NULL) and the separate Hadamard kernel is not launched.  The arithmetic is that of
- * lp_grad_act followed by lp_act_grad, element for element: dA is rounded to the act type before the product,
- * so every result is bit-identical with the switch off.  Default: on.  enable = 0 restores the two-kernel form
- * (every dA inspectable).  The per-layer entry points are not affected.  May be called at any time between steps. */
+/* The moved Hadamard product inside lp_step (Eq. 3, placement of Sec. III-B): in an LP_BF16 context, where layer l-1
+ * applies ReLU or GELU element-wise (not pooled: a pooled layer routes its gradient), the dX task of layer l (fully
+ * connected or convolution) multiplies by f'(S_{l-1}) in its own epilogue and writes dY_{l-1} directly; dA_{l-1} is
+ * then never stored (LP_T_DA of layer l-1 is NULL) and the separate Hadamard kernel is not launched.  The arithmetic
+ * is that of lp_grad_act followed by lp_act_grad, element for element: dA is rounded to the act type before the
+ * product, so every result is bit-identical with the switch off.  Default: on.  enable = 0 restores the two-kernel
+ * form (every dA inspectable).  The per-layer entry points are not affected.  May be called at any time between steps. */
 int lp_set_fused_hadamard(lp_ctx* ctx, int enable);
 
 /* Forward run-ahead across steps (Sec. III-A, the schedule of Fig. 6 on one device): with enable != 0,

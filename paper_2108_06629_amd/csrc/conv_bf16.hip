@@ -49,6 +49,8 @@ struct ConvKArgs {
   unsigned img_bytes, mat_bytes;
   int kt_per_split;            // dW: K tiles per workgroup in y
   int vec_out;
+  const unsigned short* had_s; // dX: stash of the layer below, laid out like out_z; its Hadamard product (Eq. 3) is then applied on the way out
+  const float* had_lut;        // ... with f' looked up here (null: the ReLU form)
   FastDiv divW, divH, divC;    // by W, by H, by the gathered image's channel count
 };
 
@@ -404,7 +406,7 @@ __global__ void __launch_bounds__(DNT) conv_dx_dl_kernel(ConvKArgs p) {
   oa.init(p, tm * DBM, true, wave);
   WeightsDX ob;
   ob.init(p, tn * DBN);
-  StoreEpilogue epi{p.out_z, nullptr, nullptr, p.M, p.N, p.ldc, 0, tm * DBM, tn * DBN, p.vec_out != 0};
+  StoreEpilogueT<true> epi{p.out_z, nullptr, nullptr, p.M, p.N, p.ldc, 0, tm * DBM, tn * DBN, p.vec_out != 0, nullptr, p.had_s, p.had_lut};
   dl::gemm_tile_dl<DBM, DBN, DBK, DSTAGES, DWM, DWN>(oa, ob, 0, (p.K + DBK - 1) / DBK, smem, epi);
 }
 
@@ -642,7 +644,8 @@ __global__ void __launch_bounds__(WM* WN * 64) conv_halo_kernel(ConvKArgs p) {
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   Tile<PBM, WM, WN, DX> tl;
   tl.init(p, tm * PBM, tn * HBN, wave, wave / WN);
-  StoreEpilogue epi{p.out_z, DX ? nullptr : p.out_a, nullptr, p.M, p.N, p.ldc, DX ? 0 : p.act, tm * PBM, tn * HBN, p.vec_out != 0};
+  StoreEpilogueT<DX> epi{p.out_z, DX ? nullptr : p.out_a, nullptr, p.M, p.N, p.ldc, DX ? 0 : p.act, tm * PBM, tn * HBN, p.vec_out != 0, nullptr,
+                         DX ? p.had_s : nullptr, DX ? p.had_lut : nullptr};
   run<PBM, WM, WN, DX>(tl, smem, epi);
 }
 
@@ -704,7 +707,7 @@ __global__ void __launch_bounds__(NT) conv_dx_kernel(ConvKArgs p) {
   sa.init(p, tm * BM, true);
   StageWeightsDX sb;
   sb.init(p, tn * BN);
-  StoreEpilogue epi{p.out_z, nullptr, nullptr, p.M, p.N, p.ldc, 0, tm * BM, tn * BN, p.vec_out != 0};
+  StoreEpilogueT<true> epi{p.out_z, nullptr, nullptr, p.M, p.N, p.ldc, 0, tm * BM, tn * BN, p.vec_out != 0, nullptr, p.had_s, p.had_lut};
   gemm_tile<BM, BN, BK, WM, WN>(sa, sb, 0, (p.K + BK - 1) / BK, smem, epi);
 }
 
@@ -845,7 +848,8 @@ hipError_t launch_conv_fwd(const ConvDesc& c, bool bf16, const void* x, const vo
   return hipGetLastError();
 }
 
-hipError_t launch_conv_grad_act(const ConvDesc& c, bool bf16, const void* dy, const void* w, void* dx, int c0, int c1, hipStream_t s) {
+hipError_t launch_conv_grad_act(const ConvDesc& c, bool bf16, const void* dy, const void* w, void* dx, int c0, int c1, hipStream_t s,
+                                const void* had_s, const float* had_lut) {
   if (!bf16) return hipErrorNotSupported;
   if (!fits32(c) || !dy || !w || !dx || c0 < 0 || c1 > c.Cin || c0 >= c1) return hipErrorInvalidValue;
   // 16-byte chunks of dy and of w along the output channels
@@ -858,6 +862,11 @@ hipError_t launch_conv_grad_act(const ConvDesc& c, bool bf16, const void* dy, co
   p.ldc = c.Cin; p.act = 0;
   p.img_bytes = (unsigned)((size_t)p.M * c.Cout * 2); p.mat_bytes = (unsigned)((size_t)9 * c.Cin * c.Cout * 2);
   p.vec_out = (p.N % 4 == 0) && (c.Cin % 4 == 0) && ((uintptr_t)p.out_z % 8 == 0);
+  if (had_s) {
+    p.had_s = (const unsigned short*)had_s + c0;
+    p.had_lut = had_lut;
+    p.vec_out = p.vec_out && ((uintptr_t)p.had_s % 8 == 0);
+  }
   set_divs(p, c);
   const int nb = ((p.M + BM - 1) / BM) * ((p.N + BN - 1) / BN);
   if (halo::ok(c, c.Cout, dy, w)) return halo::launch<true>(p, s);

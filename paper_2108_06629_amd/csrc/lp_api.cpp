@@ -243,7 +243,8 @@ hipError_t do_forward(lp_ctx* c, Layer& ly, const void* X, void* Z, void* A, hip
 hipError_t do_grad_act(lp_ctx* c, Layer& ly, const void* dY, void* dX, int c0, int c1, hipStream_t s, const Layer* had_of = nullptr,
                        const void* S = nullptr) {
   ProfScope prof(c, LP_TASK_DX, layer_no(c, ly), s);
-  if (had_of && (ly.d.kind != LP_LINEAR || !is_bf16(c) || !S)) return hipErrorInvalidValue;
+  if (had_of && (!is_bf16(c) || !S)) return hipErrorInvalidValue;
+  const float* had_lut = had_of && had_of->d.act == LP_ACT_GELU ? c->gelu_grad_lut : nullptr;
   if (ly.d.kind == LP_LINEAR) {
     lp::GemmDesc g;
     const size_t es = esize(c);
@@ -254,7 +255,7 @@ hipError_t do_grad_act(lp_ctx* c, Layer& ly, const void* dY, void* dX, int c0, i
     g.out_z = (char*)dX + (size_t)c0 * es;
     if (had_of) {
       g.had_s = (const char*)S + (size_t)c0 * es;
-      g.had_lut = had_of->d.act == LP_ACT_GELU ? c->gelu_grad_lut : nullptr;
+      g.had_lut = had_lut;
     }
     // K is cut as for the whole product, whatever the column range: the split changes no bits
     const int sk = c0 == 0 ? 0 : 2;
@@ -262,7 +263,7 @@ hipError_t do_grad_act(lp_ctx* c, Layer& ly, const void* dY, void* dX, int c0, i
     g.splitk_scratch = (float*)(c->ws + c->off_splitk[sk]); g.splitk_bytes = c->splitk_bytes[sk];
     return is_bf16(c) ? lp::launch_gemm_bf16(g, s) : lp::launch_gemm_f32(g, s);
   }
-  return lp::launch_conv_grad_act(conv_desc(c, ly), is_bf16(c), dY, work_w(c, ly), dX, c0, c1, s);
+  return lp::launch_conv_grad_act(conv_desc(c, ly), is_bf16(c), dY, work_w(c, ly), dX, c0, c1, s, had_of ? S : nullptr, had_lut);
 }
 
 hipError_t do_grad_weight(lp_ctx* c, Layer& ly, const void* X, const void* dY, float* G, hipStream_t s) {
@@ -288,11 +289,12 @@ hipError_t do_act_grad(lp_ctx* c, Layer& ly, const void* dA, const void* S, void
 }
 
 // Whether lp_step applies the Hadamard product of layer `pv` inside the dX product of the layer `ly` above it
-// (Sec. III-B moves that product next to the task that feeds it; here it shares its kernel): a fully connected `ly`
-// of a bf16 context, an element-wise ReLU or GELU below it (a pooled layer routes its gradient, tanh / sigmoid keep
-// the stand-alone kernel).  Same bits either way.
+// (Sec. III-B moves that product next to the task that feeds it; here it shares its kernel): a bf16 context and an
+// element-wise ReLU or GELU below (a pooled layer routes its gradient, tanh / sigmoid keep the stand-alone kernel).
+// Same bits either way.
 bool hadamard_fused(const lp_ctx* c, const Layer& ly, const Layer& pv) {
-  if (!c->fuse_hadamard || !is_bf16(c) || ly.d.kind != LP_LINEAR) return false;
+  (void)ly;
+  if (!c->fuse_hadamard || !is_bf16(c)) return false;
   if (pv.off_dY == pv.off_dA) return false;   // identity: there is no product
   if (pv.d.kind == LP_CONV3X3 && pv.d.pool == 2) return false;
   return pv.d.act == LP_ACT_RELU || (pv.d.act == LP_ACT_GELU && c->gelu_grad_lut != nullptr);

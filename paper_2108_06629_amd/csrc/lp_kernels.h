@@ -69,9 +69,11 @@ struct ConvDesc {
 // F: z[b,y,x,o] = sum xpad[b,y+kh,x+kw,c] w[kh,kw,c,o]; writes out_z and/or out_a=act(z) (full res).
 hipError_t launch_conv_fwd(const ConvDesc& c, bool bf16, const void* x, const void* w, void* out_z, void* out_a,
                            int act, hipStream_t s);
-// dX: dx[b,y,x,c] for c in [c0,c1) (dx has Cin channels).
+// dX: dx[b,y,x,c] for c in [c0,c1) (dx has Cin channels).  had_s (optional): stash of the layer below, [b,y,x,Cin]
+// like dx; dx then receives dY of that layer, q(q(dA) * f'(S)), as GemmDesc::had_s does for a fully connected layer
+// (f' = [S > 0], or looked up in had_lut).
 hipError_t launch_conv_grad_act(const ConvDesc& c, bool bf16, const void* dy, const void* w, void* dx, int c0, int c1,
-                                hipStream_t s);
+                                hipStream_t s, const void* had_s = nullptr, const float* had_lut = nullptr);
 // dW: g[kh,kw,c,o] fp32.  `partial` is scratch of conv_grad_weight_scratch_bytes().
 hipError_t launch_conv_grad_weight(const ConvDesc& c, bool bf16, const void* x, const void* dy, float* g,
                                    float* partial, hipStream_t s);

@@ -111,13 +111,14 @@ def test_pool_forward_and_routing_with_ties():
     net.close()
 
 
-def run_cnn(wl, steps, exact=True, product_steps=None):
+def run_cnn(wl, steps, exact=True, product_steps=None, fused=True):
     """As run_trajectory of test_gpu_parity.py, for networks with convolution layers: free-running loss, Z_L, W_l and
     G_l (max-norm) against the oracle trajectory, and every task on the tensors it actually read on the GPU.
     `product_steps` (None = all) limits the recomputation of the products; the Hadamard / pool routing, the update
-    from the ring and the frozen prefix are checked in every step."""
+    from the ring and the frozen prefix are checked in every step.  `fused` = False runs the Hadamard products of the
+    unpooled layers as kernels of their own, so that their dA exists and is compared."""
     W0 = WL.init_weights(wl)
-    net = lp.Network(wl.layers, wl.batch, wl.dtype, wl.loss, wl.lr, wl.delays)
+    net = lp.Network(wl.layers, wl.batch, wl.dtype, wl.loss, wl.lr, wl.delays, fused_hadamard=fused)
     net.set_weights(W0)
     ora = O.DelayedGradientTrainer(wl.layers, W0, wl.delays, wl.lr, wl.loss, "bf16")
     exact = O.DelayedGradientTrainer(wl.layers, W0, wl.delays, wl.lr, wl.loss, "f64") if exact else None
@@ -176,18 +177,28 @@ def run_cnn(wl, steps, exact=True, product_steps=None):
             flips, units = relu_flips(net, wl, l, ora.trace["Z"][l - 1])
             if l > 1:
                 prev = wl.layers[l - 2]
-                da = net.tensor_np(l - 1, lp.LP_T_DA).reshape(prev.out_shape(wl.batch))
-                if products:
-                    da_ref = O.store(O.grad_act(dy, Wk[l - 1]), "bf16").reshape(da.shape)
-                    assert relerr(da, da_ref) <= 2e-2, ("dX", l, n)
+                da = net.tensor_np(l - 1, lp.LP_T_DA)
                 dyp = net.tensor_np(l - 1, lp.LP_T_DY).reshape(prev.z_shape(wl.batch))
-                if prev.pool == 2:
-                    zp = net.tensor_np(l - 1, lp.LP_T_Z).reshape(prev.z_shape(wl.batch))
-                    _, idx = O.maxpool2x2(O.activation(zp, prev.act))
-                    ref_dy = O.store(O.act_grad(da, zp, prev.act, idx), "bf16")
+                if da is None:
+                    # the Hadamard product of an unpooled layer rode in the epilogue of dX_l: dA_{l-1} was never stored.
+                    # The pair of tasks on the GPU's own dY_l, weights and stash, and the mask, which stays exact
+                    assert fused and prev.pool != 2 and prev.act == WL.RELU, ("dA missing", l - 1, n)
+                    if products:
+                        da_ref = O.store(O.grad_act(dy, Wk[l - 1]), "bf16").reshape(prev.out_shape(wl.batch))
+                        assert relerr(dyp, O.store(O.act_grad(da_ref, A[l - 1], prev.act), "bf16")) <= 2e-2, ("dX + Hadamard", l, n)
+                    assert np.all(dyp[A[l - 1] <= 0.0] == 0.0), ("ReLU mask", l - 1, n)
                 else:
-                    ref_dy = O.store(O.act_grad(da, A[l - 1], prev.act), "bf16")
-                assert np.array_equal(dyp, ref_dy), ("Hadamard/pool routing", l - 1, n)
+                    da = da.reshape(prev.out_shape(wl.batch))
+                    if products:
+                        da_ref = O.store(O.grad_act(dy, Wk[l - 1]), "bf16").reshape(da.shape)
+                        assert relerr(da, da_ref) <= 2e-2, ("dX", l, n)
+                    if prev.pool == 2:
+                        zp = net.tensor_np(l - 1, lp.LP_T_Z).reshape(prev.z_shape(wl.batch))
+                        _, idx = O.maxpool2x2(O.activation(zp, prev.act))
+                        ref_dy = O.store(O.act_grad(da, zp, prev.act, idx), "bf16")
+                    else:
+                        ref_dy = O.store(O.act_grad(da, A[l - 1], prev.act), "bf16")
+                    assert np.array_equal(dyp, ref_dy), ("Hadamard/pool routing", l - 1, n)
             src = n - wl.delays[l - 1]
             w_new = net.get_weights(l)
             if src < 1:
@@ -204,14 +215,16 @@ def run_cnn(wl, steps, exact=True, product_steps=None):
     _dump_records(run_key(wl))
 
 
-def test_trajectory_cnn_small_unaligned_first_layer():
-    run_cnn(WL.vgg_small(batch=4, hw=8, chans=(8, 8, 16, 16)), 8)
+@pytest.mark.parametrize("fused", [True, False])
+def test_trajectory_cnn_small_unaligned_first_layer(fused):
+    run_cnn(WL.vgg_small(batch=4, hw=8, chans=(8, 8, 16, 16)), 8, fused=fused)
 
 
-def test_trajectory_cnn_vgg_channels_reduced_batch():
+@pytest.mark.parametrize("fused", [True, False])
+def test_trajectory_cnn_vgg_channels_reduced_batch(fused):
     wl = WL.vgg_small(batch=8, hw=32)      # the full channel plan 64,64,128,128,256,256 and 32x32 images, 8 of the 128 samples
     assert [l.d_out for l in wl.layers] == [64, 64, 128, 128, 256, 256, 10] and wl.delays == (12, 10, 8, 6, 4, 2, 0)
-    run_cnn(wl, 3)
+    run_cnn(wl, 3, fused=fused)
 
 
 def test_conv_needs_bf16_context():

@@ -112,8 +112,8 @@ def test_fused_hadamard_under_graph_replay():
 
 
 def test_which_layers_are_fused():
-    """Fused: a fully connected layer above an element-wise ReLU / GELU layer of a bf16 context.  Not fused (dA stays in
-    memory): tanh and sigmoid below, a pooled convolution below (its gradient is routed), a convolution above, fp32."""
+    """Fused: the dX product (fully connected or convolution) above an element-wise ReLU / GELU layer of a bf16 context.
+    Not fused (dA stays in memory): tanh and sigmoid below, a pooled convolution below (its gradient is routed), fp32."""
     acts = [WL.RELU, WL.TANH, WL.GELU, WL.SIGMOID, WL.IDENTITY]
     layers = tuple(WL.Layer(WL.LINEAR, 64, 64, a) for a in acts) + (WL.Layer(WL.LINEAR, 64, 8, WL.IDENTITY),)
     for dtype, want in (("bf16", [False, True, False, True]), ("f32", [True, True, True, True])):
@@ -127,7 +127,7 @@ def test_which_layers_are_fused():
            WL.Layer(WL.LINEAR, 4 * 4 * 8, 16, WL.RELU), WL.Layer(WL.LINEAR, 16, 8, WL.IDENTITY))
     net = lp.Network(cnn, 4, "bf16", WL.SOFTMAX_CE, 0.01, (0, 0, 0, 0))
     net.set_weights([np.zeros(l.weight_shape, dtype=np.float32) for l in cnn])
-    assert [net.tensor(l, lp.LP_T_DA) is not None for l in (1, 2, 3)] == [True, True, False]
+    assert [net.tensor(l, lp.LP_T_DA) is not None for l in (1, 2, 3)] == [False, True, False]
     net.close()
 
 
@@ -141,3 +141,19 @@ def test_unpooled_convolution_below_a_fully_connected_layer():
     got = run(wl, W0, 8)
     assert got[3][:2] == [False, False] and ref[3][:2] == [True, True]
     assert_same(ref, got)
+
+
+@pytest.mark.parametrize("batch,hw,chans,splits", [(4, 8, (8, 8, 16, 16), None), (8, 32, (64, 64, 128, 128, 256, 256), None),
+                                                   (6, 16, (16, 24, 40, 40), {2: 4, 3: 16, 4: 8})])
+def test_convolution_dx_with_fused_hadamard_bits_equal_two_kernel_form(batch, hw, chans, splits):
+    """The three forms of the convolution dX kernel (pixel halo in LDS, direct-to-LDS gather, register-staged gather for a
+    channel range that starts off a multiple of 8), whole and cut into channel ranges (delta' | delta'')."""
+    wl = WL.vgg_small(batch=batch, hw=hw, chans=chans)
+    W0 = WL.init_weights(wl)
+    steps = 2 * (wl.L - 1) + 2
+    ref = run(wl, W0, steps, fused_hadamard=False)
+    assert np.all(np.isfinite(ref[0])) and all(ref[3][:-1])
+    got = run(wl, W0, steps, splits=splits)
+    assert got[3][:-1] == [i % 2 == 1 for i in range(wl.L - 1)], "dA exists for the pooled layers only"
+    assert_same(ref, got)
+    assert_same(ref, run(wl, W0, steps, splits=splits, run_ahead=True))
