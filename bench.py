@@ -30,7 +30,7 @@ PEAK_HBM_GBS = 8000.0
 # its template arguments) has no entry and reports "traffic": null until it is profiled again.
 MEASURED_TRAFFIC = {
     ("ffn_stack_bf16", "gemm_bf16_dl_kernel<256,256,64,2,2,4,true,false,false>"):
-        {"bytes": 1.6323e9 + 3.020e8, "profile": "profiles/hbm_traffic_ffn_stack.md"},
+        {"bytes": 1.6255e9 + 3.020e8, "profile": "profiles/hbm_traffic_ffn_stack.md"},
 }
 # the kernel that runs the forward product of the default workload (every layer of it takes this instantiation)
 F_KERNEL = {"ffn_stack_bf16": "gemm_bf16_dl_kernel<256,256,64,2,2,4,true,false,false>"}
@@ -102,6 +102,59 @@ def cpu_baseline(wl):
                       "of %s of %s at full widths on %d of the %d samples "
                       "of a minibatch took %.1f s; scaled by the per-sample flop ratio %.2f to the whole network" % (
                           threads, blas, os.cpu_count(), what, wl.name, sub.batch, wl.batch, dt, scale)}
+
+
+def operand_values(reps=20):
+    """F, dX and dW of one (4096 -> 16384 GELU, 16384 -> 4096) pair of ffn_stack_bf16 through the per-layer entry points, once
+    on operands drawn as the benchmark draws them (N(0,1) activations and gradients, He-normal weights) and once with every
+    operand element equal to 2^-7.  Kernels, addresses and bytes moved are the same in both; what differs is how many bits
+    toggle in the multipliers, i.e. the energy of a multiply, which is what this chip's clock follows."""
+    import numpy as np
+    import torch
+    import lp_workloads as WL
+    import paper_2108_06629_amd as lp
+    wl = WL.ffn_stack(n_linear=2)
+    B, d, h = wl.batch, wl.layers[0].d_in, wl.layers[0].d_out
+    rows = []
+    for uniform in (False, True):
+        net = lp.Network(wl.layers, B, wl.dtype, wl.loss, wl.lr, (0, 0), n_streams=1)
+        W = [np.full(ly.weight_shape, 2.0 ** -7, dtype=np.float32) for ly in wl.layers] if uniform else WL.init_weights(wl)
+        net.set_weights(W)
+        del W
+        s = net.streams[0]
+
+        def gen(rows_, cols):
+            t = torch.empty(rows_, cols, dtype=torch.bfloat16, device="cuda:0")
+            return t.fill_(2.0 ** -7) if uniform else t.normal_()
+        x1, dy1, x2, dy2 = gen(B, d), gen(B, h), gen(B, h), gen(B, d)
+        z1, a1, z2 = torch.empty_like(dy1), torch.empty_like(dy1), torch.empty_like(dy2)
+        dx1, dx2 = torch.empty_like(x1), torch.empty_like(x2)
+        g = torch.empty(d * h, dtype=torch.float32, device="cuda:0")
+        torch.cuda.synchronize()
+        tasks = (("F up (Z and A = GELU(Z))", (B, h, d), lambda: lp.lp_forward(net.ctx, 1, x1, z1, a1, s)),
+                 ("F down", (B, d, h), lambda: lp.lp_forward(net.ctx, 2, x2, z2, None, s)),
+                 ("dX of the down-projection", (B, h, d), lambda: lp.lp_grad_act(net.ctx, 2, dy2, dx2, 0, h, s)),
+                 ("dX of the up-projection", (B, d, h), lambda: lp.lp_grad_act(net.ctx, 1, dy1, dx1, 0, d, s)),
+                 ("dW of the up-projection", (d, h, B), lambda: lp.lp_grad_weight(net.ctx, 1, x1, dy1, g, s)),
+                 ("dW of the down-projection", (h, d, B), lambda: lp.lp_grad_weight(net.ctx, 2, x2, dy2, g, s)))
+        for i, (name, (M, N, K), fn) in enumerate(tasks):
+            for _ in range(3):
+                fn()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(s)
+            for _ in range(reps):
+                fn()
+            e1.record(s)
+            s.synchronize()
+            ms = e0.elapsed_time(e1) / reps
+            tf = 2.0 * M * N * K / (ms * 1e-3) / 1e12
+            if not uniform:
+                rows.append({"task": name, "M_N_K": [M, N, K]})
+            rows[i]["uniform" if uniform else "random"] = {"ms_per_launch": ms, "TFLOP/s": tf, "frac_of_bf16_peak": tf / PEAK_BF16_TFLOPS}
+        net.close()
+        del net, x1, dy1, x2, dy2, z1, a1, z2, dx1, dx2, g
+        torch.cuda.empty_cache()
+    return rows
 
 
 def partition_report(wl, max_stages):
@@ -252,6 +305,9 @@ def main():
                          "print the balanced stage times next to the best whole-layer (PipeDream-style) assignment")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run five 1 GiB device-to-device copy kernels (reference for the FETCH_SIZE / WRITE_SIZE counters)")
+    ap.add_argument("--calibrate-operands", action="store_true",
+                    help="time the three products of one ffn_stack layer pair on the benchmark's random operands and on operands that all "
+                         "hold one small value: same kernels and bytes, different switching activity in the multipliers")
     ap.add_argument("--calibrate-mfma", action="store_true",
                     help="only run the matrix-instruction-only kernel (lp_probe_mfma) with one and with two workgroups per CU and "
                          "print what it sustains: the practical ceiling of the bf16 MFMA roofline on this machine")
@@ -302,6 +358,10 @@ def main():
             rows.append({"workgroups": wgs, "iters": iters, "operands": "uniform small values" if uniform else "pseudo-random in [-1, 1)",
                          "ms_per_launch": ms, "TFLOP/s": tf, "frac_of_bf16_peak": tf / PEAK_BF16_TFLOPS, "checksum": chk})
         print(json.dumps({"calibrate_mfma": rows}))
+        return
+
+    if args.calibrate_operands:
+        print(json.dumps({"calibrate_operands": operand_values()}))
         return
 
     wl = WL.CONFIGS[args.workload]()
