@@ -430,6 +430,11 @@ def main():
         # its clock with the energy the work draws, so this, not the nominal peak, is what dense bf16 work can reach)
         if not args.no_others:
             roofline["mfma_only_TFLOP/s_on_random_operands"] = mfma_only(1, False, 4)[3]
+            if wl.name == "ffn_stack_bf16":
+                # ... and this very kernel, stand-alone, on the benchmark's operands and on operands that all hold one value
+                # (same bytes, same schedule, fewer bits toggling): the gap is the clock the chip gives up to power
+                f_up = operand_values(reps=10)[0]
+                roofline["F_kernel_alone_frac_random_vs_uniform_operands"] = [f_up["random"]["frac_of_bf16_peak"], f_up["uniform"]["frac_of_bf16_peak"]]
     elif "F" in tasks:
         flops_per_launch = work["F"] / wl.L
         ach = flops_per_launch / (tasks["F"]["avg_ms"] * 1e-3) / 1e12

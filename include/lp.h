@@ -230,7 +230,9 @@ int lp_set_run_ahead(lp_ctx* ctx, int enable);
  * tile to the weights in its epilogue, so G never travels through memory: same arithmetic and same bits
  * as the product ring, less memory and less traffic (per parameter 10 bytes instead of 4 + 14).
  * A layer whose G product lp_grad_weight splits over K ranges (fewer than 256 output tiles of 128 x 128
- * and batch >= 2048) would be summed in another order by the fused update, so it is excluded:
+ * and batch >= 2048), or runs on the short-vector kernels of a layer with a handful of outputs (at most 16
+ * outputs, inputs a multiple of 8, batch <= 2048), would be summed in another order by the fused update, so
+ * it is excluded:
  * l = 0 selects every linear layer but those (they keep the product ring), l > 0 on such a layer is
  * LP_ERR_LAYER.  Applies to lp_step and to lp_grad_weight / lp_update called with
  * G = NULL; LP_T_G_LAST of such a layer is NULL.  Call after lp_create and before lp_workspace_bytes /

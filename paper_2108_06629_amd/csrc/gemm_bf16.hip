@@ -405,6 +405,11 @@ hipError_t launch_gemm_bf16(const GemmDesc& d, hipStream_t s, int tile_cfg) {
                                                  : (unsigned long long)(d.K - 1) * d.ldb + d.N;
   // byte offsets are 32-bit inside the kernel and 0x80000000 marks "out of range"
   if (a_elems * 2 >= 0x7fffffffull || b_elems * 2 >= 0x7fffffffull) return hipErrorInvalidValue;
+  if (tile_cfg < 0) {   // a layer with a handful of outputs has its own kernels (gemm_skinny.hip)
+    bool taken = false;
+    const hipError_t e = launch_gemm_skinny(d, s, &taken);
+    if (taken || e != hipSuccess) return e;
+  }
 
   GemmKArgs a;
   a.A = (const unsigned short*)d.A;

@@ -1016,11 +1016,14 @@ int lp_set_factor_ring(lp_ctx* c, int l, int enable) {
     if (l != 0)
       if (int r = check_layer(c, l)) return r;
     if (l != 0 && c->layers[l - 1].d.kind != LP_LINEAR) return fail(c, LP_ERR_LAYER, "lp_set_factor_ring: layer %d is not a linear layer", l);
-    // A G product that lp_grad_weight cuts into K ranges (few output tiles, long batch) is summed in another
-    // order than the fused update, which never cuts K: such a layer keeps its product ring.
-    auto k_is_cut = [&](const Layer& ly) { return lp::gemm_bf16_splitk_splits(ly.d.in, ly.d.out, c->batch) > 1; };
+    // A layer whose stand-alone G product is not the plain tiled GEMM that the fused update runs -- K cut into ranges
+    // (few output tiles, long batch), or the short-vector kernels of a layer with a handful of outputs -- is summed
+    // in another order there: such a layer keeps its product ring.
+    auto k_is_cut = [&](const Layer& ly) {
+      return lp::gemm_bf16_splitk_splits(ly.d.in, ly.d.out, c->batch) > 1 || lp::gemm_skinny_shape(c->batch, ly.d.in, ly.d.out);
+    };
     if (l != 0 && enable && k_is_cut(c->layers[l - 1]))
-      return fail(c, LP_ERR_LAYER, "lp_set_factor_ring: the G product of layer %d is split over K at this batch size; it keeps the product ring", l);
+      return fail(c, LP_ERR_LAYER, "lp_set_factor_ring: the G product of layer %d is split over K (or runs on the few-outputs kernels) at this batch size; it keeps the product ring", l);
     for (int i = 0; i < c->L; ++i) {
       Layer& ly = c->layers[i];
       if ((l == 0 || i == l - 1) && ly.d.kind == LP_LINEAR) ly.factor_ring = enable != 0 && !k_is_cut(ly);

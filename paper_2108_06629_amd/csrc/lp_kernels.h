@@ -59,6 +59,11 @@ size_t gemm_bf16_splitk_bytes(int M, int N, int K);
 // tile_cfg < 0: pick by problem size.  Returns hipErrorInvalidValue for impossible shapes.
 hipError_t launch_gemm_bf16(const GemmDesc& d, hipStream_t s, int tile_cfg = -1);
 hipError_t launch_gemm_f32(const GemmDesc& d, hipStream_t s);
+// Layers with at most 16 outputs (d_in a multiple of 8, batch <= 2048) run their three products on short vector
+// kernels instead of MFMA tiles; launch_gemm_bf16 goes there by itself.  gemm_skinny_shape tells which layers those are
+// (their summation order differs from the tiled kernels', which matters to whoever promises equal bits).
+bool gemm_skinny_shape(int batch, int d_in, int d_out);
+hipError_t launch_gemm_skinny(const GemmDesc& d, hipStream_t s, bool* taken);
 int gemm_bf16_num_cfgs();
 const char* gemm_bf16_cfg_name(int cfg);
 

@@ -211,7 +211,10 @@ def test_factor_ring_shrinks_the_delay_elements():
     lp.lp_destroy(ctx)
     cnn = WL.vgg_small(batch=2, hw=8, chans=(8, 8))
     ctx = lp.lp_create(descs(cnn), cnn.L, 2, lp.LP_BF16, lp.LP_LOSS_SOFTMAX_CE, 0.01)
-    assert L.lp_set_factor_ring(ctx, 1, 1) == 4 and L.lp_set_factor_ring(ctx, cnn.L, 1) == 0      # conv: LP_ERR_LAYER; the FC layer: fine
+    n_cnn = lp.lp_workspace_bytes(ctx)
+    # conv: LP_ERR_LAYER; the 128 -> 10 classifier too: its G product runs on the few-outputs kernels, not the tiled GEMM of the fused update
+    assert L.lp_set_factor_ring(ctx, 1, 1) == 4 and L.lp_set_factor_ring(ctx, cnn.L, 1) == 4
+    assert L.lp_set_factor_ring(ctx, 0, 1) == 0 and lp.lp_workspace_bytes(ctx) == n_cnn             # "every layer": none qualifies
     lp.lp_destroy(ctx)
     # A G product that lp_grad_weight splits over K keeps its product ring: the fused update never splits K, so its
     # bits would differ.  Batch 2048: 512 x 512, 512 x 4096 and 4096 x 16 outputs have fewer than 256 tiles of

@@ -7,7 +7,7 @@ import torch
 import lp_workloads as WL
 import paper_2108_06629_amd as lp
 from oracle import layerpipe_oracle as O
-from test_gpu_parity import DEV, dev, host, relerr, frob, check_g_free_running, relu_flips, run_key, RECORDS, RECORDING, ZL_BOUND, _dump_records
+from test_gpu_parity import synced, DEV, dev, host, relerr, frob, check_g_free_running, relu_flips, run_key, RECORDS, RECORDING, ZL_BOUND, _dump_records
 
 pytestmark = pytest.mark.gpu
 
@@ -55,14 +55,14 @@ def test_conv_grad_act_and_channel_partition(shape):
     net, Wt, rng = conv_net(B, H, W, ci, co)
     dy = (rng.standard_normal((B, H, W, co)) / np.sqrt(9 * co)).astype(np.float32)
     dyd = dev(dy, torch.bfloat16)
-    dX = torch.full((B, H, W, ci), float("nan"), dtype=torch.bfloat16, device=DEV)
+    dX = synced(torch.full((B, H, W, ci), float("nan"), dtype=torch.bfloat16, device=DEV))
     lp.lp_grad_act(net.ctx, 1, dyd, dX, 0, ci, net.streams[0])
     lp.lp_sync(net.ctx)
     ref = O.store(O.grad_act(O.round_bf16(dy), O.round_bf16(Wt[0])), "bf16")
     assert relerr(host(dX), ref) <= 2e-2
     if ci >= 2:
         cut = max(1, ci // 3)
-        parts = torch.full((B, H, W, ci), float("nan"), dtype=torch.bfloat16, device=DEV)
+        parts = synced(torch.full((B, H, W, ci), float("nan"), dtype=torch.bfloat16, device=DEV))
         lp.lp_grad_act(net.ctx, 1, dyd, parts, 0, cut, net.streams[0])
         lp.lp_grad_act(net.ctx, 1, dyd, parts, cut, ci, net.streams[1])
         lp.lp_sync(net.ctx)
@@ -76,7 +76,7 @@ def test_conv_grad_weight(shape):
     net, Wt, rng = conv_net(B, H, W, ci, co)
     x = rng.standard_normal((B, H, W, ci)).astype(np.float32)
     dy = (rng.standard_normal((B, H, W, co)) / (B * H * W)).astype(np.float32)
-    G = torch.full((3, 3, ci, co), float("nan"), dtype=torch.float32, device=DEV)
+    G = synced(torch.full((3, 3, ci, co), float("nan"), dtype=torch.float32, device=DEV))
     lp.lp_grad_weight(net.ctx, 1, dev(x, torch.bfloat16), dev(dy, torch.bfloat16), G, net.streams[0])
     lp.lp_sync(net.ctx)
     ref = O.grad_weight(O.round_bf16(x), O.round_bf16(dy))
@@ -101,7 +101,7 @@ def test_pool_forward_and_routing_with_ties():
     # backward routing on the tie-rich tensor: exact
     da = rng.standard_normal((B, H // 2, W // 2, C)).astype(np.float32)
     dad = dev(da, torch.bfloat16)
-    dY = torch.full((B, H, W, C), float("nan"), dtype=torch.bfloat16, device=DEV)
+    dY = synced(torch.full((B, H, W, C), float("nan"), dtype=torch.bfloat16, device=DEV))
     lp.lp_act_grad(net.ctx, 1, dad, zd, dY, net.streams[0])
     lp.lp_sync(net.ctx)
     a_full = O.activation(host(zd), "relu")

@@ -48,9 +48,9 @@ def mlp(widths, batch, act=WL.RELU, **kw):
 
 # kernel variants of the dX product: 128 x 128 direct-to-LDS tiles (aligned), the register-staged loop with scalar stores
 # (ragged widths), 256 x 256 tiles (a 2304 x 5632 output), K cut into ranges with the epilogue in the reduction kernel
-# (batch 256, widths 4096: fewer than 256 tiles of 128 x 128, K = 4096)
+# (batch 256, widths 4096: fewer than 256 tiles of 128 x 128, K = 4096), the short-vector kernels of a 10-output classifier
 CASES = [([256, 320, 192, 136, 40], 96), ([77, 130, 45, 19, 10], 33), ([512, 5632, 4096, 264, 16], 2304), ([4096, 4096, 4096, 1000], 256),
-         ([264, 2056, 1160, 72], 300)]
+         ([264, 2056, 1160, 72], 300), ([256, 320, 72, 10], 96)]
 
 
 @pytest.mark.parametrize("widths,batch", CASES)
@@ -79,6 +79,19 @@ def test_fused_hadamard_with_delta_split_run_ahead_and_graph_replay(act):
     assert_same(ref, run(wl, W0, 12, run_ahead=True))
     assert_same(ref, run(wl, W0, 12, run_ahead=True, splits=splits))
     assert_same(ref, run(wl, W0, 12, factor_ring=True))
+
+
+@pytest.mark.parametrize("act", [WL.RELU, WL.GELU])
+def test_fused_hadamard_in_the_few_outputs_kernels_with_column_ranges(act):
+    """A 72 -> 10 classifier: its dX runs on the short-vector kernel, whole (16-byte accesses) and cut at column 52 (a range
+    that starts and ends off a multiple of 8: 2-byte accesses, same sums)."""
+    wl = mlp([256, 320, 72, 10], 96, act)
+    W0 = WL.init_weights(wl)
+    ref = run(wl, W0, 8, fused_hadamard=False)
+    assert_same(ref, run(wl, W0, 8))
+    assert_same(ref, run(wl, W0, 8, splits={3: 20, 2: 8}))
+    assert_same(ref, run(wl, W0, 8, splits={3: 20}, fused_hadamard=False))
+    assert_same(ref, run(wl, W0, 8, splits={3: 16}, run_ahead=True))
 
 
 def test_fused_hadamard_under_graph_replay():

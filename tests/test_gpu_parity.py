@@ -36,6 +36,13 @@ def dev(x, dtype):
     return t
 
 
+def synced(t):
+    """A tensor torch has just filled on its own stream, safe to hand to the library: its streams are not ordered after
+    torch's, so a fill still in flight could land on top of what a library kernel writes (or be read half done)."""
+    torch.cuda.synchronize()
+    return t
+
+
 def host(t):
     return t.to(torch.float32).cpu().numpy().astype(np.float64)
 
@@ -56,7 +63,9 @@ def one_layer_net(d_in, d_out, batch, act="relu", dtype="bf16", seed=0):
 # degenerate sizes.
 FWD_SHAPES = [(96, 200, 136), (33, 77, 19), (1, 8, 8), (7, 1, 3), (300, 520, 264), (64, 4096, 64),
               (1100, 72, 3000), (2304, 96, 5632), (256, 512, 1000), (1024, 136, 6200), (2300, 100, 5700),
-              (1101, 71, 3001), (256, 2048, 512), (300, 2056, 1160), (200, 1160, 3080)]
+              (1101, 71, 3001), (256, 2048, 512), (300, 2056, 1160), (200, 1160, 3080),
+              (128, 4096, 10), (33, 264, 16), (5, 72, 1), (2048, 512, 13), (2049, 512, 10)]
+# The last five are layers with at most 16 outputs: short-vector kernels (gemm_skinny.hip) up to batch 2048, MFMA tiles beyond.
 # K is split over workgroups for F of (64, 4096, 64), (256, 2048, 512), (300, 2056, 1160) (ragged last range), for dX of
 # (1100, 72, 3000), (200, 1160, 3080) and for dW of (2304, 96, 5632)
 
@@ -127,7 +136,7 @@ def test_grad_act_and_column_partition_bf16(shape):
     net, W, rng = one_layer_net(K, N, B)
     dy = (rng.standard_normal((B, N)) / np.sqrt(N)).astype(np.float32)
     dyd = dev(dy, torch.bfloat16)
-    dX = torch.full((B, K), float("nan"), dtype=torch.bfloat16, device=DEV)
+    dX = synced(torch.full((B, K), float("nan"), dtype=torch.bfloat16, device=DEV))
     lp.lp_grad_act(net.ctx, 1, dyd, dX, 0, K, net.streams[0])
     lp.lp_sync(net.ctx)
     ref = O.store(O.grad_act(O.round_bf16(dy), O.round_bf16(W[0])), "bf16")
@@ -135,7 +144,7 @@ def test_grad_act_and_column_partition_bf16(shape):
     if K >= 2:
         # delta' | delta'': two independent calls on complementary column ranges, different streams
         cut = max(1, (K * 2) // 3)
-        parts = torch.full((B, K), float("nan"), dtype=torch.bfloat16, device=DEV)
+        parts = synced(torch.full((B, K), float("nan"), dtype=torch.bfloat16, device=DEV))
         lp.lp_grad_act(net.ctx, 1, dyd, parts, 0, cut, net.streams[0])
         lp.lp_grad_act(net.ctx, 1, dyd, parts, cut, K, net.streams[1])
         lp.lp_sync(net.ctx)
@@ -152,7 +161,7 @@ def test_grad_weight_bf16(shape):
     net, W, rng = one_layer_net(K, N, B)
     x = rng.standard_normal((B, K)).astype(np.float32)
     dy = (rng.standard_normal((B, N)) / B).astype(np.float32)
-    G = torch.full((K, N), float("nan"), dtype=torch.float32, device=DEV)
+    G = synced(torch.full((K, N), float("nan"), dtype=torch.float32, device=DEV))
     lp.lp_grad_weight(net.ctx, 1, dev(x, torch.bfloat16), dev(dy, torch.bfloat16), G, net.streams[0])
     lp.lp_sync(net.ctx)
     ref = O.grad_weight(O.round_bf16(x), O.round_bf16(dy))
@@ -182,7 +191,7 @@ def test_reduction_lengths_around_the_k_step(red, big):
     # dX: reduction over the layer's outputs
     net, W, _ = one_layer_net(n, red, m)
     dy = (rng.standard_normal((m, red)) / np.sqrt(red)).astype(np.float32)
-    dX = torch.full((m, n), float("nan"), dtype=torch.bfloat16, device=DEV)
+    dX = synced(torch.full((m, n), float("nan"), dtype=torch.bfloat16, device=DEV))
     lp.lp_grad_act(net.ctx, 1, dev(dy, torch.bfloat16), dX, 0, n, net.streams[0])
     lp.lp_sync(net.ctx)
     assert relerr(host(dX), O.store(O.grad_act(O.round_bf16(dy), O.round_bf16(W[0])), "bf16")) <= 2e-2
@@ -191,7 +200,7 @@ def test_reduction_lengths_around_the_k_step(red, big):
     net, W, _ = one_layer_net(m, n, red)
     x = rng.standard_normal((red, m)).astype(np.float32)
     dy = (rng.standard_normal((red, n)) / red).astype(np.float32)
-    G = torch.full((m, n), float("nan"), dtype=torch.float32, device=DEV)
+    G = synced(torch.full((m, n), float("nan"), dtype=torch.float32, device=DEV))
     lp.lp_grad_weight(net.ctx, 1, dev(x, torch.bfloat16), dev(dy, torch.bfloat16), G, net.streams[0])
     lp.lp_sync(net.ctx)
     assert relerr(host(G), O.grad_weight(O.round_bf16(x), O.round_bf16(dy))) <= 2e-4
@@ -217,7 +226,8 @@ def test_act_grad_hadamard(n_feat, act, dtype):
         assert np.array_equal(host(dY), ref)              # the mask is a decision: exact
         # the stashed A (same sign as Z) serves as well
         dY2 = torch.empty_like(dad)
-        lp.lp_act_grad(net.ctx, 1, dad, torch.relu(zd), dY2, net.streams[0])
+        ad = synced(torch.relu(zd))
+        lp.lp_act_grad(net.ctx, 1, dad, ad, dY2, net.streams[0])
         lp.lp_sync(net.ctx)
         assert torch.equal(dY2, dY)
     else:
@@ -238,7 +248,7 @@ def test_softmax_ce(rows, cols, dtype):
     y = rng.integers(0, cols, rows).astype(np.int32)
     zd = dev(z, td)
     dY = torch.empty_like(zd)
-    loss = torch.zeros(1, dtype=torch.float32, device=DEV)
+    loss = synced(torch.zeros(1, dtype=torch.float32, device=DEV))
     lp.lp_loss_grad(net.ctx, zd, dev(y, torch.int32), dY, loss, net.streams[0])
     lp.lp_sync(net.ctx)
     ref_loss, ref_dy = O.softmax_ce(host(zd), y)
@@ -260,7 +270,7 @@ def test_mse(rows, cols, dtype):
     rng = np.random.default_rng(rows + cols)
     zd, tg = dev(rng.standard_normal((rows, cols)).astype(np.float32), td), dev(rng.standard_normal((rows, cols)).astype(np.float32), td)
     dY = torch.empty_like(zd)
-    loss = torch.zeros(1, dtype=torch.float32, device=DEV)
+    loss = synced(torch.zeros(1, dtype=torch.float32, device=DEV))
     lp.lp_loss_grad(net.ctx, zd, tg, dY, loss, net.streams[0])
     lp.lp_sync(net.ctx)
     ref_loss, ref_dy = O.mse(host(zd), host(tg))
@@ -281,7 +291,7 @@ def test_cast_rounds_to_nearest_even_like_the_oracle(n):
     x[:min(n, special.size)] = special[:min(n, special.size)]
     net = lp.Network(layers, 4, "bf16", WL.MSE, 0.01, (0,))
     src = torch.from_numpy(x).to(DEV)
-    dst = torch.full((n,), float("nan"), dtype=torch.bfloat16, device=DEV)
+    dst = synced(torch.full((n,), float("nan"), dtype=torch.bfloat16, device=DEV))
     torch.cuda.synchronize()
     lp.lp_cast(net.ctx, src, dst, n, net.streams[0])
     lp.lp_sync(net.ctx)
@@ -291,7 +301,7 @@ def test_cast_rounds_to_nearest_even_like_the_oracle(n):
     assert torch.equal(net.to_device(x.reshape(1, -1)).view(torch.int16).cpu().view(-1), dst.view(torch.int16).cpu())
     net.close()
     net = lp.Network(layers, 4, "f32", WL.MSE, 0.01, (0,))
-    out = torch.zeros(n, dtype=torch.float32, device=DEV)
+    out = synced(torch.zeros(n, dtype=torch.float32, device=DEV))
     lp.lp_cast(net.ctx, src, out, n, net.streams[0])
     lp.lp_sync(net.ctx)
     assert torch.equal(out.view(torch.int32), src.view(torch.int32))
@@ -738,9 +748,10 @@ def test_softmax_label_outside_the_classes_is_not_dereferenced():
         y = rng.integers(0, cols, rows).astype(np.int32)
         bad = y.copy(); bad[2] = cols; bad[4] = -7
         dY, dYb = torch.empty_like(zd), torch.empty_like(zd)
-        loss, lossb = torch.zeros(1, device=DEV), torch.zeros(1, device=DEV)
-        lp.lp_loss_grad(net.ctx, zd, dev(y, torch.int32), dY, loss, net.streams[0])
-        lp.lp_loss_grad(net.ctx, zd, dev(bad, torch.int32), dYb, lossb, net.streams[0])
+        loss, lossb = synced(torch.zeros(1, device=DEV)), synced(torch.zeros(1, device=DEV))
+        yd, badd = dev(y, torch.int32), dev(bad, torch.int32)      # both alive until the kernels that read them have run
+        lp.lp_loss_grad(net.ctx, zd, yd, dY, loss, net.streams[0])
+        lp.lp_loss_grad(net.ctx, zd, badd, dYb, lossb, net.streams[0])
         lp.lp_sync(net.ctx)
         assert np.isfinite(float(loss)) and np.isnan(float(lossb))
         good = [0, 1, 3, 5]
@@ -753,8 +764,8 @@ def test_softmax_label_outside_the_classes_is_not_dereferenced():
 def test_mfma_probe_runs_the_rounds_it_is_asked_for():
     """The calibration kernel of the matrix-core roofline: with the uniform operands every product and every
     partial sum is a small multiple of 2^-20, so the checksums are exact and linear in the number of rounds."""
-    out1 = torch.zeros(4 * 512, dtype=torch.float32, device=DEV)
-    out2 = torch.zeros(4 * 512, dtype=torch.float32, device=DEV)
+    out1 = synced(torch.zeros(4 * 512, dtype=torch.float32, device=DEV))
+    out2 = synced(torch.zeros(4 * 512, dtype=torch.float32, device=DEV))
     s = torch.cuda.Stream()
     lp.lp_probe_mfma(out1, 4, 100, True, s)
     lp.lp_probe_mfma(out2, 4, 200, True, s)

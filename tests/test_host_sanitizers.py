@@ -13,7 +13,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 CLANG = "/opt/rocm/lib/llvm/bin/clang"
 CSRC = os.path.join(ROOT, "paper_2108_06629_amd", "csrc")
-KERNEL_OBJECTS = ["gemm_bf16.o", "gemm_f32.o", "elementwise.o", "conv_bf16.o", "conv_thin.o"]
+KERNEL_OBJECTS = ["gemm_bf16.o", "gemm_skinny.o", "gemm_f32.o", "elementwise.o", "conv_bf16.o", "conv_thin.o"]
 SAN = ["-fsanitize=address", "-fsanitize=undefined", "-fno-sanitize-recover=undefined"]
 
 

@@ -11,6 +11,13 @@ import torch
 import lp_workloads as WL
 import paper_2108_06629_amd as lp
 
+
+def synced(t):
+    """A tensor torch has just filled on its own stream; the library's streams are not ordered after it."""
+    torch.cuda.synchronize()
+    return t
+
+
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
@@ -25,7 +32,7 @@ def reference(rows, cols, dtype, loss, z, target):
     layers = (WL.Layer(WL.LINEAR, 16, cols, WL.IDENTITY),)
     net = lp.Network(layers, rows, dtype, loss, 0.01, (0,))
     dY = torch.full_like(z, float("nan"))
-    out = torch.full((1,), float("nan"), dtype=torch.float32, device=DEV)
+    out = synced(torch.full((1,), float("nan"), dtype=torch.float32, device=DEV))
     lp.lp_loss_grad(net.ctx, z, target, dY, out, net.streams[0])
     lp.lp_sync(net.ctx)
     net.close()
@@ -49,7 +56,7 @@ def test_static_scratch_loss_equals_workspace_loss_on_two_calls_in_a_row(dtype, 
         dY_ref, loss_ref = reference(rows, cols, dtype, loss, z, target)
         ctx = bare_context(rows, cols, dtype, loss)
         dY = torch.full_like(z, float("nan"))
-        out = torch.full((1,), float("nan"), dtype=torch.float32, device=DEV)
+        out = synced(torch.full((1,), float("nan"), dtype=torch.float32, device=DEV))
         st = lp.lib().lp_loss_grad_static(ctx, z.data_ptr(), target.data_ptr(), dY.data_ptr(), out.data_ptr(), stream.cuda_stream)
         assert st == 0, lp.lib().lp_last_error(ctx)
         stream.synchronize()
