@@ -199,8 +199,9 @@ int lp_update(lp_ctx* ctx, int l, const float* G, void* stream);
 int lp_set_delta_split(lp_ctx* ctx, int l, int cols);
 
 /* The moved Hadamard product inside lp_step (Eq. 3, placement of Sec. III-B): in an LP_BF16 context, where layer l-1
- * applies ReLU or GELU element-wise (not pooled: a pooled layer routes its gradient), the dX task of layer l (fully
- * connected or convolution) multiplies by f'(S_{l-1}) in its own epilogue and writes dY_{l-1} directly; dA_{l-1} is
+ * applies ReLU or GELU element-wise, the dX task of layer l (fully connected or convolution) multiplies by
+ * f'(S_{l-1}) in its own epilogue and writes dY_{l-1} directly; where layer l-1 is a 2x2 max-pooled ReLU convolution
+ * and layer l a convolution, that epilogue also routes each gradient to the first maximum of its window; dA_{l-1} is
  * then never stored (LP_T_DA of layer l-1 is NULL) and the separate Hadamard kernel is not launched.  The arithmetic
  * is that of lp_grad_act followed by lp_act_grad, element for element: dA is rounded to the act type before the
  * product, so every result is bit-identical with the switch off.  Default: on.  enable = 0 restores the two-kernel

@@ -51,6 +51,7 @@ struct ConvKArgs {
   int vec_out;
   const unsigned short* had_s; // dX: stash of the layer below, laid out like out_z; its Hadamard product (Eq. 3) is then applied on the way out
   const float* had_lut;        // ... with f' looked up here (null: the ReLU form)
+  int pool_wp;                 // ... and, when > 0, routed to the 2 x 2 windows of a pooled layer (this product's image width)
   FastDiv divW, divH, divC;    // by W, by H, by the gathered image's channel count
 };
 
@@ -406,7 +407,7 @@ __global__ void __launch_bounds__(DNT) conv_dx_dl_kernel(ConvKArgs p) {
   oa.init(p, tm * DBM, true, wave);
   WeightsDX ob;
   ob.init(p, tn * DBN);
-  StoreEpilogueT<true> epi{p.out_z, nullptr, nullptr, p.M, p.N, p.ldc, 0, tm * DBM, tn * DBN, p.vec_out != 0, nullptr, p.had_s, p.had_lut};
+  StoreEpilogueT<true> epi{p.out_z, nullptr, nullptr, p.M, p.N, p.ldc, 0, tm * DBM, tn * DBN, p.vec_out != 0, nullptr, p.had_s, p.had_lut, p.pool_wp};
   dl::gemm_tile_dl<DBM, DBN, DBK, DSTAGES, DWM, DWN>(oa, ob, 0, (p.K + DBK - 1) / DBK, smem, epi);
 }
 
@@ -645,7 +646,7 @@ __global__ void __launch_bounds__(WM* WN * 64) conv_halo_kernel(ConvKArgs p) {
   Tile<PBM, WM, WN, DX> tl;
   tl.init(p, tm * PBM, tn * HBN, wave, wave / WN);
   StoreEpilogueT<DX> epi{p.out_z, DX ? nullptr : p.out_a, nullptr, p.M, p.N, p.ldc, DX ? 0 : p.act, tm * PBM, tn * HBN, p.vec_out != 0, nullptr,
-                         DX ? p.had_s : nullptr, DX ? p.had_lut : nullptr};
+                         DX ? p.had_s : nullptr, DX ? p.had_lut : nullptr, DX ? p.pool_wp : 0};
   run<PBM, WM, WN, DX>(tl, smem, epi);
 }
 
@@ -707,7 +708,7 @@ __global__ void __launch_bounds__(NT) conv_dx_kernel(ConvKArgs p) {
   sa.init(p, tm * BM, true);
   StageWeightsDX sb;
   sb.init(p, tn * BN);
-  StoreEpilogueT<true> epi{p.out_z, nullptr, nullptr, p.M, p.N, p.ldc, 0, tm * BM, tn * BN, p.vec_out != 0, nullptr, p.had_s, p.had_lut};
+  StoreEpilogueT<true> epi{p.out_z, nullptr, nullptr, p.M, p.N, p.ldc, 0, tm * BM, tn * BN, p.vec_out != 0, nullptr, p.had_s, p.had_lut, p.pool_wp};
   gemm_tile<BM, BN, BK, WM, WN>(sa, sb, 0, (p.K + BK - 1) / BK, smem, epi);
 }
 
@@ -849,7 +850,7 @@ hipError_t launch_conv_fwd(const ConvDesc& c, bool bf16, const void* x, const vo
 }
 
 hipError_t launch_conv_grad_act(const ConvDesc& c, bool bf16, const void* dy, const void* w, void* dx, int c0, int c1, hipStream_t s,
-                                const void* had_s, const float* had_lut) {
+                                const void* had_s, const float* had_lut, bool had_pooled) {
   if (!bf16) return hipErrorNotSupported;
   if (!fits32(c) || !dy || !w || !dx || c0 < 0 || c1 > c.Cin || c0 >= c1) return hipErrorInvalidValue;
   // 16-byte chunks of dy and of w along the output channels
@@ -865,6 +866,8 @@ hipError_t launch_conv_grad_act(const ConvDesc& c, bool bf16, const void* dy, co
   if (had_s) {
     p.had_s = (const unsigned short*)had_s + c0;
     p.had_lut = had_lut;
+    p.pool_wp = had_pooled ? c.W : 0;
+    if (had_pooled && had_lut) return hipErrorInvalidValue;   // routing exists in the ReLU form only
     p.vec_out = p.vec_out && ((uintptr_t)p.had_s % 8 == 0);
   }
   set_divs(p, c);

@@ -402,6 +402,10 @@ struct StoreEpilogueT {
   // bit pattern z as fp32 (null: f' = [S > 0], the ReLU form)
   const unsigned short* had_s;
   const float* had_lut;
+  // HAD with pool_wp > 0: the layer below is a 2 x 2 max-pooled ReLU layer, whose gradient is routed, not only masked.
+  // Row r of this product is then the pooled pixel (b, y, x) with x = r % pool_wp, had_s is that layer's full-resolution
+  // Z and out_z its full-resolution dY, both [.., 2 Hp, 2 pool_wp, ldc].
+  int pool_wp;
 
   // ACT < 0: the activation is read from `act`; 5: table look-up
   template <int ACT>
@@ -468,6 +472,54 @@ struct StoreEpilogueT {
     }
   }
 
+  // The four pixels of the window of pooled pixel (r, c..c+3) receive q(q(dA) * [z > 0]) at the first maximum of relu(z)
+  // (row-major order inside the window, strict '>' keeps the first) and 0 elsewhere: the arithmetic of the stand-alone
+  // routing kernel, element for element.  Every full-resolution pixel belongs to exactly one window, so dY is written whole.
+  __device__ __forceinline__ void store_pool_route(int r, int c, const f32x4& v) const {
+    const int row = m0 + r, col = n0 + c;
+    if (row >= M || col >= N) return;
+    const int ry = row / pool_wp, x = row - ry * pool_wp;   // ry = b * Hp + y
+    const size_t base = ((size_t)4 * ry * pool_wp + 2 * x) * ldc + col;
+    const size_t down = (size_t)2 * pool_wp * ldc;
+    const size_t offs[4] = {base, base + ldc, base + down, base + down + ldc};
+    unsigned short zb[4][4], ob[4][4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      if (vec) {
+        const u32x2 zz = *reinterpret_cast<const u32x2*>(had_s + offs[k]);
+        zb[k][0] = (unsigned short)(zz[0] & 0xffffu); zb[k][1] = (unsigned short)(zz[0] >> 16);
+        zb[k][2] = (unsigned short)(zz[1] & 0xffffu); zb[k][3] = (unsigned short)(zz[1] >> 16);
+      } else {
+#pragma unroll
+        for (int t = 0; t < 4; ++t) zb[k][t] = col + t < N ? had_s[offs[k] + t] : (unsigned short)0;
+      }
+    }
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      float best = 0.f;
+      int arg = 0;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const float z = bf16_to_f32(zb[k][t]);
+        const float a = z > 0.f ? z : 0.f;
+        if (k == 0 || a > best) { best = a; arg = k; }
+      }
+      const float da = bf16_to_f32(bf16_bits(v[t]));
+#pragma unroll
+      for (int k = 0; k < 4; ++k) ob[k][t] = bf16_bits(k == arg ? da * (bf16_to_f32(zb[k][t]) > 0.f ? 1.f : 0.f) : 0.f);
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      if (vec) {
+        *reinterpret_cast<u32x2*>(out_z + offs[k]) = u32x2{(unsigned)ob[k][0] | ((unsigned)ob[k][1] << 16), (unsigned)ob[k][2] | ((unsigned)ob[k][3] << 16)};
+      } else {
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+          if (col + t < N) out_z[offs[k] + t] = ob[k][t];
+      }
+    }
+  }
+
   template <int ACT>
   struct StaticAct {
     const StoreEpilogueT& e;
@@ -486,12 +538,21 @@ struct StoreEpilogueT {
     __device__ __forceinline__ void operator()(int r, int c, const f32x4& v, const u32x2& sd) const { e.template store_had<LUT>(r, c, v, sd); }
     __device__ __forceinline__ void operator()(int r, int c, const f32x4& v) const { e.template store_had<LUT>(r, c, v, e.had_side(r, c)); }
   };
+  struct PoolRoute {
+    const StoreEpilogueT& e;
+    static constexpr bool kHasSide = false;
+    using Side = NoSide;
+    __device__ __forceinline__ NoSide side(int, int) const { return NoSide{}; }
+    __device__ __forceinline__ void operator()(int r, int c, const f32x4& v) const { e.store_pool_route(r, c, v); }
+    __device__ __forceinline__ void operator()(int r, int c, const f32x4& v, NoSide) const { e.store_pool_route(r, c, v); }
+  };
   // calls f with a view of this epilogue whose activation is a compile-time constant (same arithmetic, element for element)
   template <class F>
   __device__ __forceinline__ void with_static_act(F&& f) const {
     if constexpr (HAD) {
       if (had_s) {
-        if (had_lut) f(Hadamard<true>{*this});
+        if (pool_wp > 0) f(PoolRoute{*this});
+        else if (had_lut) f(Hadamard<true>{*this});
         else f(Hadamard<false>{*this});
         return;
       }

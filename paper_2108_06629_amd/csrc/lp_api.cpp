@@ -263,7 +263,8 @@ hipError_t do_grad_act(lp_ctx* c, Layer& ly, const void* dY, void* dX, int c0, i
     g.splitk_scratch = (float*)(c->ws + c->off_splitk[sk]); g.splitk_bytes = c->splitk_bytes[sk];
     return is_bf16(c) ? lp::launch_gemm_bf16(g, s) : lp::launch_gemm_f32(g, s);
   }
-  return lp::launch_conv_grad_act(conv_desc(c, ly), is_bf16(c), dY, work_w(c, ly), dX, c0, c1, s, had_of ? S : nullptr, had_lut);
+  const bool pooled_below = had_of && had_of->d.kind == LP_CONV3X3 && had_of->d.pool == 2;
+  return lp::launch_conv_grad_act(conv_desc(c, ly), is_bf16(c), dY, work_w(c, ly), dX, c0, c1, s, had_of ? S : nullptr, had_lut, pooled_below);
 }
 
 hipError_t do_grad_weight(lp_ctx* c, Layer& ly, const void* X, const void* dY, float* G, hipStream_t s) {
@@ -290,13 +291,13 @@ hipError_t do_act_grad(lp_ctx* c, Layer& ly, const void* dA, const void* S, void
 
 // Whether lp_step applies the Hadamard product of layer `pv` inside the dX product of the layer `ly` above it
 // (Sec. III-B moves that product next to the task that feeds it; here it shares its kernel): a bf16 context and an
-// element-wise ReLU or GELU below (a pooled layer routes its gradient, tanh / sigmoid keep the stand-alone kernel).
+// element-wise ReLU or GELU below (tanh / sigmoid keep the stand-alone kernel), or a 2 x 2 max-pooled ReLU
+// convolution below a convolution, whose epilogue then also routes each gradient to its window's maximum.
 // Same bits either way.
 bool hadamard_fused(const lp_ctx* c, const Layer& ly, const Layer& pv) {
-  (void)ly;
   if (!c->fuse_hadamard || !is_bf16(c)) return false;
+  if (pv.d.kind == LP_CONV3X3 && pv.d.pool == 2) return ly.d.kind == LP_CONV3X3 && pv.d.act == LP_ACT_RELU && pv.has_Z;
   if (pv.off_dY == pv.off_dA) return false;   // identity: there is no product
-  if (pv.d.kind == LP_CONV3X3 && pv.d.pool == 2) return false;
   return pv.d.act == LP_ACT_RELU || (pv.d.act == LP_ACT_GELU && c->gelu_grad_lut != nullptr);
 }
 

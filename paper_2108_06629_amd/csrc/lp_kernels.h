@@ -76,9 +76,11 @@ hipError_t launch_conv_fwd(const ConvDesc& c, bool bf16, const void* x, const vo
                            int act, hipStream_t s);
 // dX: dx[b,y,x,c] for c in [c0,c1) (dx has Cin channels).  had_s (optional): stash of the layer below, [b,y,x,Cin]
 // like dx; dx then receives dY of that layer, q(q(dA) * f'(S)), as GemmDesc::had_s does for a fully connected layer
-// (f' = [S > 0], or looked up in had_lut).
+// (f' = [S > 0], or looked up in had_lut).  had_pooled: the layer below is a 2x2 max-pooled ReLU layer; had_s is then
+// its full-resolution Z [b,2H,2W,Cin] and dx its full-resolution dY: each element of this product goes to the first
+// maximum of its window (times [z > 0]), the other three pixels get 0, as launch_act_grad_pool routes a stored dA.
 hipError_t launch_conv_grad_act(const ConvDesc& c, bool bf16, const void* dy, const void* w, void* dx, int c0, int c1,
-                                hipStream_t s, const void* had_s = nullptr, const float* had_lut = nullptr);
+                                hipStream_t s, const void* had_s = nullptr, const float* had_lut = nullptr, bool had_pooled = false);
 // dW: g[kh,kw,c,o] fp32.  `partial` is scratch of conv_grad_weight_scratch_bytes().
 hipError_t launch_conv_grad_weight(const ConvDesc& c, bool bf16, const void* x, const void* dy, float* g,
                                    float* partial, hipStream_t s);

@@ -182,11 +182,22 @@ def run_cnn(wl, steps, exact=True, product_steps=None, fused=True):
                 if da is None:
                     # the Hadamard product of an unpooled layer rode in the epilogue of dX_l: dA_{l-1} was never stored.
                     # The pair of tasks on the GPU's own dY_l, weights and stash, and the mask, which stays exact
-                    assert fused and prev.pool != 2 and prev.act == WL.RELU, ("dA missing", l - 1, n)
-                    if products:
-                        da_ref = O.store(O.grad_act(dy, Wk[l - 1]), "bf16").reshape(prev.out_shape(wl.batch))
-                        assert relerr(dyp, O.store(O.act_grad(da_ref, A[l - 1], prev.act), "bf16")) <= 2e-2, ("dX + Hadamard", l, n)
-                    assert np.all(dyp[A[l - 1] <= 0.0] == 0.0), ("ReLU mask", l - 1, n)
+                    assert fused and prev.act == WL.RELU, ("dA missing", l - 1, n)
+                    if prev.pool == 2:
+                        # ... of a pooled layer: the epilogue also routed every gradient to its window's first maximum
+                        assert ly.kind == WL.CONV3X3, ("dA missing", l - 1, n)
+                        zp = net.tensor_np(l - 1, lp.LP_T_Z).reshape(prev.z_shape(wl.batch))
+                        _, idx = O.maxpool2x2(O.activation(zp, prev.act))
+                        if products:
+                            da_ref = O.store(O.grad_act(dy, Wk[l - 1]), "bf16").reshape(prev.out_shape(wl.batch))
+                            assert relerr(dyp, O.store(O.act_grad(da_ref, zp, prev.act, idx), "bf16")) <= 2e-2, ("dX + routing", l, n)
+                        route = O.act_grad(np.ones(prev.out_shape(wl.batch)), zp, prev.act, idx)
+                        assert np.all(dyp[route == 0.0] == 0.0), ("pool routing", l - 1, n)
+                    else:
+                        if products:
+                            da_ref = O.store(O.grad_act(dy, Wk[l - 1]), "bf16").reshape(prev.out_shape(wl.batch))
+                            assert relerr(dyp, O.store(O.act_grad(da_ref, A[l - 1], prev.act), "bf16")) <= 2e-2, ("dX + Hadamard", l, n)
+                        assert np.all(dyp[A[l - 1] <= 0.0] == 0.0), ("ReLU mask", l - 1, n)
                 else:
                     da = da.reshape(prev.out_shape(wl.batch))
                     if products:

@@ -126,7 +126,7 @@ def test_fused_hadamard_under_graph_replay():
 
 def test_which_layers_are_fused():
     """Fused: the dX product (fully connected or convolution) above an element-wise ReLU / GELU layer of a bf16 context.
-    Not fused (dA stays in memory): tanh and sigmoid below, a pooled convolution below (its gradient is routed), fp32."""
+    Not fused (dA stays in memory): tanh and sigmoid below, a pooled convolution below a fully connected layer, fp32."""
     acts = [WL.RELU, WL.TANH, WL.GELU, WL.SIGMOID, WL.IDENTITY]
     layers = tuple(WL.Layer(WL.LINEAR, 64, 64, a) for a in acts) + (WL.Layer(WL.LINEAR, 64, 8, WL.IDENTITY),)
     for dtype, want in (("bf16", [False, True, False, True]), ("f32", [True, True, True, True])):
@@ -167,6 +167,8 @@ def test_convolution_dx_with_fused_hadamard_bits_equal_two_kernel_form(batch, hw
     ref = run(wl, W0, steps, fused_hadamard=False)
     assert np.all(np.isfinite(ref[0])) and all(ref[3][:-1])
     got = run(wl, W0, steps, splits=splits)
-    assert got[3][:-1] == [i % 2 == 1 for i in range(wl.L - 1)], "dA exists for the pooled layers only"
+    # unpooled layers: masked in the dX epilogue above them; pooled layers below a convolution: masked and routed there;
+    # the last pooled layer sits below the fully connected classifier and keeps its routing kernel and its dA
+    assert got[3][:-1] == [i == wl.L - 2 for i in range(wl.L - 1)]
     assert_same(ref, got)
     assert_same(ref, run(wl, W0, steps, splits=splits, run_ahead=True))
