@@ -52,6 +52,7 @@ struct ConvKArgs {
   const unsigned short* had_s; // dX: stash of the layer below, laid out like out_z; its Hadamard product (Eq. 3) is then applied on the way out
   const float* had_lut;        // ... with f' looked up here (null: the ReLU form)
   int pool_wp;                 // ... and, when > 0, routed to the 2 x 2 windows of a pooled layer (this product's image width)
+  unsigned short* pool_a;      // F (halo form): when set, also A[b, y/2, x/2, :] = max over the 2 x 2 window of relu(z), computed from the stored Z
   FastDiv divW, divH, divC;    // by W, by H, by the gathered image's channel count
 };
 
@@ -648,6 +649,42 @@ __global__ void __launch_bounds__(WM* WN * 64) conv_halo_kernel(ConvKArgs p) {
   StoreEpilogueT<DX> epi{p.out_z, DX ? nullptr : p.out_a, nullptr, p.M, p.N, p.ldc, DX ? 0 : p.act, tm * PBM, tn * HBN, p.vec_out != 0, nullptr,
                          DX ? p.had_s : nullptr, DX ? p.had_lut : nullptr, DX ? p.pool_wp : 0};
   run<PBM, WM, WN, DX>(tl, smem, epi);
+  if constexpr (!DX) {
+    if (p.pool_a) {
+      // ReLU and 2 x 2 max-pooling of this workgroup's own tile of Z (the launcher has checked that a tile is a whole
+      // number of image row pairs): once all waves' stores of Z have completed, each lane reads the four pixels of one
+      // window for eight channels back (from L2: nobody has read these lines before) and writes the pooled activation.
+      // The arithmetic of the stand-alone pooling kernel: the maximum of relu of the stored bf16 values.
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+      __syncthreads();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+      const int C = p.ldc, W = p.W, Wp = W >> 1;
+      constexpr int CG = HBN / 8;                       // groups of eight channels in the tile
+      for (int item = threadIdx.x; item < (PBM / 4) * CG; item += WM * WN * 64) {
+        const int pp = item / CG, c = tn * HBN + (item % CG) * 8;
+        const int j = pp / Wp, xp = pp - j * Wp;
+        const int p00 = tm * PBM + j * 2 * W + 2 * xp;
+        if (p00 >= p.M || c >= p.N) continue;
+        const unsigned short* z0 = p.out_z + (size_t)p00 * C + c;
+        const u32x4 zv[4] = {*reinterpret_cast<const u32x4*>(z0), *reinterpret_cast<const u32x4*>(z0 + C),
+                             *reinterpret_cast<const u32x4*>(z0 + (size_t)W * C), *reinterpret_cast<const u32x4*>(z0 + (size_t)W * C + C)};
+        u32x4 out;
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+          float best[2];
+#pragma unroll
+          for (int k = 0; k < 4; ++k) {
+            const float lo = bf16_to_f32((unsigned short)(zv[k][d] & 0xffffu)), hi = bf16_to_f32((unsigned short)(zv[k][d] >> 16));
+            const float rl = lo > 0.f ? lo : 0.f, rh = hi > 0.f ? hi : 0.f;
+            if (k == 0 || rl > best[0]) best[0] = rl;
+            if (k == 0 || rh > best[1]) best[1] = rh;
+          }
+          out[d] = (unsigned)bf16_bits(best[0]) | ((unsigned)bf16_bits(best[1]) << 16);
+        }
+        *reinterpret_cast<u32x4*>(p.pool_a + ((size_t)(tm * PBM) / 4 + pp) * C + c) = out;
+      }
+    }
+  }
 }
 
 // the halo forms apply when both channel counts allow 16-byte chunks and 16-channel steps, and the row fits the halo
@@ -811,7 +848,9 @@ size_t conv_grad_weight_scratch_bytes(const ConvDesc& c) {
   return s > 1 ? (size_t)s * 9 * c.Cin * c.Cout * sizeof(float) : 0;
 }
 
-hipError_t launch_conv_fwd(const ConvDesc& c, bool bf16, const void* x, const void* w, void* out_z, void* out_a, int act, hipStream_t s) {
+hipError_t launch_conv_fwd(const ConvDesc& c, bool bf16, const void* x, const void* w, void* out_z, void* out_a, int act, hipStream_t s,
+                           void* pooled_a, bool* pooled_done) {
+  if (pooled_done) *pooled_done = false;
   if (!bf16) return hipErrorNotSupported;
   if (!fits32(c) || !x || !w) return hipErrorInvalidValue;
   ConvKArgs p{};
@@ -826,7 +865,15 @@ hipError_t launch_conv_fwd(const ConvDesc& c, bool bf16, const void* x, const vo
   const bool al_a = c.Cin % 8 == 0 && (uintptr_t)x % 16 == 0, al_b = c.Cout % 8 == 0 && (uintptr_t)w % 16 == 0;
   const int nb = ((p.M + BM - 1) / BM) * ((p.N + BN - 1) / BN);
   if (conv_thin_ok(c, x, w)) return launch_conv_thin_fwd(c, x, w, out_z, out_a, act, s);
-  if (halo::ok(c, c.Cin, x, w)) return halo::launch<false>(p, s);
+  if (halo::ok(c, c.Cin, x, w)) {
+    // pooling in the same launch: ReLU layers whose tiles (128 or 256 pixels) are whole numbers of image row pairs
+    if (pooled_a && pooled_done && out_z && !out_a && act == ACT_RELU && c.H % 2 == 0 && c.W % 2 == 0 && 128 % (2 * c.W) == 0 &&
+        (uintptr_t)out_z % 16 == 0 && (uintptr_t)pooled_a % 16 == 0) {
+      p.pool_a = (unsigned short*)pooled_a;
+      *pooled_done = true;
+    }
+    return halo::launch<false>(p, s);
+  }
   if (dl_ok(c, x, w)) {
     static bool attr_dl = false;
     if (hipError_t e = set_lds_dl(cdl::conv_fwd_dl_kernel, attr_dl)) return e;

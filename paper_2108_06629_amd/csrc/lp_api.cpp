@@ -231,8 +231,9 @@ hipError_t do_forward(lp_ctx* c, Layer& ly, const void* X, void* Z, void* A, hip
   }
   const lp::ConvDesc cd = conv_desc(c, ly);
   if (ly.d.pool == 2) {
-    hipError_t e = lp::launch_conv_fwd(cd, is_bf16(c), X, work_w(c, ly), Z, nullptr, ly.d.act, s);
-    if (e != hipSuccess || !A) return e;
+    bool pooled = false;
+    hipError_t e = lp::launch_conv_fwd(cd, is_bf16(c), X, work_w(c, ly), Z, nullptr, ly.d.act, s, A, &pooled);
+    if (e != hipSuccess || !A || pooled) return e;
     return lp::launch_relu_pool(is_bf16(c), Z, A, c->batch, ly.d.H, ly.d.W, ly.d.out, ly.d.act, s);
   }
   return lp::launch_conv_fwd(cd, is_bf16(c), X, work_w(c, ly), Z, A, ly.d.act, s);

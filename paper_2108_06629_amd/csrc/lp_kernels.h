@@ -72,8 +72,11 @@ struct ConvDesc {
   int B = 0, H = 0, W = 0, Cin = 0, Cout = 0;
 };
 // F: z[b,y,x,o] = sum xpad[b,y+kh,x+kw,c] w[kh,kw,c,o]; writes out_z and/or out_a=act(z) (full res).
+// pooled_a / pooled_done (optional, with out_z and without out_a): the caller wants a[b,y/2,x/2,o] = max over the 2x2
+// window of relu(z) as well; *pooled_done says whether this launch wrote it (the pixel-halo form of a ReLU layer whose
+// tiles hold whole image row pairs does), otherwise launch_relu_pool is still to be called.
 hipError_t launch_conv_fwd(const ConvDesc& c, bool bf16, const void* x, const void* w, void* out_z, void* out_a,
-                           int act, hipStream_t s);
+                           int act, hipStream_t s, void* pooled_a = nullptr, bool* pooled_done = nullptr);
 // dX: dx[b,y,x,c] for c in [c0,c1) (dx has Cin channels).  had_s (optional): stash of the layer below, [b,y,x,Cin]
 // like dx; dx then receives dY of that layer, q(q(dA) * f'(S)), as GemmDesc::had_s does for a fully connected layer
 // (f' = [S > 0], or looked up in had_lut).  had_pooled: the layer below is a 2x2 max-pooled ReLU layer; had_s is then
