@@ -198,16 +198,17 @@ def _run_schedule(wl, W0, steps, **kw):
 
 @pytest.mark.parametrize("name", ["mlp_4096_bf16", "vgg_small_bf16"])
 def test_full_size_schedules_and_ring_kinds_agree_bit_for_bit(name):
-    """At the benchmark's shapes: serial, run-ahead, graph replay, and the factor ring on top of each give
-    the same losses and weights.  (The serial product-ring run of these workloads is the one the tests
-    above compare with the oracle.)"""
+    """At the benchmark's shapes: serial, run-ahead, graph replay, the factor ring on top of each, and the two forms
+    of the Hadamard product (inside the dX kernels, which for the CNN includes the routing of pooled gradients, or as
+    kernels of their own) give the same losses and weights.  (The serial product-ring run of these workloads is the
+    one the tests above compare with the oracle.)"""
     wl = WL.CONFIGS[name]()
     W0 = WL.init_weights(wl)
     steps = max(wl.delays) + 22
     ref, _ = _run_schedule(wl, W0, steps)
     assert np.all(np.isfinite(ref[0]))
     for kw in (dict(run_ahead=True), dict(graphs=True), dict(factor_ring=True), dict(factor_ring=True, run_ahead=True),
-               dict(factor_ring=True, run_ahead=True, n_streams=3)):
+               dict(factor_ring=True, run_ahead=True, n_streams=3), dict(fused_hadamard=False), dict(fused_hadamard=False, run_ahead=True)):
         got, stats = _run_schedule(wl, W0, steps, **kw)
         assert np.array_equal(got[0].view(np.uint32), ref[0].view(np.uint32)), (kw, got[0][-4:], ref[0][-4:])
         for l, (a, b) in enumerate(zip(got[1], ref[1]), start=1):
@@ -224,7 +225,7 @@ def test_chip_filling_gradient_products_keep_the_serial_bits():
     W0 = WL.init_weights(wl)
     ref, _ = _run_schedule(wl, W0, 9, n_streams=1)
     assert np.all(np.isfinite(ref[0])) and ref[0][0] != ref[0][-1]
-    for kw in (dict(n_streams=3), dict(n_streams=3, graphs=True)):
+    for kw in (dict(n_streams=3), dict(n_streams=3, graphs=True), dict(n_streams=3, fused_hadamard=False)):
         got, _ = _run_schedule(wl, W0, 9, **kw)
         assert np.array_equal(got[0].view(np.uint32), ref[0].view(np.uint32)), kw
         for l, (a, b) in enumerate(zip(got[1], ref[1]), start=1):
