@@ -230,3 +230,36 @@ def test_chip_filling_gradient_products_keep_the_serial_bits():
         assert np.array_equal(got[0].view(np.uint32), ref[0].view(np.uint32)), kw
         for l, (a, b) in enumerate(zip(got[1], ref[1]), start=1):
             assert np.array_equal(a.view(np.uint32), b.view(np.uint32)), (kw, "W_%d" % l)
+
+
+@pytest.mark.timeout(600)
+def test_ffn_stack_full_size_hadamard_forms_agree_bit_for_bit():
+    """The largest workload, three steps in each form of the Hadamard product: every layer's dY (what the fused dX
+    epilogue of 256 x 256 tiles writes for the eight GELU layers, with f' from the table) and the losses, bit for bit."""
+    wl = WL.ffn_stack()
+    W0 = WL.init_weights(wl)
+
+    def run(fused):
+        net = lp.Network(wl.layers, wl.batch, wl.dtype, wl.loss, wl.lr, wl.delays, fused_hadamard=fused)
+        net.set_weights(W0)
+        xs = [net.to_device(WL.batch_input(wl, n)) for n in range(1, 4)]
+        ts = [net.to_device(WL.batch_target(wl, n)) for n in range(1, 4)]
+        losses = torch.zeros(3, dtype=torch.float32, device="cuda:0")
+        torch.cuda.synchronize()
+        for n in range(3):
+            lp.lp_step(net.ctx, xs[n], ts[n], None, losses[n:n + 1], net.streams)
+        lp.lp_sync(net.ctx)
+        has_da = [net.tensor(l, lp.LP_T_DA) is not None for l in range(1, wl.L)]
+        dys = [net.tensor(l, lp.LP_T_DY).view(torch.int16).clone() for l in range(1, wl.L + 1)]
+        torch.cuda.synchronize()
+        out = (losses.cpu().numpy().copy(), dys, has_da)
+        net.close()
+        return out
+
+    a = run(True)
+    assert a[2] == [l % 2 == 0 for l in range(1, wl.L)], "dA is stored for the identity layers only"
+    b = run(False)
+    assert all(b[2])
+    assert np.all(np.isfinite(a[0])) and np.array_equal(a[0].view(np.uint32), b[0].view(np.uint32))
+    for l, (ya, yb) in enumerate(zip(a[1], b[1]), start=1):
+        assert torch.equal(ya, yb), "dY_%d" % l
