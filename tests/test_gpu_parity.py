@@ -64,8 +64,11 @@ def one_layer_net(d_in, d_out, batch, act="relu", dtype="bf16", seed=0):
 FWD_SHAPES = [(96, 200, 136), (33, 77, 19), (1, 8, 8), (7, 1, 3), (300, 520, 264), (64, 4096, 64),
               (1100, 72, 3000), (2304, 96, 5632), (256, 512, 1000), (1024, 136, 6200), (2300, 100, 5700),
               (1101, 71, 3001), (256, 2048, 512), (300, 2056, 1160), (200, 1160, 3080),
-              (128, 4096, 10), (33, 264, 16), (5, 72, 1), (2048, 512, 13), (2049, 512, 10)]
-# The last five are layers with at most 16 outputs: short-vector kernels (gemm_skinny.hip) up to batch 2048, MFMA tiles beyond.
+              (128, 4096, 10), (33, 264, 16), (5, 72, 1), (2048, 512, 13), (2049, 512, 10),
+              (256, 4096, 3072), (512, 512, 4096)]
+# (128, 4096, 10) ... (2049, 512, 10) are layers with at most 16 outputs: short-vector kernels (gemm_skinny.hip) up to batch 2048,
+# MFMA tiles beyond.  The last two have too few 128 x 128 tiles for the chip but enough 64 x 64 ones: unsplit, eight LDS stages
+# (F and dX of the first, F and dW of the second).
 # K is split over workgroups for F of (64, 4096, 64), (256, 2048, 512), (300, 2056, 1160) (ragged last range), for dX of
 # (1100, 72, 3000), (200, 1160, 3080) and for dW of (2304, 96, 5632)
 
