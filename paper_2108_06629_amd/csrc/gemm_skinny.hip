@@ -3,9 +3,10 @@
 // for F with its K split and reduction, 6 us for dX, 10 us for dW); here the whole weight matrix row block W[k..k+8)[0..N)
 // is N consecutive 16-byte vectors, so each product is a short vector kernel:
 //
-//   F   one wavefront per batch row: lanes stride over k in steps of 8, fp32 partial sums, butterfly reduction
+//   F   one workgroup per batch row: lanes stride over k in steps of 8, fp32 partial sums, butterfly reduction per
+//       wavefront, the four wavefronts added in a fixed order
 //   dX  one lane per (row, 8 input features): N-term dot products against the same N vectors of W
-//   dW  one lane per input feature and quarter of the batch rows, the four quarters summed in a fixed order
+//   dW  one lane per input feature and sixteenth of the batch rows, the sixteen parts summed in a fixed tree
 //
 // fp32 accumulation in a fixed order everywhere (no atomics); every output element is summed in the same order whatever
 // column range of dX is asked for.  The launcher (launch_gemm_bf16) comes here for shapes gemm_skinny_shape() accepts.
@@ -35,19 +36,21 @@ __device__ __forceinline__ float wave_sum64(float v) {
   return v;
 }
 
-// Z[m][0..N) = X[m][0..K) . W[0..K)[0..N), A = f(Z).  K % 8 == 0; X rows and W 16-byte aligned.
+// Z[m][0..N) = X[m][0..K) . W[0..K)[0..N), A = f(Z).  K % 8 == 0; X rows and W 16-byte aligned.  One workgroup per
+// batch row: lane t takes k = 8 t, 8 t + 2048, ...; a butterfly sums each wavefront, the four wavefronts' sums are added
+// as (0 + 1) + (2 + 3).
 template <int N>
 __global__ void __launch_bounds__(256) skinny_fwd_kernel(const unsigned short* __restrict__ X, const unsigned short* __restrict__ W,
                                                          unsigned short* __restrict__ Z, unsigned short* __restrict__ A, int M, int K, int lda,
                                                          int ldc, int act, const unsigned short* __restrict__ act_lut) {
-  const int lane = threadIdx.x & 63;
-  const int m = blockIdx.x * 4 + (int)(threadIdx.x >> 6);
-  if (m >= M) return;   // a whole wavefront leaves; the kernel has no barrier
+  __shared__ float part[4][N];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int m = blockIdx.x;   // the grid has exactly M workgroups
   float acc[N];
 #pragma unroll
   for (int n = 0; n < N; ++n) acc[n] = 0.f;
   const unsigned short* x = X + (size_t)m * lda;
-  for (int k = lane * 8; k < K; k += 512) {
+  for (int k = threadIdx.x * 8; k < K; k += 2048) {
     const u32x4 xv = *reinterpret_cast<const u32x4*>(x + k);
     u32x4 w[N];
 #pragma unroll
@@ -60,14 +63,16 @@ __global__ void __launch_bounds__(256) skinny_fwd_kernel(const unsigned short* _
     }
   }
 #pragma unroll
-  for (int n = 0; n < N; ++n) acc[n] = wave_sum64(acc[n]);
-  if (lane == 0) {
-#pragma unroll
-    for (int n = 0; n < N; ++n) {
-      const unsigned short zb = bf16_bits(acc[n]);
-      if (Z) Z[(size_t)m * ldc + n] = zb;
-      if (A) A[(size_t)m * ldc + n] = (act == ACT_GELU && act_lut) ? act_lut[zb] : bf16_bits(apply_act(bf16_to_f32(zb), act));
-    }
+  for (int n = 0; n < N; ++n) {
+    const float v = wave_sum64(acc[n]);
+    if (lane == 0) part[wave][n] = v;
+  }
+  __syncthreads();
+  if ((int)threadIdx.x < N) {
+    const int n = threadIdx.x;
+    const unsigned short zb = bf16_bits((part[0][n] + part[1][n]) + (part[2][n] + part[3][n]));
+    if (Z) Z[(size_t)m * ldc + n] = zb;
+    if (A) A[(size_t)m * ldc + n] = (act == ACT_GELU && act_lut) ? act_lut[zb] : bf16_bits(apply_act(bf16_to_f32(zb), act));
   }
 }
 
@@ -135,29 +140,37 @@ __global__ void __launch_bounds__(256) skinny_dx_kernel(const unsigned short* __
   }
 }
 
-// G[k][0..N) = sum_m X[m][k] dY[m][0..N), fp32.  A workgroup owns 64 input features; wavefront q sums the batch rows
-// m = q, q + 4, ...; the four partial sums are added as (0 + 1) + (2 + 3).
+// G[k][0..N) = sum_m X[m][k] dY[m][0..N), fp32.  A workgroup owns 16 input features; its 16 groups of 16 lanes sum the
+// batch rows m = g, g + 16, ... each, and the sixteen partial sums are added pairwise in a fixed tree.
 template <int N>
 __global__ void __launch_bounds__(256) skinny_dw_kernel(const unsigned short* __restrict__ X, const unsigned short* __restrict__ dY,
                                                         float* __restrict__ G, int B, int K, int lda) {
-  __shared__ float part[4][64 * N];
-  const int kl = threadIdx.x & 63;
-  const int q = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int k0 = blockIdx.x * 64, k = k0 + kl;
+  __shared__ float part[16][16 * N];
+  const int kl = threadIdx.x & 15, g = threadIdx.x >> 4;
+  const int k0 = blockIdx.x * 16, k = k0 + kl;
   float acc[N];
 #pragma unroll
   for (int n = 0; n < N; ++n) acc[n] = 0.f;
 #pragma unroll 4
-  for (int m = q; m < B; m += 4) {
+  for (int m = g; m < B; m += 16) {
     const float x = k < K ? bf16_to_f32(X[(size_t)m * lda + k]) : 0.f;
 #pragma unroll
     for (int n = 0; n < N; ++n) acc[n] = fmaf(x, bf16_to_f32(dY[(size_t)m * N + n]), acc[n]);
   }
 #pragma unroll
-  for (int n = 0; n < N; ++n) part[q][kl * N + n] = acc[n];
+  for (int n = 0; n < N; ++n) part[g][kl * N + n] = acc[n];
   __syncthreads();
-  for (int e = threadIdx.x; e < 64 * N; e += 256) {
-    if (k0 + e / N < K) G[(size_t)k0 * N + e] = (part[0][e] + part[1][e]) + (part[2][e] + part[3][e]);
+  for (int e = threadIdx.x; e < 16 * N; e += 256) {
+    if (k0 + e / N < K) {
+      float q[16];
+#pragma unroll
+      for (int u = 0; u < 16; ++u) q[u] = part[u][e];
+#pragma unroll
+      for (int w = 8; w > 0; w >>= 1)
+#pragma unroll
+        for (int u = 0; u < w; ++u) q[u] = q[2 * u] + q[2 * u + 1];
+      G[(size_t)k0 * N + e] = q[0];
+    }
   }
 }
 
@@ -166,7 +179,7 @@ inline bool al16(const void* p) { return ((uintptr_t)p % 16) == 0; }
 template <int N>
 hipError_t launch_n(int form, const GemmDesc& d, hipStream_t s) {
   if (form == 0) {
-    hipLaunchKernelGGL(skinny_fwd_kernel<N>, dim3((unsigned)((d.M + 3) / 4)), dim3(256), 0, s, (const unsigned short*)d.A, (const unsigned short*)d.B,
+    hipLaunchKernelGGL(skinny_fwd_kernel<N>, dim3((unsigned)d.M), dim3(256), 0, s, (const unsigned short*)d.A, (const unsigned short*)d.B,
                        (unsigned short*)d.out_z, (unsigned short*)d.out_a, d.M, d.K, d.lda, d.ldc, d.act, (const unsigned short*)d.act_lut);
   } else if (form == 1) {
     const size_t n = (size_t)d.M * ((d.N + 7) / 8);
@@ -178,7 +191,7 @@ hipError_t launch_n(int form, const GemmDesc& d, hipStream_t s) {
       hipLaunchKernelGGL((skinny_dx_kernel<N, false>), dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, (const unsigned short*)d.A, (const unsigned short*)d.B,
                          (unsigned short*)d.out_z, d.M, d.N, d.ldc, (const unsigned short*)d.had_s, d.had_s ? d.had_lut : nullptr);
   } else {
-    hipLaunchKernelGGL(skinny_dw_kernel<N>, dim3((unsigned)((d.M + 63) / 64)), dim3(256), 0, s, (const unsigned short*)d.A, (const unsigned short*)d.B,
+    hipLaunchKernelGGL(skinny_dw_kernel<N>, dim3((unsigned)((d.M + 15) / 16)), dim3(256), 0, s, (const unsigned short*)d.A, (const unsigned short*)d.B,
                        d.out_f32, d.K, d.M, d.lda);
   }
   return hipGetLastError();
