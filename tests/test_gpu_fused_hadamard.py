@@ -174,3 +174,20 @@ def test_convolution_dx_with_fused_hadamard_bits_equal_two_kernel_form(batch, hw
     assert got[3][:-1] == [i == wl.L - 2 for i in range(wl.L - 1)]
     assert_same(ref, got)
     assert_same(ref, run(wl, W0, steps, splits=splits, run_ahead=True))
+
+
+def test_gelu_convolutions_look_the_derivative_up_in_both_forms():
+    """A CNN with GELU: the unpooled layers' Hadamard products ride in the dX epilogues above them (convolution and fully
+    connected) with f' from the table; the pooled GELU layer is routed by the stand-alone kernel (the fused routing is
+    the ReLU form only).  Both forms agree bit for bit."""
+    layers = (WL.Layer(WL.CONV3X3, 8, 16, WL.GELU, H=8, W=8, pool=0), WL.Layer(WL.CONV3X3, 16, 16, WL.GELU, H=8, W=8, pool=2),
+              WL.Layer(WL.CONV3X3, 16, 24, WL.GELU, H=4, W=4, pool=0), WL.Layer(WL.LINEAR, 4 * 4 * 24, 40, WL.GELU),
+              WL.Layer(WL.LINEAR, 40, 10, WL.IDENTITY))
+    wl = WL.vgg_small(batch=6, hw=8, chans=(8, 8)).with_(layers=layers, delays=(8, 6, 4, 2, 0))
+    W0 = WL.init_weights(wl)
+    ref = run(wl, W0, 12, fused_hadamard=False)
+    assert np.all(np.isfinite(ref[0])) and all(ref[3][:-1])
+    got = run(wl, W0, 12)
+    assert got[3][:-1] == [False, True, False, False]
+    assert_same(ref, got)
+    assert_same(ref, run(wl, W0, 12, splits={2: 8, 3: 8}, run_ahead=True))
