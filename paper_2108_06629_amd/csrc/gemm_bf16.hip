@@ -190,7 +190,6 @@ constexpr TileCfg kCfgs[] = {
     {"256x256x64_w2x2", 256, 256, 0},     // 3
     {"256x256x64_dl_w2x4", 256, 256, 1},  // 4
     {"128x128x64_dl_w2x2", 128, 128, 1},  // 5
-    {"64x64x64_dl_w2x2_s8", 64, 64, 1},   // 6: eight LDS stages, for products with few rows and a long reduction
 };
 
 template <int BM, int BN, int BK, int WM, int WN, bool AKC, bool BKC, bool ALIGNED, bool SGD = false>
@@ -253,20 +252,8 @@ hipError_t launch_cfg_dl(int cfg, const GemmKArgs& a, hipStream_t s) {
   switch (cfg) {
     case 4: return launch_dl<256, 256, 64, 2, 2, 4, AKC, BKC>(a, s);
     case 5: return launch_dl<128, 128, 64, 2, 2, 2, AKC, BKC>(a, s);
-    case 6: return launch_dl<64, 64, 64, 8, 2, 2, AKC, BKC>(a, s);
   }
   return hipErrorInvalidValue;
-}
-
-// A product too small for a chip's worth of 128 x 128 tiles but with one for (nearly) every CU in 64 x 64 tiles, and a
-// reduction of moderate length, runs unsplit on 64 x 64 tiles with eight LDS stages: as fast stand-alone as four K
-// ranges plus their reduction (21 against 23 us for 256 x 4096 x 4096), with one launch instead of two and without the
-// partial sums' trip through memory (mlp_4096: 0.81 -> 0.77 ms per step).  Longer reductions keep the K ranges: a
-// single wavefront per SIMD takes about 0.33 us per K step of 64.
-bool deep_64x64(int M, int N, int K) {
-  const long t128 = (long)((M + 127) / 128) * ((N + 127) / 128);
-  const long t64 = (long)((M + 63) / 64) * ((N + 63) / 64);
-  return t128 < 192 && t64 >= 192 && K <= 4096 && M % 8 == 0 && N % 8 == 0 && K % 8 == 0;
 }
 
 // how many K ranges a product on 128x128 tiles is cut into (1: not split)
@@ -274,7 +261,6 @@ int splitk_factor(int M, int N, int K) {
   const long t256 = (long)((M + 255) / 256) * ((N + 255) / 256);
   const long t128 = (long)((M + 127) / 128) * ((N + 127) / 128);
   if (t256 >= 192 || t128 >= 256 || K < 2048) return 1;
-  if (deep_64x64(M, N, K)) return 1;
   long s = 512 / t128;               // two workgroups per CU
   // at least sixteen K steps each (shorter ranges cost more in partial-sum traffic than they gain), four
   // when the whole output is so small (64 K elements) that its partials do not matter
@@ -473,7 +459,7 @@ hipError_t launch_gemm_bf16(const GemmDesc& d, hipStream_t s, int tile_cfg) {
     const long t256 = (long)((d.M + 255) / 256) * ((d.N + 255) / 256);
     const long t128 = (long)((d.M + 127) / 128) * ((d.N + 127) / 128);
     if (t256 >= 192) cfg = aligned ? 4 : (both_kc ? 0 : 3);
-    else if (aligned) cfg = (!sgd && d.splitk_splits <= 1 && deep_64x64(d.M, d.N, d.K)) ? 6 : 5;
+    else if (aligned) cfg = 5;
     else cfg = t128 >= 64 ? 1 : 2;
   }
   if (cfg < 0 || cfg >= gemm_bf16_num_cfgs()) return hipErrorInvalidValue;

@@ -52,10 +52,9 @@ def test_factor_ring_bits_equal_product_ring(widths, batch):
 
 
 def test_factor_ring_skips_layers_whose_gradient_product_is_split_over_k():
-    """Batch 2048: the G product of the 512 x 512 layer is cut into K ranges by lp_grad_weight (the fused update never
-    cuts K) and that of the 4096 x 16 layer runs on the few-outputs kernels, so "every layer" leaves those two on the
-    product ring; the 512 x 4096 layer (unsplit on 64 x 64 tiles) and the 4096 x 4096 layer keep their factors.  Bits
-    equal the all-product-ring run."""
+    """Batch 2048: the G products of 512 x 512, 512 x 4096 and 4096 x 16 layers are cut into K ranges by
+    lp_grad_weight; the fused update never cuts K, so "every layer" leaves those on the product ring and only the
+    4096 x 4096 layer keeps its factors.  Bits equal the all-product-ring run."""
     wl = WL.mlp_4096().with_(layers=WL._mlp([512, 512, 4096, 4096, 16], WL.RELU), batch=2048, delays=(6, 4, 2, 0))
     W0 = WL.init_weights(wl)
     ref = run(wl, W0, 9)
@@ -64,7 +63,7 @@ def test_factor_ring_skips_layers_whose_gradient_product_is_split_over_k():
     net = lp.Network(wl.layers, wl.batch, wl.dtype, wl.loss, wl.lr, wl.delays, factor_ring=True)
     net.set_weights(W0)
     net.step(WL.batch_input(wl, 1), WL.batch_target(wl, 1))
-    assert [net.tensor(l, lp.LP_T_G_LAST) is None for l in (1, 2, 3, 4)] == [False, True, True, False]
+    assert [net.tensor(l, lp.LP_T_G_LAST) is None for l in (1, 2, 3, 4)] == [False, False, True, False]
     net.close()
     with pytest.raises(lp.LpError) as e:
         lp.Network(wl.layers, wl.batch, wl.dtype, wl.loss, wl.lr, wl.delays, factor_ring=[1])

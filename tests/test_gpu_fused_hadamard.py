@@ -48,8 +48,7 @@ def mlp(widths, batch, act=WL.RELU, **kw):
 
 # kernel variants of the dX product: 128 x 128 direct-to-LDS tiles (aligned), the register-staged loop with scalar stores
 # (ragged widths), 256 x 256 tiles (a 2304 x 5632 output), K cut into ranges with the epilogue in the reduction kernel
-# (batch 256, a 2048-wide layer below a 4096-wide one: 128 tiles of 64 x 64, K = 4096), 64 x 64 tiles with eight LDS stages
-# (batch 256, widths 4096), the short-vector kernels of a 10-output classifier
+# (batch 256, widths 2048 and 4096: fewer than 256 tiles of 128 x 128, K = 4096), the short-vector kernels of a 10-output classifier
 CASES = [([256, 320, 192, 136, 40], 96), ([77, 130, 45, 19, 10], 33), ([512, 5632, 4096, 264, 16], 2304), ([4096, 2048, 4096, 1000], 256),
          ([4096, 4096, 4096, 1000], 256),
          ([264, 2056, 1160, 72], 300), ([256, 320, 72, 10], 96)]

@@ -67,8 +67,8 @@ FWD_SHAPES = [(96, 200, 136), (33, 77, 19), (1, 8, 8), (7, 1, 3), (300, 520, 264
               (128, 4096, 10), (33, 264, 16), (5, 72, 1), (2048, 512, 13), (2049, 512, 10),
               (256, 4096, 3072), (512, 512, 4096)]
 # (128, 4096, 10) ... (2049, 512, 10) are layers with at most 16 outputs: short-vector kernels (gemm_skinny.hip) up to batch 2048,
-# MFMA tiles beyond.  The last two have too few 128 x 128 tiles for the chip but enough 64 x 64 ones: unsplit, eight LDS stages
-# (F and dX of the first, F and dW of the second).
+# MFMA tiles beyond.  The last two are skinny against a wide layer (64 and 128 tiles of 128 x 128): K cut into ranges for F and dX
+# of the first, one short pass for the second.
 # K is split over workgroups for F of (64, 4096, 64), (256, 2048, 512), (300, 2056, 1160) (ragged last range), for dX of
 # (1100, 72, 3000), (200, 1160, 3080) and for dW of (2304, 96, 5632)
 
