@@ -190,3 +190,32 @@ def test_gelu_convolutions_look_the_derivative_up_in_both_forms():
     assert got[3][:-1] == [False, True, False, False]
     assert_same(ref, got)
     assert_same(ref, run(wl, W0, 12, splits={2: 8, 3: 8}, run_ahead=True))
+
+
+def test_switching_the_form_between_steps_changes_no_bits():
+    """lp_set_fused_hadamard may be called between steps (also under graph replay, where it drops the captured steps)."""
+    wl = mlp([256, 320, 192, 136, 40], 96, WL.GELU)
+    W0 = WL.init_weights(wl)
+    steps = 24
+    ref = run(wl, W0, steps)
+    for graphs in (False, True):
+        net = lp.Network(wl.layers, wl.batch, wl.dtype, wl.loss, wl.lr, wl.delays, graphs=graphs)
+        net.set_weights(W0)
+        xs = [net.to_device(WL.batch_input(wl, n)) for n in range(1, steps + 1)]
+        ts = [net.to_device(WL.batch_target(wl, n), is_label=True) for n in range(1, steps + 1)]
+        losses = torch.zeros(steps, dtype=torch.float32, device=DEV)
+        slot = torch.zeros(1, dtype=torch.float32, device=DEV)
+        torch.cuda.synchronize()
+        for n in range(steps):
+            if n % 5 == 3:
+                lp.lp_sync(net.ctx)
+                lp.lp_set_fused_hadamard(net.ctx, (n // 5) % 2 == 1)
+            lp.lp_step(net.ctx, xs[n], ts[n], None, slot, net.streams)
+            with torch.cuda.stream(net.streams[0]):
+                losses[n:n + 1].copy_(slot)
+        lp.lp_sync(net.ctx)
+        torch.cuda.synchronize()
+        assert np.array_equal(losses.cpu().numpy().view(np.uint32), ref[0].view(np.uint32)), graphs
+        for l in range(1, wl.L + 1):
+            assert np.array_equal(net.get_weights(l).view(np.uint32), ref[1][l - 1].view(np.uint32)), (graphs, l)
+        net.close()
