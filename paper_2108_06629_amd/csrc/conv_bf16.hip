@@ -808,7 +808,7 @@ hipError_t set_lds(K kern) {
 int dw_splits(const ConvDesc& c) {
   const long M = 9L * c.Cin, N = c.Cout, K = (long)c.B * c.H * c.W;
   const long tiles = ((M + BM - 1) / BM) * ((N + BN - 1) / BN);
-  long s = (768 + tiles - 1) / tiles;   // aim at about three workgroups per CU
+  long s = (512 + tiles - 1) / tiles;   // aim at two workgroups per CU (measured on the six layers of the VGG-style workload: 384, 448, 576 ... 2048 are all slower)
   if (s > K / 512) s = K / 512;
   if (s > 256) s = 256;
   if (s < 1) s = 1;
