@@ -118,6 +118,54 @@ __global__ void __launch_bounds__(256) act_grad_bf16_kernel(const u32x4* __restr
   }
 }
 
+// The GELU form for large tensors.  The look-up of the kernel above is a 4-byte gather per element through the vector
+// memory path, which the streaming loads and stores of the same kernel also use: 0.22 ms for 134 M elements, against
+// 0.15 ms when f' was computed.  Here one workgroup per CU first copies the part of the table that real pre-activations
+// hit (|z| < 16: bit patterns below 0x4180 of either sign, 2 x 16768 floats = 131 KiB) into LDS and then walks the
+// tensor with a grid stride; a look-up is an LDS read, anything outside the cached range goes to the table in memory.
+// Same table, same product: the bits of the kernel above.
+constexpr int LUT_CACHED = 0x4180;
+__global__ void __launch_bounds__(1024) act_grad_bf16_lds_lut_kernel(const u32x4* __restrict__ dA, const u32x4* __restrict__ S,
+                                                                     u32x4* __restrict__ dY, size_t nvec, size_t n, const float* __restrict__ lut) {
+  extern __shared__ float tab[];
+  for (int i = threadIdx.x; i < 2 * LUT_CACHED / 4; i += 1024) {
+    const int e = i * 4;                                  // LUT_CACHED % 4 == 0: a quad never straddles the two halves
+    const int bits = e < LUT_CACHED ? e : 0x8000 + (e - LUT_CACHED);
+    *reinterpret_cast<f32x4*>(tab + e) = *reinterpret_cast<const f32x4*>(lut + bits);
+  }
+  __syncthreads();
+  auto df = [&](unsigned short b) -> float {
+    const int m = b & 0x7fff;
+    return m < LUT_CACHED ? tab[m + (b >> 15) * LUT_CACHED] : lut[b];
+  };
+  const size_t stride = (size_t)gridDim.x * 1024;
+  for (size_t i = (size_t)blockIdx.x * 1024 + threadIdx.x; i < nvec; i += 2 * stride) {
+    const size_t i2 = i + stride;
+    const bool two = i2 < nvec;
+    const u32x4 a0 = __builtin_nontemporal_load(dA + i), s0 = __builtin_nontemporal_load(S + i);
+    u32x4 a1 = {0u, 0u, 0u, 0u}, s1 = {0u, 0u, 0u, 0u};
+    if (two) { a1 = __builtin_nontemporal_load(dA + i2); s1 = __builtin_nontemporal_load(S + i2); }
+    u32x4 o0, o1;
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+      o0[d] = (unsigned)f2bf(bf2f((unsigned short)(a0[d] & 0xffffu)) * df((unsigned short)(s0[d] & 0xffffu))) |
+              ((unsigned)f2bf(bf2f((unsigned short)(a0[d] >> 16)) * df((unsigned short)(s0[d] >> 16))) << 16);
+      o1[d] = (unsigned)f2bf(bf2f((unsigned short)(a1[d] & 0xffffu)) * df((unsigned short)(s1[d] & 0xffffu))) |
+              ((unsigned)f2bf(bf2f((unsigned short)(a1[d] >> 16)) * df((unsigned short)(s1[d] >> 16))) << 16);
+    }
+    __builtin_nontemporal_store(o0, dY + i);
+    if (two) __builtin_nontemporal_store(o1, dY + i2);
+  }
+  if (blockIdx.x == 0) {   // scalar tail (n not a multiple of 8)
+    const size_t i = nvec * 8 + threadIdx.x;
+    if (i < n) {
+      const unsigned short* a16 = (const unsigned short*)dA;
+      const unsigned short* s16 = (const unsigned short*)S;
+      ((unsigned short*)dY)[i] = f2bf(bf2f(a16[i]) * df(s16[i]));
+    }
+  }
+}
+
 template <int ACT>
 __global__ void __launch_bounds__(256) act_grad_f32_kernel(const f32x4* __restrict__ dA, const f32x4* __restrict__ S,
                                                            f32x4* __restrict__ dY, size_t nvec, size_t n) {
@@ -515,6 +563,23 @@ hipError_t launch_act_grad(bool bf16, int act, const void* dA, const void* S, vo
   if (bf16) {
     const float* no_lut = nullptr;
     if (act == ACT_RELU) hipLaunchKernelGGL(act_grad_bf16_kernel<ACT_RELU>, dim3(nb), dim3(256), 0, s, (const u32x4*)dA, (const u32x4*)S, (u32x4*)dY, nvec, n, no_lut);
+    else if (act == ACT_GELU && gelu_grad_lut && n >= ((size_t)1 << 22)) {
+      // large tensors: the table's live part in LDS, one workgroup of 1024 lanes per CU
+      constexpr int lds = 2 * LUT_CACHED * (int)sizeof(float);
+      struct Setup { hipError_t err; int cus; };
+      static const Setup setup = [] {          // once per process (one GPU per process)
+        Setup u{hipSuccess, 0};
+        int dev = 0;
+        u.err = hipGetDevice(&dev);
+        if (u.err == hipSuccess) u.err = hipDeviceGetAttribute(&u.cus, hipDeviceAttributeMultiprocessorCount, dev);
+        if (u.err == hipSuccess) u.err = hipFuncSetAttribute((const void*)act_grad_bf16_lds_lut_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        if (u.cus < 1) u.cus = 256;
+        return u;
+      }();
+      if (setup.err != hipSuccess) return setup.err;
+      const int cus = setup.cus;
+      hipLaunchKernelGGL(act_grad_bf16_lds_lut_kernel, dim3((unsigned)cus), dim3(1024), lds, s, (const u32x4*)dA, (const u32x4*)S, (u32x4*)dY, nvec, n, gelu_grad_lut);
+    }
     else if (act == ACT_GELU && gelu_grad_lut) hipLaunchKernelGGL(act_grad_bf16_kernel<ACT_LUT>, dim3(nb), dim3(256), 0, s, (const u32x4*)dA, (const u32x4*)S, (u32x4*)dY, nvec, n, gelu_grad_lut);
     else if (act == ACT_GELU) hipLaunchKernelGGL(act_grad_bf16_kernel<ACT_GELU>, dim3(nb), dim3(256), 0, s, (const u32x4*)dA, (const u32x4*)S, (u32x4*)dY, nvec, n, no_lut);
     else if (act == ACT_TANH) hipLaunchKernelGGL(act_grad_bf16_kernel<ACT_TANH>, dim3(nb), dim3(256), 0, s, (const u32x4*)dA, (const u32x4*)S, (u32x4*)dY, nvec, n, no_lut);

@@ -238,6 +238,37 @@ def test_act_grad_hadamard(n_feat, act, dtype):
     net.close()
 
 
+def test_act_grad_hadamard_gelu_large_tensor_matches_small():
+    """Tensors of 4 M elements and more take the GELU form that keeps the derivative table's live part in LDS; smaller
+    ones gather from the table in memory.  Both must give the same bits, also for pre-activations outside the cached
+    range (|z| >= 16, infinities, NaN) and in the scalar tail (element count not a multiple of 8)."""
+    n_feat, B, Bs = 4099, 1031, 37
+    assert n_feat * B >= 1 << 22 and (n_feat * B) % 8 != 0
+    big, _, rng = one_layer_net(n_feat, n_feat, B, "gelu", "bf16")
+    small, _, _ = one_layer_net(n_feat, n_feat, Bs, "gelu", "bf16")
+    z = (rng.standard_normal((B, n_feat)) * 2.0).astype(np.float32)
+    z[0, :10] = [0.0, -0.0, 1e-30, -1e-30, 15.9375, 16.0, -16.0, 300.0, -300.0, 3e38]
+    z[1, :4] = [np.inf, -np.inf, np.nan, -15.9375]
+    z[-1, -5:] = [17.0, -17.0, 0.5, -0.5, 4.0]            # the last five elements are the scalar tail
+    da = rng.standard_normal((B, n_feat)).astype(np.float32)
+    zd, dad = dev(z, torch.bfloat16), dev(da, torch.bfloat16)
+    dY = synced(torch.full_like(dad, float("nan")))
+    lp.lp_act_grad(big.ctx, 1, dad, zd, dY, big.streams[0])
+    lp.lp_sync(big.ctx)
+    for r0 in (0, B - Bs):                                 # head and tail rows through the small-tensor form
+        zs, das = synced(zd[r0:r0 + Bs].clone()), synced(dad[r0:r0 + Bs].clone())
+        dYs = torch.empty_like(das)
+        lp.lp_act_grad(small.ctx, 1, das, zs, dYs, small.streams[0])
+        lp.lp_sync(small.ctx)
+        a, b = dY[r0:r0 + Bs].view(torch.int16), dYs.view(torch.int16)
+        assert torch.equal(a, b)
+    fin = np.isfinite(host(zd))
+    ref = O.store(O.act_grad(host(dad)[fin], host(zd)[fin], "gelu"), "bf16")
+    assert relerr(host(dY)[fin], ref) <= 2.0 ** -7
+    big.close()
+    small.close()
+
+
 # row lengths: not a multiple of the 16-byte vector (scalar kernel), one / two / four / eight vectors per lane of the
 # register-resident kernel, and a row too long for it
 @pytest.mark.parametrize("rows,cols", [(32, 10), (256, 1000), (5, 33), (1, 1), (1024, 1000), (9, 8), (7, 2048), (6, 4096), (3, 4104), (2, 8192)])
