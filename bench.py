@@ -5,7 +5,10 @@
 
 One "step" is one whole delayed-gradient training iteration (lp_step: F, loss, dX, the moved
 Hadamard, dW and the delayed update of every layer) over one synthetic minibatch that is already
-resident in HBM.  Prints ONE JSON line: training samples/s of the whole job, the roofline of the
+resident in HBM.  By default Eq. 6 runs in its retimed form (lp_set_retimed_update: the delays sit on
+the weights, the G task applies its gradient in the product's epilogue; losses and working weights are
+those of the gradient-ring form bit for bit, which --gradient-ring times instead and the default run
+times beside it).  Prints ONE JSON line: training samples/s of the whole job, the roofline of the
 dominant kernel (the bf16 MFMA GEMM of the forward product), per-task achieved rates, and the CPU
 oracle timed on a bounded sample of the same workload.
 """
@@ -234,10 +237,27 @@ def partition_report(wl, max_stages):
             "partitions": rows, "step_ms_three_streams": times}
 
 
+RETIMED_UPDATE = True    # --gradient-ring clears it; lp_set_retimed_update on every layer that qualifies (bf16 contexts)
 FUSED_HADAMARD = True   # --separate-hadamard clears it: Eq. 3 then runs as a kernel of its own after every dX product
 
 
-def run_workload(wl, steps, warmup, n_streams, profile=True, weights=None, run_ahead=False, factor_ring=False):
+def fills_chip(wl):
+    """Every product of every layer covers the chip with 256 x 256 tiles on its own (one per CU at least)."""
+    import lp_workloads as WL
+    t = lambda m, n: -(-m // 256) * -(-n // 256)
+    return all(ly.kind == WL.LINEAR and t(wl.batch, ly.d_out) >= 256 and t(wl.batch, ly.d_in) >= 256 and t(ly.d_in, ly.d_out) >= 256
+               for ly in wl.layers)
+
+
+def default_streams(wl, retimed):
+    """Streams of the serial schedule when --streams is not given: three, on which small kernels run side by side and the
+    delayed updates overlap the products -- but one for a network whose every product fills the chip alone once the
+    retimed update has removed the update tasks: nothing is left to run beside the products, and the forks and joins
+    of a step only cost (ffn_stack: 44.43 ms on three streams, 44.22 ms on one, same box)."""
+    return 1 if (retimed and wl.dtype == "bf16" and fills_chip(wl)) else 3
+
+
+def run_workload(wl, steps, warmup, n_streams, profile=True, weights=None, run_ahead=False, factor_ring=False, retimed=None):
     import numpy as np
     import torch
     import lp_workloads as WL
@@ -245,7 +265,8 @@ def run_workload(wl, steps, warmup, n_streams, profile=True, weights=None, run_a
 
     dev = torch.device("cuda:0")
     net = lp.Network(wl.layers, wl.batch, wl.dtype, wl.loss, wl.lr, wl.delays, device="cuda:0", n_streams=n_streams,
-                     run_ahead=run_ahead, factor_ring=(True if factor_ring else None), fused_hadamard=FUSED_HADAMARD)
+                     run_ahead=run_ahead, factor_ring=(True if factor_ring else None), fused_hadamard=FUSED_HADAMARD,
+                     retimed_update=(True if (RETIMED_UPDATE if retimed is None else retimed) and wl.dtype == "bf16" and not factor_ring else None))
     net.set_weights(WL.init_weights(wl) if weights is None else weights)
     # a small pool of resident minibatches, reused round-robin
     pool = 4
@@ -273,10 +294,12 @@ def run_workload(wl, steps, warmup, n_streams, profile=True, weights=None, run_a
         for k, name in enumerate(lp.TASK_NAMES):
             ms, cnt = lp.lp_profile_read(net.ctx, k, reset=True)
             prof[name] = (ms, cnt)
-    # how many layer updates ran in the timed steps (layers with n <= d_l are still frozen)
+    # how many layer updates ran in the timed steps (layers with n <= d_l are still frozen; a layer with the retimed
+    # update -- it keeps no gradients, like a factor ring, which this script never combines with it -- applies one in every step)
+    applies_at_once = [not factor_ring and net.tensor(l, lp.LP_T_G_LAST) is None for l in range(1, wl.L + 1)]
     upd_params = 0
     for n in range(n0 + 1, n0 + steps + 1):
-        upd_params += sum(ly.n_params for ly, d in zip(wl.layers, wl.delays) if n - d >= 1)
+        upd_params += sum(ly.n_params for ly, d, now in zip(wl.layers, wl.delays, applies_at_once) if now or n - d >= 1)
     net.close()
     del net
     torch.cuda.empty_cache()
@@ -289,13 +312,18 @@ def main():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=32)
     ap.add_argument("--workload", default="ffn_stack_bf16")
-    ap.add_argument("--streams", type=int, default=3)
+    ap.add_argument("--streams", type=int, default=None,
+                    help="streams of the serial schedule (default: 3; 1 for a network whose every product fills the chip, with the retimed update)")
     ap.add_argument("--no-task-timing", action="store_true", help="no per-task events in the timed steps (they cost host time; roofline and tasks are then empty)")
     ap.add_argument("--ra-streams", type=int, default=4, help="distinct streams of the run-ahead schedule (2, 3 or 4)")
     ap.add_argument("--run-ahead", action="store_true",
                     help="forward run-ahead across steps (lp_set_run_ahead): F(n+1) on a fourth stream next to the backward pass of step n")
     ap.add_argument("--factor-ring", action="store_true",
                     help="keep (A, dY) pairs instead of G in the delay elements and fuse the product into the delayed update (lp_set_factor_ring)")
+    ap.add_argument("--gradient-ring", action="store_true",
+                    help="Eq. 6 as printed: G_l(n) into a ring of d_l + 1 gradients, a delayed update task per layer and step.  Default is its retimed form "
+                         "(lp_set_retimed_update: the G task applies its gradient in the product's epilogue, steps read weight versions d_l + 1 steps old; "
+                         "same losses and working weights bit for bit, no gradient ring, no update task)")
     ap.add_argument("--separate-hadamard", action="store_true",
                     help="run the Hadamard products f'(S) (.) dA as kernels of their own instead of inside the dX products (lp_set_fused_hadamard 0)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -316,8 +344,9 @@ def main():
         print("bench.py: this build runs on ONE GPU (one MI355X per box, no collectives); --gpus %d is not supported" % args.gpus,
               file=sys.stderr)
         sys.exit(2)
-    global FUSED_HADAMARD
+    global FUSED_HADAMARD, RETIMED_UPDATE
     FUSED_HADAMARD = not args.separate_hadamard
+    RETIMED_UPDATE = not args.gradient_ring and not args.factor_ring
 
     import torch
     import lp_workloads as WL
@@ -365,6 +394,9 @@ def main():
         return
 
     wl = WL.CONFIGS[args.workload]()
+    streams_given = args.streams is not None
+    if not streams_given:
+        args.streams = default_streams(wl, RETIMED_UPDATE)
     if args.partition:
         print(json.dumps(partition_report(wl, args.partition)))
         return
@@ -372,10 +404,12 @@ def main():
     weights = WL.init_weights(wl)
     dt, loss, prof, upd_params = run_workload(wl, args.steps, args.warmup, args.ra_streams if args.run_ahead else args.streams, not args.no_task_timing, weights, args.run_ahead, args.factor_ring)
     del weights
+    retimed_here = RETIMED_UPDATE and wl.dtype == "bf16"
     ms_per_step = dt / args.steps * 1e3
     value = wl.batch * args.steps / dt
 
-    def task_rates(prof, steps, upd_params, factor_ring):
+    def task_rates(prof, steps, upd_params, factor_ring, retimed=None):
+        retimed = retimed_here if retimed is None else retimed
         out = {}
         for name in ("F", "dX", "dW"):
             ms, cnt = prof.get(name, (0.0, 0))
@@ -389,6 +423,9 @@ def main():
             if cnt:
                 tf = work[name] * steps / (ms * 1e-3) / 1e12
                 out[name] = {"launches": cnt, "avg_ms": ms / cnt, "TFLOP/s": tf, "frac_of_bf16_peak": tf / PEAK_BF16_TFLOPS}
+                if name == "dW" and retimed:
+                    out[name]["note"] = ("retimed update: the epilogue of this product applies Eq. 6 to the master weights and writes the next bf16 weight "
+                                         "version (10 B per parameter on top of the product's operands); the flops counted are the product's alone")
         for name in ("hadamard", "loss"):
             ms, cnt = prof.get(name, (0.0, 0))
             if cnt and ms > 0:
@@ -400,15 +437,28 @@ def main():
         if cnt and ms > 0 and not factor_ring:
             gbs = upd_params * work["update_per_param"] / (ms * 1e-3) / 1e9
             out["update"] = {"launches": cnt, "avg_ms": ms / cnt, "GB/s": gbs, "frac_of_hbm_peak": gbs / PEAK_HBM_GBS}
+            if retimed:
+                out["update"]["note"] = "layers that keep a gradient ring (convolutions, products split over K, few outputs); the others update inside dW"
+        elif retimed and not factor_ring:
+            out["update"] = {"launches": 0, "note": "applied in the epilogue of the dW products (its time is part of dW; --gradient-ring times it alone)"}
         return out
 
     tasks = task_rates(prof, args.steps, upd_params, args.factor_ring)
     # The same tasks with nothing running next to them (one stream, 4 steps): each kernel's own rate.  In the timed
     # region above dX and dW share the GPU and the updates run next to F, so those durations include the sharing.
+    # On one stream the timed region is that measurement.
     tasks_alone = None
-    if not args.no_others and not args.run_ahead and args.streams > 1:
+    if not args.run_ahead and args.streams == 1:
+        tasks_alone = tasks
+    elif not args.no_others and not args.run_ahead:
         _, _, prof1, upd1 = run_workload(wl, 4, args.warmup, 1, True, None, False, args.factor_ring)
         tasks_alone = task_rates(prof1, 4, upd1, args.factor_ring)
+    # Eq. 6 as printed, for comparison: gradient rings and one delayed update task per layer on three streams
+    ring_form = None
+    if retimed_here and not args.no_others and not args.run_ahead:
+        gdt, gloss, gprof, gupd = run_workload(wl, args.steps, args.warmup, 3, True, None, False, False, retimed=False)
+        ring_form = {"streams": 3, "ms_per_step": gdt / args.steps * 1e3, "value": wl.batch * args.steps / gdt, "final_loss": gloss,
+                     "updated_params_per_step": gupd / args.steps, "tasks": task_rates(gprof, args.steps, gupd, False, retimed=False)}
 
     # dominant kernel: the bf16 MFMA GEMM of the forward products (same instantiation for all layers
     # of the default workload)
@@ -449,13 +499,19 @@ def main():
                 continue
             o = mk()
             try:
-                odt, oloss, _, _ = run_workload(o, o.steps, 3, args.streams, False)
+                o_streams = args.streams if streams_given else default_streams(o, RETIMED_UPDATE)
+                odt, oloss, _, _ = run_workload(o, o.steps, 3, o_streams, False)
                 others[name] = {"samples_per_s": o.batch * o.steps / odt, "ms_per_step": odt / o.steps * 1e3, "steps": o.steps,
                                 "final_loss": oloss}
                 if o.n_params < 5e8:
                     # steady state: every layer's delayed update is active (n > max d_l) in all timed steps
-                    ydt, _, _, _ = run_workload(o, 100, max(o.delays) + 2, args.streams, False)
+                    ydt, _, _, _ = run_workload(o, 100, max(o.delays) + 2, o_streams, False)
                     others[name]["steady_state_ms_per_step"] = ydt / 100 * 1e3
+                if o.dtype == "bf16" and RETIMED_UPDATE and o.n_params < 5e8:
+                    gdt, gloss, _, _ = run_workload(o, o.steps, 3, 3, False, retimed=False)
+                    ydt, _, _, _ = run_workload(o, 100, max(o.delays) + 2, 3, False, retimed=False)
+                    others[name]["gradient_ring"] = {"samples_per_s": o.batch * o.steps / gdt, "ms_per_step": gdt / o.steps * 1e3,
+                                                     "steady_state_ms_per_step": ydt / 100 * 1e3, "final_loss": gloss}
                 if o.n_params < 5e8:
                     # one stream: a third of the host's enqueue time (no cross-stream waits), best for launch-bound networks
                     sdt, sloss, _, _ = run_workload(o, o.steps, 3, 1, False)
@@ -465,7 +521,7 @@ def main():
                     for label, kw in (("run_ahead", dict(run_ahead=True)), ("factor_ring", dict(factor_ring=True)),
                                       ("factor_ring+run_ahead", dict(run_ahead=True, factor_ring=True)),
                                       ("factor_ring+run_ahead_3_streams", dict(run_ahead=True, factor_ring=True, ns=3))):
-                        ns = kw.pop("ns", args.ra_streams if "run_ahead" in kw else args.streams)
+                        ns = kw.pop("ns", args.ra_streams if "run_ahead" in kw else o_streams)
                         rdt, rloss, _, _ = run_workload(o, o.steps, 3, ns, False, **kw)
                         ydt, _, _, _ = run_workload(o, 100, max(o.delays) + 2, ns, False, **kw)
                         others[name][label] = {"samples_per_s": o.batch * o.steps / rdt, "ms_per_step": rdt / o.steps * 1e3,
@@ -482,6 +538,8 @@ def main():
     # the same number of steps is timed once more behind a warm-up of max d_l + 1 steps.
     d_max = max(wl.delays)
     full_steps = sum(1 for n in range(args.warmup + 1, args.warmup + args.steps + 1) if n > d_max)
+    if upd_params == wl.n_params * args.steps:
+        full_steps = args.steps    # every layer has the retimed update: its G task applies a gradient in every step, from the first
     steady = None
     if full_steps < args.steps and not args.run_ahead:
         sdt, _, _, supd = run_workload(wl, args.steps, d_max + 1, args.streams, False, None, False, args.factor_ring)
@@ -492,16 +550,19 @@ def main():
         "metric": "training samples/sec (1 GPU)", "value": value, "unit": "samples/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": wl.dtype, "data": "synthetic",
-        "config": {"workload": "%s: %d layers, batch %d, delays %s, %s loss, lr %g, %d streams; %d of the %d timed steps update every layer "
-                               "(step number > max delay %d)" % (
+        "config": {"workload": "%s: %d layers, batch %d, delays %s, %s loss, lr %g, %d stream%s; %d of the %d timed steps update every layer%s" % (
             wl.name, wl.L, wl.batch, list(wl.delays), wl.loss, wl.lr, args.ra_streams if args.run_ahead else args.streams,
-            full_steps, args.steps, d_max) + (
+            "" if (args.ra_streams if args.run_ahead else args.streams) == 1 else "s",
+            full_steps, args.steps, "" if retimed_here else " (step number > max delay %d)" % d_max) + (
                 ", forward run-ahead" if args.run_ahead else "") + (", factor ring" if args.factor_ring else "") + (
-                ", Hadamard products as separate kernels" if args.separate_hadamard else ""),
+                ", Hadamard products as separate kernels" if args.separate_hadamard else "") + (
+                ", retimed update (Eq. 6 with its delays on the weights: weight versions in place of gradient rings, the dW launches apply the updates; "
+                "same losses bit for bit, see gradient_ring)" if retimed_here else ", gradient rings"),
             "params": wl.n_params, "flops_per_step": sum(wl.flops_per_step()),
             "updated_params_per_step": upd_params / args.steps},
         "steady_state": steady,
-        "roofline": roofline, "cpu_baseline": cpu, "tasks": tasks, "tasks_one_stream": tasks_alone, "other_workloads": others,
+        "roofline": roofline, "cpu_baseline": cpu, "tasks": tasks, "tasks_one_stream": tasks_alone, "gradient_ring": ring_form,
+        "other_workloads": others,
         "final_loss": loss,
     }
     print(json.dumps(out))

@@ -60,7 +60,7 @@ typedef enum {
   LP_ERR_SHAPE = 2,     /* a size or range is impossible (batch <= 0, col range, H/W odd with pool ...) */
   LP_ERR_DTYPE = 3,     /* unknown dtype / loss / activation / layer kind */
   LP_ERR_LAYER = 4,     /* layer index outside 1..L, or consecutive layers do not fit */
-  LP_ERR_DELAY = 5,     /* negative delay */
+  LP_ERR_DELAY = 5,     /* delay negative, above the configured one, or changed on a layer with the retimed update */
   LP_ERR_STATE = 6,     /* call needs a bound workspace or weights that were never set */
   LP_ERR_WORKSPACE = 7, /* workspace too small or misaligned */
   LP_ERR_HIP = 8        /* a HIP runtime call failed (message holds hipGetErrorString) */
@@ -240,6 +240,25 @@ int lp_set_run_ahead(lp_ctx* ctx, int enable);
  * lp_bind_workspace (LP_ERR_STATE afterwards).  LP_BF16 contexts (LP_ERR_DTYPE), linear layers
  * (LP_ERR_LAYER). */
 int lp_set_factor_ring(lp_ctx* ctx, int l, int enable);
+
+/* Retimed update: Eq. 6 with its d_l delay elements moved from the gradient, in front of the update, to the weights,
+ * behind it (the retiming of Sec. III-A, which ends with the delays between W and its readers: weight stashing).
+ * The G task of step n applies its gradient at once, in the epilogue of the product (tile by tile, the arithmetic
+ * of lp_update; G never travels through memory), to master weights that hold every gradient computed so far, and
+ * writes the bf16 copy of the result as weight version n; F and dX of step n read version n - 1 - d_l (version 0 =
+ * the weights given to lp_set_weights), held in a ring of d_l + 2 bf16 versions that takes the place of the gradient
+ * ring.  There is no update task.  The weights every step reads, and with them every activation, delta and the loss,
+ * are bit-identical with the gradient ring (the same gradients are applied in the same order; only the moment of the
+ * arithmetic differs); per parameter and step 10 bytes move instead of 4 + 14.  What differs for the caller:
+ * lp_get_weights / LP_T_MASTER_W of such a layer are d_l gradients ahead of the weights the next step reads
+ * (LP_T_WORK_W is those); LP_T_G_LAST is NULL; lp_update on it is LP_ERR_STATE; lp_step accepts only the layer's own
+ * d_l in `delay` (LP_ERR_DELAY); lp_set_weights sets the master weights and every held version.
+ * Linear layers of LP_BF16 contexts (LP_ERR_DTYPE) whose G product is neither split over K nor run on the few-outputs
+ * kernels (see lp_set_factor_ring) and that have no factor ring: l = 0 selects every such layer and leaves the others
+ * as they are, l > 0 on another layer is LP_ERR_LAYER.  Works with every schedule of lp_step (streams, run-ahead,
+ * graph replay, delta split).  Call after lp_create and before lp_workspace_bytes / lp_bind_workspace (LP_ERR_STATE
+ * afterwards). */
+int lp_set_retimed_update(lp_ctx* ctx, int l, int enable);
 
 /* Graph replay of whole steps: with enable != 0, lp_step captures the tasks of a step into a HIP graph
  * the first time it sees that step's combination of buffers (ring slots, working-weight copies, the

@@ -34,7 +34,7 @@ STATUS_NAMES = ["LP_OK", "LP_ERR_NULL", "LP_ERR_SHAPE", "LP_ERR_DTYPE", "LP_ERR_
 
 EXPORTS = ["lp_create", "lp_destroy", "lp_last_error", "lp_workspace_bytes", "lp_bind_workspace", "lp_set_weights",
            "lp_get_weights", "lp_cast", "lp_forward", "lp_loss_grad", "lp_loss_grad_static", "lp_act_grad", "lp_grad_act", "lp_grad_weight", "lp_update",
-           "lp_advance", "lp_step", "lp_step_index", "lp_sync", "lp_tensor", "lp_profile", "lp_profile_read", "lp_profile_read_layer", "lp_partition", "lp_set_delta_split", "lp_set_run_ahead", "lp_set_graphs", "lp_graph_stats", "lp_set_factor_ring", "lp_set_fused_hadamard", "lp_probe_mfma"]
+           "lp_advance", "lp_step", "lp_step_index", "lp_sync", "lp_tensor", "lp_profile", "lp_profile_read", "lp_profile_read_layer", "lp_partition", "lp_set_delta_split", "lp_set_run_ahead", "lp_set_graphs", "lp_graph_stats", "lp_set_factor_ring", "lp_set_retimed_update", "lp_set_fused_hadamard", "lp_probe_mfma"]
 
 
 class lp_layer_desc(C.Structure):
@@ -89,6 +89,7 @@ def load_library():
     L.lp_set_fused_hadamard.argtypes = [vp, ip]
     L.lp_set_graphs.argtypes = [vp, ip]
     L.lp_set_factor_ring.argtypes = [vp, ip, ip]
+    L.lp_set_retimed_update.argtypes = [vp, ip, ip]
     L.lp_graph_stats.argtypes = [vp, C.POINTER(C.c_long), C.POINTER(C.c_long), C.POINTER(C.c_long)]
     L.lp_profile_read_layer.argtypes = [vp, ip, ip, C.POINTER(C.c_double), C.POINTER(C.c_long), ip]
     L.lp_profile.argtypes = [vp, ip]
@@ -244,6 +245,10 @@ def lp_set_factor_ring(ctx, l: int, enable: bool):
     _check(ctx, lib().lp_set_factor_ring(ctx, l, int(enable)))
 
 
+def lp_set_retimed_update(ctx, l: int, enable: bool):
+    _check(ctx, lib().lp_set_retimed_update(ctx, l, int(enable)))
+
+
 def lp_set_graphs(ctx, enable: bool):
     _check(ctx, lib().lp_set_graphs(ctx, int(enable)))
 
@@ -292,7 +297,8 @@ class Network:
     objects (kind, d_in, d_out, act, H, W, pool)."""
 
     def __init__(self, layers, batch: int, dtype: str, loss: str, lr: float, delays, device: str = "cuda:0", n_streams: int = None,
-                 run_ahead: bool = False, graphs: bool = False, factor_ring=None, fused_hadamard: bool = True):
+                 run_ahead: bool = False, graphs: bool = False, factor_ring=None, fused_hadamard: bool = True,
+                 retimed_update=None):
         import torch
         self.torch = torch
         if n_streams is None:
@@ -303,6 +309,8 @@ class Network:
         self.act_dtype = torch.bfloat16 if dtype == "bf16" else torch.float32
         for l in ([] if factor_ring is None else ([0] if factor_ring is True else list(factor_ring))):
             lp_set_factor_ring(self.ctx, l, True)
+        for l in ([] if retimed_update is None else ([0] if retimed_update is True else list(retimed_update))):
+            lp_set_retimed_update(self.ctx, l, True)
         if graphs:
             lp_set_graphs(self.ctx, True)
         if not fused_hadamard:

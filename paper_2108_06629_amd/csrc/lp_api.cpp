@@ -35,6 +35,12 @@ struct Layer {
   int delay = 0;       // active d_l
   bool factor_ring = false;   // the ring holds (A_{l-1}, dY_l) pairs instead of G_l; the update multiplies them itself
   size_t ring_x_bytes = 0, ring_slot_bytes = 0;
+  // Retimed update (lp_set_retimed_update): the delay elements of Eq. 6 sit on the weights.  The G task applies its
+  // gradient at once (master = all gradients so far applied) and writes the result's bf16 copy as a new version;
+  // F and dX of step n read version n - 1 - d_l.  There is no gradient ring and no update task.
+  bool retimed = false;
+  int n_versions = 0;          // d_l + 2 (a power of two with graph replay)
+  size_t off_versions = 0, version_bytes = 0;
   int split_cols = 0;  // last columns of dA_{l-1} computed as a second, independent kernel (delta'')
   int cur = 0;         // working-weight buffer F and dX read now
   bool weights_set = false;
@@ -202,7 +208,13 @@ int need_weights(lp_ctx* c, int l) {
 }
 
 inline int layer_no(const lp_ctx* c, const Layer& ly) { return (int)(&ly - c->layers.data()) + 1; }
+// Version v of a retimed layer's working weights (v gradients applied).
+inline void* version_slot(lp_ctx* c, const Layer& ly, long v) {
+  return c->ws + ly.off_versions + (size_t)(v % ly.n_versions) * ly.version_bytes;
+}
+// The weights that the tasks of step c->n + 1 read.
 inline void* work_w(lp_ctx* c, Layer& ly) {
+  if (ly.retimed) { const long v = c->n - ly.d.delay; return version_slot(c, ly, v > 0 ? v : 0); }
   return is_bf16(c) ? (void*)(c->ws + ly.off_work[ly.cur]) : (void*)(c->ws + ly.off_master);
 }
 inline float* ring_slot(lp_ctx* c, Layer& ly, long step) {
@@ -314,6 +326,21 @@ hipError_t do_loss(lp_ctx* c, const void* ZL, const void* target, void* dYL, flo
 // The G task of step `step` as lp_step runs it: the product into its ring slot, or, for a layer with a
 // factor ring, only a copy of the two factors (the product is left to the delayed update).
 hipError_t enqueue_G(lp_ctx* c, Layer& ly, const void* X, const void* dY, long step, hipStream_t s) {
+  if (ly.retimed) {
+    // Eq. 6 retimed: G_l(step) is applied to the master weights tile by tile as the product leaves the accumulators
+    // (SgdEpilogue: the arithmetic of sgd_kernel) and the bf16 copy of the result becomes version `step`, which
+    // the steps from step + d_l + 1 on read.  Same product kernel and tile choice as lp_grad_weight.
+    ProfScope prof(c, LP_TASK_DW, layer_no(c, ly), s);
+    lp::GemmDesc g;
+    g.A = X; g.B = dY;
+    g.M = ly.d.in; g.N = ly.d.out; g.K = c->batch;
+    g.lda = ly.d.in; g.ldb = ly.d.out; g.ldc = ly.d.out;
+    g.a_kcontig = false; g.b_kcontig = false;
+    g.out_z = version_slot(c, ly, step);
+    g.sgd_master = (float*)(c->ws + ly.off_master);
+    g.sgd_lr = c->lr;
+    return lp::launch_gemm_bf16(g, s);
+  }
   if (!ly.factor_ring) return do_grad_weight(c, ly, X, dY, ring_slot(c, ly, step), s);
   ProfScope prof(c, LP_TASK_DW, layer_no(c, ly), s);
   char* slot = c->ws + ly.off_ring + (size_t)(step % ly.ring_slots) * ly.ring_slot_bytes;
@@ -385,13 +412,22 @@ void layout_workspace(lp_ctx* c) {
     const bool last = i == L - 1;
     const bool pooled = ly.d.kind == LP_CONV3X3 && ly.d.pool == 2;
     ly.off_master = take(ly.n_params * 4);
-    if (c->dtype == LP_BF16) { ly.off_work[0] = take(ly.n_params * 2); ly.off_work[1] = take(ly.n_params * 2); }
+    if (c->dtype == LP_BF16 && !ly.retimed) { ly.off_work[0] = take(ly.n_params * 2); ly.off_work[1] = take(ly.n_params * 2); }
     // d_l + 1 slots; with graph replay rounded up to a power of two, so that the slot a step uses repeats
     // with a short common period
     ly.ring_slots = ly.d.delay + 1;
     if (c->graphs) { int r = 1; while (r < ly.ring_slots) r *= 2; ly.ring_slots = r; }
-    if (ly.ring_slots > c->graph_period) c->graph_period = ly.ring_slots;
-    if (ly.factor_ring) {
+    if (ly.ring_slots > c->graph_period && !ly.retimed) c->graph_period = ly.ring_slots;
+    if (ly.retimed) {
+      // d_l + 2 versions: step n writes version n while it (and, with run-ahead, F of step n + 1) still reads
+      // versions n - 1 - d_l and n - d_l
+      ly.n_versions = ly.d.delay + 2;
+      if (c->graphs) { int r = 1; while (r < ly.n_versions) r *= 2; ly.n_versions = r; }
+      if (ly.n_versions > c->graph_period) c->graph_period = ly.n_versions;
+      ly.version_bytes = align_up(ly.n_params * 2);
+      ly.off_versions = take((size_t)ly.n_versions * ly.version_bytes);
+      ly.off_ring = 0;
+    } else if (ly.factor_ring) {
       ly.ring_x_bytes = align_up(ly.in_elems * es);
       ly.ring_slot_bytes = ly.ring_x_bytes + align_up(ly.z_elems * es);
       ly.off_ring = take((size_t)ly.ring_slots * ly.ring_slot_bytes);
@@ -478,7 +514,10 @@ int step_run_ahead(lp_ctx* c, const void* X0, const void* target, float* loss_de
     Layer& ly = c->layers[i];
     void* Z = ly.has_Z ? c->ws + ly.off_Z[p] : nullptr;
     void* A = ly.has_A ? c->ws + ly.off_A[p] : nullptr;
-    LP_HIP(c, wait_on(c, sF, c->ev_upd[i]));   // W_l(n-1) is complete (recorded by update_l(n-1) at the latest)
+    // W_l(n-1) is complete (recorded by update_l(n-1) at the latest).  A retimed layer reads the version that the G
+    // task of step n - 1 - d_l wrote: finished with B(n-2) for d_l > 0, else the newest G task
+    if (!ly.retimed) LP_HIP(c, wait_on(c, sF, c->ev_upd[i]));
+    else if (ly.d.delay == 0) LP_HIP(c, wait_on(c, sF, c->ev_dw[i]));
     LP_HIP(c, do_forward(c, ly, a_prev, Z, A, sF, 3));
     a_prev = A;
   }
@@ -491,7 +530,7 @@ int step_run_ahead(lp_ctx* c, const void* X0, const void* target, float* loss_de
   // Updates that need no gradient of this step (their G tasks ran in earlier steps).  Enqueued after
   // the forward chain so that F_l(n) above waited for update_l(n-1), not for these.
   for (int i = L - 1; i >= 0; --i)
-    if (c->layers[i].delay > 0)
+    if (c->layers[i].delay > 0 && !c->layers[i].retimed)
       if (int r = issue_update(i)) return r;
 
   // backward pass of step n
@@ -522,10 +561,12 @@ int step_run_ahead(lp_ctx* c, const void* X0, const void* target, float* loss_de
       LP_HIP(c, record_on(c, c->ev_dy[i - 1], sC));
     }
     LP_HIP(c, wait_on(c, sW, c->ev_dy[i]));
-    LP_HIP(c, wait_on(c, sW, c->ev_upd[i]));   // the ring slot's previous gradient has been applied
+    // the ring slot's previous gradient has been applied.  (The version a retimed G task overwrites was last read by
+    // F_l and dX_l of step n-1, which precede this step's delta chain on sC and therefore ev_dy above.)
+    if (!ly.retimed) LP_HIP(c, wait_on(c, sW, c->ev_upd[i]));
     LP_HIP(c, enqueue_G(c, ly, x_in, dY, n, sW));
     LP_HIP(c, record_on(c, c->ev_dw[i], sW));
-    if (!updated[i])
+    if (!updated[i] && !ly.retimed)
       if (int r = issue_update(i)) return r;
   }
   LP_HIP(c, record_on(c, c->ev_join_w, sW));
@@ -571,7 +612,7 @@ int enqueue_step(lp_ctx* c, const void* X0, const void* target, float* loss_dev,
   };
   if (bf)
     for (int i = L - 1; i >= 0; --i)
-      if (c->layers[i].delay > 0)
+      if (c->layers[i].delay > 0 && !c->layers[i].retimed)
         if (int r = issue_update(i)) return r;
 
   // forward chain
@@ -622,6 +663,7 @@ int enqueue_step(lp_ctx* c, const void* X0, const void* target, float* loss_dev,
     hipStream_t sG = fills_chip ? sC : sW;
     if (multi && sG != sC) LP_HIP(c, wait_on(c, sG, c->ev_dy[i]));
     LP_HIP(c, enqueue_G(c, ly, x_in, dY, n, sG));
+    if (ly.retimed) continue;   // the G task has applied its gradient itself; nothing in this step reads what it wrote
     if (multi && !updated[i]) LP_HIP(c, record_on(c, c->ev_dw[i], sG));   // only this step's own update waits for it
     if (!updated[i]) {
       // d_l = 0 needs this step's G; an F32 context updates in place, so it also has to wait for
@@ -843,7 +885,12 @@ int lp_set_weights(lp_ctx* c, int l, const float* W, int is_device, void* stream
       LP_HIP(c, hipStreamSynchronize(s));
       LP_HIP(c, hipMemcpy(master, W, ly.n_params * 4, hipMemcpyHostToDevice));
     }
-    if (is_bf16(c)) LP_HIP(c, lp::launch_cast_bf16(master, c->ws + ly.off_work[ly.cur], ly.n_params, s));
+    if (ly.retimed) {
+      // every held version: the steps to come read these weights until versions written after this call come of age
+      for (int v = 0; v < ly.n_versions; ++v) LP_HIP(c, lp::launch_cast_bf16(master, version_slot(c, ly, v), ly.n_params, s));
+    } else if (is_bf16(c)) {
+      LP_HIP(c, lp::launch_cast_bf16(master, c->ws + ly.off_work[ly.cur], ly.n_params, s));
+    }
     // the table the F epilogue of a GELU layer looks its activation up in: made ready here, outside any step
     if (is_bf16(c) && ly.d.kind == LP_LINEAR && ly.d.act == LP_ACT_GELU && !c->gelu_lut) LP_HIP(c, lp::gelu_lut_bf16(&c->gelu_lut, s));
     if (is_bf16(c) && ly.d.act == LP_ACT_GELU && !c->gelu_grad_lut) LP_HIP(c, lp::gelu_grad_lut_f32(&c->gelu_grad_lut, s));
@@ -983,6 +1030,7 @@ int lp_update(lp_ctx* c, int l, const float* G, void* stream) {
     if (int r = check_layer(c, l)) return r;
     if (int r = need_weights(c, l)) return r;
     Layer& ly = c->layers[l - 1];
+    if (ly.retimed) return fail(c, LP_ERR_STATE, "lp_update: layer %d has the retimed update; its G task inside lp_step applies the gradient", l);
     if (!G) {
       const long src = c->n + 1 - ly.delay;
       if (src < 1) return LP_OK;  // the delay elements are still empty
@@ -1024,11 +1072,38 @@ int lp_set_factor_ring(lp_ctx* c, int l, int enable) {
     auto k_is_cut = [&](const Layer& ly) {
       return lp::gemm_bf16_splitk_splits(ly.d.in, ly.d.out, c->batch) > 1 || lp::gemm_skinny_shape(c->batch, ly.d.in, ly.d.out);
     };
+    if (l != 0 && enable && c->layers[l - 1].retimed)
+      return fail(c, LP_ERR_LAYER, "lp_set_factor_ring: layer %d has the retimed update, which keeps no gradients", l);
     if (l != 0 && enable && k_is_cut(c->layers[l - 1]))
       return fail(c, LP_ERR_LAYER, "lp_set_factor_ring: the G product of layer %d is split over K (or runs on the few-outputs kernels) at this batch size; it keeps the product ring", l);
     for (int i = 0; i < c->L; ++i) {
       Layer& ly = c->layers[i];
-      if ((l == 0 || i == l - 1) && ly.d.kind == LP_LINEAR) ly.factor_ring = enable != 0 && !k_is_cut(ly);
+      if ((l == 0 || i == l - 1) && ly.d.kind == LP_LINEAR) ly.factor_ring = enable != 0 && !k_is_cut(ly) && !ly.retimed;
+    }
+    layout_workspace(c);
+    return LP_OK;
+  });
+}
+
+int lp_set_retimed_update(lp_ctx* c, int l, int enable) {
+  return guarded(c, "lp_set_retimed_update", [&]() -> int {
+    if (!c) return LP_ERR_NULL;
+    if (c->ws) return fail(c, LP_ERR_STATE, "lp_set_retimed_update: call it before lp_bind_workspace (it changes the workspace size)");
+    if (!is_bf16(c)) return fail(c, LP_ERR_DTYPE, "lp_set_retimed_update: needs an LP_BF16 context");
+    if (l != 0)
+      if (int r = check_layer(c, l)) return r;
+    // The fused product-and-update kernel is the plain tiled GEMM: a layer whose stand-alone G product is summed in
+    // another order (K cut into ranges, few-outputs kernels) would get other bits, and keeps its gradient ring.
+    auto eligible = [&](const Layer& ly) {
+      return ly.d.kind == LP_LINEAR && !ly.factor_ring && lp::gemm_bf16_splitk_splits(ly.d.in, ly.d.out, c->batch) <= 1 &&
+             !lp::gemm_skinny_shape(c->batch, ly.d.in, ly.d.out);
+    };
+    if (l != 0 && enable && !eligible(c->layers[l - 1]))
+      return fail(c, LP_ERR_LAYER, "lp_set_retimed_update: layer %d is a convolution, has a factor ring, or its G product is split over K (or runs on the "
+                  "few-outputs kernels) at this batch size; it keeps its gradient ring", l);
+    for (int i = 0; i < c->L; ++i) {
+      Layer& ly = c->layers[i];
+      if (l == 0 || i == l - 1) ly.retimed = enable != 0 && eligible(ly);
     }
     layout_workspace(c);
     return LP_OK;
@@ -1093,6 +1168,9 @@ int lp_step(lp_ctx* c, const void* X0, const void* target, const int* delay, flo
       for (int l = 0; l < c->L; ++l)
         if (delay[l] < 0 || delay[l] > c->layers[l].d.delay)
           return fail(c, LP_ERR_DELAY, "lp_step: delay[%d] = %d outside [0, %d]", l, delay[l], c->layers[l].d.delay);
+      for (int l = 0; l < c->L; ++l)
+        if (c->layers[l].retimed && delay[l] != c->layers[l].d.delay)
+          return fail(c, LP_ERR_DELAY, "lp_step: layer %d has the retimed update, whose delay is fixed at %d (delay[%d] = %d)", l + 1, c->layers[l].d.delay, l, delay[l]);
       for (int l = 0; l < c->L; ++l) c->layers[l].delay = delay[l];
     }
     if (c->run_ahead) {
@@ -1115,7 +1193,7 @@ int lp_step(lp_ctx* c, const void* X0, const void* target, const int* delay, flo
     if (int r = run_or_replay_step(c, X0, target, loss_dev, sC, sW, sU, multi, updated)) return r;
     if (bf)
       for (int i = 0; i < L; ++i)
-        if (updated[i]) c->layers[i].cur ^= 1;
+        if (updated[i] && !c->layers[i].retimed) c->layers[i].cur ^= 1;
     c->n = n;
     return LP_OK;
   });
@@ -1153,7 +1231,7 @@ int lp_tensor(lp_ctx* c, int l, int which, void** dev_ptr, size_t* bytes) {
         if (ly.has_dA && !(l < c->L && hadamard_fused(c, c->layers[l], ly))) { *dev_ptr = c->ws + ly.off_dA; *bytes = ly.a_elems * es; }
         break;
       case LP_T_DY: *dev_ptr = c->ws + ly.off_dY; *bytes = ly.z_elems * es; break;
-      case LP_T_G_LAST: if (c->n >= 1 && !ly.factor_ring) { *dev_ptr = ring_slot(c, ly, c->n); *bytes = ly.n_params * 4; } break;
+      case LP_T_G_LAST: if (c->n >= 1 && !ly.factor_ring && !ly.retimed) { *dev_ptr = ring_slot(c, ly, c->n); *bytes = ly.n_params * 4; } break;
       default: return fail(c, LP_ERR_DTYPE, "lp_tensor: unknown tensor id %d", which);
     }
     return LP_OK;

@@ -232,6 +232,55 @@ def test_factor_ring_shrinks_the_delay_elements():
     lp.lp_destroy(ctx)
 
 
+def test_retimed_update_trades_the_gradient_ring_for_weight_versions():
+    """Host bookkeeping only: a retimed layer holds d + 2 bf16 weight versions in place of d + 1 fp32 gradients and its
+    two working copies; which layers qualify; which calls it refuses."""
+    wl = WL.mlp_4096()
+    L = lp.lib()
+    ctx = lp.lp_create(descs(wl), wl.L, wl.batch, lp.LP_BF16, lp.LP_LOSS_SOFTMAX_CE, 1e-3)
+    n0 = lp.lp_workspace_bytes(ctx)
+    assert L.lp_set_retimed_update(ctx, 0, 1) == 0
+    n1 = lp.lp_workspace_bytes(ctx)
+    saved = sum((d + 1) * ly.n_params * 4 + 2 * ly.n_params * 2 - (d + 2) * ly.n_params * 2 for d, ly in zip(wl.delays, wl.layers))
+    assert abs((n0 - n1) - saved) < 2 ** 16, (n0 - n1, saved)
+    assert L.lp_set_retimed_update(ctx, 9, 1) == 4
+    assert L.lp_set_factor_ring(ctx, 2, 1) == 4 and b"retimed" in L.lp_last_error(ctx)     # one kind of delay element per layer
+    assert L.lp_set_retimed_update(ctx, 2, 0) == 0 and L.lp_set_factor_ring(ctx, 2, 1) == 0
+    assert L.lp_set_retimed_update(ctx, 2, 1) == 4                                           # ... either way round
+    assert L.lp_set_retimed_update(ctx, 0, 1) == 0                                           # "every layer" leaves layer 2 its factors
+    assert L.lp_bind_workspace(ctx, 0x10000, 1 << 40) == 0
+    assert L.lp_set_retimed_update(ctx, 0, 1) == 6                                           # LP_ERR_STATE: already bound
+    assert not lp.lp_tensor(ctx, 1, lp.LP_T_G_LAST)[0] and not lp.lp_tensor(ctx, wl.L, lp.LP_T_G_LAST)[0]   # no step yet
+    # the weights the first step reads are version 0, whatever the delay
+    w1, w3 = lp.lp_tensor(ctx, 1, lp.LP_T_WORK_W), lp.lp_tensor(ctx, 3, lp.LP_T_WORK_W)
+    assert w1[0] and w1[1] == wl.layers[0].n_params * 2 and w3[0] and w3[0] != w1[0]
+    assert L.lp_advance(ctx) == 0
+    assert lp.lp_tensor(ctx, 1, lp.LP_T_WORK_W)[0] == w1[0]                                  # d = 14: still version 0 after one step
+    lp.lp_destroy(ctx)
+    small = WL.mlp_small()
+    ctx = lp.lp_create(descs(small), small.L, small.batch, lp.LP_F32, lp.LP_LOSS_SOFTMAX_CE, 0.01)
+    assert L.lp_set_retimed_update(ctx, 0, 1) == 3                                           # LP_ERR_DTYPE
+    lp.lp_destroy(ctx)
+    assert L.lp_set_retimed_update(None, 0, 1) == 1
+    cnn = WL.vgg_small(batch=2, hw=8, chans=(8, 8))
+    ctx = lp.lp_create(descs(cnn), cnn.L, 2, lp.LP_BF16, lp.LP_LOSS_SOFTMAX_CE, 0.01)
+    n_cnn = lp.lp_workspace_bytes(ctx)
+    assert L.lp_set_retimed_update(ctx, 1, 1) == 4                                           # a convolution
+    assert L.lp_set_retimed_update(ctx, 0, 1) == 0 and lp.lp_workspace_bytes(ctx) == n_cnn   # "every layer": none qualifies
+    lp.lp_destroy(ctx)
+    # batch 2048: only the 4096 x 4096 layer's G product is the plain tiled GEMM (the others are split over K or run on
+    # the few-outputs kernels)
+    mixed = WL.mlp_4096().with_(layers=WL._mlp([512, 512, 4096, 4096, 16], WL.RELU), batch=2048, delays=(6, 4, 2, 0))
+    ctx = lp.lp_create(descs(mixed), mixed.L, mixed.batch, lp.LP_BF16, lp.LP_LOSS_SOFTMAX_CE, 1e-3)
+    n0 = lp.lp_workspace_bytes(ctx)
+    for l in (1, 2, 4):
+        assert L.lp_set_retimed_update(ctx, l, 1) == 4 and b"split over K" in L.lp_last_error(ctx)
+    assert L.lp_set_retimed_update(ctx, 0, 1) == 0
+    # layer 3 (d = 2): three gradients and two working copies become four versions
+    assert n0 - lp.lp_workspace_bytes(ctx) == 4096 * 4096 * (3 * 4 + 2 * 2 - 4 * 2)
+    lp.lp_destroy(ctx)
+
+
 def test_mfma_probe_checks_its_arguments_before_launching():
     L = lp.lib()
     assert L.lp_probe_mfma(None, 0, 1, 1, 0, None) == 1          # LP_ERR_NULL

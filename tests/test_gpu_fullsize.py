@@ -263,3 +263,46 @@ def test_ffn_stack_full_size_hadamard_forms_agree_bit_for_bit():
     assert np.all(np.isfinite(a[0])) and np.array_equal(a[0].view(np.uint32), b[0].view(np.uint32))
     for l, (ya, yb) in enumerate(zip(a[1], b[1]), start=1):
         assert torch.equal(ya, yb), "dY_%d" % l
+
+
+@pytest.mark.timeout(900)
+def test_ffn_stack_full_size_retimed_update_equals_gradient_ring_bit_for_bit():
+    """The largest workload in the two forms of Eq. 6, side by side for 36 steps (past the largest delay, 30, so that
+    every layer reads weights that the retimed G tasks wrote): gradient rings with update tasks on three streams, and
+    the retimed update on one stream, which is what bench.py times.  Losses after every step and the working weights
+    of every layer at steps 1, 17 and 36, bit for bit; the retimed master weights of the last layer (d = 0) equal the
+    gradient ring's."""
+    wl = WL.ffn_stack()
+    W0 = WL.init_weights(wl)
+    ref = lp.Network(wl.layers, wl.batch, wl.dtype, wl.loss, wl.lr, wl.delays, n_streams=3)
+    net = lp.Network(wl.layers, wl.batch, wl.dtype, wl.loss, wl.lr, wl.delays, n_streams=1, retimed_update=True)
+    ref.set_weights(W0)
+    net.set_weights(W0)
+    del W0
+    pool, steps = 3, 36
+    xs = [ref.to_device(WL.batch_input(wl, n)) for n in range(1, pool + 1)]
+    ts = [ref.to_device(WL.batch_target(wl, n)) for n in range(1, pool + 1)]
+    la = torch.zeros(steps, dtype=torch.float32, device="cuda:0")
+    lb = torch.zeros(steps, dtype=torch.float32, device="cuda:0")
+    torch.cuda.synchronize()
+    assert all(net.tensor(l, lp.LP_T_G_LAST) is None for l in range(1, wl.L + 1))
+    for n in range(steps):
+        lp.lp_step(ref.ctx, xs[n % pool], ts[n % pool], None, la[n:n + 1], ref.streams)
+        lp.lp_step(net.ctx, xs[n % pool], ts[n % pool], None, lb[n:n + 1], net.streams)
+        if n + 1 in (1, 17, steps):
+            lp.lp_sync(ref.ctx)
+            lp.lp_sync(net.ctx)
+            for l in range(1, wl.L + 1):
+                a, b = ref.tensor(l, lp.LP_T_WORK_W), net.tensor(l, lp.LP_T_WORK_W)
+                assert torch.equal(a.view(torch.int16), b.view(torch.int16)), "working W_%d after step %d" % (l, n + 1)
+            print("ffn_stack full size, retimed against gradient ring: step %d of %d" % (n + 1, steps), flush=True)
+    lp.lp_sync(ref.ctx)
+    lp.lp_sync(net.ctx)
+    losses = la.cpu().numpy()
+    assert np.all(np.isfinite(losses)) and len(set(losses.tolist())) > steps // 2
+    assert np.array_equal(losses.view(np.uint32), lb.cpu().numpy().view(np.uint32))
+    assert torch.equal(ref.tensor(wl.L, lp.LP_T_MASTER_W).view(torch.int32), net.tensor(wl.L, lp.LP_T_MASTER_W).view(torch.int32))
+    # a layer with d > 0: the retimed master weights are ahead of the gradient ring's by the gradients still in the ring
+    assert not torch.equal(ref.tensor(1, lp.LP_T_MASTER_W).view(torch.int32), net.tensor(1, lp.LP_T_MASTER_W).view(torch.int32))
+    ref.close()
+    net.close()
