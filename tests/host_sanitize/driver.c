@@ -123,6 +123,30 @@ static void layouts(void) {
   EXPECT(lp_set_graphs(c, 0) == LP_OK);
   EXPECT(lp_set_factor_ring(c, 0, 1) == LP_OK && lp_workspace_bytes(c, &n1) == LP_OK && n1 < n0);
   EXPECT(lp_set_factor_ring(c, 9, 1) == LP_ERR_LAYER);
+  /* retimed update: weight versions in place of gradients; one kind of delay element per layer */
+  void* fake = (void*)(uintptr_t)0x10000;   /* never dereferenced */
+  EXPECT(lp_set_retimed_update(c, 2, 1) == LP_ERR_LAYER);
+  EXPECT(lp_set_factor_ring(c, 0, 0) == LP_OK && lp_workspace_bytes(c, &n1) == LP_OK && n1 == n0);
+  EXPECT(lp_set_retimed_update(c, 0, 1) == LP_OK && lp_workspace_bytes(c, &n1) == LP_OK && n1 < n0);
+  EXPECT(lp_set_factor_ring(c, 2, 1) == LP_ERR_LAYER);
+  EXPECT(lp_set_retimed_update(c, 9, 1) == LP_ERR_LAYER && lp_set_retimed_update(NULL, 0, 1) == LP_ERR_NULL);
+  EXPECT(lp_set_graphs(c, 1) == LP_OK && lp_set_graphs(c, 0) == LP_OK);
+  EXPECT(lp_bind_workspace(c, fake, (size_t)1 << 40) == LP_OK);
+  EXPECT(lp_set_retimed_update(c, 0, 0) == LP_ERR_STATE);
+  {
+    void* p0 = NULL; void* p1 = NULL; size_t nb = 0;
+    EXPECT(lp_tensor(c, 1, LP_T_WORK_W, &p0, &nb) == LP_OK && p0 != NULL && nb == (size_t)512 * 1024 * 2);
+    EXPECT(lp_tensor(c, 5, LP_T_WORK_W, &p1, &nb) == LP_OK && p1 != NULL);
+    void* g = fake;
+    EXPECT(lp_tensor(c, 1, LP_T_G_LAST, &g, &nb) == LP_OK && g == NULL);
+    /* eight steps on: step 9 of layer 1 (d = 8) still reads version 0, layer 5 (d = 0) another one; step 10 reads version 1 */
+    for (int i = 0; i < 8; ++i) EXPECT(lp_advance(c) == LP_OK);
+    void* q0 = NULL; void* q1 = NULL;
+    EXPECT(lp_tensor(c, 1, LP_T_WORK_W, &q0, &nb) == LP_OK && q0 == p0);
+    EXPECT(lp_tensor(c, 5, LP_T_WORK_W, &q1, &nb) == LP_OK && q1 != p1);
+    EXPECT(lp_advance(c) == LP_OK && lp_tensor(c, 1, LP_T_WORK_W, &q0, &nb) == LP_OK && q0 != p0);
+    EXPECT(lp_update(c, 1, NULL, NULL) == LP_ERR_STATE);
+  }
   long a = -1, b = -1, e = -1;
   EXPECT(lp_graph_stats(c, &a, &b, &e) == LP_OK && a == 0 && b == 0 && e == 0);
   EXPECT(lp_destroy(c) == LP_OK);
