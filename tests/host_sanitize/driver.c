@@ -136,14 +136,14 @@ static void layouts(void) {
   {
     void* p0 = NULL; void* p1 = NULL; size_t nb = 0;
     EXPECT(lp_tensor(c, 1, LP_T_WORK_W, &p0, &nb) == LP_OK && p0 != NULL && nb == (size_t)512 * 1024 * 2);
-    EXPECT(lp_tensor(c, 5, LP_T_WORK_W, &p1, &nb) == LP_OK && p1 != NULL);
+    EXPECT(lp_tensor(c, 4, LP_T_WORK_W, &p1, &nb) == LP_OK && p1 != NULL);
     void* g = fake;
     EXPECT(lp_tensor(c, 1, LP_T_G_LAST, &g, &nb) == LP_OK && g == NULL);
-    /* eight steps on: step 9 of layer 1 (d = 8) still reads version 0, layer 5 (d = 0) another one; step 10 reads version 1 */
+    /* eight steps on: step 9 of layer 1 (d = 8) still reads version 0, layer 4 (d = 2, four slots) version 6 in slot 2; step 10 of layer 1 reads version 1 */
     for (int i = 0; i < 8; ++i) EXPECT(lp_advance(c) == LP_OK);
     void* q0 = NULL; void* q1 = NULL;
     EXPECT(lp_tensor(c, 1, LP_T_WORK_W, &q0, &nb) == LP_OK && q0 == p0);
-    EXPECT(lp_tensor(c, 5, LP_T_WORK_W, &q1, &nb) == LP_OK && q1 != p1);
+    EXPECT(lp_tensor(c, 4, LP_T_WORK_W, &q1, &nb) == LP_OK && q1 != p1);
     EXPECT(lp_advance(c) == LP_OK && lp_tensor(c, 1, LP_T_WORK_W, &q0, &nb) == LP_OK && q0 != p0);
     EXPECT(lp_update(c, 1, NULL, NULL) == LP_ERR_STATE);
   }
