@@ -306,3 +306,16 @@ def test_ffn_stack_full_size_retimed_update_equals_gradient_ring_bit_for_bit():
     assert not torch.equal(ref.tensor(1, lp.LP_T_MASTER_W).view(torch.int32), net.tensor(1, lp.LP_T_MASTER_W).view(torch.int32))
     ref.close()
     net.close()
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("name", ["mlp_4096_bf16", "mlp_imbalanced_bf16"])
+def test_full_size_retimed_update_equals_gradient_ring_bit_for_bit(name):
+    """The two mid-size workloads at their full sizes in the form bench.py times by default (retimed update on every
+    layer that qualifies, three streams) against the gradient-ring form, step by step past the largest delay:
+    losses and working weights of every layer after every step, and the master weights of the retimed layers
+    against the gradient-ring run continued for d_l more steps, bit for bit."""
+    from test_gpu_retimed_update import lockstep
+    wl = WL.CONFIGS[name]()
+    W0 = WL.init_weights(wl)
+    lockstep(wl, W0, max(wl.delays) + 4, {}, dict(retimed_update=True), None)

@@ -41,7 +41,7 @@ def lockstep(wl, W0, steps, ref_kw, kw, retimed_layers):
     l_net = torch.zeros(steps, dtype=torch.float32, device=DEV)
     torch.cuda.synchronize()
     masters, ref_now = {}, {}
-    retimed_only = set(retimed_layers) - set(kw.get("factor_ring") or [])
+    retimed_only = set(retimed_layers or ()) - set(kw.get("factor_ring") or [])
     for n in range(steps + d_max):
         lp.lp_step(ref.ctx, xs[n], ts[n], None, l_ref[n:n + 1], ref.streams)
         lp.lp_sync(ref.ctx)
@@ -60,6 +60,10 @@ def lockstep(wl, W0, steps, ref_kw, kw, retimed_layers):
     losses = l_net.cpu().numpy()
     assert np.all(np.isfinite(losses)) and losses[0] != losses[-1]
     assert np.array_equal(losses.view(np.uint32), l_ref[:steps].cpu().numpy().view(np.uint32))
+    if retimed_layers is None:          # whatever "every layer" selected
+        retimed_layers = {l for l in range(1, wl.L + 1) if net.tensor(l, lp.LP_T_G_LAST) is None}
+        retimed_only = set(retimed_layers)
+        assert retimed_only
     for l in range(1, wl.L + 1):
         is_ret = net.tensor(l, lp.LP_T_G_LAST) is None
         assert is_ret == (l in retimed_layers), (l, is_ret)
