@@ -603,10 +603,28 @@ struct SgdEpilogue {
       }
     }
   }
-  static constexpr bool kHasSide = false;
-  using Side = NoSide;
-  __device__ __forceinline__ NoSide side(int, int) const { return NoSide{}; }
-  __device__ __forceinline__ void operator()(int r, int c, const f32x4& g, NoSide) const { (*this)(r, c, g); }
+  // The master weights of a band are fetched while the band before it is on its trip through LDS (16-byte form only:
+  // the element-wise form loads them where it uses them).  Same arithmetic either way.
+  static constexpr bool kHasSide = true;
+  using Side = f32x4;
+  __device__ __forceinline__ f32x4 side(int r, int c) const {
+    const int row = m0 + r, col = n0 + c;
+    f32x4 w = {0.f, 0.f, 0.f, 0.f};
+    if (vec && row < M && col < N) w = *reinterpret_cast<const f32x4*>(master + (size_t)row * ldc + col);
+    return w;
+  }
+  __device__ __forceinline__ void operator()(int r, int c, const f32x4& g, const f32x4& w0) const {
+    if (!vec) { (*this)(r, c, g); return; }
+    const int row = m0 + r, col = n0 + c;
+    if (row >= M || col >= N) return;
+    const size_t o = (size_t)row * ldc + col;
+    f32x4 w;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) w[t] = fmaf(neg_lr, g[t], w0[t]);
+    *reinterpret_cast<f32x4*>(master + o) = w;
+    *reinterpret_cast<u32x2*>(work_out + o) = u32x2{(unsigned)bf16_bits(w[0]) | ((unsigned)bf16_bits(w[1]) << 16),
+                                                    (unsigned)bf16_bits(w[2]) | ((unsigned)bf16_bits(w[3]) << 16)};
+  }
   template <class F>
   __device__ __forceinline__ void with_static_act(F&& f) const { f(*this); }
 };
