@@ -156,6 +156,34 @@ def test_delayed_schedule_equals_bruteforce_replay(mk, delays):
         assert any(np.max(np.abs(tr0.W[l] - tr.W[l])) > 1e-8 for l in range(wl.L))
 
 
+@pytest.mark.parametrize("storage", ["f64", "bf16"])
+@pytest.mark.parametrize("delays", [(4, 2, 0), (1, 5, 0), (3, 0, 1)])
+def test_delays_on_the_gradient_equal_delays_on_the_weights(storage, delays):
+    """Retiming the update of Eq. 6 (Sec. III-A: delays may be moved from the inputs of a node to its outputs): with
+    U_l(m) = U_l(m-1) - eta G_l(m), U_l(0) = W_l(0) -- every gradient applied the moment it exists -- the weights that
+    step n of Eq. 6 reads are W_l(n-1) = U_l(n-1-d_l) (U_l(0) while n-1-d_l <= 0), exactly: the same numbers are
+    subtracted from the same accumulator in the same order, with the same roundings of the stored master.  This is
+    the identity behind the library's retimed update; it is checked here on the oracle's own trajectory."""
+    wl = tiny_mlp("relu", (7, 6, 5, 4), 3)
+    W0 = [w.astype(np.float64) for w in WL.init_weights(wl)]
+    tr = O.DelayedGradientTrainer(wl.layers, W0, delays, wl.lr, wl.loss, storage)
+    master = "f64" if storage == "f64" else "f32"
+    U = [[O.store(w, master)] for w in W0]       # U[l][m]
+    T = 12
+    for n in range(1, T + 1):
+        x, t = WL.batch_input(wl, n).astype(np.float64), WL.batch_target(wl, n)
+        tr.step(x, t)
+        for l in range(wl.L):
+            v = max(0, n - 1 - delays[l])
+            assert np.array_equal(tr.trace["Wk"][l], O.store(U[l][v], storage)), (n, l)
+            U[l].append(O.store(O.delayed_sgd(U[l][n - 1], tr.trace["G"][l], tr.eta), master))
+    # after T steps Eq. 6 has applied G(1..T-d_l): its master weights are U_l(T-d_l), d_l gradients behind U_l(T)
+    for l in range(wl.L):
+        assert np.array_equal(tr.W[l], U[l][T - delays[l]])
+        if delays[l] > 0:
+            assert not np.array_equal(tr.W[l], U[l][T])
+
+
 def test_update_counts_closed_form_and_frozen_prefix():
     """W_l(T) = W_l(0) - eta * sum_{k=1}^{T-d_l} G_l(k); W_l(n) is bit-identical to W_l(0) for n <= d_l."""
     wl = WL.mlp_small().with_(layers=WL._mlp([20, 12, 9, 7, 5], WL.RELU), batch=4)
