@@ -461,6 +461,12 @@ hipError_t launch_gemm_bf16(const GemmDesc& d, hipStream_t s, int tile_cfg) {
     if (t256 >= 192) cfg = aligned ? 4 : (both_kc ? 0 : 3);
     else if (aligned) cfg = 5;
     else cfg = t128 >= 64 ? 1 : 2;
+    // A product with the update in its epilogue and a short reduction is bound by the 10 bytes per weight of that
+    // epilogue: 128 x 128 tiles, two workgroups per CU, let one workgroup's main loop run under the other's epilogue
+    // (4096 x 4096 outputs over K = 256: 40 us per launch, and the step of eight such layers 0.69 -> 0.64 ms; at K = 1024
+    // the larger tile is ahead again).  Every element is summed over k
+    // in the same order in both tilings, so the bits do not depend on the choice.
+    if (sgd && cfg == 4 && d.K <= 512) cfg = 5;
   }
   if (cfg < 0 || cfg >= gemm_bf16_num_cfgs()) return hipErrorInvalidValue;
   if (tile_cfg < 0 && !sgd && (cfg == 5 || cfg == 1 || cfg == 2)) {
