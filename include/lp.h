@@ -251,7 +251,8 @@ int lp_set_factor_ring(lp_ctx* ctx, int l, int enable);
  * are bit-identical with the gradient ring (the same gradients are applied in the same order; only the moment of the
  * arithmetic differs); per parameter and step 10 bytes move instead of 4 + 14.  What differs for the caller:
  * lp_get_weights / LP_T_MASTER_W of such a layer are d_l gradients ahead of the weights the next step reads
- * (LP_T_WORK_W is those); LP_T_G_LAST is NULL; lp_update on it is LP_ERR_STATE; lp_step accepts only the layer's own
+ * (LP_T_WORK_W is those); LP_T_G_LAST is NULL; lp_grad_weight with G == NULL is the whole G task (it applies the
+ * gradient and writes version n + 1: call it once per step) and lp_update is LP_ERR_STATE; lp_step accepts only the layer's own
  * d_l in `delay` (LP_ERR_DELAY); lp_set_weights sets the master weights and every held version.
  * Linear layers of LP_BF16 contexts (LP_ERR_DTYPE) whose G product is neither split over K nor run on the few-outputs
  * kernels (see lp_set_factor_ring) and that have no factor ring: l = 0 selects every such layer and leaves the others

@@ -210,6 +210,39 @@ def test_retimed_update_entry_points_and_errors():
     assert e.value.status == 4
 
 
+def test_retimed_update_per_layer_calls():
+    """Driving a step by hand: lp_grad_weight with G == NULL is the whole G task of a retimed layer."""
+    from test_gpu_parity import dev, host
+    B, K, N = 64, 264, 136
+    net = lp.Network((WL.Layer(WL.LINEAR, K, N, WL.RELU), WL.Layer(WL.LINEAR, N, 8, WL.IDENTITY)), B, "bf16", WL.SOFTMAX_CE, 0.05, (1, 0),
+                     retimed_update=[1])
+    rng = np.random.default_rng(5)
+    W = [(rng.standard_normal(l.weight_shape) * 0.1).astype(np.float32) for l in net.layers]
+    net.set_weights(W)
+    x = rng.standard_normal((B, K)).astype(np.float32)
+    dy = (rng.standard_normal((B, N)) / N).astype(np.float32)
+    xd, dyd = dev(x, torch.bfloat16), dev(dy, torch.bfloat16)
+    s = net.streams[0]
+    lp.lp_grad_weight(net.ctx, 1, xd, dyd, None, s)
+    lp.lp_sync(net.ctx)
+    g = O.grad_weight(O.round_bf16(x), O.round_bf16(dy))
+    ref = O.store(O.delayed_sgd(W[0].astype(np.float64), g, float(np.float32(0.05))), "f32")
+    w = net.get_weights(1)
+    assert np.max(np.abs(w - ref)) <= 2e-4 * 0.05 * np.max(np.abs(g)) + 2.0 ** -22 * np.max(np.abs(ref))
+    # d = 1: the next step (n = 2) still reads version 0, the one after it the version just written
+    lp.lp_advance(net.ctx)
+    assert np.array_equal(net.tensor_np(1, lp.LP_T_WORK_W).reshape(w.shape), O.round_bf16(W[0]))
+    lp.lp_advance(net.ctx)
+    assert np.array_equal(net.tensor_np(1, lp.LP_T_WORK_W).reshape(w.shape), O.round_bf16(w))
+    # an explicit G still goes through the stand-alone kernel and leaves the weights alone
+    G = torch.empty(K, N, dtype=torch.float32, device=DEV)
+    lp.lp_grad_weight(net.ctx, 1, xd, dyd, G, s)
+    lp.lp_sync(net.ctx)
+    assert np.max(np.abs(host(G) - g)) <= 2e-4 * np.max(np.abs(g))
+    assert np.array_equal(net.get_weights(1), w)
+    net.close()
+
+
 def test_retimed_update_against_oracle():
     """Losses against the oracle step by step; the master weights, which run d_l gradients ahead, against the oracle's
     weights d_l steps later (the oracle goes on for max d_l steps on batches whose gradients are not yet applied)."""
