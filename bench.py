@@ -438,7 +438,7 @@ def main():
             gbs = upd_params * work["update_per_param"] / (ms * 1e-3) / 1e9
             out["update"] = {"launches": cnt, "avg_ms": ms / cnt, "GB/s": gbs, "frac_of_hbm_peak": gbs / PEAK_HBM_GBS}
             if retimed:
-                out["update"]["note"] = "layers that keep a gradient ring (convolutions, products split over K, few outputs); the others update inside dW"
+                out["update"]["note"] = "layers that keep a gradient ring (linear layers whose G product is split over K, convolutions whose G product is not); the others update inside dW"
         elif retimed and not factor_ring:
             out["update"] = {"launches": 0, "note": "applied in the epilogue of the dW products (its time is part of dW; --gradient-ring times it alone)"}
         return out

@@ -770,7 +770,10 @@ __global__ void __launch_bounds__(NT) conv_dw_kernel(ConvKArgs p) {
 // Sums the split-K partials of dW in a fixed order.  A block handles 32 consecutive outputs; its eight
 // waves-halves each add up one eighth of the splits (a contiguous range, in order, eight loads in flight),
 // and the eight sub-sums are added in order through LDS: short dependent chains even for 128 splits.
-__global__ void __launch_bounds__(256) reduce_partials_kernel(const float* __restrict__ part, float* __restrict__ g, size_t n, int splits) {
+// With `master` set the sum is not stored: it is applied to the fp32 master weights (w <- fma(-lr, g, w), the arithmetic of
+// the stand-alone update kernel) and the bf16 copy of the result goes to `work` (Eq. 6 moved into the task that forms G).
+__global__ void __launch_bounds__(256) reduce_partials_kernel(const float* __restrict__ part, float* __restrict__ g, size_t n, int splits,
+                                                              float* __restrict__ master, unsigned short* __restrict__ work, float neg_lr) {
   __shared__ float sub[8][32];
   const int o = threadIdx.x & 31, grp = threadIdx.x >> 5;
   const size_t i = (size_t)blockIdx.x * 32 + o;
@@ -793,7 +796,13 @@ __global__ void __launch_bounds__(256) reduce_partials_kernel(const float* __res
     float t = sub[0][o];
 #pragma unroll
     for (int k = 1; k < 8; ++k) t += sub[k][o];
-    g[i] = t;
+    if (master) {
+      const float w = fmaf(neg_lr, t, master[i]);
+      master[i] = w;
+      work[i] = bf16_bits(w);
+    } else {
+      g[i] = t;
+    }
   }
 }
 
@@ -936,16 +945,21 @@ hipError_t launch_conv_grad_act(const ConvDesc& c, bool bf16, const void* dy, co
   return hipGetLastError();
 }
 
-hipError_t launch_conv_grad_weight(const ConvDesc& c, bool bf16, const void* x, const void* dy, float* g, float* partial, hipStream_t s) {
+hipError_t launch_conv_grad_weight(const ConvDesc& c, bool bf16, const void* x, const void* dy, float* g, float* partial, hipStream_t s,
+                                   float* sgd_master, void* sgd_work, float sgd_lr) {
   if (!bf16) return hipErrorNotSupported;
-  if (!fits32(c) || !x || !dy || !g) return hipErrorInvalidValue;
+  if (!fits32(c) || !x || !dy || (!g && !sgd_master)) return hipErrorInvalidValue;
   const int splits = dw_splits(c);
   if (splits > 1 && !partial) return hipErrorInvalidValue;
+  // the fused update lives in the kernel that sums the split-K partials
+  if (sgd_master && (splits <= 1 || !sgd_work || g)) return hipErrorInvalidValue;
+  unsigned short* const work = (unsigned short*)sgd_work;
+  const float neg_lr = -sgd_lr;
   if (splits > 1 && conv_thin_ok(c, x, dy)) {
     const int chunks = conv_thin_dw_chunks(c), groups = chunks < splits ? chunks : splits;   // the scratch holds `splits` partials
     if (hipError_t e = launch_conv_thin_dw(c, x, dy, partial, groups, s)) return e;
     const size_t n = (size_t)9 * c.Cin * c.Cout;
-    hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)((n + 31) / 32)), dim3(256), 0, s, (const float*)partial, g, n, groups);
+    hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)((n + 31) / 32)), dim3(256), 0, s, (const float*)partial, g, n, groups, sgd_master, work, neg_lr);
     return hipGetLastError();
   }
   ConvKArgs p{};
@@ -984,7 +998,7 @@ hipError_t launch_conv_grad_weight(const ConvDesc& c, bool bf16, const void* x, 
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || splits == 1) return e;
   const size_t n = (size_t)p.M * p.N;
-  hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)((n + 31) / 32)), dim3(256), 0, s, (const float*)partial, g, n, splits);
+  hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)((n + 31) / 32)), dim3(256), 0, s, (const float*)partial, g, n, splits, sgd_master, work, neg_lr);
   return hipGetLastError();
 }
 

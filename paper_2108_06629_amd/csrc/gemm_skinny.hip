@@ -142,9 +142,12 @@ __global__ void __launch_bounds__(256) skinny_dx_kernel(const unsigned short* __
 
 // G[k][0..N) = sum_m X[m][k] dY[m][0..N), fp32.  A workgroup owns 16 input features; its 16 groups of 16 lanes sum the
 // batch rows m = g, g + 16, ... each, and the sixteen partial sums are added pairwise in a fixed tree.
+// With `master` set G is not stored: each element is applied to the fp32 master weights (w <- fma(-lr, g, w), the arithmetic
+// of the stand-alone update kernel) and the bf16 copy of the result goes to `work` (Eq. 6 moved into the task that forms G).
 template <int N>
 __global__ void __launch_bounds__(256) skinny_dw_kernel(const unsigned short* __restrict__ X, const unsigned short* __restrict__ dY,
-                                                        float* __restrict__ G, int B, int K, int lda) {
+                                                        float* __restrict__ G, int B, int K, int lda,
+                                                        float* __restrict__ master, unsigned short* __restrict__ work, float neg_lr) {
   __shared__ float part[16][16 * N];
   const int kl = threadIdx.x & 15, g = threadIdx.x >> 4;
   const int k0 = blockIdx.x * 16, k = k0 + kl;
@@ -169,7 +172,14 @@ __global__ void __launch_bounds__(256) skinny_dw_kernel(const unsigned short* __
       for (int w = 8; w > 0; w >>= 1)
 #pragma unroll
         for (int u = 0; u < w; ++u) q[u] = q[2 * u] + q[2 * u + 1];
-      G[(size_t)k0 * N + e] = q[0];
+      const size_t o = (size_t)k0 * N + e;
+      if (master) {
+        const float w = fmaf(neg_lr, q[0], master[o]);
+        master[o] = w;
+        work[o] = bf16_bits(w);
+      } else {
+        G[o] = q[0];
+      }
     }
   }
 }
@@ -192,7 +202,7 @@ hipError_t launch_n(int form, const GemmDesc& d, hipStream_t s) {
                          (unsigned short*)d.out_z, d.M, d.N, d.ldc, (const unsigned short*)d.had_s, d.had_s ? d.had_lut : nullptr);
   } else {
     hipLaunchKernelGGL(skinny_dw_kernel<N>, dim3((unsigned)((d.M + 15) / 16)), dim3(256), 0, s, (const unsigned short*)d.A, (const unsigned short*)d.B,
-                       d.out_f32, d.K, d.M, d.lda);
+                       d.out_f32, d.K, d.M, d.lda, d.sgd_master, d.sgd_master ? (unsigned short*)d.out_z : nullptr, -d.sgd_lr);
   }
   return hipGetLastError();
 }
@@ -205,7 +215,7 @@ bool gemm_skinny_shape(int batch, int d_in, int d_out) { return d_out >= 1 && d_
 // runs the tiled GEMM).
 hipError_t launch_gemm_skinny(const GemmDesc& d, hipStream_t s, bool* taken) {
   *taken = false;
-  if (d.sgd_master) return hipSuccess;
+  if (d.sgd_master && (d.a_kcontig || d.b_kcontig)) return hipSuccess;   // the update rides in the dW form only
   if (d.had_s && !(d.a_kcontig && d.b_kcontig)) return hipSuccess;   // the tiled launcher reports the misuse
   int form, batch, d_in = 0, d_out;
   if (d.a_kcontig && !d.b_kcontig) {            // F: X [batch][in] . W [in][out]
@@ -221,7 +231,9 @@ hipError_t launch_gemm_skinny(const GemmDesc& d, hipStream_t s, bool* taken) {
       return hipSuccess;
   } else if (!d.a_kcontig && !d.b_kcontig) {    // dW: X [batch][in]^T . dY [batch][out]
     form = 2; batch = d.K; d_in = d.M; d_out = d.N;
-    if (!gemm_skinny_shape(batch, d_in, d_out) || d.ldb != d_out || d.ldc != d_out || d.lda < d_in || !d.out_f32 || d.out_z || d.out_a) return hipSuccess;
+    // plain: G to out_f32; with the update: master weights in sgd_master, their bf16 copy to out_z, nothing else
+    const bool outs_ok = d.sgd_master ? (d.out_z && !d.out_f32 && !d.out_a) : (d.out_f32 && !d.out_z && !d.out_a);
+    if (!gemm_skinny_shape(batch, d_in, d_out) || d.ldb != d_out || d.ldc != d_out || d.lda < d_in || !outs_ok) return hipSuccess;
   } else {
     return hipSuccess;
   }

@@ -329,8 +329,12 @@ hipError_t enqueue_G(lp_ctx* c, Layer& ly, const void* X, const void* dY, long s
   if (ly.retimed) {
     // Eq. 6 retimed: G_l(step) is applied to the master weights tile by tile as the product leaves the accumulators
     // (SgdEpilogue: the arithmetic of sgd_kernel) and the bf16 copy of the result becomes version `step`, which
-    // the steps from step + d_l + 1 on read.  Same product kernel and tile choice as lp_grad_weight.
+    // the steps from step + d_l + 1 on read.  Same product kernel and summation order as lp_grad_weight (a convolution
+    // applies the update where it sums its split-K partials).
     ProfScope prof(c, LP_TASK_DW, layer_no(c, ly), s);
+    if (ly.d.kind == LP_CONV3X3)
+      return lp::launch_conv_grad_weight(conv_desc(c, ly), true, X, dY, nullptr, (float*)(c->ws + c->off_conv_scratch), s,
+                                         (float*)(c->ws + ly.off_master), version_slot(c, ly, step), c->lr);
     lp::GemmDesc g;
     g.A = X; g.B = dY;
     g.M = ly.d.in; g.N = ly.d.out; g.K = c->batch;
@@ -1092,15 +1096,17 @@ int lp_set_retimed_update(lp_ctx* c, int l, int enable) {
     if (!is_bf16(c)) return fail(c, LP_ERR_DTYPE, "lp_set_retimed_update: needs an LP_BF16 context");
     if (l != 0)
       if (int r = check_layer(c, l)) return r;
-    // The fused product-and-update kernel is the plain tiled GEMM: a layer whose stand-alone G product is summed in
-    // another order (K cut into ranges, few-outputs kernels) would get other bits, and keeps its gradient ring.
+    // The update rides in the kernel that finishes G, in the summation order of lp_grad_weight: the epilogue of the tiled
+    // GEMM or of the few-outputs kernel for a linear layer, the kernel that sums the split-K partials for a convolution.
+    // A linear layer whose G product is cut into K ranges, and a convolution whose G product is not, have no such
+    // place, and keep their gradient rings.
     auto eligible = [&](const Layer& ly) {
-      return ly.d.kind == LP_LINEAR && !ly.factor_ring && lp::gemm_bf16_splitk_splits(ly.d.in, ly.d.out, c->batch) <= 1 &&
-             !lp::gemm_skinny_shape(c->batch, ly.d.in, ly.d.out);
+      if (ly.d.kind == LP_CONV3X3) return lp::conv_grad_weight_scratch_bytes(conv_desc(c, ly)) > 0;
+      return !ly.factor_ring && (lp::gemm_skinny_shape(c->batch, ly.d.in, ly.d.out) || lp::gemm_bf16_splitk_splits(ly.d.in, ly.d.out, c->batch) <= 1);
     };
     if (l != 0 && enable && !eligible(c->layers[l - 1]))
-      return fail(c, LP_ERR_LAYER, "lp_set_retimed_update: layer %d is a convolution, has a factor ring, or its G product is split over K (or runs on the "
-                  "few-outputs kernels) at this batch size; it keeps its gradient ring", l);
+      return fail(c, LP_ERR_LAYER, "lp_set_retimed_update: layer %d has a factor ring, is a linear layer whose G product is split over K at this batch "
+                  "size, or a convolution whose G product is not; it keeps its gradient ring", l);
     for (int i = 0; i < c->L; ++i) {
       Layer& ly = c->layers[i];
       if (l == 0 || i == l - 1) ly.retimed = enable != 0 && eligible(ly);

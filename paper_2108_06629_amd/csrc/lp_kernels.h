@@ -85,8 +85,10 @@ hipError_t launch_conv_fwd(const ConvDesc& c, bool bf16, const void* x, const vo
 hipError_t launch_conv_grad_act(const ConvDesc& c, bool bf16, const void* dy, const void* w, void* dx, int c0, int c1,
                                 hipStream_t s, const void* had_s = nullptr, const float* had_lut = nullptr, bool had_pooled = false);
 // dW: g[kh,kw,c,o] fp32.  `partial` is scratch of conv_grad_weight_scratch_bytes().
+// sgd_master (with g == nullptr; only where that scratch is non-empty, i.e. the product is split over K): the gradient is
+// not stored but applied, w <- fma(-sgd_lr, g, w) on the fp32 master, and the bf16 copy of the result goes to sgd_work.
 hipError_t launch_conv_grad_weight(const ConvDesc& c, bool bf16, const void* x, const void* dy, float* g,
-                                   float* partial, hipStream_t s);
+                                   float* partial, hipStream_t s, float* sgd_master = nullptr, void* sgd_work = nullptr, float sgd_lr = 0.f);
 size_t conv_grad_weight_scratch_bytes(const ConvDesc& c);
 
 // dY = dA (.) f'(S), n elements.

@@ -265,19 +265,30 @@ def test_retimed_update_trades_the_gradient_ring_for_weight_versions():
     cnn = WL.vgg_small(batch=2, hw=8, chans=(8, 8))
     ctx = lp.lp_create(descs(cnn), cnn.L, 2, lp.LP_BF16, lp.LP_LOSS_SOFTMAX_CE, 0.01)
     n_cnn = lp.lp_workspace_bytes(ctx)
-    assert L.lp_set_retimed_update(ctx, 1, 1) == 4                                           # a convolution
-    assert L.lp_set_retimed_update(ctx, 0, 1) == 0 and lp.lp_workspace_bytes(ctx) == n_cnn   # "every layer": none qualifies
+    # 2 x 8 x 8 = 128 pixels: the G products of these convolutions are not split over K, so there is no kernel that sums
+    # partials for the update to ride in; the 128 -> 10 classifier (few-outputs kernels) qualifies
+    assert L.lp_set_retimed_update(ctx, 1, 1) == 4 and b"convolution whose G product is not" in L.lp_last_error(ctx)
+    assert L.lp_set_retimed_update(ctx, 0, 1) == 0 and n_cnn - lp.lp_workspace_bytes(ctx) == 128 * 10 * (1 * 4 + 2 * 2 - 2 * 2)
     lp.lp_destroy(ctx)
-    # batch 2048: only the 4096 x 4096 layer's G product is the plain tiled GEMM (the others are split over K or run on
-    # the few-outputs kernels)
+    # the benchmark's CNN (128 x 32 x 32 pixels): every convolution's G product is split over K, every layer qualifies
+    cnn = WL.vgg_small()
+    ctx = lp.lp_create(descs(cnn), cnn.L, cnn.batch, lp.LP_BF16, lp.LP_LOSS_SOFTMAX_CE, 0.01)
+    n_cnn = lp.lp_workspace_bytes(ctx)
+    for l in range(1, cnn.L + 1):
+        assert L.lp_set_retimed_update(ctx, l, 1) == 0, l
+    saved = sum((d + 1) * ly.n_params * 4 + 2 * ly.n_params * 2 - (d + 2) * ly.n_params * 2 for d, ly in zip(cnn.delays, cnn.layers))
+    assert abs((n_cnn - lp.lp_workspace_bytes(ctx)) - saved) < 2 ** 14
+    lp.lp_destroy(ctx)
+    # batch 2048: the G products of the 512 x 512 and 512 x 4096 layers are split over K; the 4096 x 4096 layer (tiled GEMM)
+    # and the 4096 x 16 layer (few-outputs kernel) finish G in one kernel and qualify
     mixed = WL.mlp_4096().with_(layers=WL._mlp([512, 512, 4096, 4096, 16], WL.RELU), batch=2048, delays=(6, 4, 2, 0))
     ctx = lp.lp_create(descs(mixed), mixed.L, mixed.batch, lp.LP_BF16, lp.LP_LOSS_SOFTMAX_CE, 1e-3)
     n0 = lp.lp_workspace_bytes(ctx)
-    for l in (1, 2, 4):
+    for l in (1, 2):
         assert L.lp_set_retimed_update(ctx, l, 1) == 4 and b"split over K" in L.lp_last_error(ctx)
     assert L.lp_set_retimed_update(ctx, 0, 1) == 0
-    # layer 3 (d = 2): three gradients and two working copies become four versions
-    assert n0 - lp.lp_workspace_bytes(ctx) == 4096 * 4096 * (3 * 4 + 2 * 2 - 4 * 2)
+    # layer 3 (d = 2): three gradients and two working copies become four versions; layer 4 (d = 0): one and two become two
+    assert n0 - lp.lp_workspace_bytes(ctx) == 4096 * 4096 * (3 * 4 + 2 * 2 - 4 * 2) + 4096 * 16 * (1 * 4 + 2 * 2 - 2 * 2)
     lp.lp_destroy(ctx)
 
 

@@ -309,9 +309,9 @@ def test_ffn_stack_full_size_retimed_update_equals_gradient_ring_bit_for_bit():
 
 
 @pytest.mark.timeout(600)
-@pytest.mark.parametrize("name", ["mlp_4096_bf16", "mlp_imbalanced_bf16"])
+@pytest.mark.parametrize("name", ["mlp_4096_bf16", "mlp_imbalanced_bf16", "vgg_small_bf16"])
 def test_full_size_retimed_update_equals_gradient_ring_bit_for_bit(name):
-    """The two mid-size workloads at their full sizes in the form bench.py times by default (retimed update on every
+    """The mid-size workloads at their full sizes in the form bench.py times by default (retimed update on every
     layer that qualifies, three streams) against the gradient-ring form, step by step past the largest delay:
     losses and working weights of every layer after every step, and the master weights of the retimed layers
     against the gradient-ring run continued for d_l more steps, bit for bit."""

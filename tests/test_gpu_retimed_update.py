@@ -146,26 +146,30 @@ def test_retimed_update_with_delta_split():
 
 
 def test_retimed_update_skips_layers_it_cannot_serve():
-    """Batch 2048: the G products of 512 x 512, 512 x 4096 and 4096 x 16 layers are cut into K ranges (or run on the
-    few-outputs kernels); the fused product-and-update kernel never cuts K, so "every layer" leaves those on the
-    gradient ring and only the 4096 x 4096 layer is retimed.  Naming one of the others is LP_ERR_LAYER."""
+    """Batch 2048: the G products of the 512 x 512 and 512 x 4096 layers are cut into K ranges, so no single kernel
+    finishes G and "every layer" leaves them on the gradient ring; the 4096 x 4096 layer (tiled GEMM) and the
+    4096 x 16 layer (few-outputs kernel) are retimed.  Naming one of the others is LP_ERR_LAYER."""
     wl = WL.mlp_4096().with_(layers=WL._mlp([512, 512, 4096, 4096, 16], WL.RELU), batch=2048, delays=(6, 4, 2, 0))
     W0 = WL.init_weights(wl)
-    lockstep(wl, W0, 9, {}, dict(retimed_update=True), {3})
+    lockstep(wl, W0, 9, {}, dict(retimed_update=True), {3, 4})
     with pytest.raises(lp.LpError) as e:
         lp.Network(wl.layers, wl.batch, wl.dtype, wl.loss, wl.lr, wl.delays, retimed_update=[1])
     assert e.value.status == 4
 
 
 def test_retimed_update_in_a_network_with_convolutions():
-    """Convolution layers keep their gradient rings; the classifier of the small VGG (few outputs) does too, so a
-    wider linear head is put on top here and is the one retimed layer."""
-    base = WL.vgg_small()
+    """A convolution applies its update in the kernel that sums the split-K partials of its G product (also the
+    three-channel image layer), the ten-output classifier in the few-outputs kernel: every layer of the small VGG is
+    retimed.  With a wider head on top (tiled GEMM) as well; and with only some of the layers retimed."""
+    base = WL.vgg_small(batch=16)
+    W0 = WL.init_weights(base)
+    lockstep(base, W0, 16, {}, dict(retimed_update=True), set(range(1, base.L + 1)))
+    lockstep(base, W0, 8, {}, dict(retimed_update=[2, 5, base.L]), {2, 5, base.L})
+    lockstep(base, W0, 16, {}, dict(retimed_update=True, run_ahead=True), set(range(1, base.L + 1)))
     layers = tuple(base.layers[:-1]) + (WL.Layer(WL.LINEAR, base.layers[-1].d_in, 256, WL.RELU), WL.Layer(WL.LINEAR, 256, 64, WL.IDENTITY))
     L = len(layers)
-    wl = base.with_(layers=layers, batch=16, delays=tuple(2 * (L - l) for l in range(1, L + 1)))
-    W0 = WL.init_weights(wl)
-    lockstep(wl, W0, 6, {}, dict(retimed_update=True), {L - 1, L})
+    wl = base.with_(layers=layers, delays=tuple(2 * (L - l) for l in range(1, L + 1)))
+    lockstep(wl, WL.init_weights(wl), 6, {}, dict(retimed_update=True), set(range(1, L + 1)))
 
 
 def test_retimed_update_entry_points_and_errors():
