@@ -166,6 +166,7 @@ def test_retimed_update_in_a_network_with_convolutions():
     lockstep(base, W0, 16, {}, dict(retimed_update=True), set(range(1, base.L + 1)))
     lockstep(base, W0, 8, {}, dict(retimed_update=[2, 5, base.L]), {2, 5, base.L})
     lockstep(base, W0, 16, {}, dict(retimed_update=True, run_ahead=True), set(range(1, base.L + 1)))
+    lockstep(base, W0, 20, {}, dict(retimed_update=True, graphs=True), set(range(1, base.L + 1)))   # steps past the warm-up run as captured graphs
     layers = tuple(base.layers[:-1]) + (WL.Layer(WL.LINEAR, base.layers[-1].d_in, 256, WL.RELU), WL.Layer(WL.LINEAR, 256, 64, WL.IDENTITY))
     L = len(layers)
     wl = base.with_(layers=layers, delays=tuple(2 * (L - l) for l in range(1, L + 1)))
