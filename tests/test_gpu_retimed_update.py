@@ -100,6 +100,16 @@ def test_retimed_update_with_run_ahead_graphs_factor_ring_and_odd_delays():
     lockstep(wl, W0, 30, {}, dict(retimed_update=[1, 4], factor_ring=[2, 3], run_ahead=True), every)
 
 
+@pytest.mark.parametrize("act", [WL.TANH, WL.SIGMOID, WL.GELU])
+def test_retimed_update_with_other_activations_and_separate_hadamard_kernels(act):
+    """tanh / sigmoid layers keep the stand-alone Hadamard kernels; GELU is run here with the fused form switched off."""
+    wl = WL.mlp_4096().with_(layers=WL._mlp([136, 264, 200, 72, 24], act), batch=40, delays=(5, 2, 1, 0))
+    W0 = WL.init_weights(wl)
+    every = {1, 2, 3, 4}
+    lockstep(wl, W0, 14, {}, dict(retimed_update=True, fused_hadamard=False), every)
+    lockstep(wl, W0, 14, dict(fused_hadamard=False), dict(retimed_update=True, run_ahead=True), every)
+
+
 def test_retimed_update_graph_replay_really_replays():
     wl = WL.mlp_4096().with_(layers=WL._mlp([256, 320, 192, 40], WL.RELU), batch=96, delays=(4, 2, 0))
     W0 = WL.init_weights(wl)
