@@ -459,6 +459,9 @@ def main():
         gdt, gloss, gprof, gupd = run_workload(wl, args.steps, args.warmup, 3, True, None, False, False, retimed=False)
         ring_form = {"streams": 3, "ms_per_step": gdt / args.steps * 1e3, "value": wl.batch * args.steps / gdt, "final_loss": gloss,
                      "updated_params_per_step": gupd / args.steps, "tasks": task_rates(gprof, args.steps, gupd, False, retimed=False)}
+        # ... and its kernels' own rates (one stream, 4 steps): the stand-alone update kernel is the HBM-bound one
+        _, _, gprof1, gupd1 = run_workload(wl, 4, args.warmup, 1, True, None, False, False, retimed=False)
+        ring_form["tasks_one_stream"] = task_rates(gprof1, 4, gupd1, False, retimed=False)
 
     # dominant kernel: the bf16 MFMA GEMM of the forward products (same instantiation for all layers
     # of the default workload)
