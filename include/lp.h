@@ -254,10 +254,9 @@ int lp_set_factor_ring(lp_ctx* ctx, int l, int enable);
  * (LP_T_WORK_W is those); LP_T_G_LAST is NULL; lp_grad_weight with G == NULL is the whole G task (it applies the
  * gradient and writes version n + 1: call it once per step) and lp_update is LP_ERR_STATE; lp_step accepts only the layer's own
  * d_l in `delay` (LP_ERR_DELAY); lp_set_weights sets the master weights and every held version.
- * LP_BF16 contexts (LP_ERR_DTYPE).  The update rides in the kernel that finishes G: a linear layer qualifies unless its
- * G product is split over K ranges (see lp_set_factor_ring) or it has a factor ring; a convolution qualifies when its G
- * product is split over K (batch x H x W >= 1024 pixels and fewer than 512 output tiles of 128 x 64: the update is applied
- * where the partial sums are added).  l = 0 selects every such layer and leaves the others as they are, l > 0 on another
+ * LP_BF16 contexts (LP_ERR_DTYPE).  The update rides in the kernel that finishes G (where K is cut into ranges: the one
+ * that adds the partial sums): every linear layer without a factor ring qualifies; a convolution qualifies when its G
+ * product is split over K (batch x H x W >= 1024 pixels and fewer than 512 output tiles of 128 x 64).  l = 0 selects every such layer and leaves the others as they are, l > 0 on another
  * layer is LP_ERR_LAYER.  Works with every schedule of lp_step (streams, run-ahead,
  * graph replay, delta split).  Call after lp_create and before lp_workspace_bytes / lp_bind_workspace (LP_ERR_STATE
  * afterwards). */

@@ -148,6 +148,11 @@ __global__ void __launch_bounds__(256) splitk_reduce_kernel(const float* __restr
         }
     }
   }
+  if (p.sgd_master) {   // a weight-gradient product that is consumed on the spot: Eq. 6 applied to the summed tile
+    SgdEpilogue epi{p.sgd_master, p.out_z, p.neg_lr, p.M, p.N, p.ldc, 0, 0, p.vec_out != 0};
+    epi(row, col, acc);
+    return;
+  }
   StoreEpilogueT<true> epi{p.out_z, p.out_a, p.out_f32, p.M, p.N, p.ldc, p.act, 0, 0, p.vec_out != 0, p.act_lut, p.had_s, p.had_lut};
   epi.with_static_act([&](auto store) { store(row, col, acc); });
 }
@@ -461,15 +466,11 @@ hipError_t launch_gemm_bf16(const GemmDesc& d, hipStream_t s, int tile_cfg) {
     if (t256 >= 192) cfg = aligned ? 4 : (both_kc ? 0 : 3);
     else if (aligned) cfg = 5;
     else cfg = t128 >= 64 ? 1 : 2;
-    // A product with the update in its epilogue and a short reduction is bound by the 10 bytes per weight of that
-    // epilogue: 128 x 128 tiles, two workgroups per CU, let one workgroup's main loop run under the other's epilogue
-    // (4096 x 4096 outputs over K = 256: 40 us per launch, and the step of eight such layers 0.69 -> 0.64 ms; at K = 1024
-    // the larger tile is ahead again).  Every element is summed over k
-    // in the same order in both tilings, so the bits do not depend on the choice.
-    if (sgd && cfg == 4 && d.K <= 512) cfg = 5;
   }
   if (cfg < 0 || cfg >= gemm_bf16_num_cfgs()) return hipErrorInvalidValue;
-  if (tile_cfg < 0 && !sgd && (cfg == 5 || cfg == 1 || cfg == 2)) {
+  // (with the update in the epilogue the same rule holds: K is cut exactly where the plain product's would be, the
+  // partial sums are added in the same order, and the kernel that adds them applies the update)
+  if (tile_cfg < 0 && (cfg == 5 || cfg == 1 || cfg == 2)) {
     // small tiles that do not fill the chip and a long reduction: split K over workgroups.  A caller
     // that multiplies a column range of a larger product passes the split count of the whole product,
     // so that every output element is summed in the same order however the columns are cut.
@@ -486,15 +487,22 @@ hipError_t launch_gemm_bf16(const GemmDesc& d, hipStream_t s, int tile_cfg) {
       }
     }
   }
+  // A product with the update in its epilogue and a short reduction is bound by the 10 bytes per weight of that
+  // epilogue: 128 x 128 tiles, two workgroups per CU, let one workgroup's main loop run under the other's epilogue
+  // (4096 x 4096 outputs over K = 256: 40 us per launch, and the step of eight such layers 0.69 -> 0.64 ms; at K = 1024
+  // the larger tile is ahead again).  Every element is summed over k in the same order in both tilings, so the bits
+  // do not depend on the choice.
+  if (tile_cfg < 0 && sgd && cfg == 4 && d.K <= 512) cfg = 5;
+  const bool sgd_in_tile = sgd && a.kt_per_split == 0;   // otherwise the reduction kernel applies it
   if (kCfgs[cfg].kind == 1) {
     if (!aligned) return hipErrorInvalidValue;
-    if (sgd) return launch_cfg_dl_sgd(cfg, a, s);
+    if (sgd_in_tile) return launch_cfg_dl_sgd(cfg, a, s);
     if (d.a_kcontig && d.b_kcontig) return launch_cfg_dl<true, true>(cfg, a, s);
     if (d.a_kcontig && !d.b_kcontig) return launch_cfg_dl<true, false>(cfg, a, s);
     if (!d.a_kcontig && !d.b_kcontig) return launch_cfg_dl<false, false>(cfg, a, s);
     return launch_cfg_dl<false, true>(cfg, a, s);
   }
-  if (sgd) return aligned ? launch_cfg_sgd<true>(cfg, a, s) : launch_cfg_sgd<false>(cfg, a, s);
+  if (sgd_in_tile) return aligned ? launch_cfg_sgd<true>(cfg, a, s) : launch_cfg_sgd<false>(cfg, a, s);
   if (aligned) {
     if (d.a_kcontig && d.b_kcontig) return launch_cfg<true, true, true>(cfg, a, s);
     if (d.a_kcontig && !d.b_kcontig) return launch_cfg<true, false, true>(cfg, a, s);

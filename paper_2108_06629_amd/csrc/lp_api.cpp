@@ -343,6 +343,8 @@ hipError_t enqueue_G(lp_ctx* c, Layer& ly, const void* X, const void* dY, long s
     g.out_z = version_slot(c, ly, step);
     g.sgd_master = (float*)(c->ws + ly.off_master);
     g.sgd_lr = c->lr;
+    // K is cut where lp_grad_weight cuts it (same scratch region, same rule), and the kernel that adds the partial sums applies the update
+    g.splitk_scratch = (float*)(c->ws + c->off_splitk[1]); g.splitk_bytes = c->splitk_bytes[1];
     return lp::launch_gemm_bf16(g, s);
   }
   if (!ly.factor_ring) return do_grad_weight(c, ly, X, dY, ring_slot(c, ly, step), s);
@@ -1096,17 +1098,17 @@ int lp_set_retimed_update(lp_ctx* c, int l, int enable) {
     if (!is_bf16(c)) return fail(c, LP_ERR_DTYPE, "lp_set_retimed_update: needs an LP_BF16 context");
     if (l != 0)
       if (int r = check_layer(c, l)) return r;
-    // The update rides in the kernel that finishes G, in the summation order of lp_grad_weight: the epilogue of the tiled
-    // GEMM or of the few-outputs kernel for a linear layer, the kernel that sums the split-K partials for a convolution.
-    // A linear layer whose G product is cut into K ranges, and a convolution whose G product is not, have no such
-    // place, and keep their gradient rings.
+    // The update rides in the kernel that finishes G, in the summation order of lp_grad_weight: for a linear layer the
+    // epilogue of the tiled GEMM or of the few-outputs kernel, or the kernel that adds the partial sums where K is cut into
+    // ranges; for a convolution the kernel that adds the split-K partial sums.  A convolution whose G product is not split
+    // has no such kernel, and keeps its gradient ring.
     auto eligible = [&](const Layer& ly) {
       if (ly.d.kind == LP_CONV3X3) return lp::conv_grad_weight_scratch_bytes(conv_desc(c, ly)) > 0;
-      return !ly.factor_ring && (lp::gemm_skinny_shape(c->batch, ly.d.in, ly.d.out) || lp::gemm_bf16_splitk_splits(ly.d.in, ly.d.out, c->batch) <= 1);
+      return !ly.factor_ring;
     };
     if (l != 0 && enable && !eligible(c->layers[l - 1]))
-      return fail(c, LP_ERR_LAYER, "lp_set_retimed_update: layer %d has a factor ring, is a linear layer whose G product is split over K at this batch "
-                  "size, or a convolution whose G product is not; it keeps its gradient ring", l);
+      return fail(c, LP_ERR_LAYER, "lp_set_retimed_update: layer %d has a factor ring, or is a convolution whose G product is not split over K at "
+                  "this batch size; it keeps its gradient ring", l);
     for (int i = 0; i < c->L; ++i) {
       Layer& ly = c->layers[i];
       if (l == 0 || i == l - 1) ly.retimed = enable != 0 && eligible(ly);

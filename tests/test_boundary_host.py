@@ -279,16 +279,18 @@ def test_retimed_update_trades_the_gradient_ring_for_weight_versions():
     saved = sum((d + 1) * ly.n_params * 4 + 2 * ly.n_params * 2 - (d + 2) * ly.n_params * 2 for d, ly in zip(cnn.delays, cnn.layers))
     assert abs((n_cnn - lp.lp_workspace_bytes(ctx)) - saved) < 2 ** 14
     lp.lp_destroy(ctx)
-    # batch 2048: the G products of the 512 x 512 and 512 x 4096 layers are split over K; the 4096 x 4096 layer (tiled GEMM)
-    # and the 4096 x 16 layer (few-outputs kernel) finish G in one kernel and qualify
+    # batch 2048: the G products of the 512 x 512 and 512 x 4096 layers are split over K (the kernel that adds the partial
+    # sums applies the update), the 4096 x 4096 layer runs the tiled GEMM and the 4096 x 16 layer the few-outputs kernel:
+    # every linear layer qualifies
     mixed = WL.mlp_4096().with_(layers=WL._mlp([512, 512, 4096, 4096, 16], WL.RELU), batch=2048, delays=(6, 4, 2, 0))
     ctx = lp.lp_create(descs(mixed), mixed.L, mixed.batch, lp.LP_BF16, lp.LP_LOSS_SOFTMAX_CE, 1e-3)
     n0 = lp.lp_workspace_bytes(ctx)
-    for l in (1, 2):
-        assert L.lp_set_retimed_update(ctx, l, 1) == 4 and b"split over K" in L.lp_last_error(ctx)
+    assert L.lp_set_retimed_update(ctx, 3, 1) == 0
+    # layer 3 (d = 2): three gradients and two working copies become four versions
+    assert n0 - lp.lp_workspace_bytes(ctx) == 4096 * 4096 * (3 * 4 + 2 * 2 - 4 * 2)
     assert L.lp_set_retimed_update(ctx, 0, 1) == 0
-    # layer 3 (d = 2): three gradients and two working copies become four versions; layer 4 (d = 0): one and two become two
-    assert n0 - lp.lp_workspace_bytes(ctx) == 4096 * 4096 * (3 * 4 + 2 * 2 - 4 * 2) + 4096 * 16 * (1 * 4 + 2 * 2 - 2 * 2)
+    saved = sum((d + 1) * ly.n_params * 4 + 2 * ly.n_params * 2 - (d + 2) * ly.n_params * 2 for d, ly in zip(mixed.delays, mixed.layers))
+    assert n0 - lp.lp_workspace_bytes(ctx) == saved
     lp.lp_destroy(ctx)
 
 

@@ -155,16 +155,18 @@ def test_retimed_update_with_delta_split():
     net.close()
 
 
-def test_retimed_update_skips_layers_it_cannot_serve():
-    """Batch 2048: the G products of the 512 x 512 and 512 x 4096 layers are cut into K ranges, so no single kernel
-    finishes G and "every layer" leaves them on the gradient ring; the 4096 x 4096 layer (tiled GEMM) and the
-    4096 x 16 layer (few-outputs kernel) are retimed.  Naming one of the others is LP_ERR_LAYER."""
+def test_retimed_update_where_the_gradient_product_is_split_over_k():
+    """Batch 2048: the G products of the 512 x 512 and 512 x 4096 layers are cut into K ranges -- the kernel that adds
+    their partial sums applies the update, K cut exactly where lp_grad_weight cuts it; the 4096 x 4096 layer runs the
+    tiled GEMM and the 4096 x 16 layer the few-outputs kernel.  All four are retimed, alone and together."""
     wl = WL.mlp_4096().with_(layers=WL._mlp([512, 512, 4096, 4096, 16], WL.RELU), batch=2048, delays=(6, 4, 2, 0))
     W0 = WL.init_weights(wl)
-    lockstep(wl, W0, 9, {}, dict(retimed_update=True), {3, 4})
-    with pytest.raises(lp.LpError) as e:
-        lp.Network(wl.layers, wl.batch, wl.dtype, wl.loss, wl.lr, wl.delays, retimed_update=[1])
-    assert e.value.status == 4
+    lockstep(wl, W0, 9, {}, dict(retimed_update=True), {1, 2, 3, 4})
+    lockstep(wl, W0, 9, {}, dict(retimed_update=[1, 2]), {1, 2})
+    lockstep(wl, W0, 9, {}, dict(retimed_update=True, run_ahead=True), {1, 2, 3, 4})
+    # ragged: 520 x 264 outputs (the register-staged loop) over a batch of 2100
+    wl = WL.mlp_4096().with_(layers=WL._mlp([520, 264, 72], WL.RELU), batch=2100, delays=(2, 0))
+    lockstep(wl, WL.init_weights(wl), 6, {}, dict(retimed_update=True), {1, 2})
 
 
 def test_retimed_update_in_a_network_with_convolutions():
