@@ -138,23 +138,28 @@ __global__ void __launch_bounds__(1024) act_grad_bf16_lds_lut_kernel(const u32x4
     const int m = b & 0x7fff;
     return m < LUT_CACHED ? tab[m + (b >> 15) * LUT_CACHED] : lut[b];
   };
+  // four 16-byte vectors of each operand in flight per lane: one workgroup per CU has to keep the whole of that CU's
+  // share of the memory pipeline busy (128 KiB per CU)
+  constexpr int U = 4;
   const size_t stride = (size_t)gridDim.x * 1024;
-  for (size_t i = (size_t)blockIdx.x * 1024 + threadIdx.x; i < nvec; i += 2 * stride) {
-    const size_t i2 = i + stride;
-    const bool two = i2 < nvec;
-    const u32x4 a0 = __builtin_nontemporal_load(dA + i), s0 = __builtin_nontemporal_load(S + i);
-    u32x4 a1 = {0u, 0u, 0u, 0u}, s1 = {0u, 0u, 0u, 0u};
-    if (two) { a1 = __builtin_nontemporal_load(dA + i2); s1 = __builtin_nontemporal_load(S + i2); }
-    u32x4 o0, o1;
+  for (size_t i = (size_t)blockIdx.x * 1024 + threadIdx.x; i < nvec; i += U * stride) {
+    u32x4 a[U], sv[U];
 #pragma unroll
-    for (int d = 0; d < 4; ++d) {
-      o0[d] = (unsigned)f2bf(bf2f((unsigned short)(a0[d] & 0xffffu)) * df((unsigned short)(s0[d] & 0xffffu))) |
-              ((unsigned)f2bf(bf2f((unsigned short)(a0[d] >> 16)) * df((unsigned short)(s0[d] >> 16))) << 16);
-      o1[d] = (unsigned)f2bf(bf2f((unsigned short)(a1[d] & 0xffffu)) * df((unsigned short)(s1[d] & 0xffffu))) |
-              ((unsigned)f2bf(bf2f((unsigned short)(a1[d] >> 16)) * df((unsigned short)(s1[d] >> 16))) << 16);
+    for (int u = 0; u < U; ++u) {
+      const size_t k = i + u * stride;
+      if (k < nvec) { a[u] = __builtin_nontemporal_load(dA + k); sv[u] = __builtin_nontemporal_load(S + k); }
+      else { a[u] = u32x4{0u, 0u, 0u, 0u}; sv[u] = u32x4{0u, 0u, 0u, 0u}; }
     }
-    __builtin_nontemporal_store(o0, dY + i);
-    if (two) __builtin_nontemporal_store(o1, dY + i2);
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const size_t k = i + u * stride;
+      u32x4 o;
+#pragma unroll
+      for (int d = 0; d < 4; ++d)
+        o[d] = (unsigned)f2bf(bf2f((unsigned short)(a[u][d] & 0xffffu)) * df((unsigned short)(sv[u][d] & 0xffffu))) |
+               ((unsigned)f2bf(bf2f((unsigned short)(a[u][d] >> 16)) * df((unsigned short)(sv[u][d] >> 16))) << 16);
+      if (k < nvec) __builtin_nontemporal_store(o, dY + k);
+    }
   }
   if (blockIdx.x == 0) {   // scalar tail (n not a multiple of 8)
     const size_t i = nvec * 8 + threadIdx.x;
