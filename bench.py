@@ -253,7 +253,12 @@ def default_streams(wl, retimed):
     """Streams of the serial schedule when --streams is not given: three, on which small kernels run side by side and the
     delayed updates overlap the products -- but one for a network whose every product fills the chip alone once the
     retimed update has removed the update tasks: nothing is left to run beside the products, and the forks and joins
-    of a step only cost (ffn_stack: 44.43 ms on three streams, 44.22 ms on one, same box)."""
+    of a step only cost (ffn_stack: 44.43 ms on three streams, 44.22 ms on one, same box); and one for a network so
+    small that the host's enqueue time bounds its step."""
+    if sum(wl.flops_per_step()) < 1e10:
+        # a step of a few microseconds of GPU work is bound by the host's enqueue time, and cross-stream waits are the
+        # expensive part of that (mlp_small: 0.13 ms per step on one stream, 0.22 ms on three)
+        return 1
     return 1 if (retimed and wl.dtype == "bf16" and fills_chip(wl)) else 3
 
 
