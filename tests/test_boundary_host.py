@@ -321,3 +321,14 @@ def test_fused_hadamard_switch_decides_whether_dA_is_materialised():
     assert L.lp_bind_workspace(ctx, 0x10000, 1 << 40) == 0
     assert all(lp.lp_tensor(ctx, l, lp.LP_T_DA)[0] for l in range(1, small.L))
     lp.lp_destroy(ctx)
+
+
+def test_bench_picks_its_streams_from_the_shape_of_the_network():
+    """Host logic of bench.py: one stream for a network whose every product fills the chip once the retimed update has
+    removed the update tasks, and for one so small that the host's enqueue time bounds its step; three otherwise."""
+    import bench
+    want = {"mlp_small_f32": 1, "mlp_4096_bf16": 3, "vgg_small_bf16": 3, "ffn_stack_bf16": 1, "mlp_imbalanced_bf16": 3}
+    for name, mk in WL.CONFIGS.items():
+        assert bench.default_streams(mk(), True) == want[name], name
+    assert bench.default_streams(WL.ffn_stack(), False) == 3          # gradient rings: the updates overlap the products
+    assert bench.fills_chip(WL.ffn_stack()) and not bench.fills_chip(WL.mlp_4096()) and not bench.fills_chip(WL.vgg_small())
